@@ -1,0 +1,102 @@
+"""Seeded synthetic inputs for the dense-op workloads.
+
+This module only draws random numbers and shapes them; it contains none of the
+ops' arithmetic.  It serves both the CPU oracle's tests and the GPU library's
+tests/benchmark so that the two sides always see the same arrays.
+
+All arrays are float32, C-contiguous, NHWC for images, HWIO for conv filters
+and [fh,fw,C,mult] for depthwise filters.  Values come from
+numpy.random.Generator(PCG64(seed)) in float64 and are cast to float32 on the
+host.  Tensors are drawn in a fixed order: inputs first, then weights layer by
+layer (filter before bias).
+
+The workloads stand in for the trained MobileNet v1 1.0 / 224x224x3 image of
+Section 3.9 (Table 1): same shapes, random values.  "He-normal" means an
+untruncated normal with std = sqrt(2 / fan_in), fan_in being the number of
+products summed per output value (fh*fw*Cin for conv2d, fh*fw for depthwise,
+1024 for the fully connected layer); biases are N(0, 0.01^2).
+"""
+import numpy as np
+
+MOBILENET_V1_CHANNELS = (64, 128, 128, 256, 256, 512, 512, 512, 512, 512, 512, 1024, 1024)
+MOBILENET_V1_STRIDES = (1, 2, 1, 2, 1, 2, 1, 1, 1, 1, 1, 2, 1)
+BIAS_STD = 0.01
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def uniform(rng, shape, lo=-1.0, hi=1.0):
+    return rng.uniform(lo, hi, size=shape).astype(np.float32)
+
+
+def normal(rng, shape, std=1.0):
+    return (rng.standard_normal(size=shape) * std).astype(np.float32)
+
+
+def he_normal(rng, shape, fan_in):
+    return normal(rng, shape, np.sqrt(2.0 / fan_in))
+
+
+def matmul_small(seed=0, m=64, k=128, n=64):
+    """tf.matMul A[m,k] x B[k,n], entries uniform[-1,1)."""
+    rng = _rng(seed)
+    return {"a": uniform(rng, (m, k)), "b": uniform(rng, (k, n)), "transpose_a": False, "transpose_b": False}
+
+
+def pointwise_conv(seed=1, n=1, h=56, w=56, cin=128, cout=128):
+    """1x1 conv2d: x uniform[-1,1), filter He-normal, bias N(0,0.01^2); stride 1, same, ReLU6."""
+    rng = _rng(seed)
+    x = uniform(rng, (n, h, w, cin))
+    f = he_normal(rng, (1, 1, cin, cout), cin)
+    b = normal(rng, (cout,), BIAS_STD)
+    return {"x": x, "filter": f, "bias": b, "stride": 1}
+
+
+def depthwise_conv(seed=2, n=1, h=112, w=112, c=64, k=3, mult=1):
+    """depthwiseConv2d kxk: x uniform[-1,1), filter He-normal (fan_in k*k), bias N(0,0.01^2)."""
+    rng = _rng(seed)
+    x = uniform(rng, (n, h, w, c))
+    f = he_normal(rng, (k, k, c, mult), k * k)
+    b = normal(rng, (c * mult,), BIAS_STD)
+    return {"x": x, "filter": f, "bias": b}
+
+
+def batch_matmul(seed=3, batch=8, m=1024, k=1024, n=1024):
+    """batchMatMul with transposeB: A[batch,m,k], B stored [batch,n,k], entries N(0,1)."""
+    rng = _rng(seed)
+    return {"a": normal(rng, (batch, m, k)), "b": normal(rng, (batch, n, k)),
+            "transpose_a": False, "transpose_b": True}
+
+
+def conv_general(seed, n, h, w, cin, cout, fh, fw):
+    rng = _rng(seed)
+    x = uniform(rng, (n, h, w, cin))
+    f = he_normal(rng, (fh, fw, cin, cout), fh * fw * cin)
+    b = normal(rng, (cout,), BIAS_STD)
+    return {"x": x, "filter": f, "bias": b}
+
+
+def mobilenet_v1_weights(rng):
+    """Random MobileNet-v1 1.0 weights (batch norm folded into the biases)."""
+    w = {"dw_w": [], "dw_b": [], "pw_w": [], "pw_b": []}
+    w["conv0_w"] = he_normal(rng, (3, 3, 3, 32), 27)
+    w["conv0_b"] = normal(rng, (32,), BIAS_STD)
+    cin = 32
+    for cout in MOBILENET_V1_CHANNELS:
+        w["dw_w"].append(he_normal(rng, (3, 3, cin, 1), 9))
+        w["dw_b"].append(normal(rng, (cin,), BIAS_STD))
+        w["pw_w"].append(he_normal(rng, (1, 1, cin, cout), cin))
+        w["pw_b"].append(normal(rng, (cout,), BIAS_STD))
+        cin = cout
+    w["fc_w"] = he_normal(rng, (1024, 1000), 1024)
+    w["fc_b"] = normal(rng, (1000,), BIAS_STD)
+    return w
+
+
+def mobilenet_v1(seed=4, batch=1):
+    """Image [batch,224,224,3] uniform[-1,1) and random MobileNet-v1 1.0 weights."""
+    rng = _rng(seed)
+    image = uniform(rng, (batch, 224, 224, 3))
+    return {"image": image, "weights": mobilenet_v1_weights(rng)}

@@ -1,0 +1,131 @@
+"""Pins for the oracle's MobileNet-v1 tail ops and forward chain (CPU only)."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1901_05350_amd import inputs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "mobilenet_v1_totals.txt")
+
+
+def golden():
+    out = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            k, *v = line.split()
+            out[k] = [int(t) for t in v]
+    return out
+
+
+def test_layer_walk_totals_match_the_published_network_size():
+    g = golden()
+    macs = params = 0
+    shape = (1, 224, 224, 3)
+    f = (3, 3, 3, 32)
+    shape_out, _ = oracle.conv2d_out_shape(shape, f, 2, oracle.PAD_SAME)
+    macs += math.prod(shape_out) * 27
+    params += math.prod(f) + 32
+    shape = shape_out
+    for cout, s in zip(oracle.MOBILENET_V1_CHANNELS, oracle.MOBILENET_V1_STRIDES):
+        cin = shape[3]
+        shape, _ = oracle.depthwise_conv2d_out_shape(shape, (3, 3, cin, 1), s, oracle.PAD_SAME)
+        macs += math.prod(shape) * 9
+        params += 9 * cin + cin
+        shape, _ = oracle.conv2d_out_shape(shape, (1, 1, cin, cout), 1, oracle.PAD_SAME)
+        macs += math.prod(shape) * cin
+        params += cin * cout + cout
+    assert list(shape[1:]) == g["final_map"]
+    macs += 1024 * 1000
+    params += 1024 * 1000 + 1000
+    assert macs == g["macs"][0]
+    assert params == g["params"][0]
+    # the input generator's tables agree with the oracle's own
+    assert inputs.MOBILENET_V1_CHANNELS == oracle.MOBILENET_V1_CHANNELS
+    assert inputs.MOBILENET_V1_STRIDES == oracle.MOBILENET_V1_STRIDES
+
+
+def test_global_avg_pool_closed_forms():
+    const = np.full((2, 7, 7, 5), 3.25, np.float32)
+    assert np.array_equal(oracle.global_avg_pool(const), np.full((2, 5), 3.25, np.float32))
+    a = np.arange(2 * 2 * 3 * 2, dtype=np.float32).reshape(2, 2, 3, 2)
+    want = a.reshape(2, 6, 2).astype(np.float64).mean(axis=1)
+    assert np.allclose(oracle.global_avg_pool(a), want, rtol=1e-7)
+    # one channel of one image set to 49 at a single pixel of a 7x7 map -> mean exactly 1
+    z = np.zeros((1, 7, 7, 3), np.float32)
+    z[0, 4, 2, 1] = 49
+    assert oracle.global_avg_pool(z).tolist() == [[0, 1, 0]]
+
+
+def test_softmax_closed_forms():
+    u = oracle.softmax(np.zeros((2, 8), np.float32))
+    assert np.array_equal(u, np.full((2, 8), 0.125, np.float32))
+    p = oracle.softmax(np.array([[0.0, math.log(2.0)]], np.float32))
+    assert np.allclose(p, [[1 / 3, 2 / 3]], rtol=1e-6)
+    r = np.random.Generator(np.random.PCG64(0))
+    l = r.standard_normal((3, 1000)).astype(np.float32) * 5
+    p = oracle.softmax(l)
+    assert np.all(p >= 0) and np.allclose(p.sum(axis=1), 1.0, atol=1e-6)
+    assert np.array_equal(p.argmax(axis=1), l.argmax(axis=1))
+    # shift invariance and no overflow for large logits
+    big = oracle.softmax(l + np.float32(1000.0))
+    assert np.isfinite(big).all() and np.allclose(big, oracle.softmax((l + np.float32(1000.0)) - np.float32(1000.0)), rtol=1e-4)
+    # ratio of two entries = exp(difference)
+    assert np.allclose(p[:, 3] / p[:, 7], np.exp(l[:, 3].astype(np.float64) - l[:, 7].astype(np.float64)), rtol=1e-5)
+
+
+@pytest.fixture(scope="module")
+def net():
+    data = inputs.mobilenet_v1(seed=4, batch=1)
+    probs, logits, acts = oracle.mobilenet_v1_forward(data["image"], data["weights"], return_activations=True)
+    return data, probs, logits, acts
+
+
+def test_forward_shapes_and_probabilities(net):
+    data, probs, logits, acts = net
+    assert probs.shape == (1, 1000) and logits.shape == (1, 1000)
+    assert len(acts) == 28
+    assert acts[0].shape == (1, 112, 112, 32)
+    assert acts[26].shape == (1, 7, 7, 1024) and acts[27].shape == (1, 1024)
+    assert np.isfinite(probs).all() and np.all(probs >= 0)
+    assert abs(float(probs.astype(np.float64).sum()) - 1.0) < 1e-6
+
+
+def test_forward_is_the_chain_of_single_ops(net):
+    data, probs, logits, acts = net
+    w = data["weights"]
+    # re-run three links of the chain by hand from the recorded activations
+    a1 = oracle.depthwise_conv2d(acts[0], w["dw_w"][0], w["dw_b"][0], 1, oracle.PAD_SAME, oracle.ACT_RELU6)
+    assert np.array_equal(a1, acts[1])
+    a4 = oracle.conv2d(acts[3], w["pw_w"][1], w["pw_b"][1], 1, oracle.PAD_SAME, oracle.ACT_RELU6)
+    assert np.array_equal(a4, acts[4])
+    assert acts[3].shape == (1, 56, 56, 64)      # stride-2 depthwise of the second block
+    want_logits = acts[27].astype(np.float64) @ w["fc_w"].astype(np.float64) + w["fc_b"].astype(np.float64)
+    assert np.allclose(logits, want_logits, rtol=1e-6, atol=1e-6)
+
+
+def test_forward_is_deterministic_and_inputs_are_seeded(net):
+    data, probs, logits, acts = net
+    again = inputs.mobilenet_v1(seed=4, batch=1)
+    assert np.array_equal(again["image"], data["image"])
+    assert all(np.array_equal(a, b) for a, b in zip(again["weights"]["pw_w"], data["weights"]["pw_w"]))
+    p2, l2 = oracle.mobilenet_v1_forward(again["image"], again["weights"])
+    assert np.array_equal(p2, probs) and np.array_equal(l2, logits)
+    other = inputs.mobilenet_v1(seed=5, batch=1)
+    assert not np.array_equal(other["image"], data["image"])
+
+
+def test_random_network_is_not_degenerate(net):
+    # With He-normal weights the activations must neither die (all 0) nor saturate (all 6);
+    # otherwise a parity check against this network would be trivially true.
+    data, probs, logits, acts = net
+    for i, a in enumerate(acts[:27]):
+        zero = float((a == 0).mean())
+        six = float((a == 6).mean())
+        assert zero < 0.9 and six < 0.5, (i, zero, six)
+        assert a.std() > 0.05, (i, float(a.std()))
+    assert logits.std() > 0.05
