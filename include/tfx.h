@@ -1,0 +1,155 @@
+/*
+ * tfx.h -- C ABI of the dense-op library for AMD MI355X (gfx950).
+ *
+ * The ops are the ones that dominate the MobileNet v1 inference timed in
+ * Section 3.9 (Table 1) of the TensorFlow.js paper (arxiv 1901.05350):
+ * matMul / batchMatMul, conv2d, depthwiseConv2d, with a fused bias + activation
+ * epilogue, and the whole MobileNet v1 1.0 / 224 forward pass.
+ *
+ * Conventions common to every device entry point
+ *   - All tensors are float32, dense, row-major.  Images are NHWC (the index
+ *     order batch,row,column,depth of the conv2d sampler in Section 4.1), conv
+ *     filters are HWIO [fh,fw,inC,outC], depthwise filters are [fh,fw,inC,mult].
+ *   - Every data pointer is a DEVICE pointer.  Shape arrays and the weights
+ *     struct are HOST memory and are read before the call returns.
+ *   - Ownership: the caller owns every buffer.  The library allocates nothing,
+ *     frees nothing and keeps no state between calls.  Inputs are never written
+ *     (ops are functional, Section 3.7); the output must not overlap any input
+ *     (overlap is not detected; the result is then undefined).
+ *   - Asynchrony: a call validates its arguments on the host, enqueues its
+ *     kernels on `stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and returns without synchronising, like the enqueue-and-return
+ *     ops of Section 3.6 / 4.1.  The caller synchronises before reading.
+ *   - Errors: the return value is a tfx_status.  Validation happens before any
+ *     HIP call: a NULL pointer gives TFX_ERR_NULL; non-positive or mismatching
+ *     dimensions, or a VALID convolution whose filter exceeds the image, give
+ *     TFX_ERR_SHAPE; a stride < 1 or an unknown enum value gives TFX_ERR_ARG;
+ *     a tensor of 2^31 or more elements gives TFX_ERR_UNSUPPORTED; a workspace
+ *     that is too small or misaligned gives TFX_ERR_WORKSPACE; a failed kernel
+ *     enqueue gives TFX_ERR_LAUNCH.  On error nothing has been enqueued, except
+ *     for TFX_ERR_LAUNCH (earlier kernels of the same call may have been).
+ *   - Zero-sized tensors are rejected with TFX_ERR_SHAPE.
+ */
+#ifndef TFX_H_
+#define TFX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TFX_OK = 0,
+  TFX_ERR_NULL = -1,
+  TFX_ERR_SHAPE = -2,
+  TFX_ERR_ARG = -3,
+  TFX_ERR_UNSUPPORTED = -4,
+  TFX_ERR_WORKSPACE = -5,
+  TFX_ERR_LAUNCH = -6
+} tfx_status;
+
+typedef enum { TFX_PAD_VALID = 0, TFX_PAD_SAME = 1 } tfx_padding;
+typedef enum { TFX_ACT_NONE = 0, TFX_ACT_RELU = 1, TFX_ACT_RELU6 = 2 } tfx_activation;
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* tfx_status_string(int status);
+
+/* ------------------------------------------------------------------------- *
+ * Host-only shape rules (no GPU needed, no HIP call made).
+ *
+ * The paper defines no padding rule; its API is modelled after TensorFlow
+ * (Section 3.1), so per spatial dimension (in = input extent, k = filter
+ * extent, s = stride):
+ *   VALID: out = floor((in - k) / s) + 1, no padding, in < k is TFX_ERR_SHAPE;
+ *   SAME : out = ceil(in / s), pad_total = max((out - 1) * s + k - in, 0),
+ *          pad_before = floor(pad_total / 2), pad_after = pad_total - pad_before
+ *          (the odd unit goes to the bottom / right).
+ * pad_tblr receives top, bottom, left, right.
+ * ------------------------------------------------------------------------- */
+
+/* Output shape [M,N] of op(a) x op(b); a_shape / b_shape are the stored shapes.
+ * M = ta ? a[1] : a[0], K = ta ? a[0] : a[1], N = tb ? b[0] : b[1]; the two K must agree. */
+int tfx_matmul_out_shape(const int64_t a_shape[2], const int64_t b_shape[2],
+                         int transpose_a, int transpose_b, int64_t out_shape[2]);
+
+/* x_shape [N,H,W,inC], f_shape [fh,fw,inC,outC] -> out_shape [N,oh,ow,outC]. */
+int tfx_conv2d_out_shape(const int64_t x_shape[4], const int64_t f_shape[4],
+                         int stride_h, int stride_w, tfx_padding pad,
+                         int64_t out_shape[4], int64_t pad_tblr[4]);
+
+/* x_shape [N,H,W,C], f_shape [fh,fw,C,mult] -> out_shape [N,oh,ow,C*mult]. */
+int tfx_depthwise_conv2d_out_shape(const int64_t x_shape[4], const int64_t f_shape[4],
+                                   int stride_h, int stride_w, tfx_padding pad,
+                                   int64_t out_shape[4], int64_t pad_tblr[4]);
+
+/* ------------------------------------------------------------------------- *
+ * Device entry points.
+ * ------------------------------------------------------------------------- */
+
+/* matMul (Section 4.1, Listing 2): c[i,j] = sum_k A'(i,k) * B'(k,j) where
+ * A'(i,k) = transpose_a ? a[k,i] : a[i,k] and B'(k,j) = transpose_b ? b[j,k] : b[k,j].
+ * a, b: device, stored shapes a_shape / b_shape; c: device, [M,N].  Any M,N,K >= 1
+ * (the listing's "shared dimension is a multiple of 4" is not required). */
+int tfx_matmul(const float* a, const int64_t a_shape[2], const float* b, const int64_t b_shape[2],
+               int transpose_a, int transpose_b, float* c, void* stream);
+
+/* batchMatMul: tfx_matmul independently for each leading index.  a_shape and
+ * b_shape are [B,rows,cols] with equal B (no broadcasting); c is [B,M,N]. */
+int tfx_batch_matmul(const float* a, const int64_t a_shape[3], const float* b, const int64_t b_shape[3],
+                     int transpose_a, int transpose_b, float* c, void* stream);
+
+/* conv2d (cross-correlation, NHWC x HWIO; index order per Section 4.1) with
+ * fused epilogue:
+ *   y[n,oh,ow,o] = act( sum_{kh,kw,c} X(n, oh*sh - pt + kh, ow*sw - pl + kw, c) * filter[kh,kw,c,o] + bias[o] )
+ * X is 0 outside the image.  bias is a device pointer to [outC] or NULL (= 0).
+ * y: device, shape from tfx_conv2d_out_shape. */
+int tfx_conv2d(const float* x, const int64_t x_shape[4], const float* filter, const int64_t f_shape[4],
+               const float* bias, int stride_h, int stride_w, tfx_padding pad, tfx_activation act,
+               float* y, void* stream);
+
+/* depthwiseConv2d with fused epilogue:
+ *   y[n,oh,ow,c*mult+q] = act( sum_{kh,kw} X(n, oh*sh - pt + kh, ow*sw - pl + kw, c) * filter[kh,kw,c,q]
+ *                              + bias[c*mult+q] )
+ * bias is a device pointer to [C*mult] or NULL.  y: device, shape from
+ * tfx_depthwise_conv2d_out_shape. */
+int tfx_depthwise_conv2d(const float* x, const int64_t x_shape[4], const float* filter, const int64_t f_shape[4],
+                         const float* bias, int stride_h, int stride_w, tfx_padding pad, tfx_activation act,
+                         float* y, void* stream);
+
+/* MobileNet v1 1.0 / 224 weights (Section 3.9, Table 1 workload), batch norm
+ * already folded into the biases.  The struct lives in host memory; every
+ * member is a device pointer owned by the caller.  Block i (0-based) has
+ * dw_w[i] [3,3,Cin_i,1], dw_b[i] [Cin_i], pw_w[i] [1,1,Cin_i,Cout_i], pw_b[i] [Cout_i] with
+ * Cout = 64,128,128,256,256,512,512,512,512,512,512,1024,1024, Cin_0 = 32,
+ * and depthwise stride 2 in blocks 1, 3, 5 and 11, else 1. */
+typedef struct {
+  const float* conv0_w; /* [3,3,3,32] */
+  const float* conv0_b; /* [32] */
+  const float* dw_w[13];
+  const float* dw_b[13];
+  const float* pw_w[13];
+  const float* pw_b[13];
+  const float* fc_w; /* [1024,1000] */
+  const float* fc_b; /* [1000] */
+} tfx_mobilenet_v1_weights;
+
+/* Bytes of device workspace tfx_mobilenet_v1_forward needs for `batch` images
+ * (0 if batch < 1).  Host-only. */
+size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch);
+
+/* Full forward pass: 3x3 stride-2 conv to 32 channels, 13 x (depthwise 3x3 ->
+ * pointwise 1x1), bias + ReLU6 after each of the 27 convolutions, SAME padding
+ * throughout, global average pool, fully connected 1024 -> 1000, softmax.
+ * input: device [batch,224,224,3]; workspace: device, >= the size above, 256-byte
+ * aligned, contents undefined before and after; probs: device [batch,1000];
+ * logits: device [batch,1000] or NULL.  All kernels are enqueued on `stream`. */
+int tfx_mobilenet_v1_forward(const float* input, int64_t batch, const tfx_mobilenet_v1_weights* weights,
+                             void* workspace, size_t workspace_bytes, float* probs, float* logits,
+                             void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TFX_H_ */

@@ -1,0 +1,211 @@
+"""ctypes binding of libtfx.so: same names as the C ABI, torch tensors in and out."""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libtfx.so")
+
+PAD_VALID, PAD_SAME = 0, 1
+ACT_NONE, ACT_RELU, ACT_RELU6 = 0, 1, 2
+
+_I64P = ctypes.POINTER(ctypes.c_int64)
+_VP = ctypes.c_void_p
+
+
+class TfxWeights(ctypes.Structure):
+    """Mirror of tfx_mobilenet_v1_weights (host struct of device pointers)."""
+    _fields_ = [("conv0_w", _VP), ("conv0_b", _VP),
+                ("dw_w", _VP * 13), ("dw_b", _VP * 13), ("pw_w", _VP * 13), ("pw_b", _VP * 13),
+                ("fc_w", _VP), ("fc_b", _VP)]
+
+
+class TfxError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        try:
+            msg = lib().tfx_status_string(status).decode()
+        except Exception:
+            msg = str(status)
+        super().__init__("%s failed: %s" % (where, msg))
+
+
+_lib = None
+
+_SIGNATURES = {
+    "tfx_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "tfx_matmul_out_shape": (ctypes.c_int, [_I64P, _I64P, ctypes.c_int, ctypes.c_int, _I64P]),
+    "tfx_conv2d_out_shape": (ctypes.c_int, [_I64P, _I64P, ctypes.c_int, ctypes.c_int, ctypes.c_int, _I64P, _I64P]),
+    "tfx_depthwise_conv2d_out_shape": (ctypes.c_int, [_I64P, _I64P, ctypes.c_int, ctypes.c_int, ctypes.c_int, _I64P, _I64P]),
+    "tfx_matmul": (ctypes.c_int, [_VP, _I64P, _VP, _I64P, ctypes.c_int, ctypes.c_int, _VP, _VP]),
+    "tfx_batch_matmul": (ctypes.c_int, [_VP, _I64P, _VP, _I64P, ctypes.c_int, ctypes.c_int, _VP, _VP]),
+    "tfx_conv2d": (ctypes.c_int, [_VP, _I64P, _VP, _I64P, _VP, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                  ctypes.c_int, _VP, _VP]),
+    "tfx_depthwise_conv2d": (ctypes.c_int, [_VP, _I64P, _VP, _I64P, _VP, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                            ctypes.c_int, _VP, _VP]),
+    "tfx_mobilenet_v1_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64]),
+    "tfx_mobilenet_v1_forward": (ctypes.c_int, [_VP, ctypes.c_int64, ctypes.POINTER(TfxWeights), _VP,
+                                                ctypes.c_size_t, _VP, _VP, _VP]),
+}
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def lib():
+    """Load libtfx.so (once).  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError("libtfx.so is not built: run `python -m paper_1901_05350_amd.build`")
+        handle = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)  # AttributeError if the symbol is missing
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _shape(dims):
+    return (ctypes.c_int64 * len(dims))(*[int(d) for d in dims])
+
+
+def _pair(stride):
+    if isinstance(stride, (tuple, list)):
+        return int(stride[0]), int(stride[1])
+    return int(stride), int(stride)
+
+
+def _check(status, where):
+    if status != 0:
+        raise TfxError(status, where)
+
+
+def _dev(t, name):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a tensor in GPU memory" % name)
+    if t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError("%s must be contiguous float32" % name)
+    return t
+
+
+def _stream(t):
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def tfx_status_string(status):
+    return lib().tfx_status_string(int(status)).decode()
+
+
+def tfx_matmul_out_shape(a_shape, b_shape, transpose_a=False, transpose_b=False):
+    out = _shape((0, 0))
+    _check(lib().tfx_matmul_out_shape(_shape(a_shape), _shape(b_shape), int(transpose_a), int(transpose_b), out),
+           "tfx_matmul_out_shape")
+    return tuple(out)
+
+
+def tfx_conv2d_out_shape(x_shape, f_shape, stride, pad):
+    sh, sw = _pair(stride)
+    out, pads = _shape((0,) * 4), _shape((0,) * 4)
+    _check(lib().tfx_conv2d_out_shape(_shape(x_shape), _shape(f_shape), sh, sw, int(pad), out, pads),
+           "tfx_conv2d_out_shape")
+    return tuple(out), tuple(pads)
+
+
+def tfx_depthwise_conv2d_out_shape(x_shape, f_shape, stride, pad):
+    sh, sw = _pair(stride)
+    out, pads = _shape((0,) * 4), _shape((0,) * 4)
+    _check(lib().tfx_depthwise_conv2d_out_shape(_shape(x_shape), _shape(f_shape), sh, sw, int(pad), out, pads),
+           "tfx_depthwise_conv2d_out_shape")
+    return tuple(out), tuple(pads)
+
+
+def tfx_matmul(a, b, transpose_a=False, transpose_b=False, out=None):
+    import torch
+    _dev(a, "a"), _dev(b, "b")
+    m, n = tfx_matmul_out_shape(a.shape, b.shape, transpose_a, transpose_b)
+    c = torch.empty((m, n), dtype=torch.float32, device=a.device) if out is None else _dev(out, "out")
+    _check(lib().tfx_matmul(a.data_ptr(), _shape(a.shape), b.data_ptr(), _shape(b.shape), int(transpose_a),
+                            int(transpose_b), c.data_ptr(), _stream(a)), "tfx_matmul")
+    return c
+
+
+def tfx_batch_matmul(a, b, transpose_a=False, transpose_b=False, out=None):
+    import torch
+    _dev(a, "a"), _dev(b, "b")
+    if a.dim() != 3 or b.dim() != 3:
+        raise TypeError("batch_matmul operands must have rank 3")
+    m, n = tfx_matmul_out_shape(a.shape[1:], b.shape[1:], transpose_a, transpose_b)
+    c = torch.empty((a.shape[0], m, n), dtype=torch.float32, device=a.device) if out is None else _dev(out, "out")
+    _check(lib().tfx_batch_matmul(a.data_ptr(), _shape(a.shape), b.data_ptr(), _shape(b.shape), int(transpose_a),
+                                  int(transpose_b), c.data_ptr(), _stream(a)), "tfx_batch_matmul")
+    return c
+
+
+def _conv(fn_name, shape_fn, x, filt, bias, stride, pad, act, out):
+    import torch
+    _dev(x, "x"), _dev(filt, "filter")
+    if bias is not None:
+        _dev(bias, "bias")
+    sh, sw = _pair(stride)
+    oshape, _ = shape_fn(x.shape, filt.shape, (sh, sw), pad)
+    y = torch.empty(oshape, dtype=torch.float32, device=x.device) if out is None else _dev(out, "out")
+    fn = getattr(lib(), fn_name)
+    _check(fn(x.data_ptr(), _shape(x.shape), filt.data_ptr(), _shape(filt.shape),
+              None if bias is None else bias.data_ptr(), sh, sw, int(pad), int(act), y.data_ptr(), _stream(x)),
+           fn_name)
+    return y
+
+
+def tfx_conv2d(x, filt, bias=None, stride=1, pad=PAD_SAME, act=ACT_NONE, out=None):
+    return _conv("tfx_conv2d", tfx_conv2d_out_shape, x, filt, bias, stride, pad, act, out)
+
+
+def tfx_depthwise_conv2d(x, filt, bias=None, stride=1, pad=PAD_SAME, act=ACT_NONE, out=None):
+    return _conv("tfx_depthwise_conv2d", tfx_depthwise_conv2d_out_shape, x, filt, bias, stride, pad, act, out)
+
+
+def tfx_mobilenet_v1_workspace_bytes(batch):
+    return int(lib().tfx_mobilenet_v1_workspace_bytes(int(batch)))
+
+
+class MobileNetV1:
+    """Device-resident MobileNet-v1 weights plus a workspace; calls tfx_mobilenet_v1_forward."""
+
+    def __init__(self, weights, batch=1, device="cuda:0"):
+        import torch
+        self.device = torch.device(device)
+        self.batch = int(batch)
+        up = lambda a: torch.as_tensor(a, dtype=torch.float32).contiguous().to(self.device)
+        self.tensors = {k: ([up(t) for t in v] if isinstance(v, (list, tuple)) else up(v)) for k, v in weights.items()}
+        self.struct = TfxWeights()
+        for k in ("conv0_w", "conv0_b", "fc_w", "fc_b"):
+            setattr(self.struct, k, self.tensors[k].data_ptr())
+        for k in ("dw_w", "dw_b", "pw_w", "pw_b"):
+            arr = getattr(self.struct, k)
+            for i in range(13):
+                arr[i] = self.tensors[k][i].data_ptr()
+        nbytes = tfx_mobilenet_v1_workspace_bytes(self.batch)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.probs = torch.empty((self.batch, 1000), dtype=torch.float32, device=self.device)
+        self.logits = torch.empty((self.batch, 1000), dtype=torch.float32, device=self.device)
+
+    def forward(self, image):
+        """Enqueue one forward pass on the current stream; returns (probs, logits) device tensors."""
+        _dev(image, "image")
+        if tuple(image.shape) != (self.batch, 224, 224, 3):
+            raise TypeError("image must be [%d,224,224,3]" % self.batch)
+        tfx_mobilenet_v1_forward(image, self.struct, self.workspace, self.probs, self.logits)
+        return self.probs, self.logits
+
+
+def tfx_mobilenet_v1_forward(image, weights_struct, workspace, probs, logits=None):
+    _dev(image, "image"), _dev(probs, "probs")
+    _check(lib().tfx_mobilenet_v1_forward(image.data_ptr(), int(image.shape[0]), ctypes.byref(weights_struct),
+                                          workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                          probs.data_ptr(), None if logits is None else logits.data_ptr(),
+                                          _stream(image)), "tfx_mobilenet_v1_forward")
+    return probs

@@ -1,0 +1,280 @@
+// C ABI of libtfx: argument validation, shape rules and kernel selection.
+// Every entry point validates on the host before any HIP call and then only enqueues
+// kernels on the caller's stream (enqueue-and-return, as the ops of Section 3.6 / 4.1).
+#include "tfx_internal.h"
+
+namespace tfx {
+
+int out_extent(int64_t in, int64_t k, int64_t s, int pad, int64_t* out, int64_t* before, int64_t* after) {
+  if (in < 1 || k < 1) return TFX_ERR_SHAPE;
+  if (s < 1) return TFX_ERR_ARG;
+  if (pad == TFX_PAD_VALID) {
+    if (in < k) return TFX_ERR_SHAPE;
+    *out = (in - k) / s + 1;
+    *before = *after = 0;
+    return TFX_OK;
+  }
+  if (pad != TFX_PAD_SAME) return TFX_ERR_ARG;
+  const int64_t o = (in + s - 1) / s;
+  const int64_t need = (o - 1) * s + k - in;
+  const int64_t total = need > 0 ? need : 0;
+  *out = o;
+  *before = total >> 1;
+  *after = total - (total >> 1);
+  return TFX_OK;
+}
+
+namespace {
+
+constexpr int64_t kMaxElems = (int64_t(1) << 31) - 1;
+
+bool valid_act(int act) { return act == TFX_ACT_NONE || act == TFX_ACT_RELU || act == TFX_ACT_RELU6; }
+
+// numel, or -1 if it does not fit below 2^31
+int64_t numel(const int64_t* d, int rank) {
+  int64_t p = 1;
+  for (int i = 0; i < rank; ++i) {
+    if (d[i] > kMaxElems) return -1;
+    p *= d[i];
+    if (p > kMaxElems) return -1;
+  }
+  return p;
+}
+
+struct ConvGeom {
+  int64_t out[4];
+  int64_t pad[4];
+};
+
+int conv_geometry(const int64_t x[4], const int64_t f[4], int sh, int sw, int pad, bool depthwise, ConvGeom* g) {
+  for (int i = 0; i < 4; ++i)
+    if (x[i] < 1 || f[i] < 1) return TFX_ERR_SHAPE;
+  if (x[3] != f[2]) return TFX_ERR_SHAPE;
+  if (sh < 1 || sw < 1) return TFX_ERR_ARG;
+  if (pad != TFX_PAD_VALID && pad != TFX_PAD_SAME) return TFX_ERR_ARG;
+  int rc = out_extent(x[1], f[0], sh, pad, &g->out[1], &g->pad[0], &g->pad[1]);
+  if (rc) return rc;
+  rc = out_extent(x[2], f[1], sw, pad, &g->out[2], &g->pad[2], &g->pad[3]);
+  if (rc) return rc;
+  g->out[0] = x[0];
+  g->out[3] = depthwise ? x[3] * f[3] : f[3];
+  return TFX_OK;
+}
+
+int matmul_geometry(const int64_t a[2], const int64_t b[2], int ta, int tb, int64_t* m, int64_t* n, int64_t* k) {
+  if (a[0] < 1 || a[1] < 1 || b[0] < 1 || b[1] < 1) return TFX_ERR_SHAPE;
+  *m = ta ? a[1] : a[0];
+  *k = ta ? a[0] : a[1];
+  const int64_t kb = tb ? b[1] : b[0];
+  *n = tb ? b[0] : b[1];
+  return *k == kb ? TFX_OK : TFX_ERR_SHAPE;
+}
+
+int batch_matmul_impl(const float* a, const int64_t* a_shape, const float* b, const int64_t* b_shape, int64_t batch,
+                      int ta, int tb, float* c, void* stream) {
+  int64_t m, n, k;
+  int rc = matmul_geometry(a_shape, b_shape, ta, tb, &m, &n, &k);
+  if (rc) return rc;
+  const int64_t da[3] = {batch, m, k}, db[3] = {batch, n, k}, dc[3] = {batch, m, n};
+  if (numel(da, 3) < 0 || numel(db, 3) < 0 || numel(dc, 3) < 0) return TFX_ERR_UNSUPPORTED;
+  // stored [M,K] (not transposed) means K is contiguous for A; stored [N,K] (transposed) for B
+  return launch_gemm(a, b, c, nullptr, (int)batch, (int)m, (int)n, (int)k, !ta, tb != 0, TFX_ACT_NONE,
+                     static_cast<hipStream_t>(stream));
+}
+
+// MobileNet v1 1.0 / 224 architecture (Section 3.9, Table 1 workload).
+constexpr int kBlocks = 13;
+constexpr int kChannels[kBlocks] = {64, 128, 128, 256, 256, 512, 512, 512, 512, 512, 512, 1024, 1024};
+constexpr int kStrides[kBlocks] = {1, 2, 1, 2, 1, 2, 1, 1, 1, 1, 1, 2, 1};
+constexpr int kImage = 224, kStemChannels = 32, kClasses = 1000, kFeatures = 1024;
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct NetPlan {
+  size_t act_floats;  // per ping-pong buffer
+  size_t off_buf[2], off_pooled, off_partial, off_logits, bytes;
+};
+
+NetPlan plan_net(int64_t batch) {
+  NetPlan p{};
+  // largest feature map: the 112 x 112 x 64 output of the first pointwise layer
+  p.act_floats = (size_t)batch * 112 * 112 * 64;
+  size_t off = 0;
+  for (int i = 0; i < 2; ++i) {
+    p.off_buf[i] = off;
+    off = align_up(off + p.act_floats * sizeof(float));
+  }
+  p.off_pooled = off;
+  off = align_up(off + (size_t)batch * kFeatures * sizeof(float));
+  p.off_partial = off;
+  off = align_up(off + fc_partial_floats((int)batch, kFeatures, kClasses) * sizeof(float));
+  p.off_logits = off;
+  off = align_up(off + (size_t)batch * kClasses * sizeof(float));
+  p.bytes = off;
+  return p;
+}
+
+}  // namespace
+}  // namespace tfx
+
+using namespace tfx;
+
+extern "C" {
+
+const char* tfx_status_string(int status) {
+  switch (status) {
+    case TFX_OK: return "TFX_OK";
+    case TFX_ERR_NULL: return "TFX_ERR_NULL: null pointer argument";
+    case TFX_ERR_SHAPE: return "TFX_ERR_SHAPE: non-positive or mismatching dimensions";
+    case TFX_ERR_ARG: return "TFX_ERR_ARG: bad stride or enum value";
+    case TFX_ERR_UNSUPPORTED: return "TFX_ERR_UNSUPPORTED: tensor too large";
+    case TFX_ERR_WORKSPACE: return "TFX_ERR_WORKSPACE: workspace too small or misaligned";
+    case TFX_ERR_LAUNCH: return "TFX_ERR_LAUNCH: kernel enqueue failed";
+    default: return "unknown tfx status";
+  }
+}
+
+int tfx_matmul_out_shape(const int64_t a_shape[2], const int64_t b_shape[2], int transpose_a, int transpose_b,
+                         int64_t out_shape[2]) {
+  if (!a_shape || !b_shape || !out_shape) return TFX_ERR_NULL;
+  int64_t m, n, k;
+  int rc = matmul_geometry(a_shape, b_shape, transpose_a, transpose_b, &m, &n, &k);
+  if (rc) return rc;
+  out_shape[0] = m;
+  out_shape[1] = n;
+  return TFX_OK;
+}
+
+int tfx_conv2d_out_shape(const int64_t x_shape[4], const int64_t f_shape[4], int stride_h, int stride_w,
+                         tfx_padding pad, int64_t out_shape[4], int64_t pad_tblr[4]) {
+  if (!x_shape || !f_shape || !out_shape || !pad_tblr) return TFX_ERR_NULL;
+  ConvGeom g;
+  int rc = conv_geometry(x_shape, f_shape, stride_h, stride_w, (int)pad, false, &g);
+  if (rc) return rc;
+  for (int i = 0; i < 4; ++i) {
+    out_shape[i] = g.out[i];
+    pad_tblr[i] = g.pad[i];
+  }
+  return TFX_OK;
+}
+
+int tfx_depthwise_conv2d_out_shape(const int64_t x_shape[4], const int64_t f_shape[4], int stride_h, int stride_w,
+                                   tfx_padding pad, int64_t out_shape[4], int64_t pad_tblr[4]) {
+  if (!x_shape || !f_shape || !out_shape || !pad_tblr) return TFX_ERR_NULL;
+  ConvGeom g;
+  int rc = conv_geometry(x_shape, f_shape, stride_h, stride_w, (int)pad, true, &g);
+  if (rc) return rc;
+  for (int i = 0; i < 4; ++i) {
+    out_shape[i] = g.out[i];
+    pad_tblr[i] = g.pad[i];
+  }
+  return TFX_OK;
+}
+
+int tfx_matmul(const float* a, const int64_t a_shape[2], const float* b, const int64_t b_shape[2], int transpose_a,
+               int transpose_b, float* c, void* stream) {
+  if (!a || !b || !c || !a_shape || !b_shape) return TFX_ERR_NULL;
+  return batch_matmul_impl(a, a_shape, b, b_shape, 1, transpose_a, transpose_b, c, stream);
+}
+
+int tfx_batch_matmul(const float* a, const int64_t a_shape[3], const float* b, const int64_t b_shape[3],
+                     int transpose_a, int transpose_b, float* c, void* stream) {
+  if (!a || !b || !c || !a_shape || !b_shape) return TFX_ERR_NULL;
+  if (a_shape[0] < 1 || a_shape[0] != b_shape[0]) return TFX_ERR_SHAPE;
+  return batch_matmul_impl(a, a_shape + 1, b, b_shape + 1, a_shape[0], transpose_a, transpose_b, c, stream);
+}
+
+int tfx_conv2d(const float* x, const int64_t x_shape[4], const float* filter, const int64_t f_shape[4],
+               const float* bias, int stride_h, int stride_w, tfx_padding pad, tfx_activation act, float* y,
+               void* stream) {
+  if (!x || !filter || !y || !x_shape || !f_shape) return TFX_ERR_NULL;
+  ConvGeom g;
+  int rc = conv_geometry(x_shape, f_shape, stride_h, stride_w, (int)pad, false, &g);
+  if (rc) return rc;
+  if (!valid_act((int)act)) return TFX_ERR_ARG;
+  if (numel(x_shape, 4) < 0 || numel(f_shape, 4) < 0 || numel(g.out, 4) < 0) return TFX_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int n = (int)x_shape[0], h = (int)x_shape[1], w = (int)x_shape[2], ci = (int)x_shape[3];
+  const int fh = (int)f_shape[0], fw = (int)f_shape[1], co = (int)f_shape[3];
+  const int oh = (int)g.out[1], ow = (int)g.out[2];
+  if (fh == 1 && fw == 1 && stride_h == 1 && stride_w == 1) {
+    // pointwise convolution = [N*H*W, Ci] x [Ci, Co] with the epilogue fused into the GEMM
+    return launch_gemm(x, filter, y, bias, 1, n * h * w, co, ci, true, false, (int)act, s);
+  }
+  const bool aligned = reinterpret_cast<uintptr_t>(y) % 16 == 0;
+  if (conv2d_stem_supported(ci, fh, fw, co, stride_h, stride_w) && aligned)
+    return launch_conv2d_stem(x, filter, bias, y, n, h, w, co, oh, ow, stride_h, stride_w, (int)g.pad[0], (int)g.pad[2],
+                              (int)act, s);
+  return launch_conv2d_direct(x, filter, bias, y, n, h, w, ci, fh, fw, co, oh, ow, stride_h, stride_w, (int)g.pad[0],
+                              (int)g.pad[2], (int)act, s);
+}
+
+int tfx_depthwise_conv2d(const float* x, const int64_t x_shape[4], const float* filter, const int64_t f_shape[4],
+                         const float* bias, int stride_h, int stride_w, tfx_padding pad, tfx_activation act, float* y,
+                         void* stream) {
+  if (!x || !filter || !y || !x_shape || !f_shape) return TFX_ERR_NULL;
+  ConvGeom g;
+  int rc = conv_geometry(x_shape, f_shape, stride_h, stride_w, (int)pad, true, &g);
+  if (rc) return rc;
+  if (!valid_act((int)act)) return TFX_ERR_ARG;
+  if (numel(x_shape, 4) < 0 || numel(f_shape, 4) < 0 || numel(g.out, 4) < 0) return TFX_ERR_UNSUPPORTED;
+  return launch_depthwise(x, filter, bias, y, (int)x_shape[0], (int)x_shape[1], (int)x_shape[2], (int)x_shape[3],
+                          (int)f_shape[0], (int)f_shape[1], (int)f_shape[3], (int)g.out[1], (int)g.out[2], stride_h,
+                          stride_w, (int)g.pad[0], (int)g.pad[2], (int)act, static_cast<hipStream_t>(stream));
+}
+
+size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch) {
+  if (batch < 1 || batch > 1024) return 0;
+  return plan_net(batch).bytes;
+}
+
+int tfx_mobilenet_v1_forward(const float* input, int64_t batch, const tfx_mobilenet_v1_weights* weights,
+                             void* workspace, size_t workspace_bytes, float* probs, float* logits, void* stream) {
+  if (!input || !weights || !workspace || !probs) return TFX_ERR_NULL;
+  if (!weights->conv0_w || !weights->conv0_b || !weights->fc_w || !weights->fc_b) return TFX_ERR_NULL;
+  for (int i = 0; i < kBlocks; ++i)
+    if (!weights->dw_w[i] || !weights->dw_b[i] || !weights->pw_w[i] || !weights->pw_b[i]) return TFX_ERR_NULL;
+  if (batch < 1) return TFX_ERR_SHAPE;
+  if (batch > 1024) return TFX_ERR_UNSUPPORTED;
+  const NetPlan plan = plan_net(batch);
+  if (workspace_bytes < plan.bytes || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TFX_ERR_WORKSPACE;
+
+  char* ws = static_cast<char*>(workspace);
+  float* buf[2] = {reinterpret_cast<float*>(ws + plan.off_buf[0]), reinterpret_cast<float*>(ws + plan.off_buf[1])};
+  float* pooled = reinterpret_cast<float*>(ws + plan.off_pooled);
+  float* partial = reinterpret_cast<float*>(ws + plan.off_partial);
+  float* lg = logits ? logits : reinterpret_cast<float*>(ws + plan.off_logits);
+
+  // stem: 3x3 stride-2 convolution to 32 channels, then the 13 depthwise-separable blocks
+  int64_t shape[4] = {batch, kImage, kImage, 3};
+  const int64_t f0[4] = {3, 3, 3, kStemChannels};
+  int rc = tfx_conv2d(input, shape, weights->conv0_w, f0, weights->conv0_b, 2, 2, TFX_PAD_SAME, TFX_ACT_RELU6, buf[0],
+                      stream);
+  if (rc) return rc;
+  ConvGeom g;
+  conv_geometry(shape, f0, 2, 2, TFX_PAD_SAME, false, &g);
+  for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
+  int cur = 0;
+  for (int b = 0; b < kBlocks; ++b) {
+    const int64_t fd[4] = {3, 3, shape[3], 1};
+    rc = tfx_depthwise_conv2d(buf[cur], shape, weights->dw_w[b], fd, weights->dw_b[b], kStrides[b], kStrides[b],
+                              TFX_PAD_SAME, TFX_ACT_RELU6, buf[cur ^ 1], stream);
+    if (rc) return rc;
+    conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
+    for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
+    cur ^= 1;
+    const int64_t fp[4] = {1, 1, shape[3], kChannels[b]};
+    rc = tfx_conv2d(buf[cur], shape, weights->pw_w[b], fp, weights->pw_b[b], 1, 1, TFX_PAD_SAME, TFX_ACT_RELU6,
+                    buf[cur ^ 1], stream);
+    if (rc) return rc;
+    shape[3] = kChannels[b];
+    cur ^= 1;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = launch_global_avg_pool(buf[cur], pooled, (int)batch, (int)(shape[1] * shape[2]), (int)shape[3], s);
+  if (rc) return rc;
+  return launch_fc_softmax(pooled, weights->fc_w, weights->fc_b, partial, lg, probs, (int)batch, kFeatures, kClasses, s);
+}
+
+}  // extern "C"

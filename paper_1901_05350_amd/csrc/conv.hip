@@ -1,0 +1,136 @@
+// Direct convolutions for gfx950: a general conv2d for any filter / stride, and the
+// 3x3 stride-s, 3-input-channel "stem" convolution of MobileNet v1 (K = 27 is too thin
+// for the matrix cores; the layer is bound by its 2.2 MB of activations).
+// Index order is NHWC (the batch,row,column,depth sampler of Section 4.1), filters HWIO.
+#include "tfx_internal.h"
+
+namespace tfx {
+namespace {
+
+// One thread per output element, output channel fastest so that filter reads and output
+// writes are coalesced.  Correct for every shape; used when no specialised kernel applies.
+__global__ __launch_bounds__(256) void conv2d_direct_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                            const float* __restrict__ bias, float* __restrict__ y,
+                                                            int N, int H, int W, int Ci, int fh, int fw, int Co,
+                                                            int OH, int OW, int sh, int sw, int pt, int pl, int act,
+                                                            long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int oc = (int)(idx % Co);
+    long long r = idx / Co;
+    const int ow = (int)(r % OW);
+    r /= OW;
+    const int oh = (int)(r % OH);
+    const int n = (int)(r / OH);
+    float acc = 0.f;
+    for (int kh = 0; kh < fh; ++kh) {
+      const int ih = oh * sh - pt + kh;
+      if (ih < 0 || ih >= H) continue;
+      for (int kw = 0; kw < fw; ++kw) {
+        const int iw = ow * sw - pl + kw;
+        if (iw < 0 || iw >= W) continue;
+        const float* xp = x + (((size_t)n * H + ih) * W + iw) * Ci;
+        const float* wp = w + ((size_t)(kh * fw + kw) * Ci) * Co + oc;
+        for (int c = 0; c < Ci; ++c) acc = fmaf(xp[c], wp[(size_t)c * Co], acc);
+      }
+    }
+    if (bias) acc += bias[oc];
+    y[idx] = apply_act(acc, act);
+  }
+}
+
+// Stem: 3x3 filter, 3 input channels, CO output channels (CO % 8 == 0, CO <= 64).
+// A thread computes 8 consecutive output channels of one output pixel: the 27 x CO filter
+// sits in LDS and is read as float4 pairs (only CO/8 distinct addresses per wave, so the
+// reads broadcast); CO/8 neighbouring lanes write one pixel's CO floats as a contiguous run.
+template <int CO>
+__global__ __launch_bounds__(256) void conv2d_stem_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                          const float* __restrict__ bias, float* __restrict__ y, int N,
+                                                          int H, int W, int OH, int OW, int sh, int sw, int pt, int pl,
+                                                          int act, int total) {
+  constexpr int G = CO / 8;
+  __shared__ __align__(16) float wl[27 * CO];
+  for (int i = threadIdx.x; i < 27 * CO; i += 256) wl[i] = w[i];
+  __syncthreads();
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int g = idx % G;
+  int r = idx / G;
+  const int ow = r % OW;
+  r /= OW;
+  const int oh = r % OH;
+  const int n = r / OH;
+  float acc[8];
+#pragma unroll
+  for (int o = 0; o < 8; ++o) acc[o] = 0.f;
+#pragma unroll
+  for (int kh = 0; kh < 3; ++kh) {
+    const int ih = oh * sh - pt + kh;
+    if (ih < 0 || ih >= H) continue;
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) {
+      const int iw = ow * sw - pl + kw;
+      if (iw < 0 || iw >= W) continue;
+      const float* xp = x + (((size_t)n * H + ih) * W + iw) * 3;
+#pragma unroll
+      for (int c = 0; c < 3; ++c) {
+        const float xv = xp[c];
+        const float4 w0 = *reinterpret_cast<const float4*>(&wl[((kh * 3 + kw) * 3 + c) * CO + 8 * g]);
+        const float4 w1 = *reinterpret_cast<const float4*>(&wl[((kh * 3 + kw) * 3 + c) * CO + 8 * g + 4]);
+        acc[0] = fmaf(xv, w0.x, acc[0]);
+        acc[1] = fmaf(xv, w0.y, acc[1]);
+        acc[2] = fmaf(xv, w0.z, acc[2]);
+        acc[3] = fmaf(xv, w0.w, acc[3]);
+        acc[4] = fmaf(xv, w1.x, acc[4]);
+        acc[5] = fmaf(xv, w1.y, acc[5]);
+        acc[6] = fmaf(xv, w1.z, acc[6]);
+        acc[7] = fmaf(xv, w1.w, acc[7]);
+      }
+    }
+  }
+  float4 o0, o1;
+  const float* bp = bias ? bias + 8 * g : nullptr;
+  o0.x = apply_act(acc[0] + (bp ? bp[0] : 0.f), act);
+  o0.y = apply_act(acc[1] + (bp ? bp[1] : 0.f), act);
+  o0.z = apply_act(acc[2] + (bp ? bp[2] : 0.f), act);
+  o0.w = apply_act(acc[3] + (bp ? bp[3] : 0.f), act);
+  o1.x = apply_act(acc[4] + (bp ? bp[4] : 0.f), act);
+  o1.y = apply_act(acc[5] + (bp ? bp[5] : 0.f), act);
+  o1.z = apply_act(acc[6] + (bp ? bp[6] : 0.f), act);
+  o1.w = apply_act(acc[7] + (bp ? bp[7] : 0.f), act);
+  float* yp = y + (((size_t)n * OH + oh) * OW + ow) * CO + 8 * g;
+  *reinterpret_cast<float4*>(yp) = o0;
+  *reinterpret_cast<float4*>(yp + 4) = o1;
+}
+
+}  // namespace
+
+int launch_conv2d_direct(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int ci,
+                         int fh, int fw, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act,
+                         hipStream_t stream) {
+  const long long total = (long long)n * oh * ow * co;
+  long long blocks = (total + 255) / 256;
+  if (blocks > 256 * 64) blocks = 256 * 64;  // grid-stride beyond 64 workgroups per CU
+  hipLaunchKernelGGL(conv2d_direct_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, x, w, bias, y, n, h, wd, ci,
+                     fh, fw, co, oh, ow, sh, sw, pt, pl, act, total);
+  return check_launch();
+}
+
+bool conv2d_stem_supported(int ci, int fh, int fw, int co, int sh, int sw) {
+  (void)sh;
+  (void)sw;
+  return ci == 3 && fh == 3 && fw == 3 && co == 32;
+}
+
+int launch_conv2d_stem(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int co,
+                       int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream) {
+  if (co != 32) return TFX_ERR_UNSUPPORTED;
+  const long long total = (long long)n * oh * ow * (co / 8);
+  if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  hipLaunchKernelGGL(conv2d_stem_kernel<32>, dim3(blocks), dim3(256), 0, stream, x, w, bias, y, n, h, wd, oh, ow, sh,
+                     sw, pt, pl, act, (int)total);
+  return check_launch();
+}
+
+}  // namespace tfx

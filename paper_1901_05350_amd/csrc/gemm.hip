@@ -1,0 +1,281 @@
+// fp32 MFMA GEMM for gfx950: C[b] = act(op(A[b]) * op(B[b]) + bias).
+//
+// This one kernel family serves matMul / batchMatMul (Section 4.1, Listing 2 of the
+// TensorFlow.js paper defines the op: one dot product per output value) and the 1x1
+// "pointwise" conv2d, which is the same contraction with M = N*H*W, K = inC, N = outC.
+// The paper's shader computes one output per fragment with no data sharing; here a
+// workgroup computes a BM x BN tile, stages A and B k-slices through LDS and feeds
+// v_mfma_f32_32x32x2_f32 (64-wide wavefronts, 32x32 accumulator tile per instruction).
+//
+// Layout of one MFMA 32x32x2 (wave64), used below:
+//   A operand: lane l holds A[i = l % 32][k = l / 32]
+//   B operand: lane l holds B[k = l / 32][j = l % 32]
+//   D result : register v of lane l holds D[i = 8*(v/4) + 4*(l/32) + v%4][j = l % 32]
+// The contraction index may be permuted freely as long as A and B agree, so within a
+// group of 8 consecutive k a lane with h = l/32 takes k = 8g + 4h + s in step s = 0..3.
+// That makes a lane's four steps one contiguous float4 in a K-contiguous LDS tile.
+#include "tfx_internal.h"
+
+namespace tfx {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int kXcds = 8;  // workgroups are dealt round-robin to the 8 XCDs, each with its own L2
+
+// LDS tile of one operand.  KC = true : stored [ROWS][BK + 4]  (k contiguous, padded rows)
+//                           KC = false: stored [BK][ROWS]      (row index contiguous)
+template <int ROWS, int BK, bool KC>
+struct Tile {
+  static constexpr int kStride = KC ? (BK + 4) : ROWS;
+  static constexpr int kFloats = KC ? ROWS * (BK + 4) : BK * ROWS;
+  static constexpr int kSlots = ROWS * BK / 4;  // float4 slots per tile
+};
+
+// Global -> registers for one operand tile.  Slot s of the tile is one float4:
+//   KC : row r = s / (BK/4), k = 4 * (s % (BK/4))       -> g[(row0 + r) * ld + k0 + k .. +3]
+//   !KC: k = s / (ROWS/4),   r = 4 * (s % (ROWS/4))     -> g[(k0 + k) * ld + row0 + r .. +3]
+// Out-of-range elements read as zero, so ragged M, N and K tails add nothing.
+template <int ROWS, int BK, bool KC, bool VEC, int NT, int NSLOT>
+__device__ __forceinline__ void load_tile(const float* __restrict__ g, int ld, int rows_total, int k_total, int row0,
+                                          int k0, int tid, float4 (&reg)[NSLOT]) {
+#pragma unroll
+  for (int it = 0; it < NSLOT; ++it) {
+    const int s = tid + it * NT;
+    int r, k;
+    if (KC) {
+      r = s / (BK / 4);
+      k = 4 * (s % (BK / 4));
+    } else {
+      k = s / (ROWS / 4);
+      r = 4 * (s % (ROWS / 4));
+    }
+    const int gr = row0 + r, gk = k0 + k;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (KC) {
+      if (gr < rows_total) {
+        const float* p = g + (size_t)gr * ld + gk;
+        if (VEC) {
+          if (gk < k_total) v = *reinterpret_cast<const float4*>(p);
+        } else {
+          if (gk + 0 < k_total) v.x = p[0];
+          if (gk + 1 < k_total) v.y = p[1];
+          if (gk + 2 < k_total) v.z = p[2];
+          if (gk + 3 < k_total) v.w = p[3];
+        }
+      }
+    } else {
+      if (gk < k_total) {
+        const float* p = g + (size_t)gk * ld + gr;
+        if (VEC) {
+          if (gr < rows_total) v = *reinterpret_cast<const float4*>(p);
+        } else {
+          if (gr + 0 < rows_total) v.x = p[0];
+          if (gr + 1 < rows_total) v.y = p[1];
+          if (gr + 2 < rows_total) v.z = p[2];
+          if (gr + 3 < rows_total) v.w = p[3];
+        }
+      }
+    }
+    reg[it] = v;
+  }
+}
+
+template <int ROWS, int BK, bool KC, int NT, int NSLOT>
+__device__ __forceinline__ void store_tile(float* __restrict__ lds, int tid, const float4 (&reg)[NSLOT]) {
+  using T = Tile<ROWS, BK, KC>;
+#pragma unroll
+  for (int it = 0; it < NSLOT; ++it) {
+    const int s = tid + it * NT;
+    int off;
+    if (KC) {
+      off = (s / (BK / 4)) * T::kStride + 4 * (s % (BK / 4));
+    } else {
+      off = (s / (ROWS / 4)) * T::kStride + 4 * (s % (ROWS / 4));
+    }
+    *reinterpret_cast<float4*>(lds + off) = reg[it];
+  }
+}
+
+// MFMA operand of one 32-row sub-tile for k-group g: four steps' values for this lane.
+template <int ROWS, int BK, bool KC>
+__device__ __forceinline__ float4 read_frag(const float* __restrict__ lds, int row, int g, int h) {
+  using T = Tile<ROWS, BK, KC>;
+  if (KC) {
+    return *reinterpret_cast<const float4*>(lds + row * T::kStride + 8 * g + 4 * h);
+  } else {
+    const float* p = lds + (8 * g + 4 * h) * T::kStride + row;
+    return make_float4(p[0], p[T::kStride], p[2 * T::kStride], p[3 * T::kStride]);
+  }
+}
+
+__device__ __forceinline__ float f4_get(const float4& v, int s) {
+  return s == 0 ? v.x : (s == 1 ? v.y : (s == 2 ? v.z : v.w));
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
+    const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, const float* __restrict__ bias,
+    int M, int N, int K, int tiles_m, int tiles_n, int total_blocks, long long strideA, long long strideB,
+    long long strideC, int act) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 8 == 0, "tile shape");
+  using TA = Tile<BM, BK, A_KC>;
+  using TB = Tile<BN, BK, B_KC>;
+  static_assert(TA::kSlots % NT == 0 && TB::kSlots % NT == 0, "loader shape");
+  constexpr int SA = TA::kSlots / NT, SB = TB::kSlots / NT;
+
+  extern __shared__ __align__(16) float smem[];
+  float* const lds_a = smem;                    // two A buffers, then two B buffers
+  float* const lds_b = smem + 2 * TA::kFloats;
+
+  // XCD-aware block order: hardware block id x lands on XCD x % 8.  Give each XCD a contiguous
+  // range of logical tiles (same batch, neighbouring tiles) so that its L2 sees each A / B panel once.
+  const int bid = blockIdx.x;
+  const int q = total_blocks / kXcds, rem = total_blocks % kXcds;
+  const int xcd = bid % kXcds;
+  const int vid = xcd * q + (xcd < rem ? xcd : rem) + bid / kXcds;
+  const int tiles = tiles_m * tiles_n;
+  const int batch = vid / tiles;
+  const int t = vid % tiles;
+  const int tile_m = t / tiles_n, tile_n = t % tiles_n;
+
+  const int lda = A_KC ? K : M;
+  const int ldb = B_KC ? K : N;
+  A += (size_t)batch * strideA;
+  B += (size_t)batch * strideB;
+  C += (size_t)batch * strideC;
+
+  const int tid = threadIdx.x;
+  const int wave = tid / 64, lane = tid % 64;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int li = lane % 32, h = lane / 32;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  float4 ra[SA], rb[SB];
+  const int nk = (K + BK - 1) / BK;
+  load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, 0, tid, ra);
+  load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, 0, tid, rb);
+  store_tile<BM, BK, A_KC, NT, SA>(lds_a, tid, ra);
+  store_tile<BN, BK, B_KC, NT, SB>(lds_b, tid, rb);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) {
+      load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, (kt + 1) * BK, tid, ra);
+      load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, (kt + 1) * BK, tid, rb);
+    }
+    const float* la = lds_a + cur * TA::kFloats;
+    const float* lb = lds_b + cur * TB::kFloats;
+#pragma unroll
+    for (int g = 0; g < BK / 8; ++g) {
+      float4 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = read_frag<BM, BK, A_KC>(la, wm0 + 32 * i + li, g, h);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = read_frag<BN, BK, B_KC>(lb, wn0 + 32 * j + li, g, h);
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f4_get(fa[i], s), f4_get(fb[j], s), acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      store_tile<BM, BK, A_KC, NT, SA>(lds_a + (cur ^ 1) * TA::kFloats, tid, ra);
+      store_tile<BN, BK, B_KC, NT, SB>(lds_b + (cur ^ 1) * TB::kFloats, tid, rb);
+    }
+    __syncthreads();
+  }
+
+  // Epilogue: bias[col] then activation, one dword per lane per register (two 128-byte rows per store).
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + wn0 + 32 * j + li;
+    if (col >= N) continue;
+    const float bv = bias ? bias[col] : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
+        if (row < M) C[(size_t)row * N + col] = apply_act(acc[i][j][v] + bv, act);
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC>
+int launch_cfg(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k, int act,
+               hipStream_t stream) {
+  using TA = Tile<BM, BK, A_KC>;
+  using TB = Tile<BN, BK, B_KC>;
+  constexpr size_t lds_bytes = 2 * (TA::kFloats + TB::kFloats) * sizeof(float);
+  static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, A_KC, B_KC, VEC>;
+  static bool attr_set = false;
+  if (!attr_set && lds_bytes > 64 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_bytes) != hipSuccess)
+      return TFX_ERR_LAUNCH;
+    attr_set = true;
+  }
+  const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
+  const long long total = (long long)batch * tiles_m * tiles_n;
+  if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, a, b, c, bias, m, n,
+                     k, tiles_m, tiles_n, (int)total, (long long)m * k, (long long)n * k, (long long)m * n, act);
+  return check_launch();
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+int launch_layout(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k,
+                  bool a_kc, bool b_kc, bool vec, int act, hipStream_t stream) {
+#define TFX_GEMM_CASE(AK, BKC, V)                                                                    \
+  if (a_kc == AK && b_kc == BKC && vec == V)                                                         \
+    return launch_cfg<BM, BN, BK, WAVES_M, WAVES_N, AK, BKC, V>(a, b, c, bias, batch, m, n, k, act, stream);
+  TFX_GEMM_CASE(true, true, true)
+  TFX_GEMM_CASE(true, false, true)
+  TFX_GEMM_CASE(false, true, true)
+  TFX_GEMM_CASE(false, false, true)
+  TFX_GEMM_CASE(true, true, false)
+  TFX_GEMM_CASE(true, false, false)
+  TFX_GEMM_CASE(false, true, false)
+  TFX_GEMM_CASE(false, false, false)
+#undef TFX_GEMM_CASE
+  return TFX_ERR_ARG;
+}
+
+}  // namespace
+
+int launch_gemm(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k, bool a_kc,
+                bool b_kc, int act, hipStream_t stream) {
+  // float4 global loads need 16-byte aligned rows: base pointers aligned and the contiguous
+  // extent of each operand a multiple of 4 (which also keeps every batch slice aligned).
+  const int a_inner = a_kc ? k : m, b_inner = b_kc ? k : n;
+  const bool vec = (reinterpret_cast<uintptr_t>(a) % 16 == 0) && (reinterpret_cast<uintptr_t>(b) % 16 == 0) &&
+                   (a_inner % 4 == 0) && (b_inner % 4 == 0);
+  // Tile choice: the largest tile that still yields at least one workgroup per CU (256 CUs);
+  // small problems fall through to smaller tiles so more CUs take part.
+  const long long blocks128 = (long long)batch * ((m + 127) / 128) * ((n + 127) / 128);
+  const long long blocks64 = (long long)batch * ((m + 63) / 64) * ((n + 63) / 64);
+  if (blocks128 >= 256) return launch_layout<128, 128, 32, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  if (blocks64 >= 256 || (m > 32 && n > 32))
+    return launch_layout<64, 64, 32, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  return launch_layout<32, 32, 32, 1, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+}
+
+}  // namespace tfx

@@ -1,0 +1,54 @@
+// Internal declarations shared by the HIP translation units of libtfx.
+// Nothing here is part of the public ABI (that is include/tfx.h).
+#ifndef TFX_INTERNAL_H_
+#define TFX_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tfx.h"
+
+namespace tfx {
+
+// Fused epilogue: bias first, then activation (relu6(v) = min(max(v,0),6)).
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == TFX_ACT_RELU) return fmaxf(v, 0.0f);
+  if (act == TFX_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
+  return v;
+}
+
+// Shape rule of one spatial dimension (see include/tfx.h); returns a tfx_status.
+int out_extent(int64_t in, int64_t k, int64_t s, int pad, int64_t* out, int64_t* before, int64_t* after);
+
+// C[b] = act(op(A[b]) * op(B[b]) + bias[col]) for b < batch.  a_kc: A is stored [M,K] (K contiguous),
+// else [K,M].  b_kc: B is stored [N,K] (K contiguous), else [K,N].  bias may be null.
+// Dimensions are validated by the callers; all fit in int32.
+int launch_gemm(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k,
+                bool a_kc, bool b_kc, int act, hipStream_t stream);
+
+// Direct convolution for any filter size / stride (one thread per output element).
+int launch_conv2d_direct(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int ci,
+                         int fh, int fw, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act,
+                         hipStream_t stream);
+
+// 3x3 stride-2 convolution with 3 input channels (the MobileNet stem).
+bool conv2d_stem_supported(int ci, int fh, int fw, int co, int sh, int sw);
+int launch_conv2d_stem(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int co,
+                       int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream);
+
+// Depthwise convolution: generic kernel and the 3x3 / multiplier-1 / C%4==0 fast path.
+int launch_depthwise(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int c,
+                     int fh, int fw, int mult, int oh, int ow, int sh, int sw, int pt, int pl, int act,
+                     hipStream_t stream);
+
+// MobileNet tail: global average pool [n,hw,c] -> [n,c]; fully connected + softmax.
+int launch_global_avg_pool(const float* a, float* p, int n, int hw, int c, hipStream_t stream);
+int launch_fc_softmax(const float* pooled, const float* w, const float* bias, float* partial, float* logits,
+                      float* probs, int n, int k, int classes, hipStream_t stream);
+size_t fc_partial_floats(int n, int k, int classes);
+
+inline int check_launch() { return hipGetLastError() == hipSuccess ? TFX_OK : TFX_ERR_LAUNCH; }
+
+}  // namespace tfx
+
+#endif  // TFX_INTERNAL_H_

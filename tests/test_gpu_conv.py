@@ -1,0 +1,161 @@
+"""GPU parity: tfx_conv2d / tfx_depthwise_conv2d against the CPU oracle, through the C ABI."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import ACT_NONE, ACT_RELU, ACT_RELU6, PAD_SAME, PAD_VALID
+from paper_1901_05350_amd import inputs
+from util import assert_close, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def gpu_conv(x, f, b, stride, pad, act):
+    import paper_1901_05350_amd as tfx
+    return host(tfx.tfx_conv2d(dev(x), dev(f), None if b is None else dev(b), stride, pad, act))
+
+
+def gpu_dw(x, f, b, stride, pad, act):
+    import paper_1901_05350_amd as tfx
+    return host(tfx.tfx_depthwise_conv2d(dev(x), dev(f), None if b is None else dev(b), stride, pad, act))
+
+
+def test_config_pointwise_conv():
+    d = inputs.pointwise_conv(seed=1)
+    got = gpu_conv(d["x"], d["filter"], d["bias"], 1, PAD_SAME, ACT_RELU6)
+    ref = oracle.conv2d(d["x"], d["filter"], d["bias"], 1, PAD_SAME, ACT_RELU6)
+    assert got.shape == (1, 56, 56, 128)
+    assert_close(got, ref, "pointwise 56x56x128->128")
+    assert got.min() == 0.0 and (ref > 0).mean() > 0.2
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_config_depthwise_conv(stride):
+    d = inputs.depthwise_conv(seed=2)
+    got = gpu_dw(d["x"], d["filter"], d["bias"], stride, PAD_SAME, ACT_RELU6)
+    ref = oracle.depthwise_conv2d(d["x"], d["filter"], d["bias"], stride, PAD_SAME, ACT_RELU6)
+    assert got.shape == ((1, 112, 112, 64) if stride == 1 else (1, 56, 56, 64))
+    assert_close(got, ref, "depthwise 112x112x64 s%d" % stride)
+
+
+def test_pointwise_shape_sweep():
+    # every MobileNet pointwise GEMM shape plus ragged channel counts and batch > 1
+    cases = [(1, 112, 112, 32, 64), (1, 56, 56, 64, 128), (1, 28, 28, 128, 256), (1, 28, 28, 256, 256),
+             (1, 14, 14, 256, 512), (1, 14, 14, 512, 512), (1, 7, 7, 512, 1024), (1, 7, 7, 1024, 1024),
+             (2, 9, 7, 5, 3), (3, 1, 1, 1, 1), (1, 15, 15, 33, 65), (2, 14, 14, 130, 36), (1, 1, 3, 4, 130)]
+    r = rng(21)
+    for i, (n, h, w, ci, co) in enumerate(cases):
+        x = r.uniform(-1, 1, (n, h, w, ci)).astype(np.float32)
+        f = (r.standard_normal((1, 1, ci, co)) * np.sqrt(2.0 / ci)).astype(np.float32)
+        b = (r.standard_normal((co,)) * 0.5).astype(np.float32)
+        act = [ACT_RELU6, ACT_NONE, ACT_RELU][i % 3]
+        bias = None if i % 4 == 3 else b
+        for pad in (PAD_SAME, PAD_VALID):
+            got = gpu_conv(x, f, bias, 1, pad, act)
+            assert_close(got, oracle.conv2d(x, f, bias, 1, pad, act), "pointwise %r" % ((n, h, w, ci, co),))
+
+
+def test_stem_conv_config_shape():
+    d = inputs.conv_general(31, 1, 224, 224, 3, 32, 3, 3)
+    got = gpu_conv(d["x"], d["filter"], d["bias"], 2, PAD_SAME, ACT_RELU6)
+    assert got.shape == (1, 112, 112, 32)
+    assert_close(got, oracle.conv2d(d["x"], d["filter"], d["bias"], 2, PAD_SAME, ACT_RELU6), "stem 224x224x3->32")
+
+
+def test_stem_conv_small_and_ragged():
+    r = rng(32)
+    for (n, h, w, s, pad) in [(2, 9, 11, 2, PAD_SAME), (1, 8, 8, 2, PAD_SAME), (1, 7, 5, 1, PAD_SAME),
+                              (1, 10, 9, 2, PAD_VALID), (1, 3, 3, 3, PAD_VALID), (1, 1, 1, 2, PAD_SAME)]:
+        x = r.uniform(-1, 1, (n, h, w, 3)).astype(np.float32)
+        f = r.standard_normal((3, 3, 3, 32)).astype(np.float32)
+        b = r.standard_normal((32,)).astype(np.float32)
+        got = gpu_conv(x, f, b, s, pad, ACT_RELU6)
+        assert_close(got, oracle.conv2d(x, f, b, s, pad, ACT_RELU6), "stem %r" % ((n, h, w, s, pad),))
+
+
+def test_general_conv_sweep():
+    r = rng(33)
+    hw = [(1, 1), (2, 3), (7, 7), (14, 15)]
+    for (h, w), (fh, fw), s, pad, (ci, co) in itertools.product(
+            hw, [(3, 3), (2, 5), (1, 1)], [1, 2, 3], [PAD_SAME, PAD_VALID], [(1, 1), (3, 4), (5, 32), (4, 5)]):
+        if pad == PAD_VALID and (h < fh or w < fw):
+            continue
+        if fh == 1 and s == 1:
+            continue
+        x = r.uniform(-1, 1, (2, h, w, ci)).astype(np.float32)
+        f = r.standard_normal((fh, fw, ci, co)).astype(np.float32)
+        b = r.standard_normal((co,)).astype(np.float32)
+        got = gpu_conv(x, f, b, (s, 1 + (s % 2)), pad, ACT_RELU6)
+        ref = oracle.conv2d(x, f, b, (s, 1 + (s % 2)), pad, ACT_RELU6)
+        assert_close(got, ref, "conv %r" % ((h, w, fh, fw, s, pad, ci, co),))
+
+
+def test_general_conv_3x3_many_channels():
+    d = inputs.conv_general(34, 1, 14, 14, 64, 48, 3, 3)
+    got = gpu_conv(d["x"], d["filter"], d["bias"], 1, PAD_SAME, ACT_RELU)
+    assert_close(got, oracle.conv2d(d["x"], d["filter"], d["bias"], 1, PAD_SAME, ACT_RELU), "conv 3x3 64->48")
+
+
+def test_depthwise_fast_path_sweep():
+    # 3x3, multiplier 1, channels a multiple of 4: every MobileNet depthwise shape, odd / even
+    # extents, tiny images, both strides and both paddings
+    r = rng(41)
+    shapes = [(1, 112, 112, 32), (1, 56, 56, 128), (1, 28, 28, 256), (1, 14, 14, 512), (1, 7, 7, 1024),
+              (2, 15, 14, 8), (3, 1, 1, 4), (1, 2, 3, 12), (1, 3, 3, 4), (2, 33, 9, 64), (1, 5, 70, 20)]
+    for (n, h, w, c), s, pad in itertools.product(shapes, [1, 2], [PAD_SAME, PAD_VALID]):
+        if pad == PAD_VALID and (h < 3 or w < 3):
+            continue
+        x = r.uniform(-1, 1, (n, h, w, c)).astype(np.float32)
+        f = (r.standard_normal((3, 3, c, 1)) * np.sqrt(2.0 / 9)).astype(np.float32)
+        b = (r.standard_normal((c,)) * 0.5).astype(np.float32)
+        got = gpu_dw(x, f, b, s, pad, ACT_RELU6)
+        assert_close(got, oracle.depthwise_conv2d(x, f, b, s, pad, ACT_RELU6), "dw %r s%d pad%d" % ((n, h, w, c), s, pad))
+    x = r.uniform(-1, 1, (1, 9, 9, 8)).astype(np.float32)
+    f = r.standard_normal((3, 3, 8, 1)).astype(np.float32)
+    assert_close(gpu_dw(x, f, None, 1, PAD_SAME, ACT_NONE), oracle.depthwise_conv2d(x, f, None, 1, PAD_SAME, ACT_NONE),
+                 "dw no bias")
+
+
+def test_depthwise_generic_sweep():
+    r = rng(42)
+    for (h, w), (fh, fw), s, pad, (c, mult) in itertools.product(
+            [(1, 1), (3, 2), (7, 7), (14, 15)], [(3, 3), (5, 2), (1, 1)], [1, 2, 3], [PAD_SAME, PAD_VALID],
+            [(1, 1), (3, 1), (5, 2), (4, 3), (64, 1)]):
+        if pad == PAD_VALID and (h < fh or w < fw):
+            continue
+        x = r.uniform(-1, 1, (2, h, w, c)).astype(np.float32)
+        f = r.standard_normal((fh, fw, c, mult)).astype(np.float32)
+        b = r.standard_normal((c * mult,)).astype(np.float32)
+        got = gpu_dw(x, f, b, (s, 1 + (s % 2)), pad, ACT_RELU)
+        ref = oracle.depthwise_conv2d(x, f, b, (s, 1 + (s % 2)), pad, ACT_RELU)
+        assert_close(got, ref, "dw generic %r" % ((h, w, fh, fw, s, pad, c, mult),))
+
+
+def test_one_hot_tap_is_a_shifted_copy_bit_exact():
+    # which side the odd padding unit goes to (stride 2, even input) shows up as a shift
+    r = rng(43)
+    x = r.standard_normal((1, 8, 8, 4)).astype(np.float32)
+    for kh, kw in [(0, 0), (2, 2), (0, 2), (1, 1)]:
+        f = np.zeros((3, 3, 4, 1), np.float32)
+        f[kh, kw, :, 0] = 1
+        for s in (1, 2):
+            got = gpu_dw(x, f, None, s, PAD_SAME, ACT_NONE)
+            assert np.array_equal(got, oracle.depthwise_conv2d(x, f, None, s, PAD_SAME, ACT_NONE))
+
+
+def test_epilogue_activation_table_and_tiny_bias():
+    vals = np.array([-1, 0, 3, 6, 7, 1e-8, -1e-8, 5.9999995], np.float32)
+    x = np.ones((1, 2, 2, 4), np.float32)
+    zf = np.zeros((1, 1, 4, 8), np.float32)
+    for act in (ACT_NONE, ACT_RELU, ACT_RELU6):
+        assert np.array_equal(gpu_conv(x, zf, vals, 1, PAD_SAME, act), oracle.conv2d(x, zf, vals, 1, PAD_SAME, act))
+    xd = np.ones((1, 2, 2, 8), np.float32)
+    zd = np.zeros((3, 3, 8, 1), np.float32)
+    for act in (ACT_NONE, ACT_RELU, ACT_RELU6):
+        assert np.array_equal(gpu_dw(xd, zd, vals, 1, PAD_SAME, act), oracle.depthwise_conv2d(xd, zd, vals, 1, PAD_SAME, act))
