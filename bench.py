@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the dense-op hot path on one MI355X.
+
+A step is one MobileNet-v1 1.0/224 batch-1 inference (stem conv, 13 x (depthwise + pointwise),
+pool, fully connected, softmax) through tfx_mobilenet_v1_forward, with weights and the image
+already resident in HBM: the quantity Table 1 of the TensorFlow.js paper reports (Section 3.9),
+on seeded random weights of the same shapes.  After the timed steps the same process times each
+layer and the four single-op workloads (small matMul, 1x1 pointwise conv, 3x3 depthwise conv at
+stride 1 and 2, the 8 x 1024^3 batchMatMul) against the fp32-MFMA or HBM roofline, and the CPU
+oracle on the host cores as a baseline.
+
+Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32 = 157.3e12   # FLOP/s, dense fp32 matrix peak of MI355X
+PEAK_HBM = 8.0e12          # B/s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--no-ops", action="store_true", help="skip the per-layer and single-op measurements")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_1901_05350_amd as tfx
+    from paper_1901_05350_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    tfx.lib()
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda:0")
+
+    def time_loop(fn, reps, warmup=5, inner=None):
+        """Mean seconds per call of `fn`, GPU-side: `inner` back-to-back launches are captured into a
+        HIP graph and the graph is replayed, so the host's per-call cost (about 10 us through Python)
+        does not hide the kernels' own duration.  Timed with HIP events on the launch stream."""
+        inner = inner or min(reps, 20)
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(inner):
+                fn()
+        g.replay()
+        torch.cuda.synchronize()
+        n_rep = max(1, reps // inner)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n_rep):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / (n_rep * inner)
+
+    def time_single(fn, reps=20):
+        """Median seconds of one isolated launch (events around a single call, queue drained before)."""
+        ts = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e-3)
+        return float(np.median(ts))
+
+    # ---------------- the timed steps: MobileNet-v1 b1 ----------------
+    data = inputs.mobilenet_v1(seed=4, batch=1)
+    model = tfx.MobileNetV1(data["weights"], batch=1)
+    image = dev(data["image"])
+    step = lambda: model.forward(image)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    ms_events = e0.elapsed_time(e1) / args.steps
+    probs = model.probs.cpu().numpy()
+    assert np.isfinite(probs).all() and abs(float(probs.sum()) - 1.0) < 1e-4
+
+    # same forward pass replayed from a captured graph (no memset nodes: the library uses none)
+    graph_ms = None
+    try:
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            step()
+        g.replay()
+        torch.cuda.synchronize()
+        ge0, ge1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ge0.record()
+        for _ in range(args.steps):
+            g.replay()
+        ge1.record()
+        torch.cuda.synchronize()
+        graph_ms = ge0.elapsed_time(ge1) / args.steps
+        torch.cuda.synchronize()
+        assert np.array_equal(model.probs.cpu().numpy(), probs)
+    except Exception as exc:  # reported, not fatal
+        graph_ms = None
+        print("bench.py: graph replay unavailable: %r" % (exc,), file=sys.stderr)
+
+    out = {
+        "metric": "MobileNet-v1 1.0/224 batch-1 ms/inference",
+        "value": round(ms_per_step, 5), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "MobileNet-v1 1.0/224 forward, batch 1, fp32 NHWC, random He-normal weights (seed 4), "
+                               "input uniform[-1,1)", "launch": "stream enqueue, one C-ABI call per inference"},
+        "ms_per_step_hip_events": round(ms_events, 5),
+        "graph_replay_ms_per_inference": None if graph_ms is None else round(graph_ms, 5),
+        "paper_table1_ms": {"plain JS (MacBook Pro 2014)": 3426, "WebGL Intel Iris Pro": 49, "WebGL GTX 1080": 5,
+                            "Node.js CPU AVX2": 87, "Node.js CUDA GTX 1080": 3},
+    }
+
+    # ---------------- per-layer times inside the network, and the roofline of its dominant kernel ----------
+    reps = max(20, min(args.steps, 200))
+    if not args.no_ops:
+        CH, ST = inputs.MOBILENET_V1_CHANNELS, inputs.MOBILENET_V1_STRIDES
+        w = model.tensors
+        layers = []
+        x = torch.empty((1, 224, 224, 3), device="cuda:0").uniform_(-1, 1)
+        y = tfx.tfx_conv2d(x, w["conv0_w"], w["conv0_b"], 2, tfx.PAD_SAME, tfx.ACT_RELU6)
+        t = time_loop(lambda: tfx.tfx_conv2d(x, w["conv0_w"], w["conv0_b"], 2, tfx.PAD_SAME, tfx.ACT_RELU6, out=y), reps)
+        layers.append({"layer": "conv0", "kind": "stem", "us": t * 1e6, "flop": 2 * 112 * 112 * 32 * 27,
+                       "bytes": 4 * (x.numel() + y.numel() + 27 * 32 + 32)})
+        x = y
+        for i in range(13):
+            s, cin, cout = ST[i], x.shape[3], CH[i]
+            y = tfx.tfx_depthwise_conv2d(x, w["dw_w"][i], w["dw_b"][i], s, tfx.PAD_SAME, tfx.ACT_RELU6)
+            t = time_loop(lambda: tfx.tfx_depthwise_conv2d(x, w["dw_w"][i], w["dw_b"][i], s, tfx.PAD_SAME, tfx.ACT_RELU6, out=y), reps)
+            layers.append({"layer": "dw%d" % (i + 1), "kind": "depthwise", "us": t * 1e6, "flop": 2 * 9 * y.numel(),
+                           "bytes": 4 * (x.numel() + y.numel() + 10 * cin)})
+            x = y
+            y = tfx.tfx_conv2d(x, w["pw_w"][i], w["pw_b"][i], 1, tfx.PAD_SAME, tfx.ACT_RELU6)
+            t = time_loop(lambda: tfx.tfx_conv2d(x, w["pw_w"][i], w["pw_b"][i], 1, tfx.PAD_SAME, tfx.ACT_RELU6, out=y), reps)
+            layers.append({"layer": "pw%d" % (i + 1), "kind": "pointwise", "us": t * 1e6,
+                           "flop": 2 * y.numel() * cin, "bytes": 4 * (x.numel() + y.numel() + cin * cout + cout)})
+            x = y
+        pw = [l for l in layers if l["kind"] == "pointwise"]
+        dw = [l for l in layers if l["kind"] == "depthwise"]
+        pw_flop, pw_s = sum(l["flop"] for l in pw), sum(l["us"] for l in pw) * 1e-6
+        dw_bytes, dw_s = sum(l["bytes"] for l in dw), sum(l["us"] for l in dw) * 1e-6
+        out["roofline"] = {
+            "kernel": "gemm_mfma_kernel (13 pointwise layers of one inference)", "bound": "mfma",
+            "achieved": round(pw_flop / pw_s / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
+            "frac": round(pw_flop / pw_s / PEAK_MFMA_F32, 5), "traffic": None,
+            "launches_per_step": 13, "avg_launch_us": round(pw_s * 1e6 / 13, 3)}
+        out["mobilenet_layers"] = {
+            "sum_layer_us": round(sum(l["us"] for l in layers), 2),
+            "pointwise_us": round(pw_s * 1e6, 2), "depthwise_us": round(dw_s * 1e6, 2),
+            "depthwise_GBps": round(dw_bytes / dw_s / 1e9, 1),
+            "per_layer_us": {l["layer"]: round(l["us"], 2) for l in layers}}
+
+        # ---------------- the four single-op workloads ----------------
+        ops = {}
+
+        def gemm_entry(name, fn, flop, nbytes):
+            t = time_loop(fn, reps)
+            ops[name] = {"us": round(t * 1e6, 3), "single_launch_us": round(time_single(fn) * 1e6, 2),
+                         "TFLOPs": round(flop / t / 1e12, 4), "GBps": round(nbytes / t / 1e9, 1),
+                         "roofline": {"bound": "mfma", "achieved": round(flop / t / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12,
+                                      "unit": "TFLOP/s", "frac": round(flop / t / PEAK_MFMA_F32, 5), "traffic": None}}
+
+        d = inputs.matmul_small(seed=0)
+        a, b = dev(d["a"]), dev(d["b"])
+        c = tfx.tfx_matmul(a, b)
+        gemm_entry("matmul_64x128x64", lambda: tfx.tfx_matmul(a, b, out=c), 2 * 64 * 128 * 64, 81920)
+
+        d = inputs.batch_matmul(seed=3)
+        a4, b4 = dev(d["a"]), dev(d["b"])
+        c4 = tfx.tfx_batch_matmul(a4, b4, False, True)
+        gemm_entry("batch_matmul_8x1024x1024x1024_tB", lambda: tfx.tfx_batch_matmul(a4, b4, False, True, out=c4),
+                   2 * 8 * 1024 ** 3, 3 * 8 * 1024 * 1024 * 4)
+        del a4, b4, c4
+
+        for n in (1, 8, 64):
+            d = inputs.pointwise_conv(seed=1, n=n)
+            xx, ff, bb = dev(d["x"]), dev(d["filter"]), dev(d["bias"])
+            yy = tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6)
+            gemm_entry("pointwise_%dx56x56x128_to_128" % n,
+                       lambda: tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6, out=yy),
+                       2 * n * 56 * 56 * 128 * 128, 4 * (xx.numel() + yy.numel() + 128 * 128 + 128))
+
+        def dw_entry(name, n, s, copies):
+            """copies > 1: rotate over distinct tensors whose total size exceeds the 256 MB last-level cache."""
+            d = inputs.depthwise_conv(seed=2, n=n)
+            ff, bb = dev(d["filter"]), dev(d["bias"])
+            xs = [dev(d["x"])]
+            for _ in range(copies - 1):
+                xs.append(xs[0].clone())
+            ys = [tfx.tfx_depthwise_conv2d(xv, ff, bb, s, tfx.PAD_SAME, tfx.ACT_RELU6) for xv in xs]
+            nbytes = 4 * (xs[0].numel() + ys[0].numel() + 9 * 64 + 64)
+            state = {"i": 0}
+
+            def fn():
+                i = state["i"] = (state["i"] + 1) % copies
+                tfx.tfx_depthwise_conv2d(xs[i], ff, bb, s, tfx.PAD_SAME, tfx.ACT_RELU6, out=ys[i])
+            t = time_loop(fn, max(reps, copies * 2), warmup=copies, inner=copies if copies > 1 else None)
+            ops[name] = {"us": round(t * 1e6, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
+                         "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
+                                      "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
+            if copies == 1:
+                ops[name]["single_launch_us"] = round(time_single(fn) * 1e6, 2)
+
+        for s in (1, 2):
+            dw_entry("depthwise_1x112x112x64_s%d_warm" % s, 1, s, 1)
+            dw_entry("depthwise_1x112x112x64_s%d_cold_rotation" % s, 1, s, 96)
+            dw_entry("depthwise_8x112x112x64_s%d_warm" % s, 8, s, 1)
+            dw_entry("depthwise_64x112x112x64_s%d_cold_rotation" % s, 64, s, 3)
+        out["ops"] = ops
+
+    # ---------------- CPU oracle on the host cores (baseline only) ----------------
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.get_max_threads()
+        oracle.mobilenet_v1_forward(data["image"], data["weights"])  # warm
+        n_inf, t0 = 0, time.perf_counter()
+        while n_inf < 3 or (time.perf_counter() - t0 < 10.0 and n_inf < 200):
+            oracle.mobilenet_v1_forward(data["image"], data["weights"])
+            n_inf += 1
+        cpu_ms = (time.perf_counter() - t0) * 1e3 / n_inf
+        out["cpu_baseline"] = {"value": round(cpu_ms, 3), "unit": "ms", "cores": threads, "kind": "oracle",
+                               "sample": "%d whole MobileNet-v1 b1 inferences (same seeded input), plain C loops with "
+                                         "double accumulation, OpenMP over output rows" % n_inf}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -93,7 +93,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct NetPlan {
   size_t act_floats;  // per ping-pong buffer
-  size_t off_buf[2], off_pooled, off_partial, off_logits, bytes;
+  size_t off_buf[2], off_partial, bytes;
 };
 
 NetPlan plan_net(int64_t batch) {
@@ -105,12 +105,8 @@ NetPlan plan_net(int64_t batch) {
     p.off_buf[i] = off;
     off = align_up(off + p.act_floats * sizeof(float));
   }
-  p.off_pooled = off;
-  off = align_up(off + (size_t)batch * kFeatures * sizeof(float));
-  p.off_partial = off;
+  p.off_partial = off;  // K-slice partial sums of the fully connected layer
   off = align_up(off + fc_partial_floats((int)batch, kFeatures, kClasses) * sizeof(float));
-  p.off_logits = off;
-  off = align_up(off + (size_t)batch * kClasses * sizeof(float));
   p.bytes = off;
   return p;
 }
@@ -242,9 +238,7 @@ int tfx_mobilenet_v1_forward(const float* input, int64_t batch, const tfx_mobile
 
   char* ws = static_cast<char*>(workspace);
   float* buf[2] = {reinterpret_cast<float*>(ws + plan.off_buf[0]), reinterpret_cast<float*>(ws + plan.off_buf[1])};
-  float* pooled = reinterpret_cast<float*>(ws + plan.off_pooled);
   float* partial = reinterpret_cast<float*>(ws + plan.off_partial);
-  float* lg = logits ? logits : reinterpret_cast<float*>(ws + plan.off_logits);
 
   // stem: 3x3 stride-2 convolution to 32 channels, then the 13 depthwise-separable blocks
   int64_t shape[4] = {batch, kImage, kImage, 3};
@@ -272,9 +266,8 @@ int tfx_mobilenet_v1_forward(const float* input, int64_t batch, const tfx_mobile
     cur ^= 1;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = launch_global_avg_pool(buf[cur], pooled, (int)batch, (int)(shape[1] * shape[2]), (int)shape[3], s);
-  if (rc) return rc;
-  return launch_fc_softmax(pooled, weights->fc_w, weights->fc_b, partial, lg, probs, (int)batch, kFeatures, kClasses, s);
+  return launch_pool_fc_softmax(buf[cur], weights->fc_w, weights->fc_b, partial, logits, probs, (int)batch,
+                                (int)(shape[1] * shape[2]), kFeatures, kClasses, s);
 }
 
 }  // extern "C"

@@ -114,19 +114,25 @@ __device__ __forceinline__ float f4_get(const float4& v, int s) {
   return s == 0 ? v.x : (s == 1 ? v.y : (s == 2 ? v.z : v.w));
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
+// WAVES_K > 1 splits each BK-deep tile over that many wavefronts (each takes BK / WAVES_K of the
+// depth) and adds the partial accumulators through LDS at the end: for small M x N problems this
+// puts 4x more bytes in flight per workgroup and shortens the serial K loop 4x.
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, bool A_KC, bool B_KC, bool VEC>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, const float* __restrict__ bias,
     int M, int N, int K, int tiles_m, int tiles_n, int total_blocks, long long strideA, long long strideB,
     long long strideC, int act) {
-  constexpr int NT = 64 * WAVES_M * WAVES_N;
+  constexpr int NT = 64 * WAVES_M * WAVES_N * WAVES_K;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
-  static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 8 == 0, "tile shape");
+  constexpr int GROUPS = BK / 8 / WAVES_K;  // k-groups of 8 per wavefront per tile
+  static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % (8 * WAVES_K) == 0, "tile shape");
   using TA = Tile<BM, BK, A_KC>;
   using TB = Tile<BN, BK, B_KC>;
   static_assert(TA::kSlots % NT == 0 && TB::kSlots % NT == 0, "loader shape");
   constexpr int SA = TA::kSlots / NT, SB = TB::kSlots / NT;
+  static_assert(WAVES_K == 1 || (WAVES_K - 1) * WAVES_M * WAVES_N * TM * TN * 1024 <= 2 * (TA::kFloats + TB::kFloats),
+                "split-K reduction reuses the tile buffers");
 
   extern __shared__ __align__(16) float smem[];
   float* const lds_a = smem;                    // two A buffers, then two B buffers
@@ -151,7 +157,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
 
   const int tid = threadIdx.x;
   const int wave = tid / 64, lane = tid % 64;
-  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int wk = wave / (WAVES_M * WAVES_N), wmn = wave % (WAVES_M * WAVES_N);
+  const int wm0 = (wmn / WAVES_N) * WM, wn0 = (wmn % WAVES_N) * WN;
   const int li = lane % 32, h = lane / 32;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
@@ -180,7 +187,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
     const float* la = lds_a + cur * TA::kFloats;
     const float* lb = lds_b + cur * TB::kFloats;
 #pragma unroll
-    for (int g = 0; g < BK / 8; ++g) {
+    for (int gg = 0; gg < GROUPS; ++gg) {
+      const int g = wk * GROUPS + gg;
       float4 fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) fa[i] = read_frag<BM, BK, A_KC>(la, wm0 + 32 * i + li, g, h);
@@ -201,6 +209,32 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
     __syncthreads();
   }
 
+  if (WAVES_K > 1) {
+    // all tile reads are done (barrier above): reuse LDS to add the k-waves' partial tiles.
+    // layout [wk-1][wmn][i][j][v][lane]: a register's 64 lanes are contiguous, so no bank conflicts
+    if (wk > 0) {
+      float* dst = smem + (size_t)((wk - 1) * WAVES_M * WAVES_N + wmn) * TM * TN * 1024;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) dst[((i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+    }
+    __syncthreads();
+    if (wk > 0) return;
+#pragma unroll
+    for (int w = 1; w < WAVES_K; ++w) {
+      const float* src = smem + (size_t)((w - 1) * WAVES_M * WAVES_N + wmn) * TM * TN * 1024;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][j][v] += src[((i * TN + j) * 16 + v) * 64 + lane];
+    }
+  }
+
   // Epilogue: bias[col] then activation, one dword per lane per register (two 128-byte rows per store).
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
@@ -218,14 +252,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
   }
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, bool A_KC, bool B_KC, bool VEC>
 int launch_cfg(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k, int act,
                hipStream_t stream) {
   using TA = Tile<BM, BK, A_KC>;
   using TB = Tile<BN, BK, B_KC>;
   constexpr size_t lds_bytes = 2 * (TA::kFloats + TB::kFloats) * sizeof(float);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
-  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, A_KC, B_KC, VEC>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, A_KC, B_KC, VEC>;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -236,17 +270,18 @@ int launch_cfg(const float* a, const float* b, float* c, const float* bias, int 
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
   const long long total = (long long)batch * tiles_m * tiles_n;
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, a, b, c, bias, m, n,
-                     k, tiles_m, tiles_n, (int)total, (long long)m * k, (long long)n * k, (long long)m * n, act);
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(64 * WAVES_M * WAVES_N * WAVES_K), lds_bytes, stream, a, b, c,
+                     bias, m, n, k, tiles_m, tiles_n, (int)total, (long long)m * k, (long long)n * k, (long long)m * n,
+                     act);
   return check_launch();
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K>
 int launch_layout(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k,
                   bool a_kc, bool b_kc, bool vec, int act, hipStream_t stream) {
-#define TFX_GEMM_CASE(AK, BKC, V)                                                                    \
-  if (a_kc == AK && b_kc == BKC && vec == V)                                                         \
-    return launch_cfg<BM, BN, BK, WAVES_M, WAVES_N, AK, BKC, V>(a, b, c, bias, batch, m, n, k, act, stream);
+#define TFX_GEMM_CASE(AK, BKC, V)                                                                              \
+  if (a_kc == AK && b_kc == BKC && vec == V)                                                                   \
+    return launch_cfg<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AK, BKC, V>(a, b, c, bias, batch, m, n, k, act, stream);
   TFX_GEMM_CASE(true, true, true)
   TFX_GEMM_CASE(true, false, true)
   TFX_GEMM_CASE(false, true, true)
@@ -268,14 +303,16 @@ int launch_gemm(const float* a, const float* b, float* c, const float* bias, int
   const int a_inner = a_kc ? k : m, b_inner = b_kc ? k : n;
   const bool vec = (reinterpret_cast<uintptr_t>(a) % 16 == 0) && (reinterpret_cast<uintptr_t>(b) % 16 == 0) &&
                    (a_inner % 4 == 0) && (b_inner % 4 == 0);
-  // Tile choice: the largest tile that still yields at least one workgroup per CU (256 CUs);
-  // small problems fall through to smaller tiles so more CUs take part.
+  // Tile choice.  Large problems: 128 x 128 tiles (best reuse).  Medium: 64 x 64.  Small M x N
+  // (too few 64 x 64 tiles for the 256 CUs): 32 x 32 tiles with the depth split over four
+  // wavefronts, which is bound by memory latency per K step rather than by arithmetic.
   const long long blocks128 = (long long)batch * ((m + 127) / 128) * ((n + 127) / 128);
   const long long blocks64 = (long long)batch * ((m + 63) / 64) * ((n + 63) / 64);
-  if (blocks128 >= 256) return launch_layout<128, 128, 32, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
-  if (blocks64 >= 256 || (m > 32 && n > 32))
-    return launch_layout<64, 64, 32, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
-  return launch_layout<32, 32, 32, 1, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  if (blocks128 >= 256)
+    return launch_layout<128, 128, 32, 2, 2, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  if (blocks64 >= 192 || k <= 32)
+    return launch_layout<64, 64, 32, 2, 2, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  return launch_layout<32, 32, 128, 1, 1, 4>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
 }
 
 }  // namespace tfx

@@ -1,7 +1,8 @@
 // MobileNet v1 tail for gfx950: global average pool, fully connected layer, softmax
 // (the last three steps of the network timed in Section 3.9, Table 1).
-// All three are bound by memory traffic (the 4 MB fully connected weight matrix dominates),
-// so the fully connected layer is split over K across many workgroups and the partial
+// All three are bound by memory latency and traffic (the 4 MB fully connected weight matrix
+// dominates), so the pool is fused into the fully connected kernel, that kernel is split over
+// K across many workgroups with all of a thread's loads in flight at once, and the partial
 // sums are combined by the softmax kernel.
 #include "tfx_internal.h"
 
@@ -9,44 +10,57 @@ namespace tfx {
 namespace {
 
 constexpr int kFcSlices = 32;   // K-slices of the fully connected layer
-constexpr int kFcBatchMax = 8;  // images handled per weight read in the split-K kernel
+constexpr int kFcKMax = 32;     // K elements per slice (so K <= 1024)
+constexpr int kFcBatchMax = 4;  // images handled per weight read
 
-// p[n,c] = (1/hw) * sum_i a[n,i,c]; one thread per (n,c), coalesced over c.
-__global__ __launch_bounds__(256) void global_avg_pool_kernel(const float* __restrict__ a, float* __restrict__ p, int hw,
-                                                              int c, int total) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= total) return;
-  const int n = idx / c, ch = idx % c;
-  const float* ap = a + (size_t)n * hw * c + ch;
-  float acc = 0.f;
-  for (int i = 0; i < hw; ++i) acc += ap[(size_t)i * c];
-  p[idx] = acc / (float)hw;
-}
-
-// partial[slice][n][j] = sum_{k in slice} pooled[n,k] * w[k,j].  grid = (column blocks, slices, image groups).
-__global__ __launch_bounds__(256) void fc_partial_kernel(const float* __restrict__ pooled, const float* __restrict__ w,
-                                                         float* __restrict__ partial, int n, int k, int classes,
-                                                         int kslice) {
+// partial[slice][n][j] = sum_{k in slice} mean_p(a[n,p,k]) * w[k,j].
+// grid = (column blocks, slices, image groups); a is the last feature map [n, hw, k].
+__global__ __launch_bounds__(256) void pool_fc_partial_kernel(const float* __restrict__ a, const float* __restrict__ w,
+                                                              float* __restrict__ partial, int n, int hw, int k,
+                                                              int classes, int kslice) {
   const int j = blockIdx.x * 256 + threadIdx.x;
   const int slice = blockIdx.y;
   const int n0 = blockIdx.z * kFcBatchMax;
   const int nb = min(kFcBatchMax, n - n0);
-  const int k0 = slice * kslice, k1 = min(k0 + kslice, k);
-  __shared__ float ps[kFcBatchMax][64];
-  // stage this slice of the pooled vectors (kslice <= 64)
-  for (int i = threadIdx.x; i < kFcBatchMax * 64; i += 256) {
-    const int b = i / 64, kk = i % 64;
-    ps[b][kk] = (b < nb && k0 + kk < k1) ? pooled[(size_t)(n0 + b) * k + k0 + kk] : 0.f;
+  const int k0 = slice * kslice;
+  const int kn = min(kslice, k - k0);
+  __shared__ float ps[kFcBatchMax][kFcKMax];
+
+  // this thread's weight column slice first, so the loads overlap the pooling below
+  float wv[kFcKMax];
+#pragma unroll
+  for (int kk = 0; kk < kFcKMax; ++kk) wv[kk] = (kk < kn && j < classes) ? w[(size_t)(k0 + kk) * classes + j] : 0.f;
+
+  // global average pool of this K-slice: thread t sums pixels t/32, t/32 + 8, ... of channel t % 32
+  {
+    const int kk = threadIdx.x % kFcKMax, p0 = threadIdx.x / kFcKMax;  // 8 pixel lanes
+    __shared__ float red[kFcBatchMax][8][kFcKMax];
+    for (int b = 0; b < kFcBatchMax; ++b) {
+      float acc = 0.f;
+      if (b < nb && kk < kn) {
+        const float* ap = a + ((size_t)(n0 + b) * hw) * k + k0 + kk;
+        for (int p = p0; p < hw; p += 8) acc += ap[(size_t)p * k];
+      }
+      red[b][p0][kk] = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x < kFcBatchMax * kFcKMax) {
+      const int b = threadIdx.x / kFcKMax, c = threadIdx.x % kFcKMax;
+      float s = 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) s += red[b][q][c];
+      ps[b][c] = s / (float)hw;
+    }
+    __syncthreads();
   }
-  __syncthreads();
   if (j >= classes) return;
   float acc[kFcBatchMax];
 #pragma unroll
   for (int b = 0; b < kFcBatchMax; ++b) acc[b] = 0.f;
-  for (int kk = k0; kk < k1; ++kk) {
-    const float wv = w[(size_t)kk * classes + j];
 #pragma unroll
-    for (int b = 0; b < kFcBatchMax; ++b) acc[b] = fmaf(ps[b][kk - k0], wv, acc[b]);
+  for (int kk = 0; kk < kFcKMax; ++kk) {
+#pragma unroll
+    for (int b = 0; b < kFcBatchMax; ++b) acc[b] = fmaf(ps[b][kk], wv[kk], acc[b]);
   }
   for (int b = 0; b < nb; ++b) partial[((size_t)slice * n + n0 + b) * classes + j] = acc[b];
 }
@@ -67,10 +81,10 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* scrat
   return r;
 }
 
-// One workgroup per image: logits = bias + sum of partials (or the given logits), then
+// One workgroup per image: logits = bias + sum of the K-slice partials, then
 // probs = exp(l - max l) / sum exp(l - max l).
-constexpr int kMaxPerThread = 8;  // classes <= 256 * 8
-__global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ partial, int slices,
+constexpr int kMaxPerThread = 4;  // classes <= 256 * 4
+__global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ partial,
                                                       const float* __restrict__ bias, float* __restrict__ logits,
                                                       float* __restrict__ probs, int n, int classes) {
   __shared__ float scratch[4];
@@ -82,14 +96,13 @@ __global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ 
     const int j = threadIdx.x + 256 * i;
     l[i] = -INFINITY;
     if (j < classes) {
-      float v;
-      if (partial) {
-        v = bias ? bias[j] : 0.f;
-        for (int s = 0; s < slices; ++s) v += partial[((size_t)s * n + img) * classes + j];
-        if (logits) logits[(size_t)img * classes + j] = v;
-      } else {
-        v = logits[(size_t)img * classes + j];
-      }
+      float part[kFcSlices];
+#pragma unroll
+      for (int s = 0; s < kFcSlices; ++s) part[s] = partial[((size_t)s * n + img) * classes + j];
+      float v = bias ? bias[j] : 0.f;
+#pragma unroll
+      for (int s = 0; s < kFcSlices; ++s) v += part[s];
+      if (logits) logits[(size_t)img * classes + j] = v;
       l[i] = v;
       mx = fmaxf(mx, v);
     }
@@ -115,30 +128,22 @@ __global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ 
 
 }  // namespace
 
-int launch_global_avg_pool(const float* a, float* p, int n, int hw, int c, hipStream_t stream) {
-  const long long total = (long long)n * c;
-  if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(global_avg_pool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, a, p, hw, c,
-                     (int)total);
-  return check_launch();
-}
-
 size_t fc_partial_floats(int n, int k, int classes) {
   (void)k;
   return (size_t)kFcSlices * n * classes;
 }
 
-int launch_fc_softmax(const float* pooled, const float* w, const float* bias, float* partial, float* logits,
-                      float* probs, int n, int k, int classes, hipStream_t stream) {
+int launch_pool_fc_softmax(const float* a, const float* w, const float* bias, float* partial, float* logits,
+                           float* probs, int n, int hw, int k, int classes, hipStream_t stream) {
   if (classes > 256 * kMaxPerThread) return TFX_ERR_UNSUPPORTED;
   const int kslice = (k + kFcSlices - 1) / kFcSlices;
-  if (kslice > 64) return TFX_ERR_UNSUPPORTED;
+  if (kslice > kFcKMax) return TFX_ERR_UNSUPPORTED;
   dim3 grid((classes + 255) / 256, kFcSlices, (n + kFcBatchMax - 1) / kFcBatchMax);
-  hipLaunchKernelGGL(fc_partial_kernel, grid, dim3(256), 0, stream, pooled, w, partial, n, k, classes, kslice);
+  hipLaunchKernelGGL(pool_fc_partial_kernel, grid, dim3(256), 0, stream, a, w, partial, n, hw, k, classes, kslice);
   int rc = check_launch();
   if (rc) return rc;
-  hipLaunchKernelGGL(softmax_kernel, dim3(n), dim3(256), 0, stream, (const float*)partial, kFcSlices, bias, logits,
-                     probs, n, classes);
+  hipLaunchKernelGGL(softmax_kernel, dim3(n), dim3(256), 0, stream, (const float*)partial, bias, logits, probs, n,
+                     classes);
   return check_launch();
 }
 

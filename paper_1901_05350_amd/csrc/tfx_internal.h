@@ -41,10 +41,10 @@ int launch_depthwise(const float* x, const float* w, const float* bias, float* y
                      int fh, int fw, int mult, int oh, int ow, int sh, int sw, int pt, int pl, int act,
                      hipStream_t stream);
 
-// MobileNet tail: global average pool [n,hw,c] -> [n,c]; fully connected + softmax.
-int launch_global_avg_pool(const float* a, float* p, int n, int hw, int c, hipStream_t stream);
-int launch_fc_softmax(const float* pooled, const float* w, const float* bias, float* partial, float* logits,
-                      float* probs, int n, int k, int classes, hipStream_t stream);
+// MobileNet tail: global average pool of a [n,hw,k] map fused into the fully connected layer
+// (split over K into `partial`), then bias + softmax.  logits may be null.
+int launch_pool_fc_softmax(const float* a, const float* w, const float* bias, float* partial, float* logits,
+                           float* probs, int n, int hw, int k, int classes, hipStream_t stream);
 size_t fc_partial_floats(int n, int k, int classes);
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? TFX_OK : TFX_ERR_LAUNCH; }
