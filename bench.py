@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-layer and single-op measurements")
+    ap.add_argument("--op", default=None, help="time only this single-op workload (for profiling), e.g. "
+                                               "batch_matmul, pointwise_n64, depthwise_s1_n64_cold; 'list' prints the names")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
@@ -83,6 +85,76 @@ def main():
             torch.cuda.synchronize()
             ts.append(e0.elapsed_time(e1) * 1e-3)
         return float(np.median(ts))
+
+    # ---------------- the single-op workloads (each returns its result entry) ----------------
+    reps = max(20, min(args.steps, 200))
+
+    def mfma_entry(fn, flop, nbytes):
+        t = time_loop(fn, reps)
+        return {"us": round(t * 1e6, 3), "single_launch_us": round(time_single(fn) * 1e6, 2),
+                "TFLOPs": round(flop / t / 1e12, 4), "GBps": round(nbytes / t / 1e9, 1),
+                "roofline": {"bound": "mfma", "achieved": round(flop / t / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12,
+                             "unit": "TFLOP/s", "frac": round(flop / t / PEAK_MFMA_F32, 5), "traffic": None}}
+
+    def op_matmul():
+        d = inputs.matmul_small(seed=0)
+        a, b = dev(d["a"]), dev(d["b"])
+        c = tfx.tfx_matmul(a, b)
+        return mfma_entry(lambda: tfx.tfx_matmul(a, b, out=c), 2 * 64 * 128 * 64, 81920)
+
+    def op_batch_matmul():
+        d = inputs.batch_matmul(seed=3)
+        a, b = dev(d["a"]), dev(d["b"])
+        c = tfx.tfx_batch_matmul(a, b, False, True)
+        return mfma_entry(lambda: tfx.tfx_batch_matmul(a, b, False, True, out=c), 2 * 8 * 1024 ** 3, 3 * 8 * 1024 * 1024 * 4)
+
+    def op_pointwise(n):
+        def build():
+            d = inputs.pointwise_conv(seed=1, n=n)
+            xx, ff, bb = dev(d["x"]), dev(d["filter"]), dev(d["bias"])
+            yy = tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6)
+            return mfma_entry(lambda: tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6, out=yy),
+                              2 * n * 56 * 56 * 128 * 128, 4 * (xx.numel() + yy.numel() + 128 * 128 + 128))
+        return build
+
+    def op_depthwise(n, s, copies):
+        """copies > 1: rotate over distinct tensors whose total size exceeds the 256 MB last-level cache."""
+        def build():
+            d = inputs.depthwise_conv(seed=2, n=n)
+            ff, bb = dev(d["filter"]), dev(d["bias"])
+            xs = [dev(d["x"])]
+            for _ in range(copies - 1):
+                xs.append(xs[0].clone())
+            ys = [tfx.tfx_depthwise_conv2d(xv, ff, bb, s, tfx.PAD_SAME, tfx.ACT_RELU6) for xv in xs]
+            nbytes = 4 * (xs[0].numel() + ys[0].numel() + 9 * 64 + 64)
+            state = {"i": 0}
+
+            def fn():
+                i = state["i"] = (state["i"] + 1) % copies
+                tfx.tfx_depthwise_conv2d(xs[i], ff, bb, s, tfx.PAD_SAME, tfx.ACT_RELU6, out=ys[i])
+            t = time_loop(fn, max(reps, copies * 2), warmup=copies, inner=copies if copies > 1 else None)
+            e = {"us": round(t * 1e6, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
+                 "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
+                              "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
+            if copies == 1:
+                e["single_launch_us"] = round(time_single(fn) * 1e6, 2)
+            return e
+        return build
+
+    single_ops = {"matmul_64x128x64": op_matmul, "batch_matmul_8x1024x1024x1024_tB": op_batch_matmul}
+    for n in (1, 8, 64):
+        single_ops["pointwise_%dx56x56x128_to_128" % n] = op_pointwise(n)
+    for s in (1, 2):
+        single_ops["depthwise_1x112x112x64_s%d_warm" % s] = op_depthwise(1, s, 1)
+        single_ops["depthwise_1x112x112x64_s%d_cold_rotation" % s] = op_depthwise(1, s, 96)
+        single_ops["depthwise_8x112x112x64_s%d_warm" % s] = op_depthwise(8, s, 1)
+        single_ops["depthwise_64x112x112x64_s%d_cold_rotation" % s] = op_depthwise(64, s, 3)
+    if args.op is not None:
+        if args.op not in single_ops:
+            print("\n".join(single_ops))
+            sys.exit(0 if args.op == "list" else 2)
+        print(json.dumps({"op": args.op, **single_ops[args.op]()}))
+        return
 
     # ---------------- the timed steps: MobileNet-v1 b1 ----------------
     data = inputs.mobilenet_v1(seed=4, batch=1)
@@ -146,7 +218,6 @@ def main():
     }
 
     # ---------------- per-layer times inside the network, and the roofline of its dominant kernel ----------
-    reps = max(20, min(args.steps, 200))
     if not args.no_ops:
         CH, ST = inputs.MOBILENET_V1_CHANNELS, inputs.MOBILENET_V1_STRIDES
         w = model.tensors
@@ -184,63 +255,7 @@ def main():
             "depthwise_GBps": round(dw_bytes / dw_s / 1e9, 1),
             "per_layer_us": {l["layer"]: round(l["us"], 2) for l in layers}}
 
-        # ---------------- the four single-op workloads ----------------
-        ops = {}
-
-        def gemm_entry(name, fn, flop, nbytes):
-            t = time_loop(fn, reps)
-            ops[name] = {"us": round(t * 1e6, 3), "single_launch_us": round(time_single(fn) * 1e6, 2),
-                         "TFLOPs": round(flop / t / 1e12, 4), "GBps": round(nbytes / t / 1e9, 1),
-                         "roofline": {"bound": "mfma", "achieved": round(flop / t / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12,
-                                      "unit": "TFLOP/s", "frac": round(flop / t / PEAK_MFMA_F32, 5), "traffic": None}}
-
-        d = inputs.matmul_small(seed=0)
-        a, b = dev(d["a"]), dev(d["b"])
-        c = tfx.tfx_matmul(a, b)
-        gemm_entry("matmul_64x128x64", lambda: tfx.tfx_matmul(a, b, out=c), 2 * 64 * 128 * 64, 81920)
-
-        d = inputs.batch_matmul(seed=3)
-        a4, b4 = dev(d["a"]), dev(d["b"])
-        c4 = tfx.tfx_batch_matmul(a4, b4, False, True)
-        gemm_entry("batch_matmul_8x1024x1024x1024_tB", lambda: tfx.tfx_batch_matmul(a4, b4, False, True, out=c4),
-                   2 * 8 * 1024 ** 3, 3 * 8 * 1024 * 1024 * 4)
-        del a4, b4, c4
-
-        for n in (1, 8, 64):
-            d = inputs.pointwise_conv(seed=1, n=n)
-            xx, ff, bb = dev(d["x"]), dev(d["filter"]), dev(d["bias"])
-            yy = tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6)
-            gemm_entry("pointwise_%dx56x56x128_to_128" % n,
-                       lambda: tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6, out=yy),
-                       2 * n * 56 * 56 * 128 * 128, 4 * (xx.numel() + yy.numel() + 128 * 128 + 128))
-
-        def dw_entry(name, n, s, copies):
-            """copies > 1: rotate over distinct tensors whose total size exceeds the 256 MB last-level cache."""
-            d = inputs.depthwise_conv(seed=2, n=n)
-            ff, bb = dev(d["filter"]), dev(d["bias"])
-            xs = [dev(d["x"])]
-            for _ in range(copies - 1):
-                xs.append(xs[0].clone())
-            ys = [tfx.tfx_depthwise_conv2d(xv, ff, bb, s, tfx.PAD_SAME, tfx.ACT_RELU6) for xv in xs]
-            nbytes = 4 * (xs[0].numel() + ys[0].numel() + 9 * 64 + 64)
-            state = {"i": 0}
-
-            def fn():
-                i = state["i"] = (state["i"] + 1) % copies
-                tfx.tfx_depthwise_conv2d(xs[i], ff, bb, s, tfx.PAD_SAME, tfx.ACT_RELU6, out=ys[i])
-            t = time_loop(fn, max(reps, copies * 2), warmup=copies, inner=copies if copies > 1 else None)
-            ops[name] = {"us": round(t * 1e6, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
-                         "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
-                                      "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
-            if copies == 1:
-                ops[name]["single_launch_us"] = round(time_single(fn) * 1e6, 2)
-
-        for s in (1, 2):
-            dw_entry("depthwise_1x112x112x64_s%d_warm" % s, 1, s, 1)
-            dw_entry("depthwise_1x112x112x64_s%d_cold_rotation" % s, 1, s, 96)
-            dw_entry("depthwise_8x112x112x64_s%d_warm" % s, 8, s, 1)
-            dw_entry("depthwise_64x112x112x64_s%d_cold_rotation" % s, 64, s, 3)
-        out["ops"] = ops
+        out["ops"] = {name: build() for name, build in single_ops.items()}
 
     # ---------------- CPU oracle on the host cores (baseline only) ----------------
     if not args.no_cpu_baseline:

@@ -61,6 +61,27 @@ def test_pointwise_shape_sweep():
             assert_close(got, oracle.conv2d(x, f, bias, 1, pad, act), "pointwise %r" % ((n, h, w, ci, co),))
 
 
+def test_pointwise_large_m_thin_filters():
+    # large N*H*W with the four thin MobileNet filter shapes (filter-stationary kernel), M ragged
+    cases = [(3, 112, 112, 32, 64), (1, 181, 183, 64, 128), (1, 181, 183, 128, 128), (2, 129, 130, 128, 256),
+             (64, 56, 56, 128, 128)]
+    r = rng(22)
+    for i, (n, h, w, ci, co) in enumerate(cases):
+        x = r.uniform(-1, 1, (n, h, w, ci)).astype(np.float32)
+        f = (r.standard_normal((1, 1, ci, co)) * np.sqrt(2.0 / ci)).astype(np.float32)
+        b = (r.standard_normal((co,)) * 0.5).astype(np.float32)
+        act = [ACT_RELU6, ACT_NONE, ACT_RELU][i % 3]
+        got = gpu_conv(x, f, b if i != 1 else None, 1, PAD_SAME, act)
+        if n == 64:
+            # full-size batch: the oracle checks a sample of images
+            for img in (0, 31, 63):
+                ref = oracle.conv2d(x[img:img + 1], f, b, 1, PAD_SAME, act)
+                assert_close(got[img:img + 1], ref, "pointwise batch 64 image %d" % img)
+        else:
+            assert_close(got, oracle.conv2d(x, f, b if i != 1 else None, 1, PAD_SAME, act),
+                         "pointwise large M %r" % ((n, h, w, ci, co),))
+
+
 def test_stem_conv_config_shape():
     d = inputs.conv_general(31, 1, 224, 224, 3, 32, 3, 3)
     got = gpu_conv(d["x"], d["filter"], d["bias"], 2, PAD_SAME, ACT_RELU6)
