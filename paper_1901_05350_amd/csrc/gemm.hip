@@ -117,7 +117,9 @@ __device__ __forceinline__ float f4_get(const float4& v, int s) {
 // WAVES_K > 1 splits each BK-deep tile over that many wavefronts (each takes BK / WAVES_K of the
 // depth) and adds the partial accumulators through LDS at the end: for small M x N problems this
 // puts 4x more bytes in flight per workgroup and shortens the serial K loop 4x.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, bool A_KC, bool B_KC, bool VEC>
+// STAGES = 2 double-buffers the LDS tiles (one barrier per k-slice); STAGES = 1 keeps a single, deeper
+// tile (BK up to 512) so that a small problem's whole K panel is in flight in one round trip.
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int STAGES, bool A_KC, bool B_KC, bool VEC>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, const float* __restrict__ bias,
     int M, int N, int K, int tiles_m, int tiles_n, int total_blocks, long long strideA, long long strideB,
@@ -131,12 +133,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
   using TB = Tile<BN, BK, B_KC>;
   static_assert(TA::kSlots % NT == 0 && TB::kSlots % NT == 0, "loader shape");
   constexpr int SA = TA::kSlots / NT, SB = TB::kSlots / NT;
-  static_assert(WAVES_K == 1 || (WAVES_K - 1) * WAVES_M * WAVES_N * TM * TN * 1024 <= 2 * (TA::kFloats + TB::kFloats),
+  static_assert(WAVES_K == 1 || (WAVES_K - 1) * WAVES_M * WAVES_N * TM * TN * 1024 <= STAGES * (TA::kFloats + TB::kFloats),
                 "split-K reduction reuses the tile buffers");
+  // a 1 x 1 wave tile has a single accumulator chain: split it in two to halve the MFMA dependency latency
+  constexpr int NACC = (TM * TN == 1 && GROUPS >= 1) ? 2 : 1;
 
   extern __shared__ __align__(16) float smem[];
-  float* const lds_a = smem;                    // two A buffers, then two B buffers
-  float* const lds_b = smem + 2 * TA::kFloats;
+  float* const lds_a = smem;                    // STAGES A buffers, then STAGES B buffers
+  float* const lds_b = smem + STAGES * TA::kFloats;
 
   // XCD-aware block order: hardware block id x lands on XCD x % 8.  Give each XCD a contiguous
   // range of logical tiles (same batch, neighbouring tiles) so that its L2 sees each A / B panel once.
@@ -162,13 +166,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
   const int li = lane % 32, h = lane / 32;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  floatx16 acc[TM][TN];
+  floatx16 acc[NACC][TM][TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int c = 0; c < NACC; ++c)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][i][j][v] = 0.f;
+
+  // bias for this lane's output columns, fetched now so that its latency hides under the main loop
+  float bv[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + wn0 + 32 * j + li;
+    bv[j] = (bias != nullptr && col < N) ? bias[col] : 0.f;
+  }
 
   float4 ra[SA], rb[SB];
   const int nk = (K + BK - 1) / BK;
@@ -179,7 +193,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
+    const int cur = STAGES == 2 ? (kt & 1) : 0;
+    const int nxt = STAGES == 2 ? (cur ^ 1) : 0;
     if (kt + 1 < nk) {
       load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, (kt + 1) * BK, tid, ra);
       load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, (kt + 1) * BK, tid, rb);
@@ -189,6 +204,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
 #pragma unroll
     for (int gg = 0; gg < GROUPS; ++gg) {
       const int g = wk * GROUPS + gg;
+      if (STAGES == 1 && kt * BK + 8 * g >= K) break;  // deep single tile: skip k-groups past the end of K
       float4 fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) fa[i] = read_frag<BM, BK, A_KC>(la, wm0 + 32 * i + li, g, h);
@@ -200,13 +216,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f4_get(fa[i], s), f4_get(fb[j], s), acc[i][j], 0, 0, 0);
+            acc[s % NACC][i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f4_get(fa[i], s), f4_get(fb[j], s),
+                                                                        acc[s % NACC][i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) {
-      store_tile<BM, BK, A_KC, NT, SA>(lds_a + (cur ^ 1) * TA::kFloats, tid, ra);
-      store_tile<BN, BK, B_KC, NT, SB>(lds_b + (cur ^ 1) * TB::kFloats, tid, rb);
+      if (STAGES == 1) __syncthreads();  // everyone has finished reading the only tile
+      store_tile<BM, BK, A_KC, NT, SA>(lds_a + nxt * TA::kFloats, tid, ra);
+      store_tile<BN, BK, B_KC, NT, SB>(lds_b + nxt * TB::kFloats, tid, rb);
     }
     __syncthreads();
+  }
+  if (NACC == 2) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[0][i][j][v] += acc[NACC - 1][i][j][v];
   }
 
   if (WAVES_K > 1) {
@@ -219,7 +245,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) dst[((i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+          for (int v = 0; v < 16; ++v) dst[((i * TN + j) * 16 + v) * 64 + lane] = acc[0][i][j][v];
     }
     __syncthreads();
     if (wk > 0) return;
@@ -231,7 +257,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) acc[i][j][v] += src[((i * TN + j) * 16 + v) * 64 + lane];
+          for (int v = 0; v < 16; ++v) acc[0][i][j][v] += src[((i * TN + j) * 16 + v) * 64 + lane];
     }
   }
 
@@ -240,26 +266,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
   for (int j = 0; j < TN; ++j) {
     const int col = n0 + wn0 + 32 * j + li;
     if (col >= N) continue;
-    const float bv = bias ? bias[col] : 0.f;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
-        if (row < M) C[(size_t)row * N + col] = apply_act(acc[i][j][v] + bv, act);
+        if (row < M) C[(size_t)row * N + col] = apply_act(acc[0][i][j][v] + bv[j], act);
       }
     }
   }
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, bool A_KC, bool B_KC, bool VEC>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int STAGES, bool A_KC, bool B_KC, bool VEC>
 int launch_cfg(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k, int act,
                hipStream_t stream) {
   using TA = Tile<BM, BK, A_KC>;
   using TB = Tile<BN, BK, B_KC>;
-  constexpr size_t lds_bytes = 2 * (TA::kFloats + TB::kFloats) * sizeof(float);
+  constexpr size_t lds_bytes = STAGES * (TA::kFloats + TB::kFloats) * sizeof(float);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
-  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, A_KC, B_KC, VEC>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, STAGES, A_KC, B_KC, VEC>;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -276,12 +301,12 @@ int launch_cfg(const float* a, const float* b, float* c, const float* bias, int 
   return check_launch();
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int STAGES>
 int launch_layout(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k,
                   bool a_kc, bool b_kc, bool vec, int act, hipStream_t stream) {
 #define TFX_GEMM_CASE(AK, BKC, V)                                                                              \
   if (a_kc == AK && b_kc == BKC && vec == V)                                                                   \
-    return launch_cfg<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AK, BKC, V>(a, b, c, bias, batch, m, n, k, act, stream);
+    return launch_cfg<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, STAGES, AK, BKC, V>(a, b, c, bias, batch, m, n, k, act, stream);
   TFX_GEMM_CASE(true, true, true)
   TFX_GEMM_CASE(true, false, true)
   TFX_GEMM_CASE(false, true, true)
@@ -309,10 +334,12 @@ int launch_gemm(const float* a, const float* b, float* c, const float* bias, int
   const long long blocks128 = (long long)batch * ((m + 127) / 128) * ((n + 127) / 128);
   const long long blocks64 = (long long)batch * ((m + 63) / 64) * ((n + 63) / 64);
   if (blocks128 >= 256)
-    return launch_layout<128, 128, 32, 2, 2, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+    return launch_layout<128, 128, 32, 2, 2, 1, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
   if (blocks64 >= 192 || k <= 32)
-    return launch_layout<64, 64, 32, 2, 2, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
-  return launch_layout<32, 32, 128, 1, 1, 4>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+    return launch_layout<64, 64, 32, 2, 2, 1, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  if (k <= 128) return launch_layout<32, 32, 128, 1, 1, 4, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  // deeper K: one 512-deep tile split over 8 wavefronts, the whole panel in flight at once
+  return launch_layout<32, 32, 512, 1, 1, 8, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
 }
 
 }  // namespace tfx
