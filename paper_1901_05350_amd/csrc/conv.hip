@@ -43,61 +43,84 @@ __global__ __launch_bounds__(256) void conv2d_direct_kernel(const float* __restr
 // A thread computes 8 consecutive output channels of one output pixel: the 27 x CO filter
 // sits in LDS and is read as float4 pairs (only CO/8 distinct addresses per wave, so the
 // reads broadcast); CO/8 neighbouring lanes write one pixel's CO floats as a contiguous run.
+// All 27 input values of a pixel are fetched with unconditional loads from clamped addresses
+// (out-of-image taps are zeroed afterwards), so they are all in flight at once.
 template <int CO>
 __global__ __launch_bounds__(256) void conv2d_stem_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                           const float* __restrict__ bias, float* __restrict__ y, int N,
                                                           int H, int W, int OH, int OW, int sh, int sw, int pt, int pl,
                                                           int act, int total) {
   constexpr int G = CO / 8;
+  constexpr int WPT = (27 * CO + 255) / 256;  // filter floats staged per thread
   __shared__ __align__(16) float wl[27 * CO];
-  for (int i = threadIdx.x; i < 27 * CO; i += 256) wl[i] = w[i];
-  __syncthreads();
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= total) return;
+  int idx = blockIdx.x * 256 + threadIdx.x;
+  const bool live = idx < total;
+  if (!live) idx = total - 1;
   const int g = idx % G;
   int r = idx / G;
   const int ow = r % OW;
   r /= OW;
   const int oh = r % OH;
   const int n = r / OH;
+
+  // issue the filter loads and the 27 input loads together, then stage the filter
+  float wreg[WPT];
+#pragma unroll
+  for (int i = 0; i < WPT; ++i) {
+    const int e = threadIdx.x + i * 256;
+    wreg[i] = w[e < 27 * CO ? e : 27 * CO - 1];
+  }
   float acc[8];
 #pragma unroll
-  for (int o = 0; o < 8; ++o) acc[o] = 0.f;
+  for (int o = 0; o < 8; ++o) acc[o] = bias ? bias[8 * g + o] : 0.f;
+  float xv[27];
 #pragma unroll
   for (int kh = 0; kh < 3; ++kh) {
     const int ih = oh * sh - pt + kh;
-    if (ih < 0 || ih >= H) continue;
+    const int ihc = min(max(ih, 0), H - 1);
 #pragma unroll
     for (int kw = 0; kw < 3; ++kw) {
       const int iw = ow * sw - pl + kw;
-      if (iw < 0 || iw >= W) continue;
-      const float* xp = x + (((size_t)n * H + ih) * W + iw) * 3;
+      const int iwc = min(max(iw, 0), W - 1);
+      const bool ok = ih == ihc && iw == iwc;
+      const float* xp = x + (((size_t)n * H + ihc) * W + iwc) * 3;
 #pragma unroll
       for (int c = 0; c < 3; ++c) {
-        const float xv = xp[c];
-        const float4 w0 = *reinterpret_cast<const float4*>(&wl[((kh * 3 + kw) * 3 + c) * CO + 8 * g]);
-        const float4 w1 = *reinterpret_cast<const float4*>(&wl[((kh * 3 + kw) * 3 + c) * CO + 8 * g + 4]);
-        acc[0] = fmaf(xv, w0.x, acc[0]);
-        acc[1] = fmaf(xv, w0.y, acc[1]);
-        acc[2] = fmaf(xv, w0.z, acc[2]);
-        acc[3] = fmaf(xv, w0.w, acc[3]);
-        acc[4] = fmaf(xv, w1.x, acc[4]);
-        acc[5] = fmaf(xv, w1.y, acc[5]);
-        acc[6] = fmaf(xv, w1.z, acc[6]);
-        acc[7] = fmaf(xv, w1.w, acc[7]);
+        const float v = xp[c];
+        xv[(kh * 3 + kw) * 3 + c] = ok ? v : 0.f;
       }
     }
   }
+#pragma unroll
+  for (int i = 0; i < WPT; ++i) {
+    const int e = threadIdx.x + i * 256;
+    if (e < 27 * CO) wl[e] = wreg[i];
+  }
+  __syncthreads();
+  if (!live) return;
+
+#pragma unroll
+  for (int t = 0; t < 27; ++t) {
+    const float4 w0 = *reinterpret_cast<const float4*>(&wl[t * CO + 8 * g]);
+    const float4 w1 = *reinterpret_cast<const float4*>(&wl[t * CO + 8 * g + 4]);
+    acc[0] = fmaf(xv[t], w0.x, acc[0]);
+    acc[1] = fmaf(xv[t], w0.y, acc[1]);
+    acc[2] = fmaf(xv[t], w0.z, acc[2]);
+    acc[3] = fmaf(xv[t], w0.w, acc[3]);
+    acc[4] = fmaf(xv[t], w1.x, acc[4]);
+    acc[5] = fmaf(xv[t], w1.y, acc[5]);
+    acc[6] = fmaf(xv[t], w1.z, acc[6]);
+    acc[7] = fmaf(xv[t], w1.w, acc[7]);
+  }
   float4 o0, o1;
-  const float* bp = bias ? bias + 8 * g : nullptr;
-  o0.x = apply_act(acc[0] + (bp ? bp[0] : 0.f), act);
-  o0.y = apply_act(acc[1] + (bp ? bp[1] : 0.f), act);
-  o0.z = apply_act(acc[2] + (bp ? bp[2] : 0.f), act);
-  o0.w = apply_act(acc[3] + (bp ? bp[3] : 0.f), act);
-  o1.x = apply_act(acc[4] + (bp ? bp[4] : 0.f), act);
-  o1.y = apply_act(acc[5] + (bp ? bp[5] : 0.f), act);
-  o1.z = apply_act(acc[6] + (bp ? bp[6] : 0.f), act);
-  o1.w = apply_act(acc[7] + (bp ? bp[7] : 0.f), act);
+  o0.x = apply_act(acc[0], act);
+  o0.y = apply_act(acc[1], act);
+  o0.z = apply_act(acc[2], act);
+  o0.w = apply_act(acc[3], act);
+  o1.x = apply_act(acc[4], act);
+  o1.y = apply_act(acc[5], act);
+  o1.z = apply_act(acc[6], act);
+  o1.w = apply_act(acc[7], act);
   float* yp = y + (((size_t)n * OH + oh) * OW + ow) * CO + 8 * g;
   *reinterpret_cast<float4*>(yp) = o0;
   *reinterpret_cast<float4*>(yp + 4) = o1;

@@ -31,17 +31,27 @@ __global__ __launch_bounds__(256) void pool_fc_partial_kernel(const float* __res
 #pragma unroll
   for (int kk = 0; kk < kFcKMax; ++kk) wv[kk] = (kk < kn && j < classes) ? w[(size_t)(k0 + kk) * classes + j] : 0.f;
 
-  // global average pool of this K-slice: thread t sums pixels t/32, t/32 + 8, ... of channel t % 32
+  // global average pool of this K-slice: thread t sums pixels t/32, t/32 + 8, ... of channel t % 32.
+  // The loads are unconditional from clamped addresses so that all of them are in flight at once.
   {
+    constexpr int kPixPerLane = 8;  // hw <= 64
     const int kk = threadIdx.x % kFcKMax, p0 = threadIdx.x / kFcKMax;  // 8 pixel lanes
     __shared__ float red[kFcBatchMax][8][kFcKMax];
+    const int kc = kk < kn ? kk : 0;
+#pragma unroll
     for (int b = 0; b < kFcBatchMax; ++b) {
-      float acc = 0.f;
-      if (b < nb && kk < kn) {
-        const float* ap = a + ((size_t)(n0 + b) * hw) * k + k0 + kk;
-        for (int p = p0; p < hw; p += 8) acc += ap[(size_t)p * k];
+      const int bc = b < nb ? b : 0;
+      const float* ap = a + ((size_t)(n0 + bc) * hw) * k + k0 + kc;
+      float v[kPixPerLane];
+#pragma unroll
+      for (int q = 0; q < kPixPerLane; ++q) {
+        const int p = p0 + 8 * q;
+        v[q] = ap[(size_t)(p < hw ? p : hw - 1) * k];
       }
-      red[b][p0][kk] = acc;
+      float acc = 0.f;
+#pragma unroll
+      for (int q = 0; q < kPixPerLane; ++q) acc += (p0 + 8 * q < hw) ? v[q] : 0.f;
+      red[b][p0][kk] = (b < nb && kk < kn) ? acc : 0.f;
     }
     __syncthreads();
     if (threadIdx.x < kFcBatchMax * kFcKMax) {
@@ -137,7 +147,7 @@ int launch_pool_fc_softmax(const float* a, const float* w, const float* bias, fl
                            float* probs, int n, int hw, int k, int classes, hipStream_t stream) {
   if (classes > 256 * kMaxPerThread) return TFX_ERR_UNSUPPORTED;
   const int kslice = (k + kFcSlices - 1) / kFcSlices;
-  if (kslice > kFcKMax) return TFX_ERR_UNSUPPORTED;
+  if (kslice > kFcKMax || hw > 64) return TFX_ERR_UNSUPPORTED;
   dim3 grid((classes + 255) / 256, kFcSlices, (n + kFcBatchMax - 1) / kFcBatchMax);
   hipLaunchKernelGGL(pool_fc_partial_kernel, grid, dim3(256), 0, stream, a, w, partial, n, hw, k, classes, kslice);
   int rc = check_launch();

@@ -64,7 +64,7 @@ def test_pointwise_shape_sweep():
 def test_pointwise_large_m_thin_filters():
     # large N*H*W with the four thin MobileNet filter shapes (filter-stationary kernel), M ragged
     cases = [(3, 112, 112, 32, 64), (1, 181, 183, 64, 128), (1, 181, 183, 128, 128), (2, 129, 130, 128, 256),
-             (64, 56, 56, 128, 128)]
+             (8, 56, 56, 128, 128), (64, 56, 56, 128, 128)]
     r = rng(22)
     for i, (n, h, w, ci, co) in enumerate(cases):
         x = r.uniform(-1, 1, (n, h, w, ci)).astype(np.float32)
@@ -72,11 +72,11 @@ def test_pointwise_large_m_thin_filters():
         b = (r.standard_normal((co,)) * 0.5).astype(np.float32)
         act = [ACT_RELU6, ACT_NONE, ACT_RELU][i % 3]
         got = gpu_conv(x, f, b if i != 1 else None, 1, PAD_SAME, act)
-        if n == 64:
-            # full-size batch: the oracle checks a sample of images
-            for img in (0, 31, 63):
+        if n >= 8:
+            # the benchmark's batch sizes: the oracle checks a sample of images
+            for img in (0, n // 2 - 1, n - 1):
                 ref = oracle.conv2d(x[img:img + 1], f, b, 1, PAD_SAME, act)
-                assert_close(got[img:img + 1], ref, "pointwise batch 64 image %d" % img)
+                assert_close(got[img:img + 1], ref, "pointwise batch %d image %d" % (n, img))
         else:
             assert_close(got, oracle.conv2d(x, f, b if i != 1 else None, 1, PAD_SAME, act),
                          "pointwise large M %r" % ((n, h, w, ci, co),))
@@ -141,6 +141,33 @@ def test_depthwise_fast_path_sweep():
     f = r.standard_normal((3, 3, 8, 1)).astype(np.float32)
     assert_close(gpu_dw(x, f, None, 1, PAD_SAME, ACT_NONE), oracle.depthwise_conv2d(x, f, None, 1, PAD_SAME, ACT_NONE),
                  "dw no bias")
+
+
+@pytest.mark.parametrize("n", [8, 64])
+@pytest.mark.parametrize("stride", [1, 2])
+def test_depthwise_benchmark_batches_sampled_images(n, stride):
+    # the batch sizes the benchmark times (they select the kernel variants with several rows per
+    # thread); the oracle checks a sample of whole images
+    d = inputs.depthwise_conv(seed=2, n=n)
+    got = gpu_dw(d["x"], d["filter"], d["bias"], stride, PAD_SAME, ACT_RELU6)
+    for img in sorted({0, n // 2 - 1, n - 1}):
+        ref = oracle.depthwise_conv2d(d["x"][img:img + 1], d["filter"], d["bias"], stride, PAD_SAME, ACT_RELU6)
+        assert_close(got[img:img + 1], ref, "depthwise batch %d image %d s%d" % (n, img, stride))
+
+
+def test_depthwise_rows_per_thread_variants_ragged_heights():
+    # output heights that are not multiples of the 2 / 4 / 6 rows a thread covers, at sizes that
+    # select each variant
+    r = rng(44)
+    for (n, h, w, c) in [(16, 37, 45, 64), (44, 53, 61, 32), (200, 31, 33, 32), (4, 9, 200, 128)]:
+        x = r.uniform(-1, 1, (n, h, w, c)).astype(np.float32)
+        f = (r.standard_normal((3, 3, c, 1)) * np.sqrt(2.0 / 9)).astype(np.float32)
+        b = (r.standard_normal((c,)) * 0.5).astype(np.float32)
+        for s in (1, 2):
+            got = gpu_dw(x, f, b, s, PAD_SAME, ACT_RELU6)
+            for img in (0, n - 1):
+                ref = oracle.depthwise_conv2d(x[img:img + 1], f, b, s, PAD_SAME, ACT_RELU6)
+                assert_close(got[img:img + 1], ref, "dw variants %r s%d image %d" % ((n, h, w, c), s, img))
 
 
 def test_depthwise_generic_sweep():
