@@ -97,8 +97,7 @@ __global__ __launch_bounds__(256) void depthwise3x3_kernel(const float* __restri
   for (int t = 0; t < 9; ++t) wt[t] = *reinterpret_cast<const v4f*>(w + (size_t)t * C + 4 * c4);
   v4f bv = z;
   if (bias) bv = *reinterpret_cast<const v4f*>(bias + 4 * c4);
-  const float lo = act == TFX_ACT_NONE ? -INFINITY : 0.f;       // relu / relu6 clamp below at 0
-  const float hi = act == TFX_ACT_RELU6 ? 6.f : INFINITY;       // relu6 clamps above at 6
+  const ActClamp clamp = make_act(act);
 
 #pragma unroll
   for (int o = 0; o < RS; ++o) {
@@ -110,7 +109,7 @@ __global__ __launch_bounds__(256) void depthwise3x3_kernel(const float* __restri
       for (int kw = 0; kw < 3; ++kw) acc += win[o * S + kh][kw] * wt[kh * 3 + kw];
     v4f out;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) out[e] = fminf(fmaxf(acc[e], lo), hi);
+    for (int e = 0; e < 4; ++e) out[e] = apply_act(acc[e], clamp);
     *reinterpret_cast<v4f*>(y + (((size_t)n * OH + oh0 + o) * OW + ow) * C + 4 * c4) = out;
   }
 }

@@ -261,6 +261,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
     }
   }
 
+  const ActClamp clamp = make_act(act);
   // Epilogue: bias[col] then activation, one dword per lane per register (two 128-byte rows per store).
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
@@ -271,7 +272,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
-        if (row < M) C[(size_t)row * N + col] = apply_act(acc[0][i][j][v] + bv[j], act);
+        if (row < M) C[(size_t)row * N + col] = apply_act(acc[0][i][j][v] + bv[j], clamp);
       }
     }
   }

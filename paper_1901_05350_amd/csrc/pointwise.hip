@@ -25,7 +25,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream_kernel(const float*
                                                                     const float* __restrict__ bias,
                                                                     float* __restrict__ y, int M, int slabs, int act) {
   constexpr int K = KG * 8, N = NB * 32;
-  constexpr int TN = NB < 4 ? NB : 4;
+  constexpr int TN = NB < 2 ? NB : 2;  // two accumulators live at a time: fewer registers, measured fastest
   constexpr int PASSES = NB / TN;
   static_assert(NB % TN == 0, "column blocks");
   static_assert((K * N / 4) % kThreads == 0, "filter staging");
@@ -45,6 +45,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream_kernel(const float*
 
   const int lane = tid % 64, li = lane % 32, h = lane / 32;
   constexpr int waves = kThreads / 64;
+  const ActClamp clamp = make_act(act);
   // a workgroup owns a contiguous range of 32-row slabs; its wavefronts take them round-robin
   const int s0 = (int)((long long)slabs * blockIdx.x / gridDim.x);
   const int s1 = (int)((long long)slabs * (blockIdx.x + 1) / gridDim.x);
@@ -88,11 +89,11 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream_kernel(const float*
         float* yp = y + (size_t)r0 * N + col;
         if (full) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) yp[(size_t)(8 * (v / 4) + (v % 4)) * N] = apply_act(acc[j][v] + bv, act);
+          for (int v = 0; v < 16; ++v) yp[(size_t)(8 * (v / 4) + (v % 4)) * N] = apply_act(acc[j][v] + bv, clamp);
         } else {
 #pragma unroll
           for (int v = 0; v < 16; ++v)
-            if (r0 + 8 * (v / 4) + (v % 4) < M) yp[(size_t)(8 * (v / 4) + (v % 4)) * N] = apply_act(acc[j][v] + bv, act);
+            if (r0 + 8 * (v / 4) + (v % 4) < M) yp[(size_t)(8 * (v / 4) + (v % 4)) * N] = apply_act(acc[j][v] + bv, clamp);
         }
       }
     }

@@ -10,12 +10,24 @@
 
 namespace tfx {
 
-// Fused epilogue: bias first, then activation (relu6(v) = min(max(v,0),6)).
-__device__ __forceinline__ float apply_act(float v, int act) {
-  if (act == TFX_ACT_RELU) return fmaxf(v, 0.0f);
-  if (act == TFX_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
-  return v;
+// Fused epilogue: bias first, then activation.  relu and relu6 are clamps ([0, +inf] and [0, 6]);
+// kernels turn the enum into an on/off flag and an upper bound once and apply max / min per
+// element.  With no activation the value passes through untouched (NaN and Inf included).
+struct ActClamp {
+  bool on;
+  float hi;
+};
+__device__ __forceinline__ ActClamp make_act(int act) {
+  ActClamp c;
+  c.on = act != TFX_ACT_NONE;
+  c.hi = act == TFX_ACT_RELU6 ? 6.0f : INFINITY;
+  return c;
 }
+__device__ __forceinline__ float apply_act(float v, const ActClamp& c) {
+  const float t = fminf(fmaxf(v, 0.0f), c.hi);
+  return c.on ? t : v;
+}
+__device__ __forceinline__ float apply_act(float v, int act) { return apply_act(v, make_act(act)); }
 
 // Shape rule of one spatial dimension (see include/tfx.h); returns a tfx_status.
 int out_extent(int64_t in, int64_t k, int64_t s, int pad, int64_t* out, int64_t* before, int64_t* after);

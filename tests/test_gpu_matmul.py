@@ -103,3 +103,17 @@ def test_config_batch_matmul_full_size():
     assert got.shape == (8, 1024, 1024)
     ref = oracle.batch_matmul(d["a"], d["b"], False, True)
     assert_close(got, ref, "batchMatMul 8x1024^3 transposeB")
+
+
+def test_nan_and_inf_propagate_without_activation():
+    # ops are plain arithmetic when no activation is asked for: a NaN in A poisons exactly its row of C
+    r = rng(11)
+    a = r.uniform(-1, 1, (40, 24)).astype(np.float32)
+    b = r.uniform(-1, 1, (24, 50)).astype(np.float32)
+    a[7, 3] = np.nan
+    a[9, 5] = np.inf
+    got = run_matmul(a, b, False, False)
+    ref = oracle.matmul(a, b)
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    assert np.isnan(got[7]).all() and not np.isnan(got[8]).any()
+    assert np.array_equal(np.isinf(got), np.isinf(ref)) and np.isinf(got[9]).all()
