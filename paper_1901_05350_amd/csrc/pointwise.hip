@@ -125,8 +125,8 @@ bool pointwise_stream_supported(int m, int k, int n, const void* x, const void* 
   const bool shape = (k == 32 && n == 64) || (k == 64 && n == 128) || (k == 128 && n == 128) || (k == 128 && n == 256);
   const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 &&
                        reinterpret_cast<uintptr_t>(y) % 4 == 0;
-  // worthwhile once there are enough 32-row slabs to give every CU several wavefronts
-  return shape && aligned && m >= 256 * 8 * 32 / 2;
+  // worthwhile once every one of the 256 CUs gets a full workgroup of 8 slabs (measured: below that the tiled GEMM wins)
+  return shape && aligned && m >= 65536;
 }
 
 int launch_pointwise_stream(const float* x, const float* w, const float* bias, float* y, int m, int k, int n, int act,

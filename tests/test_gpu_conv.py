@@ -63,7 +63,7 @@ def test_pointwise_shape_sweep():
 
 def test_pointwise_large_m_thin_filters():
     # large N*H*W with the four thin MobileNet filter shapes (filter-stationary kernel), M ragged
-    cases = [(3, 112, 112, 32, 64), (1, 181, 183, 64, 128), (1, 181, 183, 128, 128), (2, 129, 130, 128, 256),
+    cases = [(6, 112, 112, 32, 64), (2, 181, 183, 64, 128), (2, 181, 183, 128, 128), (4, 129, 130, 128, 256),
              (8, 56, 56, 128, 128), (64, 56, 56, 128, 128)]
     r = rng(22)
     for i, (n, h, w, ci, co) in enumerate(cases):
