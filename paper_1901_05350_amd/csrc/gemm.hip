@@ -201,24 +201,34 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
     }
     const float* la = lds_a + cur * TA::kFloats;
     const float* lb = lds_b + cur * TB::kFloats;
+    // fragments of k-group gg+1 are fetched from LDS before the MFMAs of group gg are issued
+    __builtin_amdgcn_s_setprio(1);  // MFMA phase: do not let the co-resident workgroup's wave cut in
+    float4 fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<BM, BK, A_KC>(la, wm0 + 32 * i + li, wk * GROUPS, h);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BN, BK, B_KC>(lb, wn0 + 32 * j + li, wk * GROUPS, h);
 #pragma unroll
     for (int gg = 0; gg < GROUPS; ++gg) {
       const int g = wk * GROUPS + gg;
       if (STAGES == 1 && kt * BK + 8 * g >= K) break;  // deep single tile: skip k-groups past the end of K
-      float4 fa[TM], fb[TN];
+      if (gg + 1 < GROUPS) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = read_frag<BM, BK, A_KC>(la, wm0 + 32 * i + li, g, h);
+        for (int i = 0; i < TM; ++i) fa[(gg + 1) & 1][i] = read_frag<BM, BK, A_KC>(la, wm0 + 32 * i + li, g + 1, h);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = read_frag<BN, BK, B_KC>(lb, wn0 + 32 * j + li, g, h);
+        for (int j = 0; j < TN; ++j) fb[(gg + 1) & 1][j] = read_frag<BN, BK, B_KC>(lb, wn0 + 32 * j + li, g + 1, h);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // keep those LDS reads ahead of this group's MFMAs
 #pragma unroll
       for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[s % NACC][i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f4_get(fa[i], s), f4_get(fb[j], s),
+            acc[s % NACC][i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f4_get(fa[gg & 1][i], s), f4_get(fb[gg & 1][j], s),
                                                                         acc[s % NACC][i][j], 0, 0, 0);
     }
+    __builtin_amdgcn_s_setprio(0);
     if (kt + 1 < nk) {
       if (STAGES == 1) __syncthreads();  // everyone has finished reading the only tile
       store_tile<BM, BK, A_KC, NT, SA>(lds_a + nxt * TA::kFloats, tid, ra);
