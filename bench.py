@@ -23,6 +23,31 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_F32 = 157.3e12   # FLOP/s, dense fp32 matrix peak of MI355X
 PEAK_HBM = 8.0e12          # B/s
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters'
+# reading for a plain 205.5 MB copy (profiles/hbm_traffic_counters.txt).  Each entry names the kernel
+# source it was measured on; if that file has changed since, the entry is reported as null.
+MEASURED_TRAFFIC = {
+    "batch_matmul_8x1024x1024x1024_tB": (100828040, "gemm.hip", "bd9d72bdc7fc7ac4441967d3215face435df2155d2939db7d864f48d5b7131a8"),
+    "pointwise_64x56x56x128_to_128": (206927237, "pointwise.hip", "31c35501a1061560f51e46d756c1ba310b2efa0206b8a160a10caa508c48889a"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411117364, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (256968885, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
+    "mobilenet_b1_gemm_13_launches": (80891691, "gemm.hip", "bd9d72bdc7fc7ac4441967d3215face435df2155d2939db7d864f48d5b7131a8"),
+}
+
+
+def measured_traffic(name):
+    """Counter-measured HBM bytes for a workload, or None if unknown or its kernel source changed since."""
+    import hashlib
+    if name not in MEASURED_TRAFFIC:
+        return None
+    nbytes, fname, digest = MEASURED_TRAFFIC[name]
+    path = os.path.join(ROOT, "paper_1901_05350_amd", "csrc", fname)
+    try:
+        with open(path, "rb") as f:
+            return nbytes if hashlib.sha256(f.read()).hexdigest() == digest else None
+    except OSError:
+        return None
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -89,12 +114,13 @@ def main():
     # ---------------- the single-op workloads (each returns its result entry) ----------------
     reps = max(20, min(args.steps, 200))
 
-    def mfma_entry(fn, flop, nbytes):
+    def mfma_entry(fn, flop, nbytes, name=None):
         t = time_loop(fn, reps)
         return {"us": round(t * 1e6, 3), "single_launch_us": round(time_single(fn) * 1e6, 2),
-                "TFLOPs": round(flop / t / 1e12, 4), "GBps": round(nbytes / t / 1e9, 1),
+                "TFLOPs": round(flop / t / 1e12, 4), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
                 "roofline": {"bound": "mfma", "achieved": round(flop / t / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12,
-                             "unit": "TFLOP/s", "frac": round(flop / t / PEAK_MFMA_F32, 5), "traffic": None}}
+                             "unit": "TFLOP/s", "frac": round(flop / t / PEAK_MFMA_F32, 5),
+                             "traffic": measured_traffic(name)}}
 
     def op_matmul():
         d = inputs.matmul_small(seed=0)
@@ -106,7 +132,8 @@ def main():
         d = inputs.batch_matmul(seed=3)
         a, b = dev(d["a"]), dev(d["b"])
         c = tfx.tfx_batch_matmul(a, b, False, True)
-        return mfma_entry(lambda: tfx.tfx_batch_matmul(a, b, False, True, out=c), 2 * 8 * 1024 ** 3, 3 * 8 * 1024 * 1024 * 4)
+        return mfma_entry(lambda: tfx.tfx_batch_matmul(a, b, False, True, out=c), 2 * 8 * 1024 ** 3, 3 * 8 * 1024 * 1024 * 4,
+                          "batch_matmul_8x1024x1024x1024_tB")
 
     def op_pointwise(n):
         def build():
@@ -114,7 +141,8 @@ def main():
             xx, ff, bb = dev(d["x"]), dev(d["filter"]), dev(d["bias"])
             yy = tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6)
             return mfma_entry(lambda: tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6, out=yy),
-                              2 * n * 56 * 56 * 128 * 128, 4 * (xx.numel() + yy.numel() + 128 * 128 + 128))
+                              2 * n * 56 * 56 * 128 * 128, 4 * (xx.numel() + yy.numel() + 128 * 128 + 128),
+                              "pointwise_%dx56x56x128_to_128" % n)
         return build
 
     def op_depthwise(n, s, copies):
@@ -135,13 +163,33 @@ def main():
             t = time_loop(fn, max(reps, copies * 2), warmup=copies, inner=copies if copies > 1 else None)
             e = {"us": round(t * 1e6, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
                  "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
-                              "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
+                              "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5),
+                              "traffic": measured_traffic("depthwise_%dx112x112x64_s%d_%s" % (
+                                  n, s, "cold_rotation" if copies > 1 else "warm"))}}
             if copies == 1:
                 e["single_launch_us"] = round(time_single(fn) * 1e6, 2)
             return e
         return build
 
+    def op_copy():
+        """Plain device-to-device copy of 205.5 MB (a framework elementwise kernel, not part of the library):
+        the known-size reference that the HBM traffic counters are scaled by."""
+        src = torch.empty(64 * 112 * 112 * 64, device="cuda:0").uniform_(-1, 1)
+        dsts = [torch.empty_like(src) for _ in range(2)]
+        state = {"i": 0}
+
+        def fn():
+            i = state["i"] = (state["i"] + 1) % 2
+            dsts[i].copy_(src)
+        t = time_loop(fn, reps, inner=4)
+        nbytes = 2 * src.numel() * 4
+        return {"us": round(t * 1e6, 3), "GBps": round(nbytes / t / 1e9, 1), "bytes_read": src.numel() * 4,
+                "bytes_written": src.numel() * 4,
+                "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
+                             "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
+
     single_ops = {"matmul_64x128x64": op_matmul, "batch_matmul_8x1024x1024x1024_tB": op_batch_matmul}
+    calibration_ops = {"copy_calibration_205MB": op_copy}
     for n in (1, 8, 64):
         single_ops["pointwise_%dx56x56x128_to_128" % n] = op_pointwise(n)
     for s in (1, 2):
@@ -150,10 +198,11 @@ def main():
         single_ops["depthwise_8x112x112x64_s%d_warm" % s] = op_depthwise(8, s, 1)
         single_ops["depthwise_64x112x112x64_s%d_cold_rotation" % s] = op_depthwise(64, s, 3)
     if args.op is not None:
-        if args.op not in single_ops:
-            print("\n".join(single_ops))
+        every = {**single_ops, **calibration_ops}
+        if args.op not in every:
+            print("\n".join(every))
             sys.exit(0 if args.op == "list" else 2)
-        print(json.dumps({"op": args.op, **single_ops[args.op]()}))
+        print(json.dumps({"op": args.op, **every[args.op]()}))
         return
 
     # ---------------- the timed steps: MobileNet-v1 b1 ----------------
@@ -247,7 +296,7 @@ def main():
         out["roofline"] = {
             "kernel": "gemm_mfma_kernel (13 pointwise layers of one inference)", "bound": "mfma",
             "achieved": round(pw_flop / pw_s / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
-            "frac": round(pw_flop / pw_s / PEAK_MFMA_F32, 5), "traffic": None,
+            "frac": round(pw_flop / pw_s / PEAK_MFMA_F32, 5), "traffic": (lambda tb: None if tb is None else round(tb / 13))(measured_traffic("mobilenet_b1_gemm_13_launches")),
             "launches_per_step": 13, "avg_launch_us": round(pw_s * 1e6 / 13, 3)}
         out["mobilenet_layers"] = {
             "sum_layer_us": round(sum(l["us"] for l in layers), 2),
@@ -256,6 +305,17 @@ def main():
             "per_layer_us": {l["layer"]: round(l["us"], 2) for l in layers}}
 
         out["ops"] = {name: build() for name, build in single_ops.items()}
+
+        # ---------------- whole network at larger batches (same weights; throughput, not latency) ----------
+        batched = {}
+        for nb in (8, 64):
+            mb = tfx.MobileNetV1(data["weights"], batch=nb)
+            imgs = torch.empty((nb, 224, 224, 3), device="cuda:0").uniform_(-1, 1)
+            t = time_loop(lambda: mb.forward(imgs), max(20, reps // 4), warmup=3, inner=5)
+            batched["batch_%d" % nb] = {"ms_per_batch": round(t * 1e3, 4), "images_per_s": round(nb / t, 1),
+                                        "TFLOPs": round(nb * 1.137480704e9 / t / 1e12, 3)}
+            del mb, imgs
+        out["mobilenet_batched"] = batched
 
     # ---------------- CPU oracle on the host cores (baseline only) ----------------
     if not args.no_cpu_baseline:
