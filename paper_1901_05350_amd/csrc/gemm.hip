@@ -4,8 +4,9 @@
 // TensorFlow.js paper defines the op: one dot product per output value) and the 1x1
 // "pointwise" conv2d, which is the same contraction with M = N*H*W, K = inC, N = outC.
 // The paper's shader computes one output per fragment with no data sharing; here a
-// workgroup computes a BM x BN tile, stages A and B k-slices through LDS and feeds
-// v_mfma_f32_32x32x2_f32 (64-wide wavefronts, 32x32 accumulator tile per instruction).
+// workgroup computes a tile, stages A and B k-slices through LDS and feeds the matrix cores
+// (64-wide wavefronts): v_mfma_f32_32x32x2_f32 in the tiled kernel for medium and large
+// problems, v_mfma_f32_16x16x4_f32 in the 16-row kernel for small M x N.
 //
 // Layout of one MFMA 32x32x2 (wave64), used below:
 //   A operand: lane l holds A[i = l % 32][k = l / 32]
@@ -114,36 +115,31 @@ __device__ __forceinline__ float f4_get(const float4& v, int s) {
   return s == 0 ? v.x : (s == 1 ? v.y : (s == 2 ? v.z : v.w));
 }
 
-// WAVES_K > 1 splits each BK-deep tile over that many wavefronts (each takes BK / WAVES_K of the
-// depth) and adds the partial accumulators through LDS at the end: for small M x N problems this
-// puts 4x more bytes in flight per workgroup and shortens the serial K loop 4x.
-// STAGES = 2 double-buffers the LDS tiles (one barrier per k-slice); STAGES = 1 keeps a single, deeper
-// tile (BK up to 512) so that a small problem's whole K panel is in flight in one round trip.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int STAGES, bool A_KC, bool B_KC, bool VEC>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_kernel(
+// Tiled kernel for medium and large problems: BM x BN tile, BK-deep k-slices double-buffered in LDS
+// (one barrier per slice), WAVES_M x WAVES_N wavefronts each owning a (BM/WAVES_M) x (BN/WAVES_N) sub-tile.
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, const float* __restrict__ bias,
     int M, int N, int K, int tiles_m, int tiles_n, int total_blocks, long long strideA, long long strideB,
-    long long strideC, int act) {
-  constexpr int NT = 64 * WAVES_M * WAVES_N * WAVES_K;
+    long long strideC, int act, int m_fastest) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int GROUPS = BK / 8 / WAVES_K;  // k-groups of 8 per wavefront per tile
-  static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % (8 * WAVES_K) == 0, "tile shape");
+  constexpr int GROUPS = BK / 8;  // k-groups of 8 per tile
+  static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 8 == 0, "tile shape");
   using TA = Tile<BM, BK, A_KC>;
   using TB = Tile<BN, BK, B_KC>;
   static_assert(TA::kSlots % NT == 0 && TB::kSlots % NT == 0, "loader shape");
   constexpr int SA = TA::kSlots / NT, SB = TB::kSlots / NT;
-  static_assert(WAVES_K == 1 || (WAVES_K - 1) * WAVES_M * WAVES_N * TM * TN * 1024 <= STAGES * (TA::kFloats + TB::kFloats),
-                "split-K reduction reuses the tile buffers");
-  // a 1 x 1 wave tile has a single accumulator chain: split it in two to halve the MFMA dependency latency
-  constexpr int NACC = (TM * TN == 1 && GROUPS >= 1) ? 2 : 1;
 
   extern __shared__ __align__(16) float smem[];
-  float* const lds_a = smem;                    // STAGES A buffers, then STAGES B buffers
-  float* const lds_b = smem + STAGES * TA::kFloats;
+  float* const lds_a = smem;                    // two A buffers, then two B buffers
+  float* const lds_b = smem + 2 * TA::kFloats;
 
   // XCD-aware block order: hardware block id x lands on XCD x % 8.  Give each XCD a contiguous
   // range of logical tiles (same batch, neighbouring tiles) so that its L2 sees each A / B panel once.
+  // Within a batch, consecutive tiles walk along M when B is the larger operand (every XCD then owns
+  // a column slice of B and only the smaller A is fetched by several L2s), along N otherwise.
   const int bid = blockIdx.x;
   const int q = total_blocks / kXcds, rem = total_blocks % kXcds;
   const int xcd = bid % kXcds;
@@ -151,7 +147,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
   const int tiles = tiles_m * tiles_n;
   const int batch = vid / tiles;
   const int t = vid % tiles;
-  const int tile_m = t / tiles_n, tile_n = t % tiles_n;
+  const int tile_m = m_fastest ? t % tiles_m : t / tiles_n;
+  const int tile_n = m_fastest ? t / tiles_m : t % tiles_n;
 
   const int lda = A_KC ? K : M;
   const int ldb = B_KC ? K : N;
@@ -161,20 +158,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
 
   const int tid = threadIdx.x;
   const int wave = tid / 64, lane = tid % 64;
-  const int wk = wave / (WAVES_M * WAVES_N), wmn = wave % (WAVES_M * WAVES_N);
-  const int wm0 = (wmn / WAVES_N) * WM, wn0 = (wmn % WAVES_N) * WN;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
   const int li = lane % 32, h = lane / 32;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  floatx16 acc[NACC][TM][TN];
+  floatx16 acc[TM][TN];
 #pragma unroll
-  for (int c = 0; c < NACC; ++c)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[c][i][j][v] = 0.f;
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // bias for this lane's output columns, fetched now so that its latency hides under the main loop
   float bv[TN];
@@ -193,8 +187,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
-    const int cur = STAGES == 2 ? (kt & 1) : 0;
-    const int nxt = STAGES == 2 ? (cur ^ 1) : 0;
+    const int cur = kt & 1, nxt = cur ^ 1;
     if (kt + 1 < nk) {
       load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, (kt + 1) * BK, tid, ra);
       load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, (kt + 1) * BK, tid, rb);
@@ -205,13 +198,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
     __builtin_amdgcn_s_setprio(1);  // MFMA phase: do not let the co-resident workgroup's wave cut in
     float4 fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<BM, BK, A_KC>(la, wm0 + 32 * i + li, wk * GROUPS, h);
+    for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<BM, BK, A_KC>(la, wm0 + 32 * i + li, 0, h);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BN, BK, B_KC>(lb, wn0 + 32 * j + li, wk * GROUPS, h);
+    for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BN, BK, B_KC>(lb, wn0 + 32 * j + li, 0, h);
 #pragma unroll
     for (int gg = 0; gg < GROUPS; ++gg) {
-      const int g = wk * GROUPS + gg;
-      if (STAGES == 1 && kt * BK + 8 * g >= K) break;  // deep single tile: skip k-groups past the end of K
+      const int g = gg;
       if (gg + 1 < GROUPS) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) fa[(gg + 1) & 1][i] = read_frag<BM, BK, A_KC>(la, wm0 + 32 * i + li, g + 1, h);
@@ -225,52 +217,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[s % NACC][i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f4_get(fa[gg & 1][i], s), f4_get(fb[gg & 1][j], s),
-                                                                        acc[s % NACC][i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f4_get(fa[gg & 1][i], s), f4_get(fb[gg & 1][j], s), acc[i][j],
+                                                             0, 0, 0);
     }
     __builtin_amdgcn_s_setprio(0);
     if (kt + 1 < nk) {
-      if (STAGES == 1) __syncthreads();  // everyone has finished reading the only tile
       store_tile<BM, BK, A_KC, NT, SA>(lds_a + nxt * TA::kFloats, tid, ra);
       store_tile<BN, BK, B_KC, NT, SB>(lds_b + nxt * TB::kFloats, tid, rb);
     }
     __syncthreads();
   }
-  if (NACC == 2) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[0][i][j][v] += acc[NACC - 1][i][j][v];
-  }
-
-  if (WAVES_K > 1) {
-    // all tile reads are done (barrier above): reuse LDS to add the k-waves' partial tiles.
-    // layout [wk-1][wmn][i][j][v][lane]: a register's 64 lanes are contiguous, so no bank conflicts
-    if (wk > 0) {
-      float* dst = smem + (size_t)((wk - 1) * WAVES_M * WAVES_N + wmn) * TM * TN * 1024;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) dst[((i * TN + j) * 16 + v) * 64 + lane] = acc[0][i][j][v];
-    }
-    __syncthreads();
-    if (wk > 0) return;
-#pragma unroll
-    for (int w = 1; w < WAVES_K; ++w) {
-      const float* src = smem + (size_t)((w - 1) * WAVES_M * WAVES_N + wmn) * TM * TN * 1024;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[0][i][j][v] += src[((i * TN + j) * 16 + v) * 64 + lane];
-    }
-  }
-
   const ActClamp clamp = make_act(act);
   // Epilogue: bias[col] then activation, one dword per lane per register (two 128-byte rows per store).
 #pragma unroll
@@ -282,20 +238,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) void gemm_mfma_ke
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
-        if (row < M) C[(size_t)row * N + col] = apply_act(acc[0][i][j][v] + bv[j], clamp);
+        if (row < M) C[(size_t)row * N + col] = apply_act(acc[i][j][v] + bv[j], clamp);
       }
     }
   }
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int STAGES, bool A_KC, bool B_KC, bool VEC>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC>
 int launch_cfg(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k, int act,
                hipStream_t stream) {
   using TA = Tile<BM, BK, A_KC>;
   using TB = Tile<BN, BK, B_KC>;
-  constexpr size_t lds_bytes = STAGES * (TA::kFloats + TB::kFloats) * sizeof(float);
+  constexpr size_t lds_bytes = 2 * (TA::kFloats + TB::kFloats) * sizeof(float);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
-  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, STAGES, A_KC, B_KC, VEC>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, A_KC, B_KC, VEC>;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -306,18 +262,191 @@ int launch_cfg(const float* a, const float* b, float* c, const float* bias, int 
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
   const long long total = (long long)batch * tiles_m * tiles_n;
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(64 * WAVES_M * WAVES_N * WAVES_K), lds_bytes, stream, a, b, c,
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, a, b, c,
                      bias, m, n, k, tiles_m, tiles_n, (int)total, (long long)m * k, (long long)n * k, (long long)m * n,
-                     act);
+                     act, n > m ? 1 : 0);
   return check_launch();
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int STAGES>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N>
 int launch_layout(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k,
                   bool a_kc, bool b_kc, bool vec, int act, hipStream_t stream) {
 #define TFX_GEMM_CASE(AK, BKC, V)                                                                              \
   if (a_kc == AK && b_kc == BKC && vec == V)                                                                   \
-    return launch_cfg<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, STAGES, AK, BKC, V>(a, b, c, bias, batch, m, n, k, act, stream);
+    return launch_cfg<BM, BN, BK, WAVES_M, WAVES_N, AK, BKC, V>(a, b, c, bias, batch, m, n, k, act, stream);
+  TFX_GEMM_CASE(true, true, true)
+  TFX_GEMM_CASE(true, false, true)
+  TFX_GEMM_CASE(false, true, true)
+  TFX_GEMM_CASE(false, false, true)
+  TFX_GEMM_CASE(true, true, false)
+  TFX_GEMM_CASE(true, false, false)
+  TFX_GEMM_CASE(false, true, false)
+  TFX_GEMM_CASE(false, false, false)
+#undef TFX_GEMM_CASE
+  return TFX_ERR_ARG;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Small-M variant: 16 x (16*TN) output tile with v_mfma_f32_16x16x4_f32.
+// MobileNet's 14x14 and 7x7 pointwise layers have M = 196 or 49: with 32 x 32 tiles only 64-112
+// workgroups exist and each needs >= 1.7 us of matrix-core time on its CU.  A 16-row tile doubles or
+// quadruples the number of workgroups (and wastes fewer padded rows: 208 instead of 224 for M = 196).
+// One BK-deep tile (single LDS stage) is split over WAVES_K wavefronts; the partial tiles are added
+// through LDS by 256*TN threads, which also apply the epilogue.
+// Layout of one MFMA 16x16x4 (wave64): A: lane l holds A[i = l % 16][k = l / 16]; B: lane l holds
+// B[k = l / 16][j = l % 16]; D: register v of lane l holds D[i = 4 * (l / 16) + v][j = l % 16].
+// Within a group of 16 consecutive k, lane quarter q = l / 16 takes k = 16g + 4q + s in step s.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <int ROWS, int BK, bool KC>
+__device__ __forceinline__ float4 read_frag16(const float* __restrict__ lds, int row, int g, int q) {
+  using T = Tile<ROWS, BK, KC>;
+  if (KC) {
+    return *reinterpret_cast<const float4*>(lds + row * T::kStride + 16 * g + 4 * q);
+  } else {
+    const float* p = lds + (16 * g + 4 * q) * T::kStride + row;
+    return make_float4(p[0], p[T::kStride], p[2 * T::kStride], p[3 * T::kStride]);
+  }
+}
+
+template <int TN, int BK, int WAVES_K, bool A_KC, bool B_KC, bool VEC>
+__global__ __launch_bounds__(64 * WAVES_K) void gemm_m16_kernel(
+    const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, const float* __restrict__ bias,
+    int M, int N, int K, int tiles_m, int tiles_n, int total_blocks, long long strideA, long long strideB,
+    long long strideC, int act, int m_fastest) {
+  constexpr int BM = 16, BN = 16 * TN;
+  constexpr int NT = 64 * WAVES_K;
+  constexpr int GROUPS = BK / 16 / WAVES_K;  // k-groups of 16 per wavefront per tile
+  constexpr int NACC = 4 / TN;                // accumulator chains per column tile (4 chains in all)
+  static_assert(BK % (16 * WAVES_K) == 0 && (TN == 1 || TN == 2), "tile shape");
+  using TA = Tile<BM, BK, A_KC>;
+  using TB = Tile<BN, BK, B_KC>;
+  static_assert(TA::kSlots % NT == 0 && TB::kSlots % NT == 0, "loader shape");
+  constexpr int SA = TA::kSlots / NT, SB = TB::kSlots / NT;
+  static_assert(WAVES_K * 256 * TN <= TA::kFloats + TB::kFloats, "split-K reduction reuses the tile buffers");
+  static_assert(256 * TN <= NT, "epilogue threads");
+
+  extern __shared__ __align__(16) float smem[];
+  float* const lds_a = smem;
+  float* const lds_b = smem + TA::kFloats;
+
+  const int bid = blockIdx.x;
+  const int q8 = total_blocks / kXcds, rem = total_blocks % kXcds;
+  const int xcd = bid % kXcds;
+  const int vid = xcd * q8 + (xcd < rem ? xcd : rem) + bid / kXcds;
+  const int tiles = tiles_m * tiles_n;
+  const int batch = vid / tiles;
+  const int t = vid % tiles;
+  const int tile_m = m_fastest ? t % tiles_m : t / tiles_n;
+  const int tile_n = m_fastest ? t / tiles_m : t % tiles_n;
+
+  const int lda = A_KC ? K : M;
+  const int ldb = B_KC ? K : N;
+  A += (size_t)batch * strideA;
+  B += (size_t)batch * strideB;
+  C += (size_t)batch * strideC;
+
+  const int tid = threadIdx.x;
+  const int wk = tid / 64, lane = tid % 64;
+  const int li = lane % 16, q = lane / 16;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // epilogue thread e < 256*TN owns output element (row, col) = the value of register v of lane l of
+  // column tile j with e = (j*4 + v)*64 + l; fetch its bias now
+  const int ej = tid / 256, ev = (tid / 64) % 4, el = tid % 64;
+  const int erow = m0 + 4 * (el / 16) + ev, ecol = n0 + 16 * ej + el % 16;
+  float ebias = 0.f;
+  if (tid < 256 * TN && bias != nullptr && ecol < N) ebias = bias[ecol];
+
+  floatx4 acc[NACC][TN];
+#pragma unroll
+  for (int c = 0; c < NACC; ++c)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[c][j][v] = 0.f;
+
+  float4 ra[SA], rb[SB];
+  const int nk = (K + BK - 1) / BK;
+  load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, 0, tid, ra);
+  load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, 0, tid, rb);
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt > 0) __syncthreads();  // everyone has finished reading the previous tile
+    store_tile<BM, BK, A_KC, NT, SA>(lds_a, tid, ra);
+    store_tile<BN, BK, B_KC, NT, SB>(lds_b, tid, rb);
+    __syncthreads();
+    if (kt + 1 < nk) {
+      load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, (kt + 1) * BK, tid, ra);
+      load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, (kt + 1) * BK, tid, rb);
+    }
+#pragma unroll
+    for (int gg = 0; gg < GROUPS; ++gg) {
+      const int g = wk * GROUPS + gg;
+      if (kt * BK + 16 * g >= K) break;  // k-groups past the end of K hold zeros
+      const float4 fa = read_frag16<BM, BK, A_KC>(lds_a, li, g, q);
+      float4 fb[TN];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = read_frag16<BN, BK, B_KC>(lds_b, 16 * j + li, g, q);
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[s % NACC][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(f4_get(fa, s), f4_get(fb[j], s), acc[s % NACC][j], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int c = 1; c < NACC; ++c)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[0][j][v] += acc[c][j][v];
+
+  // add the WAVES_K partial tiles through LDS: layout [wk][j][v][lane]
+  __syncthreads();
+  float* red = smem;
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[(wk * TN * 4 + j * 4 + v) * 64 + lane] = acc[0][j][v];
+  __syncthreads();
+  if (tid < 256 * TN) {
+    float sum = ebias;
+#pragma unroll
+    for (int w = 0; w < WAVES_K; ++w) sum += red[w * TN * 256 + tid];
+    if (erow < M && ecol < N) C[(size_t)erow * N + ecol] = apply_act(sum, make_act(act));
+  }
+}
+
+template <int TN, int BK, int WAVES_K, bool A_KC, bool B_KC, bool VEC>
+int launch_m16_cfg(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k, int act,
+                   hipStream_t stream) {
+  using TA = Tile<16, BK, A_KC>;
+  using TB = Tile<16 * TN, BK, B_KC>;
+  constexpr size_t lds_bytes = (TA::kFloats + TB::kFloats) * sizeof(float);
+  static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
+  auto kern = gemm_m16_kernel<TN, BK, WAVES_K, A_KC, B_KC, VEC>;
+  static bool attr_set = false;
+  if (!attr_set && lds_bytes > 64 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_bytes) != hipSuccess)
+      return TFX_ERR_LAUNCH;
+    attr_set = true;
+  }
+  const int tiles_m = (m + 15) / 16, tiles_n = (n + 16 * TN - 1) / (16 * TN);
+  const long long total = (long long)batch * tiles_m * tiles_n;
+  if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(64 * WAVES_K), lds_bytes, stream, a, b, c, bias, m, n, k,
+                     tiles_m, tiles_n, (int)total, (long long)m * k, (long long)n * k, (long long)m * n, act,
+                     n > m ? 1 : 0);
+  return check_launch();
+}
+
+template <int TN, int BK, int WAVES_K>
+int launch_m16_layout(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k,
+                      bool a_kc, bool b_kc, bool vec, int act, hipStream_t stream) {
+#define TFX_GEMM_CASE(AK, BKC, V)                                                                  \
+  if (a_kc == AK && b_kc == BKC && vec == V)                                                       \
+    return launch_m16_cfg<TN, BK, WAVES_K, AK, BKC, V>(a, b, c, bias, batch, m, n, k, act, stream);
   TFX_GEMM_CASE(true, true, true)
   TFX_GEMM_CASE(true, false, true)
   TFX_GEMM_CASE(false, true, true)
@@ -339,18 +468,27 @@ int launch_gemm(const float* a, const float* b, float* c, const float* bias, int
   const int a_inner = a_kc ? k : m, b_inner = b_kc ? k : n;
   const bool vec = (reinterpret_cast<uintptr_t>(a) % 16 == 0) && (reinterpret_cast<uintptr_t>(b) % 16 == 0) &&
                    (a_inner % 4 == 0) && (b_inner % 4 == 0);
-  // Tile choice.  Large problems: 128 x 128 tiles (best reuse).  Medium: 64 x 64.  Small M x N
-  // (too few 64 x 64 tiles for the 256 CUs): 32 x 32 tiles with the depth split over four
-  // wavefronts, which is bound by memory latency per K step rather than by arithmetic.
+  // Tile choice.  Large problems: 128 x 128 tiles (best reuse).  Medium: 64 x 64.
   const long long blocks128 = (long long)batch * ((m + 127) / 128) * ((n + 127) / 128);
   const long long blocks64 = (long long)batch * ((m + 63) / 64) * ((n + 63) / 64);
   if (blocks128 >= 256)
-    return launch_layout<128, 128, 32, 2, 2, 1, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+    return launch_layout<128, 128, 32, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
   if (blocks64 >= 192 || k <= 32)
-    return launch_layout<64, 64, 32, 2, 2, 1, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
-  if (k <= 128) return launch_layout<32, 32, 128, 1, 1, 4, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
-  // deeper K: one 512-deep tile split over 8 wavefronts, the whole panel in flight at once
-  return launch_layout<32, 32, 512, 1, 1, 8, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+    return launch_layout<64, 64, 32, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  // Small M x N (too few 64 x 64 tiles for the 256 CUs): 16-row tiles, 16 x 32 or, when even those are
+  // few, 16 x 16, so that every CU gets a workgroup; the tile depth covers K in one step when K <= 512.
+  // These problems are bound by memory latency and by the matrix-core time of a single tile, not by
+  // throughput (measured on the MobileNet 28x28 .. 7x7 pointwise layers: 3.8-6.1 us each).
+  const long long blocks16x32 = (long long)batch * ((m + 15) / 16) * ((n + 31) / 32);
+  const bool wide = blocks16x32 >= 160;
+  if (k <= 128)
+    return wide ? launch_m16_layout<2, 128, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream)
+                : launch_m16_layout<1, 128, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  if (k <= 256)
+    return wide ? launch_m16_layout<2, 256, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream)
+                : launch_m16_layout<1, 256, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+  return wide ? launch_m16_layout<2, 512, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream)
+              : launch_m16_layout<1, 512, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
 }
 
 }  // namespace tfx
