@@ -145,6 +145,16 @@ def main():
                               "pointwise_%dx56x56x128_to_128" % n)
         return build
 
+    def op_conv3x3(n):
+        """3x3 conv2d 56x56x64 -> 64, stride 1, SAME, bias + ReLU6 (implicit GEMM on the matrix cores)."""
+        def build():
+            d = inputs.conv_general(5, n, 56, 56, 64, 64, 3, 3)
+            xx, ff, bb = dev(d["x"]), dev(d["filter"]), dev(d["bias"])
+            yy = tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6)
+            return mfma_entry(lambda: tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6, out=yy),
+                              2 * n * 56 * 56 * 64 * 64 * 9, 4 * (xx.numel() + yy.numel() + 9 * 64 * 64 + 64))
+        return build
+
     def op_depthwise(n, s, copies):
         """copies > 1: rotate over distinct tensors whose total size exceeds the 256 MB last-level cache."""
         def build():
@@ -192,6 +202,7 @@ def main():
     calibration_ops = {"copy_calibration_205MB": op_copy}
     for n in (1, 8, 64):
         single_ops["pointwise_%dx56x56x128_to_128" % n] = op_pointwise(n)
+        single_ops["conv3x3_%dx56x56x64_to_64" % n] = op_conv3x3(n)
     for s in (1, 2):
         single_ops["depthwise_1x112x112x64_s%d_warm" % s] = op_depthwise(1, s, 1)
         single_ops["depthwise_1x112x112x64_s%d_cold_rotation" % s] = op_depthwise(1, s, 96)

@@ -204,6 +204,10 @@ int tfx_conv2d(const float* x, const int64_t x_shape[4], const float* filter, co
   if (conv2d_stem_supported(ci, fh, fw, co, stride_h, stride_w) && aligned)
     return launch_conv2d_stem(x, filter, bias, y, n, h, w, co, oh, ow, stride_h, stride_w, (int)g.pad[0], (int)g.pad[2],
                               (int)act, s);
+  // enough input channels and filters to fill matrix-core tiles: implicit GEMM; else one thread per output
+  if (ci >= 8 && co >= 8)
+    return launch_conv2d_gemm(x, filter, bias, y, n, h, w, ci, fh, fw, co, oh, ow, stride_h, stride_w, (int)g.pad[0],
+                              (int)g.pad[2], (int)act, s);
   return launch_conv2d_direct(x, filter, bias, y, n, h, w, ci, fh, fw, co, oh, ow, stride_h, stride_w, (int)g.pad[0],
                               (int)g.pad[2], (int)act, s);
 }

@@ -99,6 +99,75 @@ __device__ __forceinline__ void store_tile(float* __restrict__ lds, int tid, con
   }
 }
 
+// Implicit-GEMM view of a convolution input (NHWC): GEMM row = output pixel (n, oh, ow), GEMM
+// column k = (kh, kw, c) with c fastest, so A[row][k] = x[n, oh*sh - pt + kh, ow*sw - pl + kw, c]
+// (zero outside the image) and B = the HWIO filter seen as [fh*fw*Ci, Co].
+struct ConvA {
+  const float* x;
+  int H, W, Ci, OH, OW, fw, sh, sw, pt, pl;
+};
+
+// What a thread needs to know about the output pixel of one of its A-tile slots.
+struct ConvRow {
+  int ih0, iw0;      // input coordinates of filter tap (0, 0)
+  long long base;    // element offset of image n, or -1 if the row is past M
+};
+
+template <int BM, int BK, int NT, int NSLOT>
+__device__ __forceinline__ void conv_rows(const ConvA& cv, int M, int m0, int tid, ConvRow (&rows)[NSLOT]) {
+#pragma unroll
+  for (int it = 0; it < NSLOT; ++it) {
+    const int r = m0 + (tid + it * NT) / (BK / 4);
+    const int ow = r % cv.OW;
+    const int t = r / cv.OW;
+    const int oh = t % cv.OH;
+    const int n = t / cv.OH;
+    rows[it].ih0 = oh * cv.sh - cv.pt;
+    rows[it].iw0 = ow * cv.sw - cv.pl;
+    rows[it].base = r < M ? (long long)n * cv.H * cv.W * cv.Ci : -1;
+  }
+}
+
+// A-tile loader of the implicit GEMM.  All slots of a thread share the same k offset (NT is a
+// multiple of BK/4), so (kh, kw, c) is decoded once per thread per k-slice.  With VEC, Ci % 4 == 0
+// and a float4 never crosses a filter tap; otherwise each of the 4 elements is decoded on its own.
+template <int BM, int BK, bool VEC, int NT, int NSLOT>
+__device__ __forceinline__ void load_tile_conv(const ConvA& cv, int K, int k0, int tid, const ConvRow (&rows)[NSLOT],
+                                               float4 (&reg)[NSLOT]) {
+  static_assert(NT % (BK / 4) == 0, "k offset must be the same for all slots of a thread");
+  const int gk = k0 + 4 * (tid % (BK / 4));
+  int kh[4], kw[4], c[4];
+#pragma unroll
+  for (int e = 0; e < (VEC ? 1 : 4); ++e) {
+    const int k = gk + e;
+    c[e] = k % cv.Ci;
+    const int t = k / cv.Ci;
+    kw[e] = t % cv.fw;
+    kh[e] = t / cv.fw;
+  }
+#pragma unroll
+  for (int it = 0; it < NSLOT; ++it) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (rows[it].base >= 0) {
+      if (VEC) {
+        const int ih = rows[it].ih0 + kh[0], iw = rows[it].iw0 + kw[0];
+        if (gk < K && ih >= 0 && ih < cv.H && iw >= 0 && iw < cv.W)
+          v = *reinterpret_cast<const float4*>(cv.x + rows[it].base + ((long long)ih * cv.W + iw) * cv.Ci + c[0]);
+      } else {
+        float e4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int ih = rows[it].ih0 + kh[e], iw = rows[it].iw0 + kw[e];
+          if (gk + e < K && ih >= 0 && ih < cv.H && iw >= 0 && iw < cv.W)
+            e4[e] = cv.x[rows[it].base + ((long long)ih * cv.W + iw) * cv.Ci + c[e]];
+        }
+        v = make_float4(e4[0], e4[1], e4[2], e4[3]);
+      }
+    }
+    reg[it] = v;
+  }
+}
+
 // MFMA operand of one 32-row sub-tile for k-group g: four steps' values for this lane.
 template <int ROWS, int BK, bool KC>
 __device__ __forceinline__ float4 read_frag(const float* __restrict__ lds, int row, int g, int h) {
@@ -117,11 +186,13 @@ __device__ __forceinline__ float f4_get(const float4& v, int s) {
 
 // Tiled kernel for medium and large problems: BM x BN tile, BK-deep k-slices double-buffered in LDS
 // (one barrier per slice), WAVES_M x WAVES_N wavefronts each owning a (BM/WAVES_M) x (BN/WAVES_N) sub-tile.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC>
+// CONV: the A operand is the implicit im2col view `cv` of a convolution input instead of a matrix.
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC, bool CONV>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, const float* __restrict__ bias,
     int M, int N, int K, int tiles_m, int tiles_n, int total_blocks, long long strideA, long long strideB,
-    long long strideC, int act, int m_fastest) {
+    long long strideC, int act, int m_fastest, ConvA cv) {
+  static_assert(!CONV || A_KC, "the im2col view is K-contiguous");
   constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -180,7 +251,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
 
   float4 ra[SA], rb[SB];
   const int nk = (K + BK - 1) / BK;
-  load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, 0, tid, ra);
+  ConvRow crow[CONV ? SA : 1];
+  if constexpr (CONV) conv_rows<BM, BK, NT, SA>(cv, M, m0, tid, crow);
+  auto load_a = [&](int k0) {
+    if constexpr (CONV) load_tile_conv<BM, BK, VEC, NT, SA>(cv, K, k0, tid, crow, ra);
+    else load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, k0, tid, ra);
+  };
+  load_a(0);
   load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, 0, tid, rb);
   store_tile<BM, BK, A_KC, NT, SA>(lds_a, tid, ra);
   store_tile<BN, BK, B_KC, NT, SB>(lds_b, tid, rb);
@@ -189,7 +266,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1, nxt = cur ^ 1;
     if (kt + 1 < nk) {
-      load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, (kt + 1) * BK, tid, ra);
+      load_a((kt + 1) * BK);
       load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, (kt + 1) * BK, tid, rb);
     }
     const float* la = lds_a + cur * TA::kFloats;
@@ -244,14 +321,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
   }
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC, bool CONV = false>
 int launch_cfg(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k, int act,
-               hipStream_t stream) {
+               hipStream_t stream, const ConvA& cv = ConvA{}) {
   using TA = Tile<BM, BK, A_KC>;
   using TB = Tile<BN, BK, B_KC>;
   constexpr size_t lds_bytes = 2 * (TA::kFloats + TB::kFloats) * sizeof(float);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
-  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, A_KC, B_KC, VEC>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, A_KC, B_KC, VEC, CONV>;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -264,7 +341,7 @@ int launch_cfg(const float* a, const float* b, float* c, const float* bias, int 
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, a, b, c,
                      bias, m, n, k, tiles_m, tiles_n, (int)total, (long long)m * k, (long long)n * k, (long long)m * n,
-                     act, n > m ? 1 : 0);
+                     act, n > m ? 1 : 0, cv);
   return check_launch();
 }
 
@@ -459,6 +536,19 @@ int launch_m16_layout(const float* a, const float* b, float* c, const float* bia
   return TFX_ERR_ARG;
 }
 
+// Fraction of a tiling's multiply-adds that land inside the m x n output (the rest is padding).
+double tile_efficiency(long long m, long long n, int bm, int bn) {
+  const long long tm = (m + bm - 1) / bm, tn = (n + bn - 1) / bn;
+  return (double)m * (double)n / ((double)tm * bm * (double)tn * bn);
+}
+
+// 128 x 128 tiles when there is one per CU and they are not mostly padding (e.g. n = 64 would
+// waste half of every tile); else 64 x 64.
+bool prefer_128(int batch, long long m, long long n) {
+  const long long blocks128 = (long long)batch * ((m + 127) / 128) * ((n + 127) / 128);
+  return blocks128 >= 256 && tile_efficiency(m, n, 128, 128) >= 0.8 * tile_efficiency(m, n, 64, 64);
+}
+
 }  // namespace
 
 int launch_gemm(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k, bool a_kc,
@@ -469,9 +559,8 @@ int launch_gemm(const float* a, const float* b, float* c, const float* bias, int
   const bool vec = (reinterpret_cast<uintptr_t>(a) % 16 == 0) && (reinterpret_cast<uintptr_t>(b) % 16 == 0) &&
                    (a_inner % 4 == 0) && (b_inner % 4 == 0);
   // Tile choice.  Large problems: 128 x 128 tiles (best reuse).  Medium: 64 x 64.
-  const long long blocks128 = (long long)batch * ((m + 127) / 128) * ((n + 127) / 128);
   const long long blocks64 = (long long)batch * ((m + 63) / 64) * ((n + 63) / 64);
-  if (blocks128 >= 256)
+  if (prefer_128(batch, m, n))
     return launch_layout<128, 128, 32, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
   if (blocks64 >= 192 || k <= 32)
     return launch_layout<64, 64, 32, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
@@ -489,6 +578,21 @@ int launch_gemm(const float* a, const float* b, float* c, const float* bias, int
                 : launch_m16_layout<1, 256, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
   return wide ? launch_m16_layout<2, 512, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream)
               : launch_m16_layout<1, 512, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
+}
+
+int launch_conv2d_gemm(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int ci, int fh,
+                       int fw, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream) {
+  const long long m = (long long)n * oh * ow, k = (long long)fh * fw * ci;
+  if (m > 0x7fffffffLL || k > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
+  const ConvA cv{x, h, wd, ci, oh, ow, fw, sh, sw, pt, pl};
+  const bool vec = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 &&
+                   ci % 4 == 0 && co % 4 == 0;
+  if (prefer_128(1, m, co)) {
+    return vec ? launch_cfg<128, 128, 32, 2, 2, true, false, true, true>(nullptr, w, y, bias, 1, (int)m, co, (int)k, act, stream, cv)
+               : launch_cfg<128, 128, 32, 2, 2, true, false, false, true>(nullptr, w, y, bias, 1, (int)m, co, (int)k, act, stream, cv);
+  }
+  return vec ? launch_cfg<64, 64, 32, 2, 2, true, false, true, true>(nullptr, w, y, bias, 1, (int)m, co, (int)k, act, stream, cv)
+             : launch_cfg<64, 64, 32, 2, 2, true, false, false, true>(nullptr, w, y, bias, 1, (int)m, co, (int)k, act, stream, cv);
 }
 
 }  // namespace tfx

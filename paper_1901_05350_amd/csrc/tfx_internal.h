@@ -38,6 +38,10 @@ int out_extent(int64_t in, int64_t k, int64_t s, int pad, int64_t* out, int64_t*
 int launch_gemm(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k,
                 bool a_kc, bool b_kc, int act, hipStream_t stream);
 
+// conv2d as an implicit GEMM on the matrix cores: M = n*oh*ow, K = fh*fw*ci, N = co (any filter / stride).
+int launch_conv2d_gemm(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int ci, int fh,
+                       int fw, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream);
+
 // Filter-stationary pointwise conv for thin filters (K*N*4 <= 128 KB) and large M.
 bool pointwise_stream_supported(int m, int k, int n, const void* x, const void* w, const void* y);
 int launch_pointwise_stream(const float* x, const float* w, const float* bias, float* y, int m, int k, int n, int act,

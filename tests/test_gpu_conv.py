@@ -117,6 +117,33 @@ def test_general_conv_sweep():
         assert_close(got, ref, "conv %r" % ((h, w, fh, fw, s, pad, ci, co),))
 
 
+def test_conv_implicit_gemm_sweep():
+    # enough channels for the matrix-core path: filters 3x3 / 5x2 / 1x1-strided, strides 1-3, both paddings,
+    # channel counts that are and are not multiples of 4 (vector and scalar loaders), ragged M and N
+    r = rng(35)
+    for (n, h, w), (fh, fw), s, pad, (ci, co) in itertools.product(
+            [(1, 14, 15), (2, 9, 7), (1, 33, 31)], [(3, 3), (5, 2), (1, 1)], [1, 2, 3], [PAD_SAME, PAD_VALID],
+            [(8, 8), (16, 40), (9, 10), (64, 72), (12, 130)]):
+        if fh == 1 and s == 1:
+            continue
+        x = r.uniform(-1, 1, (n, h, w, ci)).astype(np.float32)
+        f = (r.standard_normal((fh, fw, ci, co)) * np.sqrt(2.0 / (fh * fw * ci))).astype(np.float32)
+        b = (r.standard_normal((co,)) * 0.5).astype(np.float32)
+        st = (s, 1 + (s % 2))
+        got = gpu_conv(x, f, b, st, pad, ACT_RELU6)
+        assert_close(got, oracle.conv2d(x, f, b, st, pad, ACT_RELU6), "implicit gemm %r" % ((n, h, w, fh, fw, s, pad, ci, co),))
+
+
+def test_conv_3x3_large_batches_sampled_images():
+    # 3x3 convolutions at the sizes the benchmark times (128 x 128 tiles); the oracle checks whole images
+    for (n, hw, ci, co, s) in [(8, 56, 64, 64, 1), (8, 56, 64, 128, 2), (4, 28, 128, 256, 1)]:
+        d = inputs.conv_general(36, n, hw, hw, ci, co, 3, 3)
+        got = gpu_conv(d["x"], d["filter"], d["bias"], s, PAD_SAME, ACT_RELU6)
+        for img in (0, n - 1):
+            ref = oracle.conv2d(d["x"][img:img + 1], d["filter"], d["bias"], s, PAD_SAME, ACT_RELU6)
+            assert_close(got[img:img + 1], ref, "conv3x3 %r image %d" % ((n, hw, ci, co, s), img))
+
+
 def test_general_conv_3x3_many_channels():
     d = inputs.conv_general(34, 1, 14, 14, 64, 48, 3, 3)
     got = gpu_conv(d["x"], d["filter"], d["bias"], 1, PAD_SAME, ACT_RELU)
