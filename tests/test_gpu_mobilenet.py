@@ -70,3 +70,28 @@ def test_workspace_checks(net):
     with pytest.raises(tfx.TfxError) as e:
         tfx.tfx_mobilenet_v1_forward(dev(data["image"]), model.struct, small, model.probs, None)
     assert e.value.status == -5
+
+
+def test_forward_captured_in_a_graph_replays_identically(net):
+    # the library only enqueues kernels (no allocation, no memset, no host sync), so a forward pass can be
+    # captured into a HIP graph; every replay, with eager work in between, must give the eager bits
+    import torch
+    import paper_1901_05350_amd as tfx
+    data, probs, logits, acts = net
+    model = tfx.MobileNetV1(data["weights"], batch=1)
+    image = dev(data["image"])
+    p_eager = host(model.forward(image)[0]).copy()
+    l_eager = host(model.logits).copy()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        model.forward(image)
+    other = dev(np.random.Generator(np.random.PCG64(99)).uniform(-1, 1, (1, 224, 224, 3)))
+    for _ in range(3):
+        model.probs.zero_()
+        model.logits.zero_()
+        # eager work on the same workspace between replays: a different image overwrites every buffer
+        model2_out = host(model.forward(other)[0]).copy()
+        assert not np.array_equal(model2_out, p_eager)
+        g.replay()
+        assert np.array_equal(host(model.probs), p_eager)
+        assert np.array_equal(host(model.logits), l_eager)
