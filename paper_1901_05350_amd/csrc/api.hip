@@ -196,7 +196,7 @@ int tfx_conv2d(const float* x, const int64_t x_shape[4], const float* filter, co
   const int oh = (int)g.out[1], ow = (int)g.out[2];
   if (fh == 1 && fw == 1 && stride_h == 1 && stride_w == 1) {
     // pointwise convolution = [N*H*W, Ci] x [Ci, Co] with the epilogue fused into the GEMM
-    if (pointwise_stream_supported(n * h * w, ci, co, x, filter, y))
+    if (pointwise_stream_supported(n * h * w, ci, co, x, filter, bias, y))
       return launch_pointwise_stream(x, filter, bias, y, n * h * w, ci, co, (int)act, s);
     return launch_gemm(x, filter, y, bias, 1, n * h * w, co, ci, true, false, (int)act, s);
   }

@@ -127,10 +127,10 @@ int launch_stream16(const float* x, const float* w, const float* bias, float* y,
 
 }  // namespace
 
-bool pointwise_stream_supported(int m, int k, int n, const void* x, const void* w, const void* y) {
+bool pointwise_stream_supported(int m, int k, int n, const void* x, const void* w, const void* bias, const void* y) {
   const bool shape = (k == 32 && n == 64) || (k == 64 && n == 128) || (k == 128 && n == 128) || (k == 128 && n == 256);
   const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 &&
-                       reinterpret_cast<uintptr_t>(y) % 16 == 0;
+                       reinterpret_cast<uintptr_t>(y) % 16 == 0 && reinterpret_cast<uintptr_t>(bias) % 16 == 0;  // a null bias passes
   // worthwhile once every one of the 256 CUs gets a full workgroup of 8 slabs (measured: below that the tiled GEMM wins)
   return shape && aligned && m >= 16384;
 }

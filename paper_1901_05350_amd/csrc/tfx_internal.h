@@ -43,7 +43,7 @@ int launch_conv2d_gemm(const float* x, const float* w, const float* bias, float*
                        int fw, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream);
 
 // Filter-stationary pointwise conv for thin filters (K*N*4 <= 128 KB) and large M.
-bool pointwise_stream_supported(int m, int k, int n, const void* x, const void* w, const void* y);
+bool pointwise_stream_supported(int m, int k, int n, const void* x, const void* w, const void* bias, const void* y);
 int launch_pointwise_stream(const float* x, const float* w, const float* bias, float* y, int m, int k, int n, int act,
                             hipStream_t stream);
 

@@ -234,3 +234,38 @@ def test_epilogue_activation_table_and_tiny_bias():
     zd = np.zeros((3, 3, 8, 1), np.float32)
     for act in (ACT_NONE, ACT_RELU, ACT_RELU6):
         assert np.array_equal(gpu_dw(xd, zd, vals, 1, PAD_SAME, act), oracle.depthwise_conv2d(xd, zd, vals, 1, PAD_SAME, act))
+
+
+def test_unaligned_buffers_take_the_scalar_paths():
+    # tensors that start 4 bytes past a 16-byte boundary: the 128-bit-load kernels must not be chosen
+    import torch
+    import paper_1901_05350_amd as tfx
+
+    def shifted(a):
+        buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda:0")
+        v = buf[1:].view(*a.shape)
+        v.copy_(torch.from_numpy(a))
+        assert v.data_ptr() % 16 != 0
+        return v
+
+    r = rng(45)
+    x = r.uniform(-1, 1, (1, 12, 12, 32)).astype(np.float32)
+    f = r.standard_normal((1, 1, 32, 64)).astype(np.float32)
+    fd = r.standard_normal((3, 3, 32, 1)).astype(np.float32)
+    f3 = r.standard_normal((3, 3, 32, 16)).astype(np.float32)
+    b = r.standard_normal((64,)).astype(np.float32)
+    bd = r.standard_normal((32,)).astype(np.float32)
+    b3 = r.standard_normal((16,)).astype(np.float32)
+    got = host(tfx.tfx_conv2d(shifted(x), shifted(f), shifted(b), 1, PAD_SAME, ACT_RELU6))
+    assert_close(got, oracle.conv2d(x, f, b, 1, PAD_SAME, ACT_RELU6), "pointwise, unaligned operands")
+    got = host(tfx.tfx_depthwise_conv2d(shifted(x), shifted(fd), shifted(bd), 2, PAD_SAME, ACT_RELU6))
+    assert_close(got, oracle.depthwise_conv2d(x, fd, bd, 2, PAD_SAME, ACT_RELU6), "depthwise, unaligned operands")
+    got = host(tfx.tfx_conv2d(shifted(x), shifted(f3), shifted(b3), 1, PAD_SAME, ACT_RELU))
+    assert_close(got, oracle.conv2d(x, f3, b3, 1, PAD_SAME, ACT_RELU), "conv 3x3, unaligned operands")
+    out = torch.empty(12 * 12 * 64 + 1, dtype=torch.float32, device="cuda:0")[1:].view(1, 12, 12, 64)
+    tfx.tfx_conv2d(dev(x), dev(f), dev(b), 1, PAD_SAME, ACT_RELU6, out=out)
+    assert_close(host(out), oracle.conv2d(x, f, b, 1, PAD_SAME, ACT_RELU6), "pointwise, unaligned output")
+    # large M with the thin filter but a bias that is not 16-byte aligned: not the filter-stationary kernel
+    xl = r.uniform(-1, 1, (2, 100, 100, 32)).astype(np.float32)
+    got = host(tfx.tfx_conv2d(dev(xl), dev(f), shifted(b), 1, PAD_SAME, ACT_RELU6))
+    assert_close(got, oracle.conv2d(xl, f, b, 1, PAD_SAME, ACT_RELU6), "pointwise large M, unaligned bias")
