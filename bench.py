@@ -5,9 +5,10 @@ A step is one MobileNet-v1 1.0/224 batch-1 inference (stem conv, 13 x (depthwise
 pool, fully connected, softmax) through tfx_mobilenet_v1_forward, with weights and the image
 already resident in HBM: the quantity Table 1 of the TensorFlow.js paper reports (Section 3.9),
 on seeded random weights of the same shapes.  After the timed steps the same process times each
-layer and the four single-op workloads (small matMul, 1x1 pointwise conv, 3x3 depthwise conv at
-stride 1 and 2, the 8 x 1024^3 batchMatMul) against the fp32-MFMA or HBM roofline, and the CPU
-oracle on the host cores as a baseline.
+layer, the single-op workloads (small matMul, the 8 x 1024^3 batchMatMul, 1x1 pointwise conv and
+3x3 conv2d at batch 1 / 8 / 64, 3x3 depthwise conv at stride 1 and 2 with warm and cold caches)
+against the fp32-MFMA or HBM roofline, the whole network at batch 8 and 64, and the CPU oracle on
+the host cores as a baseline.
 
 Prints one JSON line.
 """
@@ -27,11 +28,12 @@ PEAK_HBM = 8.0e12          # B/s
 # reading for a plain 205.5 MB copy (profiles/hbm_traffic_counters.txt).  Each entry names the kernel
 # source it was measured on; if that file has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100828040, "gemm.hip", "bd9d72bdc7fc7ac4441967d3215face435df2155d2939db7d864f48d5b7131a8"),
-    "pointwise_64x56x56x128_to_128": (206927237, "pointwise.hip", "31c35501a1061560f51e46d756c1ba310b2efa0206b8a160a10caa508c48889a"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411117364, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (256968885, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
-    "mobilenet_b1_gemm_13_launches": (80891691, "gemm.hip", "bd9d72bdc7fc7ac4441967d3215face435df2155d2939db7d864f48d5b7131a8"),
+    "batch_matmul_8x1024x1024x1024_tB": (100836033, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
+    "pointwise_64x56x56x128_to_128": (207545056, "pointwise.hip", "50947f4fbda77ef9c2f55bb75007539b43300bcfb9c65a85012606b202e1827a"),
+    "conv3x3_64x56x56x64_to_64": (104646719, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411117558, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (256974838, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
+    "mobilenet_b1_gemm_13_launches": (53651531, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
 }
 
 
@@ -57,7 +59,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-layer and single-op measurements")
     ap.add_argument("--op", default=None, help="time only this single-op workload (for profiling), e.g. "
-                                               "batch_matmul, pointwise_n64, depthwise_s1_n64_cold; 'list' prints the names")
+                                               "batch_matmul_8x1024x1024x1024_tB; 'list' prints the names")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
@@ -152,7 +154,8 @@ def main():
             xx, ff, bb = dev(d["x"]), dev(d["filter"]), dev(d["bias"])
             yy = tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6)
             return mfma_entry(lambda: tfx.tfx_conv2d(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6, out=yy),
-                              2 * n * 56 * 56 * 64 * 64 * 9, 4 * (xx.numel() + yy.numel() + 9 * 64 * 64 + 64))
+                              2 * n * 56 * 56 * 64 * 64 * 9, 4 * (xx.numel() + yy.numel() + 9 * 64 * 64 + 64),
+                              "conv3x3_%dx56x56x64_to_64" % n)
         return build
 
     def op_depthwise(n, s, copies):
@@ -305,7 +308,7 @@ def main():
         pw_flop, pw_s = sum(l["flop"] for l in pw), sum(l["us"] for l in pw) * 1e-6
         dw_bytes, dw_s = sum(l["bytes"] for l in dw), sum(l["us"] for l in dw) * 1e-6
         out["roofline"] = {
-            "kernel": "gemm_mfma_kernel (13 pointwise layers of one inference)", "bound": "mfma",
+            "kernel": "gemm_mfma_kernel / gemm_m16_kernel (the 13 pointwise layers of one inference)", "bound": "mfma",
             "achieved": round(pw_flop / pw_s / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
             "frac": round(pw_flop / pw_s / PEAK_MFMA_F32, 5), "traffic": (lambda tb: None if tb is None else round(tb / 13))(measured_traffic("mobilenet_b1_gemm_13_launches")),
             "launches_per_step": 13, "avg_launch_us": round(pw_s * 1e6 / 13, 3)}
