@@ -331,6 +331,17 @@ def main():
             del mb, imgs
         out["mobilenet_batched"] = batched
 
+        # ---------------- other members of the family (width alpha = q/4, input size), batch 1 ----------
+        family = {}
+        for q, size in ((1, 128), (2, 160), (3, 192)):
+            dv = inputs.mobilenet_v1(seed=4, batch=1, image_size=size, width_quarters=q)
+            mv = tfx.MobileNetV1(dv["weights"], batch=1, image_size=size, width_quarters=q)
+            img = dev(dv["image"])
+            t = time_loop(lambda: mv.forward(img), reps, warmup=3, inner=10)
+            family["%.2f_%d" % (q / 4, size)] = {"ms_per_inference": round(t * 1e3, 5)}
+            del mv, img
+        out["mobilenet_family_b1"] = family
+
     # ---------------- CPU oracle on the host cores (baseline only) ----------------
     if not args.no_cpu_baseline:
         import oracle

@@ -149,6 +149,32 @@ int tfx_mobilenet_v1_forward(const float* input, int64_t batch, const tfx_mobile
                              void* workspace, size_t workspace_bytes, float* probs, float* logits,
                              void* stream);
 
+/* The other members of the MobileNet v1 family (Section 3.9 times the "1.0"
+ * member at 224 x 224): same 28 layers, every channel count scaled by
+ * alpha = width_quarters / 4 and a square input of image_size pixels.
+ *   image_size:     32 ... 256 (the published members use 128, 160, 192, 224)
+ *   width_quarters: 1, 2, 3 or 4 (alpha 0.25, 0.5, 0.75, 1.0)
+ *   classes:        1 ... 1024 outputs of the fully connected layer
+ * Channel counts are alpha * the counts listed above (stem 32 alpha, fully
+ * connected input 1024 alpha); the weight struct is the same, with its arrays
+ * sized accordingly.  {224, 4, 1000} is tfx_mobilenet_v1_forward. */
+typedef struct {
+  int64_t image_size;
+  int64_t width_quarters;
+  int64_t classes;
+} tfx_mobilenet_v1_variant;
+
+/* Workspace bytes for `batch` images of a variant; 0 if the variant or batch is
+ * invalid.  Host-only. */
+size_t tfx_mobilenet_v1_variant_workspace_bytes(const tfx_mobilenet_v1_variant* variant, int64_t batch);
+
+/* As tfx_mobilenet_v1_forward for a variant: input device
+ * [batch,image_size,image_size,3], probs (and logits, if not NULL) device
+ * [batch,classes].  TFX_ERR_ARG for a variant outside the ranges above. */
+int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
+                                     const tfx_mobilenet_v1_weights* weights, void* workspace,
+                                     size_t workspace_bytes, float* probs, float* logits, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

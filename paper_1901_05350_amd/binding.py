@@ -19,6 +19,11 @@ class TfxWeights(ctypes.Structure):
                 ("fc_w", _VP), ("fc_b", _VP)]
 
 
+class TfxVariant(ctypes.Structure):
+    """Mirror of tfx_mobilenet_v1_variant."""
+    _fields_ = [("image_size", ctypes.c_int64), ("width_quarters", ctypes.c_int64), ("classes", ctypes.c_int64)]
+
+
 class TfxError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -45,6 +50,10 @@ _SIGNATURES = {
     "tfx_mobilenet_v1_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64]),
     "tfx_mobilenet_v1_forward": (ctypes.c_int, [_VP, ctypes.c_int64, ctypes.POINTER(TfxWeights), _VP,
                                                 ctypes.c_size_t, _VP, _VP, _VP]),
+    "tfx_mobilenet_v1_variant_workspace_bytes": (ctypes.c_size_t, [ctypes.POINTER(TfxVariant), ctypes.c_int64]),
+    "tfx_mobilenet_v1_variant_forward": (ctypes.c_int, [ctypes.POINTER(TfxVariant), _VP, ctypes.c_int64,
+                                                        ctypes.POINTER(TfxWeights), _VP, ctypes.c_size_t, _VP, _VP,
+                                                        _VP]),
 }
 
 
@@ -172,10 +181,18 @@ def tfx_mobilenet_v1_workspace_bytes(batch):
     return int(lib().tfx_mobilenet_v1_workspace_bytes(int(batch)))
 
 
-class MobileNetV1:
-    """Device-resident MobileNet-v1 weights plus a workspace; calls tfx_mobilenet_v1_forward."""
+def tfx_mobilenet_v1_variant_workspace_bytes(variant, batch):
+    return int(lib().tfx_mobilenet_v1_variant_workspace_bytes(ctypes.byref(variant), int(batch)))
 
-    def __init__(self, weights, batch=1, device="cuda:0"):
+
+class MobileNetV1:
+    """Device-resident MobileNet-v1 weights plus a workspace.
+
+    With the defaults (224 pixels, width 4/4, 1000 classes) forward() calls tfx_mobilenet_v1_forward;
+    any other member of the family goes through tfx_mobilenet_v1_variant_forward.
+    """
+
+    def __init__(self, weights, batch=1, device="cuda:0", image_size=224, width_quarters=4):
         import torch
         self.device = torch.device(device)
         self.batch = int(batch)
@@ -188,17 +205,27 @@ class MobileNetV1:
             arr = getattr(self.struct, k)
             for i in range(13):
                 arr[i] = self.tensors[k][i].data_ptr()
-        nbytes = tfx_mobilenet_v1_workspace_bytes(self.batch)
+        classes = int(self.tensors["fc_w"].shape[1])
+        self.variant = TfxVariant(int(image_size), int(width_quarters), classes)
+        self.is_base = (self.variant.image_size, self.variant.width_quarters, classes) == (224, 4, 1000)
+        nbytes = (tfx_mobilenet_v1_workspace_bytes(self.batch) if self.is_base
+                  else tfx_mobilenet_v1_variant_workspace_bytes(self.variant, self.batch))
+        if nbytes == 0:
+            raise ValueError("unsupported MobileNet-v1 variant or batch")
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        self.probs = torch.empty((self.batch, 1000), dtype=torch.float32, device=self.device)
-        self.logits = torch.empty((self.batch, 1000), dtype=torch.float32, device=self.device)
+        self.probs = torch.empty((self.batch, classes), dtype=torch.float32, device=self.device)
+        self.logits = torch.empty((self.batch, classes), dtype=torch.float32, device=self.device)
 
     def forward(self, image):
         """Enqueue one forward pass on the current stream; returns (probs, logits) device tensors."""
         _dev(image, "image")
-        if tuple(image.shape) != (self.batch, 224, 224, 3):
-            raise TypeError("image must be [%d,224,224,3]" % self.batch)
-        tfx_mobilenet_v1_forward(image, self.struct, self.workspace, self.probs, self.logits)
+        size = int(self.variant.image_size)
+        if tuple(image.shape) != (self.batch, size, size, 3):
+            raise TypeError("image must be [%d,%d,%d,3]" % (self.batch, size, size))
+        if self.is_base:
+            tfx_mobilenet_v1_forward(image, self.struct, self.workspace, self.probs, self.logits)
+        else:
+            tfx_mobilenet_v1_variant_forward(self.variant, image, self.struct, self.workspace, self.probs, self.logits)
         return self.probs, self.logits
 
 
@@ -208,4 +235,14 @@ def tfx_mobilenet_v1_forward(image, weights_struct, workspace, probs, logits=Non
                                           workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                           probs.data_ptr(), None if logits is None else logits.data_ptr(),
                                           _stream(image)), "tfx_mobilenet_v1_forward")
+    return probs
+
+
+def tfx_mobilenet_v1_variant_forward(variant, image, weights_struct, workspace, probs, logits=None):
+    _dev(image, "image"), _dev(probs, "probs")
+    _check(lib().tfx_mobilenet_v1_variant_forward(ctypes.byref(variant), image.data_ptr(), int(image.shape[0]),
+                                                  ctypes.byref(weights_struct), workspace.data_ptr(),
+                                                  workspace.numel() * workspace.element_size(), probs.data_ptr(),
+                                                  None if logits is None else logits.data_ptr(), _stream(image)),
+           "tfx_mobilenet_v1_variant_forward")
     return probs

@@ -96,20 +96,28 @@ struct NetPlan {
   size_t off_buf[2], off_partial, bytes;
 };
 
-NetPlan plan_net(int64_t batch) {
+bool valid_variant(const tfx_mobilenet_v1_variant* v) {
+  return v && v->image_size >= 32 && v->image_size <= 256 && v->width_quarters >= 1 && v->width_quarters <= 4 &&
+         v->classes >= 1 && v->classes <= 1024;
+}
+
+NetPlan plan_net(const tfx_mobilenet_v1_variant& v, int64_t batch) {
   NetPlan p{};
-  // largest feature map: the 112 x 112 x 64 output of the first pointwise layer
-  p.act_floats = (size_t)batch * 112 * 112 * 64;
+  // largest feature map: the output of the first pointwise layer (half the image size, 64 alpha channels)
+  const size_t half = (size_t)(v.image_size + 1) / 2;
+  p.act_floats = (size_t)batch * half * half * (size_t)(kChannels[0] * v.width_quarters / 4);
   size_t off = 0;
   for (int i = 0; i < 2; ++i) {
     p.off_buf[i] = off;
     off = align_up(off + p.act_floats * sizeof(float));
   }
   p.off_partial = off;  // K-slice partial sums of the fully connected layer
-  off = align_up(off + fc_partial_floats((int)batch, kFeatures, kClasses) * sizeof(float));
+  off = align_up(off + fc_partial_floats((int)batch, (int)(kFeatures * v.width_quarters / 4), (int)v.classes) * sizeof(float));
   p.bytes = off;
   return p;
 }
+
+constexpr tfx_mobilenet_v1_variant kBaseVariant = {kImage, 4, kClasses};
 
 }  // namespace
 }  // namespace tfx
@@ -228,27 +236,41 @@ int tfx_depthwise_conv2d(const float* x, const int64_t x_shape[4], const float* 
 
 size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch) {
   if (batch < 1 || batch > 1024) return 0;
-  return plan_net(batch).bytes;
+  return plan_net(kBaseVariant, batch).bytes;
 }
 
 int tfx_mobilenet_v1_forward(const float* input, int64_t batch, const tfx_mobilenet_v1_weights* weights,
                              void* workspace, size_t workspace_bytes, float* probs, float* logits, void* stream) {
-  if (!input || !weights || !workspace || !probs) return TFX_ERR_NULL;
+  return tfx_mobilenet_v1_variant_forward(&kBaseVariant, input, batch, weights, workspace, workspace_bytes, probs,
+                                          logits, stream);
+}
+
+size_t tfx_mobilenet_v1_variant_workspace_bytes(const tfx_mobilenet_v1_variant* variant, int64_t batch) {
+  if (!valid_variant(variant) || batch < 1 || batch > 1024) return 0;
+  return plan_net(*variant, batch).bytes;
+}
+
+int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
+                                     const tfx_mobilenet_v1_weights* weights, void* workspace,
+                                     size_t workspace_bytes, float* probs, float* logits, void* stream) {
+  if (!variant || !input || !weights || !workspace || !probs) return TFX_ERR_NULL;
   if (!weights->conv0_w || !weights->conv0_b || !weights->fc_w || !weights->fc_b) return TFX_ERR_NULL;
   for (int i = 0; i < kBlocks; ++i)
     if (!weights->dw_w[i] || !weights->dw_b[i] || !weights->pw_w[i] || !weights->pw_b[i]) return TFX_ERR_NULL;
+  if (!valid_variant(variant)) return TFX_ERR_ARG;
   if (batch < 1) return TFX_ERR_SHAPE;
   if (batch > 1024) return TFX_ERR_UNSUPPORTED;
-  const NetPlan plan = plan_net(batch);
+  const NetPlan plan = plan_net(*variant, batch);
   if (workspace_bytes < plan.bytes || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TFX_ERR_WORKSPACE;
+  const int q = (int)variant->width_quarters;
 
   char* ws = static_cast<char*>(workspace);
   float* buf[2] = {reinterpret_cast<float*>(ws + plan.off_buf[0]), reinterpret_cast<float*>(ws + plan.off_buf[1])};
   float* partial = reinterpret_cast<float*>(ws + plan.off_partial);
 
-  // stem: 3x3 stride-2 convolution to 32 channels, then the 13 depthwise-separable blocks
-  int64_t shape[4] = {batch, kImage, kImage, 3};
-  const int64_t f0[4] = {3, 3, 3, kStemChannels};
+  // stem: 3x3 stride-2 convolution to 32 alpha channels, then the 13 depthwise-separable blocks
+  int64_t shape[4] = {batch, variant->image_size, variant->image_size, 3};
+  const int64_t f0[4] = {3, 3, 3, kStemChannels * q / 4};
   int rc = tfx_conv2d(input, shape, weights->conv0_w, f0, weights->conv0_b, 2, 2, TFX_PAD_SAME, TFX_ACT_RELU6, buf[0],
                       stream);
   if (rc) return rc;
@@ -264,16 +286,17 @@ int tfx_mobilenet_v1_forward(const float* input, int64_t batch, const tfx_mobile
     conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
     for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
     cur ^= 1;
-    const int64_t fp[4] = {1, 1, shape[3], kChannels[b]};
+    const int64_t cout = kChannels[b] * q / 4;
+    const int64_t fp[4] = {1, 1, shape[3], cout};
     rc = tfx_conv2d(buf[cur], shape, weights->pw_w[b], fp, weights->pw_b[b], 1, 1, TFX_PAD_SAME, TFX_ACT_RELU6,
                     buf[cur ^ 1], stream);
     if (rc) return rc;
-    shape[3] = kChannels[b];
+    shape[3] = cout;
     cur ^= 1;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   return launch_pool_fc_softmax(buf[cur], weights->fc_w, weights->fc_b, partial, logits, probs, (int)batch,
-                                (int)(shape[1] * shape[2]), kFeatures, kClasses, s);
+                                (int)(shape[1] * shape[2]), (int)shape[3], (int)variant->classes, s);
 }
 
 }  // extern "C"

@@ -142,17 +142,25 @@ int launch_conv2d_direct(const float* x, const float* w, const float* bias, floa
 bool conv2d_stem_supported(int ci, int fh, int fw, int co, int sh, int sw) {
   (void)sh;
   (void)sw;
-  return ci == 3 && fh == 3 && fw == 3 && co == 32;
+  return ci == 3 && fh == 3 && fw == 3 && (co == 8 || co == 16 || co == 24 || co == 32);
 }
 
 int launch_conv2d_stem(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int co,
                        int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream) {
-  if (co != 32) return TFX_ERR_UNSUPPORTED;
   const long long total = (long long)n * oh * ow * (co / 8);
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
   const unsigned blocks = (unsigned)((total + 255) / 256);
-  hipLaunchKernelGGL(conv2d_stem_kernel<32>, dim3(blocks), dim3(256), 0, stream, x, w, bias, y, n, h, wd, oh, ow, sh,
-                     sw, pt, pl, act, (int)total);
+#define TFX_STEM(CO)                                                                                              \
+  hipLaunchKernelGGL(conv2d_stem_kernel<CO>, dim3(blocks), dim3(256), 0, stream, x, w, bias, y, n, h, wd, oh, ow, \
+                     sh, sw, pt, pl, act, (int)total)
+  switch (co) {
+    case 8: TFX_STEM(8); break;
+    case 16: TFX_STEM(16); break;
+    case 24: TFX_STEM(24); break;
+    case 32: TFX_STEM(32); break;
+    default: return TFX_ERR_UNSUPPORTED;
+  }
+#undef TFX_STEM
   return check_launch();
 }
 

@@ -78,25 +78,28 @@ def conv_general(seed, n, h, w, cin, cout, fh, fw):
     return {"x": x, "filter": f, "bias": b}
 
 
-def mobilenet_v1_weights(rng):
-    """Random MobileNet-v1 1.0 weights (batch norm folded into the biases)."""
+def mobilenet_v1_weights(rng, width_quarters=4, classes=1000):
+    """Random MobileNet-v1 weights (batch norm folded into the biases); every channel count of the
+    1.0 network is scaled by width_quarters / 4."""
+    q = int(width_quarters)
     w = {"dw_w": [], "dw_b": [], "pw_w": [], "pw_b": []}
-    w["conv0_w"] = he_normal(rng, (3, 3, 3, 32), 27)
-    w["conv0_b"] = normal(rng, (32,), BIAS_STD)
-    cin = 32
-    for cout in MOBILENET_V1_CHANNELS:
+    cin = 32 * q // 4
+    w["conv0_w"] = he_normal(rng, (3, 3, 3, cin), 27)
+    w["conv0_b"] = normal(rng, (cin,), BIAS_STD)
+    for base in MOBILENET_V1_CHANNELS:
+        cout = base * q // 4
         w["dw_w"].append(he_normal(rng, (3, 3, cin, 1), 9))
         w["dw_b"].append(normal(rng, (cin,), BIAS_STD))
         w["pw_w"].append(he_normal(rng, (1, 1, cin, cout), cin))
         w["pw_b"].append(normal(rng, (cout,), BIAS_STD))
         cin = cout
-    w["fc_w"] = he_normal(rng, (1024, 1000), 1024)
-    w["fc_b"] = normal(rng, (1000,), BIAS_STD)
+    w["fc_w"] = he_normal(rng, (cin, classes), cin)
+    w["fc_b"] = normal(rng, (classes,), BIAS_STD)
     return w
 
 
-def mobilenet_v1(seed=4, batch=1):
-    """Image [batch,224,224,3] uniform[-1,1) and random MobileNet-v1 1.0 weights."""
+def mobilenet_v1(seed=4, batch=1, image_size=224, width_quarters=4, classes=1000):
+    """Image [batch,size,size,3] uniform[-1,1) and random MobileNet-v1 weights (1.0 / 224 by default)."""
     rng = _rng(seed)
-    image = uniform(rng, (batch, 224, 224, 3))
-    return {"image": image, "weights": mobilenet_v1_weights(rng)}
+    image = uniform(rng, (batch, image_size, image_size, 3))
+    return {"image": image, "weights": mobilenet_v1_weights(rng, width_quarters, classes)}

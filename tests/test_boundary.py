@@ -123,6 +123,33 @@ def test_mobilenet_entry_point_validation():
     assert L.tfx_mobilenet_v1_forward(FAKE, 1, ctypes.byref(w), FAKE, one, FAKE, None, None) == -1
 
 
+def test_mobilenet_variant_validation():
+    L = tfx.lib()
+    V = binding.TfxVariant
+    base = tfx.tfx_mobilenet_v1_workspace_bytes(1)
+    assert tfx.tfx_mobilenet_v1_variant_workspace_bytes(V(224, 4, 1000), 1) == base
+    small = tfx.tfx_mobilenet_v1_variant_workspace_bytes(V(128, 1, 10), 1)
+    assert 2 * 64 * 64 * 16 * 4 <= small < base and small % 256 == 0
+    for bad in (V(16, 4, 1000), V(257, 4, 1000), V(224, 0, 1000), V(224, 5, 1000), V(224, 4, 0), V(224, 4, 1025)):
+        assert tfx.tfx_mobilenet_v1_variant_workspace_bytes(bad, 1) == 0
+    assert tfx.tfx_mobilenet_v1_variant_workspace_bytes(V(224, 4, 1000), 0) == 0
+    w = binding.TfxWeights()
+    for name in ("conv0_w", "conv0_b", "fc_w", "fc_b"):
+        setattr(w, name, 0x1000)
+    for name in ("dw_w", "dw_b", "pw_w", "pw_b"):
+        arr = getattr(w, name)
+        for i in range(13):
+            arr[i] = 0x1000
+    ok = V(160, 2, 100)
+    nbytes = tfx.tfx_mobilenet_v1_variant_workspace_bytes(ok, 1)
+    fwd = L.tfx_mobilenet_v1_variant_forward
+    assert fwd(None, FAKE, 1, ctypes.byref(w), FAKE, nbytes, FAKE, None, None) == -1
+    assert fwd(ctypes.byref(V(224, 7, 1000)), FAKE, 1, ctypes.byref(w), FAKE, base, FAKE, None, None) == -3
+    assert fwd(ctypes.byref(V(8, 4, 1000)), FAKE, 1, ctypes.byref(w), FAKE, base, FAKE, None, None) == -3
+    assert fwd(ctypes.byref(ok), FAKE, 0, ctypes.byref(w), FAKE, nbytes, FAKE, None, None) == -2
+    assert fwd(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes - 1, FAKE, None, None) == -5
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):

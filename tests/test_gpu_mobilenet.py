@@ -61,6 +61,35 @@ def test_end_to_end_batch_3():
     assert_close(host(p), probs, "probs batch 3")
 
 
+@pytest.mark.parametrize("size,q,classes,batch", [(128, 1, 10, 2), (160, 2, 1000, 1), (192, 3, 1000, 1), (224, 4, 37, 1),
+                                                  (100, 2, 5, 3), (256, 1, 1024, 1)])
+def test_family_variants_end_to_end(size, q, classes, batch):
+    """Width / resolution members of the family (and odd sizes) through tfx_mobilenet_v1_variant_forward."""
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1(seed=20 + q, batch=batch, image_size=size, width_quarters=q, classes=classes)
+    probs, logits = oracle.mobilenet_v1_forward(data["image"], data["weights"])
+    model = tfx.MobileNetV1(data["weights"], batch=batch, image_size=size, width_quarters=q)
+    assert not model.is_base
+    p, l = model.forward(dev(data["image"]))
+    p, l = host(p), host(l)
+    assert p.shape == (batch, classes)
+    assert_close(l, logits, "logits %d/%d" % (q, size))
+    assert_close(p, probs, "probs %d/%d" % (q, size))
+    np.testing.assert_allclose(p.astype(np.float64).sum(axis=1), 1.0, atol=1e-5)
+
+
+def test_base_variant_is_the_plain_entry_point(net):
+    import torch
+    import paper_1901_05350_amd as tfx
+    data, probs, logits, acts = net
+    model = tfx.MobileNetV1(data["weights"], batch=1)
+    p, _ = model.forward(dev(data["image"]))
+    p = host(p).copy()
+    out = torch.empty((1, 1000), dtype=torch.float32, device="cuda:0")
+    tfx.tfx_mobilenet_v1_variant_forward(tfx.TfxVariant(224, 4, 1000), dev(data["image"]), model.struct, model.workspace, out)
+    assert np.array_equal(host(out), p)
+
+
 def test_workspace_checks(net):
     import torch
     import paper_1901_05350_amd as tfx

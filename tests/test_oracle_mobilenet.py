@@ -49,6 +49,42 @@ def test_layer_walk_totals_match_the_published_network_size():
     assert inputs.MOBILENET_V1_STRIDES == oracle.MOBILENET_V1_STRIDES
 
 
+def test_family_members_match_their_published_sizes():
+    """Width / resolution variants: the layer walk over the generator's weights and the oracle's
+    shape rule lands on the published multiply-add and parameter counts (to their printed rounding)."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "mobilenet_v1_family_sizes.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 7
+    for q, size, mmacs, mparams in rows:
+        q, size = int(q), int(size)
+        w = inputs.mobilenet_v1_weights(np.random.default_rng(0), q, 1000)
+        params = sum(int(np.size(v)) if not isinstance(v, list) else sum(int(np.size(t)) for t in v) for v in w.values())
+        shape, _ = oracle.conv2d_out_shape((1, size, size, 3), w["conv0_w"].shape, 2, oracle.PAD_SAME)
+        macs = math.prod(shape) * 27
+        for i, s in enumerate(oracle.MOBILENET_V1_STRIDES):
+            shape, _ = oracle.depthwise_conv2d_out_shape(shape, w["dw_w"][i].shape, s, oracle.PAD_SAME)
+            macs += math.prod(shape) * 9
+            cin = shape[3]
+            shape, _ = oracle.conv2d_out_shape(shape, w["pw_w"][i].shape, 1, oracle.PAD_SAME)
+            macs += math.prod(shape) * cin
+        macs += int(np.size(w["fc_w"]))
+        assert shape[3] == 256 * q and w["fc_w"].shape == (256 * q, 1000)
+        assert abs(macs / 1e6 - float(mmacs)) <= 1.0, (q, size, macs)
+        assert abs(params / 1e6 - float(mparams)) <= 0.06, (q, size, params)
+
+
+def test_variant_forward_small_member():
+    """The oracle's chain runs the 0.25 / 128 member and returns a probability vector over its classes."""
+    d = inputs.mobilenet_v1(seed=11, batch=2, image_size=128, width_quarters=1, classes=10)
+    probs, logits, acts = oracle.mobilenet_v1_forward(d["image"], d["weights"], return_activations=True)
+    assert probs.shape == (2, 10) and logits.shape == (2, 10)
+    assert acts[0].shape == (2, 64, 64, 8) and acts[-2].shape == (2, 4, 4, 256)
+    np.testing.assert_allclose(probs.astype(np.float64).sum(axis=1), 1.0, atol=1e-6)
+    z = logits.astype(np.float64)
+    e = np.exp(z - z.max(axis=1, keepdims=True))
+    np.testing.assert_allclose(probs, e / e.sum(axis=1, keepdims=True), rtol=1e-6, atol=1e-9)
+
+
 def test_global_avg_pool_closed_forms():
     const = np.full((2, 7, 7, 5), 3.25, np.float32)
     assert np.array_equal(oracle.global_avg_pool(const), np.full((2, 5), 3.25, np.float32))
