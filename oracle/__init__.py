@@ -188,6 +188,68 @@ def softmax(logits):
     return probs
 
 
+def _u16(a):
+    """Contiguous uint16 bit patterns of a float16 (or uint16) array."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype != np.uint16:
+        raise TypeError("16-bit float storage is passed as float16 or uint16 bit patterns")
+    return a
+
+
+def _hp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16))
+
+
+def half_to_double(h):
+    """binary16 bit patterns -> float64 values (the oracle's own decoding)."""
+    h = _u16(h)
+    out = np.empty(h.shape, dtype=np.float64)
+    _check(_load().tfx_ref_half_to_double(_hp(h), ctypes.c_int64(h.size),
+                                          out.ctypes.data_as(ctypes.POINTER(ctypes.c_double))))
+    return out
+
+
+def double_to_half(v):
+    """float64 values -> binary16 (returned as a float16 array), round to nearest even."""
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    out = np.empty(v.shape, dtype=np.uint16)
+    _check(_load().tfx_ref_double_to_half(v.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                          ctypes.c_int64(v.size), _hp(out)))
+    return out.view(np.float16)
+
+
+def add(a, b):
+    a, b = _f32(a), _f32(b)
+    assert a.shape == b.shape
+    c = np.empty_like(a)
+    _check(_load().tfx_ref_add(_fp(a), _fp(b), ctypes.c_int64(a.size), _fp(c)))
+    return c
+
+
+def add_f16(a, b):
+    a, b = _u16(a), _u16(b)
+    assert a.shape == b.shape
+    c = np.empty(a.shape, dtype=np.uint16)
+    _check(_load().tfx_ref_add_f16(_hp(a), _hp(b), ctypes.c_int64(a.size), _hp(c)))
+    return c.view(np.float16)
+
+
+def batch_matmul_f16(a, b, transpose_a=False, transpose_b=False, bias=None, act=ACT_NONE):
+    """a, b: [B,rows,cols] float16; bias: [N] float16 or None.  Returns float16 [B,M,N]."""
+    a, b = _u16(a), _u16(b)
+    assert a.ndim == 3 and b.ndim == 3
+    m, n = matmul_out_shape(a.shape[1:], b.shape[1:], transpose_a, transpose_b)
+    c = np.empty((a.shape[0], m, n), dtype=np.uint16)
+    bb = None if bias is None else _u16(bias)
+    if bb is not None:
+        assert bb.shape == (n,)
+    _check(_load().tfx_ref_batch_matmul_f16(_hp(a), _shape(a.shape), _hp(b), _shape(b.shape), int(transpose_a),
+                                            int(transpose_b), None if bb is None else _hp(bb), int(act), _hp(c)))
+    return c.view(np.float16)
+
+
 def mobilenet_v1_forward(image, weights, return_activations=False):
     """MobileNet-v1 1.0 forward as a chain of the single-op oracle functions.
 

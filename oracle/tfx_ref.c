@@ -21,6 +21,9 @@
  * filter flip), HWIO filters, [fh,fw,inC,mult] depthwise filters with output
  * channel c*mult+q, and the SAME / VALID output-size rules.
  *
+ * The 16-bit float storage variants and the element-wise addition at the end of the file
+ * follow Section 4.1 (16-bit float textures; Fig. 3).
+ *
  * Parity pins for every function below live in tests/test_oracle_*.py
  * (closed forms, one-hot filters, tap counts, brute force, torch/numpy float64).
  */
@@ -260,6 +263,118 @@ int tfx_ref_softmax(const float* logits, int64_t rows, int64_t cols, float* prob
     double sum = 0.0;
     for (int64_t j = 0; j < cols; ++j) sum += exp((double)l[j] - mx);
     for (int64_t j = 0; j < cols; ++j) probs[n * cols + j] = (float)(exp((double)l[j] - mx) / sum);
+  }
+  return REF_OK;
+}
+
+/* ---- 16-bit float storage (Section 4.1: the same matMul renders to a 32-bit or to a
+ * 16-bit floating point texture depending on the device) -----------------------------
+ * IEEE 754 binary16: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits.
+ *   e = 0      : value = (-1)^s * f * 2^-24               (zero and subnormals)
+ *   1<=e<=30   : value = (-1)^s * (1024 + f) * 2^(e-25)
+ *   e = 31     : infinity (f = 0) or NaN
+ * Both conversions are written from that definition; the pins compare them with numpy's
+ * float16 casts over all 65536 patterns and over random doubles.                      */
+static double ref_half_to_double(uint16_t h) {
+  const int s = (h >> 15) & 1, e = (h >> 10) & 31, f = h & 1023;
+  double v;
+  if (e == 0) v = ldexp((double)f, -24);
+  else if (e == 31) v = f ? NAN : INFINITY;
+  else v = ldexp((double)(1024 + f), e - 25);
+  return s ? -v : v;
+}
+
+/* round to nearest, ties to even; values that round beyond 65504 become infinity */
+static uint16_t ref_double_to_half(double v) {
+  if (isnan(v)) return 0x7e00;
+  const uint16_t sign = signbit(v) ? 0x8000 : 0;
+  const double a = fabs(v);
+  if (isinf(a)) return (uint16_t)(sign | 0x7c00);
+  if (a == 0.0) return sign;
+  int ex;
+  (void)frexp(a, &ex);              /* a = m * 2^ex with 0.5 <= m < 1, i.e. 2^(ex-1) <= a < 2^ex */
+  int e = ex - 1;                   /* unbiased exponent of a                                       */
+  if (e < -14) e = -14;             /* subnormal range shares the spacing of the smallest binade    */
+  const double q = ldexp(a, -(e - 10)); /* a in units of the grid spacing 2^(e-10) (exact)          */
+  double r = floor(q);
+  const double frac = q - r;
+  if (frac > 0.5 || (frac == 0.5 && fmod(r, 2.0) == 1.0)) r += 1.0;
+  /* r is an integer in [0, 2048]; r = 2048 means the value rounded up into the next binade */
+  int64_t ri = (int64_t)r;
+  if (ri == 2048) {
+    ri = 1024;
+    e += 1;
+  }
+  if (ri < 1024) return (uint16_t)(sign | (uint16_t)ri);          /* subnormal (e == -14) or zero   */
+  if (e > 15) return (uint16_t)(sign | 0x7c00);                    /* overflow                       */
+  return (uint16_t)(sign | ((uint16_t)(e + 15) << 10) | (uint16_t)(ri - 1024));
+}
+
+int tfx_ref_half_to_double(const uint16_t* h, int64_t n, double* out) {
+  if (!h || !out) return REF_ERR_NULL;
+  if (n < 0) return REF_ERR_SHAPE;
+  for (int64_t i = 0; i < n; ++i) out[i] = ref_half_to_double(h[i]);
+  return REF_OK;
+}
+
+int tfx_ref_double_to_half(const double* v, int64_t n, uint16_t* out) {
+  if (!v || !out) return REF_ERR_NULL;
+  if (n < 0) return REF_ERR_SHAPE;
+  for (int64_t i = 0; i < n; ++i) out[i] = ref_double_to_half(v[i]);
+  return REF_OK;
+}
+
+/* ---- element-wise addition (Section 4.1, Fig. 3): c[i] = a[i] + b[i] ------------------
+ * The sum of two floats (or two halfs) is exact in double, so one rounding to the storage
+ * type gives the correctly rounded result.                                             */
+int tfx_ref_add(const float* a, const float* b, int64_t n, float* c) {
+  if (n < 0) return REF_ERR_SHAPE;
+  if (n > 0 && (!a || !b || !c)) return REF_ERR_NULL;
+  for (int64_t i = 0; i < n; ++i) c[i] = (float)((double)a[i] + (double)b[i]);
+  return REF_OK;
+}
+
+int tfx_ref_add_f16(const uint16_t* a, const uint16_t* b, int64_t n, uint16_t* c) {
+  if (n < 0) return REF_ERR_SHAPE;
+  if (n > 0 && (!a || !b || !c)) return REF_ERR_NULL;
+  for (int64_t i = 0; i < n; ++i) c[i] = ref_double_to_half(ref_half_to_double(a[i]) + ref_half_to_double(b[i]));
+  return REF_OK;
+}
+
+/* ---- batchMatMul on 16-bit float storage with fused epilogue -------------------------
+ * c[b,i,j] = half( act( sum_k A'(b,i,k) * B'(b,k,j) + bias[j] ) ), operands, bias and result
+ * stored as binary16, the sum taken in double (products of two halfs are exact there).
+ * Shapes and transposes as tfx_ref_batch_matmul; bias [N] may be NULL.                  */
+int tfx_ref_batch_matmul_f16(const uint16_t* a, const int64_t a_shape[3], const uint16_t* b,
+                             const int64_t b_shape[3], int transpose_a, int transpose_b, const uint16_t* bias,
+                             int act, uint16_t* c) {
+  if (!a || !b || !c || !a_shape || !b_shape) return REF_ERR_NULL;
+  if (act != REF_ACT_NONE && act != REF_ACT_RELU && act != REF_ACT_RELU6) return REF_ERR_ARG;
+  if (a_shape[0] < 1 || a_shape[0] != b_shape[0]) return REF_ERR_SHAPE;
+  int64_t o[2];
+  int rc = tfx_ref_matmul_out_shape(a_shape + 1, b_shape + 1, transpose_a, transpose_b, o);
+  if (rc) return rc;
+  const int64_t M = o[0], N = o[1];
+  const int64_t K = transpose_a ? a_shape[1] : a_shape[2];
+  const int64_t ac = a_shape[2], bc = b_shape[2];
+  const int64_t sa = a_shape[1] * a_shape[2], sb = b_shape[1] * b_shape[2], sc = M * N;
+  for (int64_t bi = 0; bi < a_shape[0]; ++bi) {
+    const uint16_t* ap = a + bi * sa;
+    const uint16_t* bp = b + bi * sb;
+    uint16_t* cp = c + bi * sc;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+      for (int64_t j = 0; j < N; ++j) {
+        double acc = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+          const double av = ref_half_to_double(transpose_a ? ap[k * ac + i] : ap[i * ac + k]);
+          const double bv = ref_half_to_double(transpose_b ? bp[j * bc + k] : bp[k * bc + j]);
+          acc += av * bv;
+        }
+        if (bias) acc += ref_half_to_double(bias[j]);
+        cp[i * N + j] = ref_double_to_half(ref_activate(acc, act));
+      }
+    }
   }
   return REF_OK;
 }
