@@ -118,6 +118,34 @@ int tfx_depthwise_conv2d(const float* x, const int64_t x_shape[4], const float* 
                          const float* bias, int stride_h, int stride_w, tfx_padding pad, tfx_activation act,
                          float* y, void* stream);
 
+/* Element-wise addition (Section 4.1, Fig. 3): c[i] = a[i] + b[i] for 0 <= i < n,
+ * one correctly rounded IEEE addition per element.  a, b, c: device, n elements
+ * each; c may be the same buffer as a or b (no other overlap).  n = 0 is a no-op;
+ * n < 0 is TFX_ERR_SHAPE, n > 2^40 TFX_ERR_UNSUPPORTED. */
+int tfx_add(const float* a, const float* b, int64_t n, float* c, void* stream);
+
+/* ------------------------------------------------------------------------- *
+ * 16-bit float storage (Section 4.1: the same matMul program renders to a
+ * 32-bit or to a 16-bit floating point texture, depending on the device).
+ * Tensors are IEEE 754 binary16 bit patterns (uint16_t); arithmetic inside an
+ * op is at least fp32 and the result is rounded once, to nearest even, when
+ * it is stored.  Results beyond 65504 become infinity.
+ * ------------------------------------------------------------------------- */
+
+/* c[i] = half(a[i] + b[i]); otherwise as tfx_add. */
+int tfx_add_f16(const uint16_t* a, const uint16_t* b, int64_t n, uint16_t* c, void* stream);
+
+/* batchMatMul on 16-bit storage with the fused epilogue of the fp32 ops:
+ *   c[b,i,j] = half( act( sum_k A'(b,i,k) * B'(b,k,j) + bias[j] ) )
+ * with A', B', shapes and transposes as tfx_batch_matmul (B = 1 gives matMul; a
+ * pointwise convolution is the case a = x viewed as [1, N*H*W, inC],
+ * b = filter viewed as [1, inC, outC]).  bias: device [N] binary16 or NULL.
+ * The sum is accumulated in fp32 (products of two binary16 values are exact
+ * there). */
+int tfx_batch_matmul_f16(const uint16_t* a, const int64_t a_shape[3], const uint16_t* b, const int64_t b_shape[3],
+                         int transpose_a, int transpose_b, const uint16_t* bias, tfx_activation act,
+                         uint16_t* c, void* stream);
+
 /* MobileNet v1 1.0 / 224 weights (Section 3.9, Table 1 workload), batch norm
  * already folded into the biases.  The struct lives in host memory; every
  * member is a device pointer owned by the caller.  Block i (0-based) has

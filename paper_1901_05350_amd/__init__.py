@@ -7,7 +7,7 @@ There is no CPU fallback: if the library is missing or fails to load, calls rais
 """
 from .binding import (  # noqa: F401
     ACT_NONE, ACT_RELU, ACT_RELU6, PAD_SAME, PAD_VALID, TfxError, TfxVariant, MobileNetV1, lib, library_path,
-    tfx_batch_matmul, tfx_conv2d, tfx_conv2d_out_shape, tfx_depthwise_conv2d,
+    tfx_add, tfx_add_f16, tfx_batch_matmul, tfx_batch_matmul_f16, tfx_conv2d, tfx_conv2d_out_shape, tfx_depthwise_conv2d,
     tfx_depthwise_conv2d_out_shape, tfx_matmul, tfx_matmul_out_shape, tfx_mobilenet_v1_forward,
     tfx_mobilenet_v1_variant_forward, tfx_mobilenet_v1_variant_workspace_bytes,
     tfx_mobilenet_v1_workspace_bytes, tfx_status_string,

@@ -47,6 +47,10 @@ _SIGNATURES = {
                                   ctypes.c_int, _VP, _VP]),
     "tfx_depthwise_conv2d": (ctypes.c_int, [_VP, _I64P, _VP, _I64P, _VP, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                             ctypes.c_int, _VP, _VP]),
+    "tfx_add": (ctypes.c_int, [_VP, _VP, ctypes.c_int64, _VP, _VP]),
+    "tfx_add_f16": (ctypes.c_int, [_VP, _VP, ctypes.c_int64, _VP, _VP]),
+    "tfx_batch_matmul_f16": (ctypes.c_int, [_VP, _I64P, _VP, _I64P, ctypes.c_int, ctypes.c_int, _VP, ctypes.c_int,
+                                            _VP, _VP]),
     "tfx_mobilenet_v1_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64]),
     "tfx_mobilenet_v1_forward": (ctypes.c_int, [_VP, ctypes.c_int64, ctypes.POINTER(TfxWeights), _VP,
                                                 ctypes.c_size_t, _VP, _VP, _VP]),
@@ -91,12 +95,13 @@ def _check(status, where):
         raise TfxError(status, where)
 
 
-def _dev(t, name):
+def _dev(t, name, dtype=None):
     import torch
+    dtype = torch.float32 if dtype is None else dtype
     if not isinstance(t, torch.Tensor) or not t.is_cuda:
         raise TypeError("%s must be a tensor in GPU memory" % name)
-    if t.dtype != torch.float32 or not t.is_contiguous():
-        raise TypeError("%s must be contiguous float32" % name)
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be contiguous %s" % (name, str(dtype).replace("torch.", "")))
     return t
 
 
@@ -151,6 +156,49 @@ def tfx_batch_matmul(a, b, transpose_a=False, transpose_b=False, out=None):
     c = torch.empty((a.shape[0], m, n), dtype=torch.float32, device=a.device) if out is None else _dev(out, "out")
     _check(lib().tfx_batch_matmul(a.data_ptr(), _shape(a.shape), b.data_ptr(), _shape(b.shape), int(transpose_a),
                                   int(transpose_b), c.data_ptr(), _stream(a)), "tfx_batch_matmul")
+    return c
+
+
+def _add(fn_name, dtype, a, b, out):
+    import torch
+    _dev(a, "a", dtype), _dev(b, "b", dtype)
+    if a.shape != b.shape:
+        raise TypeError("add operands must have the same shape")
+    c = torch.empty_like(a) if out is None else _dev(out, "out", dtype)
+    if c.shape != a.shape:
+        raise TypeError("out must have the operands' shape")
+    _check(getattr(lib(), fn_name)(a.data_ptr(), b.data_ptr(), a.numel(), c.data_ptr(), _stream(a)), fn_name)
+    return c
+
+
+def tfx_add(a, b, out=None):
+    """c = a + b element-wise, float32; out may be a or b."""
+    import torch
+    return _add("tfx_add", torch.float32, a, b, out)
+
+
+def tfx_add_f16(a, b, out=None):
+    """c = a + b element-wise on float16 storage; out may be a or b."""
+    import torch
+    return _add("tfx_add_f16", torch.float16, a, b, out)
+
+
+def tfx_batch_matmul_f16(a, b, transpose_a=False, transpose_b=False, bias=None, act=ACT_NONE, out=None):
+    """float16 [B,rows,cols] operands, float16 bias [N] or None, float16 result [B,M,N]."""
+    import torch
+    h = torch.float16
+    _dev(a, "a", h), _dev(b, "b", h)
+    if a.dim() != 3 or b.dim() != 3:
+        raise TypeError("batch_matmul operands must have rank 3")
+    m, n = tfx_matmul_out_shape(a.shape[1:], b.shape[1:], transpose_a, transpose_b)
+    if bias is not None:
+        _dev(bias, "bias", h)
+        if tuple(bias.shape) != (n,):
+            raise TypeError("bias must have shape [%d]" % n)
+    c = torch.empty((a.shape[0], m, n), dtype=h, device=a.device) if out is None else _dev(out, "out", h)
+    _check(lib().tfx_batch_matmul_f16(a.data_ptr(), _shape(a.shape), b.data_ptr(), _shape(b.shape), int(transpose_a),
+                                      int(transpose_b), None if bias is None else bias.data_ptr(), int(act),
+                                      c.data_ptr(), _stream(a)), "tfx_batch_matmul_f16")
     return c
 
 

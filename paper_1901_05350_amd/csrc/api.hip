@@ -234,6 +234,38 @@ int tfx_depthwise_conv2d(const float* x, const int64_t x_shape[4], const float* 
                           stride_w, (int)g.pad[0], (int)g.pad[2], (int)act, static_cast<hipStream_t>(stream));
 }
 
+int tfx_add(const float* a, const float* b, int64_t n, float* c, void* stream) {
+  if (n < 0) return TFX_ERR_SHAPE;
+  if (n == 0) return TFX_OK;
+  if (!a || !b || !c) return TFX_ERR_NULL;
+  if (n > (int64_t(1) << 40)) return TFX_ERR_UNSUPPORTED;
+  return launch_add_f32(a, b, c, n, static_cast<hipStream_t>(stream));
+}
+
+int tfx_add_f16(const uint16_t* a, const uint16_t* b, int64_t n, uint16_t* c, void* stream) {
+  if (n < 0) return TFX_ERR_SHAPE;
+  if (n == 0) return TFX_OK;
+  if (!a || !b || !c) return TFX_ERR_NULL;
+  if (n > (int64_t(1) << 40)) return TFX_ERR_UNSUPPORTED;
+  return launch_add_f16(a, b, c, n, static_cast<hipStream_t>(stream));
+}
+
+int tfx_batch_matmul_f16(const uint16_t* a, const int64_t a_shape[3], const uint16_t* b, const int64_t b_shape[3],
+                         int transpose_a, int transpose_b, const uint16_t* bias, tfx_activation act, uint16_t* c,
+                         void* stream) {
+  if (!a || !b || !c || !a_shape || !b_shape) return TFX_ERR_NULL;
+  if (!valid_act((int)act)) return TFX_ERR_ARG;
+  if (a_shape[0] < 1 || a_shape[0] != b_shape[0]) return TFX_ERR_SHAPE;
+  int64_t m, n, k;
+  int rc = matmul_geometry(a_shape + 1, b_shape + 1, transpose_a, transpose_b, &m, &n, &k);
+  if (rc) return rc;
+  const int64_t batch = a_shape[0];
+  const int64_t da[3] = {batch, m, k}, db[3] = {batch, n, k}, dc[3] = {batch, m, n};
+  if (numel(da, 3) < 0 || numel(db, 3) < 0 || numel(dc, 3) < 0) return TFX_ERR_UNSUPPORTED;
+  return launch_gemm_f16(a, b, c, bias, (int)batch, (int)m, (int)n, (int)k, !transpose_a, transpose_b != 0, (int)act,
+                         static_cast<hipStream_t>(stream));
+}
+
 size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch) {
   if (batch < 1 || batch > 1024) return 0;
   return plan_net(kBaseVariant, batch).bytes;

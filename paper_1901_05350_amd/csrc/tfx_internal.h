@@ -68,6 +68,14 @@ int launch_pool_fc_softmax(const float* a, const float* w, const float* bias, fl
                            float* probs, int n, int hw, int k, int classes, hipStream_t stream);
 size_t fc_partial_floats(int n, int k, int classes);
 
+// Element-wise c[i] = a[i] + b[i] for i < n, fp32 and IEEE binary16 storage (c may alias a or b).
+int launch_add_f32(const float* a, const float* b, float* c, long long n, hipStream_t stream);
+int launch_add_f16(const uint16_t* a, const uint16_t* b, uint16_t* c, long long n, hipStream_t stream);
+
+// batchMatMul on IEEE binary16 storage with fp32 accumulation; arguments as launch_gemm, bias binary16.
+int launch_gemm_f16(const uint16_t* a, const uint16_t* b, uint16_t* c, const uint16_t* bias, int batch, int m, int n,
+                    int k, bool a_kc, bool b_kc, int act, hipStream_t stream);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? TFX_OK : TFX_ERR_LAUNCH; }
 
 }  // namespace tfx

@@ -70,6 +70,25 @@ def batch_matmul(seed=3, batch=8, m=1024, k=1024, n=1024):
             "transpose_a": False, "transpose_b": True}
 
 
+def batch_matmul_f16(seed=6, batch=8, m=1024, k=1024, n=1024, transpose_a=False, transpose_b=True, bias=False):
+    """batchMatMul operands on 16-bit float storage: N(0,1) entries rounded to float16, stored
+    [batch,k,m] / [batch,n,k] when transposed; optional bias N(0,1) of length n."""
+    rng = _rng(seed)
+    a = normal(rng, (batch, k, m) if transpose_a else (batch, m, k)).astype(np.float16)
+    b = normal(rng, (batch, n, k) if transpose_b else (batch, k, n)).astype(np.float16)
+    out = {"a": a, "b": b, "transpose_a": transpose_a, "transpose_b": transpose_b, "bias": None}
+    if bias:
+        out["bias"] = normal(rng, (n,)).astype(np.float16)
+    return out
+
+
+def add_operands(seed=8, n=1 << 20, dtype=np.float32):
+    """Two vectors of n N(0,1) values spread over +-16 binades (so that sums round), in the storage type."""
+    rng = _rng(seed)
+    scale = lambda: np.exp2(rng.integers(-8, 9, n)).astype(np.float32)
+    return {"a": (normal(rng, (n,)) * scale()).astype(dtype), "b": (normal(rng, (n,)) * scale()).astype(dtype)}
+
+
 def conv_general(seed, n, h, w, cin, cout, fh, fw):
     rng = _rng(seed)
     x = uniform(rng, (n, h, w, cin))
