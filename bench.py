@@ -22,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32 = 157.3e12   # FLOP/s, dense fp32 matrix peak of MI355X
+PEAK_MFMA_F16 = 2.5e15     # FLOP/s, dense fp16 matrix peak (fp32 accumulate)
 PEAK_HBM = 8.0e12          # B/s
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters'
@@ -201,7 +202,47 @@ def main():
                 "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
                              "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
 
+    def op_add(n, half):
+        """Element-wise c = a + b over n elements, rotating over distinct buffer sets (> the 256 MB last-level cache)."""
+        def build():
+            dt, esz = (torch.float16, 2) if half else (torch.float32, 4)
+            copies = max(2, int(1.2e9 // (3 * n * esz)) + 1)
+            sets = [(torch.empty(n, device="cuda:0").uniform_(-1, 1).to(dt), torch.empty(n, device="cuda:0").uniform_(-1, 1).to(dt),
+                     torch.empty(n, device="cuda:0", dtype=dt)) for _ in range(copies)]
+            f = tfx.tfx_add_f16 if half else tfx.tfx_add
+            state = {"i": 0}
+
+            def fn():
+                i = state["i"] = (state["i"] + 1) % copies
+                f(sets[i][0], sets[i][1], out=sets[i][2])
+            t = time_loop(fn, max(reps, copies * 2), warmup=copies, inner=copies)
+            nbytes = 3 * n * esz
+            return {"us": round(t * 1e6, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
+                    "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
+                                 "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
+        return build
+
+    def op_matmul_f16(batch, m, n, k):
+        """batchMatMul with transposeB on 16-bit float storage (fp32 accumulation on the matrix cores)."""
+        def build():
+            a = torch.empty((batch, m, k), device="cuda:0").normal_().to(torch.float16)
+            b = torch.empty((batch, n, k), device="cuda:0").normal_().to(torch.float16)
+            c = tfx.tfx_batch_matmul_f16(a, b, False, True)
+            fn = lambda: tfx.tfx_batch_matmul_f16(a, b, False, True, out=c)
+            t = time_loop(fn, reps)
+            flop, nbytes = 2 * batch * m * n * k, 2 * batch * (m * k + n * k + m * n)
+            return {"us": round(t * 1e6, 3), "single_launch_us": round(time_single(fn) * 1e6, 2),
+                    "TFLOPs": round(flop / t / 1e12, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
+                    "roofline": {"bound": "mfma", "achieved": round(flop / t / 1e12, 3), "peak": PEAK_MFMA_F16 / 1e12,
+                                 "unit": "TFLOP/s", "frac": round(flop / t / PEAK_MFMA_F16, 5),
+                                 "traffic": measured_traffic("batch_matmul_f16_%dx%dx%dx%d_tB" % (batch, m, n, k))}}
+        return build
+
     single_ops = {"matmul_64x128x64": op_matmul, "batch_matmul_8x1024x1024x1024_tB": op_batch_matmul}
+    single_ops["batch_matmul_f16_8x1024x1024x1024_tB"] = op_matmul_f16(8, 1024, 1024, 1024)
+    single_ops["batch_matmul_f16_1x4096x4096x4096_tB"] = op_matmul_f16(1, 4096, 4096, 4096)
+    single_ops["add_f32_64M"] = op_add(1 << 26, False)
+    single_ops["add_f16_64M"] = op_add(1 << 26, True)
     calibration_ops = {"copy_calibration_205MB": op_copy}
     for n in (1, 8, 64):
         single_ops["pointwise_%dx56x56x128_to_128" % n] = op_pointwise(n)
