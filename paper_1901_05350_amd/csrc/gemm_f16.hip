@@ -315,6 +315,42 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_pipe_kernel(
   }
 
   const ActClamp clamp = make_act(act);
+  if (c_vec == 2) {
+    // Staged epilogue (N % 8 == 0, C 16-byte aligned): every wavefront converts its WM x WN block to
+    // binary16 in a private LDS region (all k-slice buffers are free after the loop's last barrier),
+    // then reads it back row-wise and stores 16 bytes per lane, whole 128-byte lines per row.
+    constexpr int kLs = WN + 8;  // staging row stride in halfs
+    static_assert((size_t)WAVES_M * WAVES_N * WM * kLs <= 2 * (size_t)(BM + BN) * kLd, "staging fits in the slice buffers");
+    half_t* stage = smem_h + wave * WM * kLs;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int cl = 32 * j + 8 * g + 4 * hh;  // column inside the wave's block
+        const int col = n0 + wn0 + cl;
+        float bv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bv[e] = (bias != nullptr && col + e < N) ? (float)bias[col + e] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          h4 pk;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pk[e] = (half_t)apply_act(acc[i][j][4 * g + e] + bv[e], clamp);
+          *reinterpret_cast<h4*>(stage + (32 * i + li) * kLs + cl) = pk;
+        }
+      }
+    }
+    constexpr int kLanesPerRow = WN / 8, kRowsPerStep = 64 / kLanesPerRow;
+    const int rr = lane / kLanesPerRow, cc = 8 * (lane % kLanesPerRow);
+    const int col = n0 + wn0 + cc;
+#pragma unroll
+    for (int r0 = 0; r0 < WM; r0 += kRowsPerStep) {
+      const int row = m0 + wm0 + r0 + rr;
+      const h8 v = *reinterpret_cast<const h8*>(stage + (r0 + rr) * kLs + cc);
+      if (row < M && col < N) *reinterpret_cast<h8*>(C + (size_t)row * N + col) = v;
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + wm0 + 32 * i + li;
@@ -362,7 +398,9 @@ int launch_pipe(const half_t* a, const half_t* b, half_t* c, const half_t* bias,
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
   const long long total = (long long)batch * tiles_m * tiles_n;
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
-  const int c_vec = (n % 4 == 0 && reinterpret_cast<uintptr_t>(c) % 8 == 0) ? 1 : 0;
+  // 2: staged 16-byte stores (every row of C starts 16-byte aligned), 1: direct 8-byte stores, 0: element stores
+  const int c_vec = (n % 8 == 0 && reinterpret_cast<uintptr_t>(c) % 16 == 0) ? 2
+                    : (n % 4 == 0 && reinterpret_cast<uintptr_t>(c) % 8 == 0) ? 1 : 0;
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(NT), lds_bytes, stream, a, b, c, bias, m, n, k, tiles_m, tiles_n,
                      (int)total, (long long)m * k, (long long)n * k, (long long)m * n, act, group_m, c_vec);
   return check_launch();
@@ -407,9 +445,10 @@ int launch_gemm_f16(const uint16_t* a16, const uint16_t* b16, uint16_t* c16, con
                    reinterpret_cast<uintptr_t>(b) % 16 == 0;
   auto tiles = [&](int bm, int bn) { return (long long)batch * ((m + bm - 1) / bm) * ((n + bn - 1) / bn); };
   if (vec) {
-    // 256 x 256 tiles (8 wavefronts) once they fill most of the 256 CUs, 128 x 128 (two workgroups
-    // per CU) for mid-size problems, 64 x 64 below that
+    // 256 x 256 tiles (8 wavefronts) once they fill most of the 256 CUs, then 256 x 128 (8 wavefronts),
+    // 128 x 128 (4 wavefronts, two workgroups per CU) for mid-size problems, 64 x 64 below that
     if (tiles(256, 256) >= 192) return launch_pipe<2, 4, 4, 2>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
+    if (tiles(256, 128) >= 192) return launch_pipe<4, 2, 2, 2>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
     if (tiles(128, 128) >= 128) return launch_pipe<2, 2, 2, 2>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
     return launch_pipe<2, 2, 1, 1>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
   }
