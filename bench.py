@@ -222,25 +222,51 @@ def main():
                                  "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
         return build
 
-    def op_matmul_f16(batch, m, n, k):
-        """batchMatMul with transposeB on 16-bit float storage (fp32 accumulation on the matrix cores)."""
+    def op_matmul_f16(batch, m, n, k, tb=True):
+        """batchMatMul on 16-bit float storage (fp32 accumulation on the matrix cores); B stored [N,K] if tb."""
         def build():
             a = torch.empty((batch, m, k), device="cuda:0").normal_().to(torch.float16)
-            b = torch.empty((batch, n, k), device="cuda:0").normal_().to(torch.float16)
-            c = tfx.tfx_batch_matmul_f16(a, b, False, True)
-            fn = lambda: tfx.tfx_batch_matmul_f16(a, b, False, True, out=c)
+            b = torch.empty((batch, n, k) if tb else (batch, k, n), device="cuda:0").normal_().to(torch.float16)
+            c = tfx.tfx_batch_matmul_f16(a, b, False, tb)
+            fn = lambda: tfx.tfx_batch_matmul_f16(a, b, False, tb, out=c)
             t = time_loop(fn, reps)
             flop, nbytes = 2 * batch * m * n * k, 2 * batch * (m * k + n * k + m * n)
             return {"us": round(t * 1e6, 3), "single_launch_us": round(time_single(fn) * 1e6, 2),
                     "TFLOPs": round(flop / t / 1e12, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
                     "roofline": {"bound": "mfma", "achieved": round(flop / t / 1e12, 3), "peak": PEAK_MFMA_F16 / 1e12,
                                  "unit": "TFLOP/s", "frac": round(flop / t / PEAK_MFMA_F16, 5),
-                                 "traffic": measured_traffic("batch_matmul_f16_%dx%dx%dx%d_tB" % (batch, m, n, k))}}
+                                 "traffic": measured_traffic("batch_matmul_f16_%dx%dx%dx%d%s" % (batch, m, n, k, "_tB" if tb else ""))}}
+        return build
+
+    def op_pointwise_f16(n):
+        """1x1 conv 56x56x128 -> 128 + bias + ReLU6 on 16-bit storage, as a matMul of x [N*56*56,128] with the
+        filter stored [128,128] (inC, outC).  3.3 flop per byte moved: bound by HBM, not by the matrix cores."""
+        def build():
+            m = n * 56 * 56
+            copies = 1 if n < 64 else 8          # rotate over > 256 MB of activations at batch 64
+            xs = [torch.empty((1, m, 128), device="cuda:0").uniform_(-1, 1).to(torch.float16) for _ in range(copies)]
+            f = (torch.empty((1, 128, 128), device="cuda:0").normal_() * (2.0 / 128) ** 0.5).to(torch.float16)
+            bias = (torch.empty(128, device="cuda:0").normal_() * 0.01).to(torch.float16)
+            ys = [tfx.tfx_batch_matmul_f16(x, f, False, False, bias, tfx.ACT_RELU6) for x in xs]
+            state = {"i": 0}
+
+            def fn():
+                i = state["i"] = (state["i"] + 1) % copies
+                tfx.tfx_batch_matmul_f16(xs[i], f, False, False, bias, tfx.ACT_RELU6, out=ys[i])
+            t = time_loop(fn, max(reps, copies * 2), warmup=copies, inner=copies if copies > 1 else None)
+            flop, nbytes = 2 * m * 128 * 128, 2 * (2 * m * 128 + 128 * 128 + 128)
+            return {"us": round(t * 1e6, 3), "TFLOPs": round(flop / t / 1e12, 3), "GBps": round(nbytes / t / 1e9, 1),
+                    "algorithmic_bytes": nbytes,
+                    "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
+                                 "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
         return build
 
     single_ops = {"matmul_64x128x64": op_matmul, "batch_matmul_8x1024x1024x1024_tB": op_batch_matmul}
     single_ops["batch_matmul_f16_8x1024x1024x1024_tB"] = op_matmul_f16(8, 1024, 1024, 1024)
     single_ops["batch_matmul_f16_1x4096x4096x4096_tB"] = op_matmul_f16(1, 4096, 4096, 4096)
+    single_ops["batch_matmul_f16_1x4096x4096x4096"] = op_matmul_f16(1, 4096, 4096, 4096, tb=False)
+    single_ops["pointwise_f16_64x56x56x128_to_128"] = op_pointwise_f16(64)
+    single_ops["pointwise_f16_8x56x56x128_to_128"] = op_pointwise_f16(8)
     single_ops["add_f32_64M"] = op_add(1 << 26, False)
     single_ops["add_f16_64M"] = op_add(1 << 26, True)
     calibration_ops = {"copy_calibration_205MB": op_copy}

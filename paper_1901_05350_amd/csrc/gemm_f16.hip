@@ -184,7 +184,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_kernel(
 // after every few MFMAs one 16-byte slot of slice kt+1 (loaded a whole iteration earlier) moves from
 // its registers to the other LDS buffer and the same registers are refilled with that slot of slice
 // kt+2; one barrier per slice.
-template <int WAVES_M, int WAVES_N, int TM, int TN>
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool B_KC>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_pipe_kernel(
     const half_t* __restrict__ A, const half_t* __restrict__ B, half_t* __restrict__ C, const half_t* __restrict__ bias,
     int M, int N, int K, int tiles_m, int tiles_n, int total_blocks, long long strideA, long long strideB,
@@ -196,6 +196,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_pipe_kernel(
   constexpr int SA = BM * 8 / kNT, SB = BN * 8 / kNT, SLOTS = SA + SB;  // 16-byte slots per thread and slice
   constexpr int STEPS = kBK / 16, MF = TM * TN;  // k-steps per slice, MFMAs per step
   static_assert(BM * 8 % kNT == 0 && BN * 8 % kNT == 0, "loader shape");
+  static_assert(B_KC || (SB == 4 && kNT / 16 == BN / 8), "the [K,N] loader moves 4 k-rows x 8 columns per thread");
   extern __shared__ __align__(16) half_t smem_h[];
   half_t* const lds_a = smem_h;
   half_t* const lds_b = smem_h + 2 * kTileA;
@@ -239,8 +240,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_pipe_kernel(
   const int srow = tid / 8, scol = 8 * (tid % 8);
   constexpr int kRowStep = kNT / 8;
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  //
+  // B stored [K,N] (!B_KC, N % 8 == 0): thread (kq = tid % 16, nb = tid / 16) loads k-rows 4 kq ... + 3 of
+  // columns 8 nb ... + 7 as four 16-byte slots (16 lanes with consecutive kq: the 8-byte LDS writes of
+  // one row are contiguous), transposes the 4 x 8 block in registers and writes, for each of the 8
+  // columns, 4 consecutive k to the K-contiguous LDS row of that column.  The block is written when
+  // its first slot comes up in the schedule, its slots are refilled one by one.
   u32x4 reg[SLOTS];
-  unsigned goff[SLOTS];  // element offset of the slot's (clamped) row start
+  unsigned goff[SLOTS];  // K-contiguous operand: element offset of the slot's (clamped) row start
+  const int kq = tid % 16, nb = tid / 16;
+  const unsigned bcol = n0 + 8 * nb < N ? (unsigned)(n0 + 8 * nb) : 0u;  // past N: any valid column block
 #pragma unroll
   for (int w = 0; w < SLOTS; ++w) {
     const bool is_a = w < SA;
@@ -251,18 +260,39 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_pipe_kernel(
   const int nk = (K + kBK - 1) / kBK;
   const int k_last = (nk - 1) * kBK;
   auto load_slot = [&](int w, int k0) {
-    const half_t* g = w < SA ? A : B;
-    const unsigned kk = k0 + scol < K ? (unsigned)(k0 + scol) : 0u;  // past K: any valid address, zeroed later
-    reg[w] = *reinterpret_cast<const u32x4*>(g + (size_t)(goff[w] + kk));
+    if (w < SA || B_KC) {
+      const half_t* g = w < SA ? A : B;
+      const unsigned kk = k0 + scol < K ? (unsigned)(k0 + scol) : 0u;  // past K: any valid address, zeroed later
+      reg[w] = *reinterpret_cast<const u32x4*>(g + (size_t)(goff[w] + kk));
+    } else {
+      const int k = k0 + 4 * kq + (w - SA);
+      const unsigned kk = k < K ? (unsigned)k : 0u;
+      reg[w] = *reinterpret_cast<const u32x4*>(B + (size_t)(kk * (unsigned)N + bcol));
+    }
   };
   // k0: first k of the slice the registers hold; the zeroing of halfs past K happens here, when the
   // registers are consumed, so that nothing waits on a load right after issuing it
   auto store_slot = [&](int w, int buf, int k0) {
-    const bool is_a = w < SA;
-    const int i = is_a ? w : w - SA;
-    half_t* l = is_a ? lds_a + buf * kTileA : lds_b + buf * kTileB;
-    const unsigned mask = k0 + scol < K ? 0xffffffffu : 0u;
-    *reinterpret_cast<u32x4*>(l + (srow + i * kRowStep) * kLd + scol) = reg[w] & mask;
+    if (w < SA || B_KC) {
+      const bool is_a = w < SA;
+      const int i = is_a ? w : w - SA;
+      half_t* l = is_a ? lds_a + buf * kTileA : lds_b + buf * kTileB;
+      const unsigned mask = k0 + scol < K ? 0xffffffffu : 0u;
+      *reinterpret_cast<u32x4*>(l + (srow + i * kRowStep) * kLd + scol) = reg[w] & mask;
+    } else if (w == SA) {
+      h8 r[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const unsigned mask = k0 + 4 * kq + kk < K ? 0xffffffffu : 0u;
+        r[kk] = __builtin_bit_cast(h8, reg[SA + kk] & mask);
+      }
+      half_t* l = lds_b + buf * kTileB + (8 * nb) * kLd + 4 * kq;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const h4 o = {r[0][i], r[1][i], r[2][i], r[3][i]};
+        *reinterpret_cast<h4*>(l + i * kLd) = o;
+      }
+    }
   };
 
 #pragma unroll
@@ -381,13 +411,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_pipe_kernel(
   }
 }
 
-template <int WAVES_M, int WAVES_N, int TM, int TN>
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool B_KC = true>
 int launch_pipe(const half_t* a, const half_t* b, half_t* c, const half_t* bias, int batch, int m, int n, int k,
                 bool, bool, int act, hipStream_t stream, int group_m = 4) {
   constexpr int BM = 32 * TM * WAVES_M, BN = 32 * TN * WAVES_N, NT = 64 * WAVES_M * WAVES_N;
   constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * kLd * sizeof(half_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
-  auto kern = gemm_f16_pipe_kernel<WAVES_M, WAVES_N, TM, TN>;
+  auto kern = gemm_f16_pipe_kernel<WAVES_M, WAVES_N, TM, TN, B_KC>;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -441,16 +471,32 @@ int launch_gemm_f16(const uint16_t* a16, const uint16_t* b16, uint16_t* c16, con
   const half_t* bias = reinterpret_cast<const half_t*>(bias16);
   // 16-byte loads: both operands K-contiguous, K a multiple of 8 (then every row and every batch
   // starts 16-byte aligned if the base pointers do)
-  const bool vec = a_kc && b_kc && k % 8 == 0 && reinterpret_cast<uintptr_t>(a) % 16 == 0 &&
-                   reinterpret_cast<uintptr_t>(b) % 16 == 0;
+  const bool aligned = reinterpret_cast<uintptr_t>(a) % 16 == 0 && reinterpret_cast<uintptr_t>(b) % 16 == 0;
+  const bool vec = a_kc && b_kc && k % 8 == 0 && aligned;
+  // A [M,K] with B stored [K,N] (matMul without transposes, a pointwise convolution's filter): 16-byte
+  // loads along N and a register transpose on the way into LDS
+  const bool vec_kn = a_kc && !b_kc && k % 8 == 0 && n % 8 == 0 && aligned;
   auto tiles = [&](int bm, int bn) { return (long long)batch * ((m + bm - 1) / bm) * ((n + bn - 1) / bn); };
+  // a tile shape is acceptable if it wastes at most 10% more of its area on padding than 128 x 128 tiles do
+  auto fits = [&](int bm, int bn) {
+    const double pad = (double)((m + bm - 1) / bm * bm) * ((n + bn - 1) / bn * bn);
+    const double pad128 = (double)((m + 127) / 128 * 128) * ((n + 127) / 128 * 128);
+    return pad <= 1.1 * pad128;
+  };
   if (vec) {
     // 256 x 256 tiles (8 wavefronts) once they fill most of the 256 CUs, then 256 x 128 (8 wavefronts),
     // 128 x 128 (4 wavefronts, two workgroups per CU) for mid-size problems, 64 x 64 below that
-    if (tiles(256, 256) >= 192) return launch_pipe<2, 4, 4, 2>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
-    if (tiles(256, 128) >= 192) return launch_pipe<4, 2, 2, 2>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
+    if (tiles(256, 256) >= 192 && fits(256, 256))
+      return launch_pipe<2, 4, 4, 2>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
+    if (tiles(256, 128) >= 192 && fits(256, 128))
+      return launch_pipe<4, 2, 2, 2>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
     if (tiles(128, 128) >= 128) return launch_pipe<2, 2, 2, 2>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
     return launch_pipe<2, 2, 1, 1>(a, b, c, bias, batch, m, n, k, true, true, act, stream);
+  }
+  if (vec_kn) {
+    if (tiles(256, 256) >= 192 && fits(256, 256))
+      return launch_pipe<2, 4, 4, 2, false>(a, b, c, bias, batch, m, n, k, true, false, act, stream);
+    return launch_pipe<2, 2, 2, 2, false>(a, b, c, bias, batch, m, n, k, true, false, act, stream);
   }
   if (tiles(128, 128) >= 256) return launch_cfg<2, 2, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, act, stream);
   return launch_cfg<2, 2, 1, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, act, stream);
