@@ -250,6 +250,69 @@ def batch_matmul_f16(a, b, transpose_a=False, transpose_b=False, bias=None, act=
     return c.view(np.float16)
 
 
+def _conv_f16(fn_name, shape_fn, x, filt, bias, stride, pad, act):
+    x, filt = _u16(x), _u16(filt)
+    assert x.ndim == 4 and filt.ndim == 4
+    sh, sw = (stride, stride) if np.isscalar(stride) else stride
+    oshape, _ = shape_fn(x.shape, filt.shape, (sh, sw), pad)
+    y = np.empty(oshape, dtype=np.uint16)
+    b = None if bias is None else _u16(bias)
+    if b is not None:
+        assert b.shape == (oshape[3],)
+    _check(getattr(_load(), fn_name)(_hp(x), _shape(x.shape), _hp(filt), _shape(filt.shape), None if b is None else _hp(b),
+                                     int(sh), int(sw), int(pad), int(act), _hp(y)))
+    return y.view(np.float16)
+
+
+def conv2d_f16(x, filt, bias=None, stride=1, pad=PAD_SAME, act=ACT_NONE):
+    return _conv_f16("tfx_ref_conv2d_f16", conv2d_out_shape, x, filt, bias, stride, pad, act)
+
+
+def depthwise_conv2d_f16(x, filt, bias=None, stride=1, pad=PAD_SAME, act=ACT_NONE):
+    return _conv_f16("tfx_ref_depthwise_conv2d_f16", depthwise_conv2d_out_shape, x, filt, bias, stride, pad, act)
+
+
+def global_avg_pool_f16(x):
+    x = _u16(x)
+    assert x.ndim == 4
+    y = np.empty((x.shape[0], x.shape[3]), dtype=np.uint16)
+    _check(_load().tfx_ref_global_avg_pool_f16(_hp(x), _shape(x.shape), _hp(y)))
+    return y.view(np.float16)
+
+
+def softmax_f16(logits):
+    logits = _u16(logits)
+    assert logits.ndim == 2
+    probs = np.empty(logits.shape, dtype=np.uint16)
+    _check(_load().tfx_ref_softmax_f16(_hp(logits), ctypes.c_int64(logits.shape[0]), ctypes.c_int64(logits.shape[1]),
+                                       _hp(probs)))
+    return probs.view(np.float16)
+
+
+def mobilenet_v1_forward_f16(image, weights, return_activations=False):
+    """The MobileNet-v1 chain on 16-bit float storage: every tensor (image, weights, biases, feature
+    maps, pooled vector, logits, probabilities) is float16 and every op rounds its result once."""
+    acts = []
+    a = conv2d_f16(image, weights["conv0_w"], weights["conv0_b"], stride=2, pad=PAD_SAME, act=ACT_RELU6)
+    acts.append(a)
+    for i in range(13):
+        a = depthwise_conv2d_f16(a, weights["dw_w"][i], weights["dw_b"][i], stride=MOBILENET_V1_STRIDES[i],
+                                 pad=PAD_SAME, act=ACT_RELU6)
+        acts.append(a)
+        a = conv2d_f16(a, weights["pw_w"][i], weights["pw_b"][i], stride=1, pad=PAD_SAME, act=ACT_RELU6)
+        acts.append(a)
+    pooled = global_avg_pool_f16(a)
+    acts.append(pooled)
+    n, c = pooled.shape
+    fc_w = np.ascontiguousarray(weights["fc_w"])
+    logits = conv2d_f16(pooled.reshape(n, 1, 1, c), fc_w.reshape(1, 1, fc_w.shape[0], fc_w.shape[1]),
+                        weights["fc_b"], stride=1, pad=PAD_SAME, act=ACT_NONE).reshape(n, -1)
+    probs = softmax_f16(logits)
+    if return_activations:
+        return probs, logits, acts
+    return probs, logits
+
+
 def mobilenet_v1_forward(image, weights, return_activations=False):
     """MobileNet-v1 1.0 forward as a chain of the single-op oracle functions.
 

@@ -378,3 +378,139 @@ int tfx_ref_batch_matmul_f16(const uint16_t* a, const int64_t a_shape[3], const 
   }
   return REF_OK;
 }
+
+/* ---- conv2d, depthwiseConv2d and the MobileNet tail on 16-bit float storage ----------
+ * Same definitions as the fp32 functions above; inputs, filters and bias are binary16, every
+ * output element is the double-precision sum rounded once to binary16.  The operands are
+ * decoded once into float arrays (every binary16 value is exactly a float) so that the loops
+ * below read like the fp32 ones.                                                        */
+#include <stdlib.h>
+
+static float* ref_decode_halfs(const uint16_t* h, int64_t n) {
+  float* f = (float*)malloc(sizeof(float) * (size_t)(n > 0 ? n : 1));
+  if (!f) return NULL;
+  for (int64_t i = 0; i < n; ++i) f[i] = (float)ref_half_to_double(h[i]);
+  return f;
+}
+
+int tfx_ref_conv2d_f16(const uint16_t* x16, const int64_t x_shape[4], const uint16_t* w16, const int64_t f_shape[4],
+                       const uint16_t* bias16, int stride_h, int stride_w, int pad, int act, uint16_t* y) {
+  if (!x16 || !w16 || !y || !x_shape || !f_shape) return REF_ERR_NULL;
+  if (act != REF_ACT_NONE && act != REF_ACT_RELU && act != REF_ACT_RELU6) return REF_ERR_ARG;
+  int64_t o[4], p[4];
+  int rc = tfx_ref_conv2d_out_shape(x_shape, f_shape, stride_h, stride_w, pad, o, p);
+  if (rc) return rc;
+  const int64_t N = x_shape[0], H = x_shape[1], W = x_shape[2], Ci = x_shape[3];
+  const int64_t fh = f_shape[0], fw = f_shape[1], Co = f_shape[3];
+  const int64_t OH = o[1], OW = o[2], pt = p[0], pl = p[2];
+  float* x = ref_decode_halfs(x16, N * H * W * Ci);
+  float* w = ref_decode_halfs(w16, fh * fw * Ci * Co);
+  float* bias = bias16 ? ref_decode_halfs(bias16, Co) : NULL;
+  if (!x || !w || (bias16 && !bias)) {
+    free(x); free(w); free(bias);
+    return REF_ERR_NULL;
+  }
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int64_t n = 0; n < N; ++n) {
+    for (int64_t oh = 0; oh < OH; ++oh) {
+      for (int64_t ow = 0; ow < OW; ++ow) {
+        for (int64_t oc = 0; oc < Co; ++oc) {
+          double acc = 0.0;
+          for (int64_t kh = 0; kh < fh; ++kh) {
+            const int64_t ih = oh * stride_h - pt + kh;
+            if (ih < 0 || ih >= H) continue;
+            for (int64_t kw = 0; kw < fw; ++kw) {
+              const int64_t iw = ow * stride_w - pl + kw;
+              if (iw < 0 || iw >= W) continue;
+              const float* xp = x + ((n * H + ih) * W + iw) * Ci;
+              const float* wp = w + ((kh * fw + kw) * Ci) * Co + oc;
+              for (int64_t c = 0; c < Ci; ++c) acc += (double)xp[c] * (double)wp[c * Co];
+            }
+          }
+          if (bias) acc += (double)bias[oc];
+          y[((n * OH + oh) * OW + ow) * Co + oc] = ref_double_to_half(ref_activate(acc, act));
+        }
+      }
+    }
+  }
+  free(x); free(w); free(bias);
+  return REF_OK;
+}
+
+int tfx_ref_depthwise_conv2d_f16(const uint16_t* x16, const int64_t x_shape[4], const uint16_t* w16,
+                                 const int64_t f_shape[4], const uint16_t* bias16, int stride_h, int stride_w,
+                                 int pad, int act, uint16_t* y) {
+  if (!x16 || !w16 || !y || !x_shape || !f_shape) return REF_ERR_NULL;
+  if (act != REF_ACT_NONE && act != REF_ACT_RELU && act != REF_ACT_RELU6) return REF_ERR_ARG;
+  int64_t o[4], p[4];
+  int rc = tfx_ref_depthwise_conv2d_out_shape(x_shape, f_shape, stride_h, stride_w, pad, o, p);
+  if (rc) return rc;
+  const int64_t N = x_shape[0], H = x_shape[1], W = x_shape[2], C = x_shape[3];
+  const int64_t fh = f_shape[0], fw = f_shape[1], mult = f_shape[3];
+  const int64_t OH = o[1], OW = o[2], OC = o[3], pt = p[0], pl = p[2];
+  float* x = ref_decode_halfs(x16, N * H * W * C);
+  float* w = ref_decode_halfs(w16, fh * fw * C * mult);
+  float* bias = bias16 ? ref_decode_halfs(bias16, OC) : NULL;
+  if (!x || !w || (bias16 && !bias)) {
+    free(x); free(w); free(bias);
+    return REF_ERR_NULL;
+  }
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int64_t n = 0; n < N; ++n) {
+    for (int64_t oh = 0; oh < OH; ++oh) {
+      for (int64_t ow = 0; ow < OW; ++ow) {
+        for (int64_t c = 0; c < C; ++c) {
+          for (int64_t q = 0; q < mult; ++q) {
+            double acc = 0.0;
+            for (int64_t kh = 0; kh < fh; ++kh) {
+              const int64_t ih = oh * stride_h - pt + kh;
+              if (ih < 0 || ih >= H) continue;
+              for (int64_t kw = 0; kw < fw; ++kw) {
+                const int64_t iw = ow * stride_w - pl + kw;
+                if (iw < 0 || iw >= W) continue;
+                acc += (double)x[((n * H + ih) * W + iw) * C + c] * (double)w[((kh * fw + kw) * C + c) * mult + q];
+              }
+            }
+            if (bias) acc += (double)bias[c * mult + q];
+            y[((n * OH + oh) * OW + ow) * OC + c * mult + q] = ref_double_to_half(ref_activate(acc, act));
+          }
+        }
+      }
+    }
+  }
+  free(x); free(w); free(bias);
+  return REF_OK;
+}
+
+/* mean over the H*W positions of each channel, rounded once to binary16 */
+int tfx_ref_global_avg_pool_f16(const uint16_t* x, const int64_t x_shape[4], uint16_t* y) {
+  if (!x || !x_shape || !y) return REF_ERR_NULL;
+  for (int i = 0; i < 4; ++i)
+    if (x_shape[i] < 1) return REF_ERR_SHAPE;
+  const int64_t N = x_shape[0], HW = x_shape[1] * x_shape[2], C = x_shape[3];
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t c = 0; c < C; ++c) {
+      double acc = 0.0;
+      for (int64_t p = 0; p < HW; ++p) acc += ref_half_to_double(x[(n * HW + p) * C + c]);
+      y[n * C + c] = ref_double_to_half(acc / (double)HW);
+    }
+  return REF_OK;
+}
+
+/* row-wise softmax of binary16 logits, each probability rounded once to binary16 */
+int tfx_ref_softmax_f16(const uint16_t* logits, int64_t rows, int64_t cols, uint16_t* probs) {
+  if (!logits || !probs) return REF_ERR_NULL;
+  if (rows < 1 || cols < 1) return REF_ERR_SHAPE;
+  for (int64_t n = 0; n < rows; ++n) {
+    const uint16_t* l = logits + n * cols;
+    double mx = ref_half_to_double(l[0]);
+    for (int64_t j = 1; j < cols; ++j) {
+      const double v = ref_half_to_double(l[j]);
+      if (v > mx) mx = v;
+    }
+    double sum = 0.0;
+    for (int64_t j = 0; j < cols; ++j) sum += exp(ref_half_to_double(l[j]) - mx);
+    for (int64_t j = 0; j < cols; ++j) probs[n * cols + j] = ref_double_to_half(exp(ref_half_to_double(l[j]) - mx) / sum);
+  }
+  return REF_OK;
+}

@@ -122,3 +122,11 @@ def mobilenet_v1(seed=4, batch=1, image_size=224, width_quarters=4, classes=1000
     rng = _rng(seed)
     image = uniform(rng, (batch, image_size, image_size, 3))
     return {"image": image, "weights": mobilenet_v1_weights(rng, width_quarters, classes)}
+
+
+def mobilenet_v1_f16(seed=4, batch=1, image_size=224, width_quarters=4, classes=1000):
+    """The MobileNet-v1 workload on 16-bit float storage: the same draws as mobilenet_v1, rounded to float16."""
+    d = mobilenet_v1(seed, batch, image_size, width_quarters, classes)
+    h = lambda a: a.astype(np.float16)
+    return {"image": h(d["image"]),
+            "weights": {k: ([h(t) for t in v] if isinstance(v, list) else h(v)) for k, v in d["weights"].items()}}
