@@ -146,6 +146,16 @@ int tfx_batch_matmul_f16(const uint16_t* a, const int64_t a_shape[3], const uint
                          int transpose_a, int transpose_b, const uint16_t* bias, tfx_activation act,
                          uint16_t* c, void* stream);
 
+/* conv2d and depthwiseConv2d on 16-bit storage: the definitions of tfx_conv2d and
+ * tfx_depthwise_conv2d with x, filter, bias and y stored as binary16, the sum
+ * accumulated in fp32 and the result rounded once. */
+int tfx_conv2d_f16(const uint16_t* x, const int64_t x_shape[4], const uint16_t* filter, const int64_t f_shape[4],
+                   const uint16_t* bias, int stride_h, int stride_w, tfx_padding pad, tfx_activation act,
+                   uint16_t* y, void* stream);
+int tfx_depthwise_conv2d_f16(const uint16_t* x, const int64_t x_shape[4], const uint16_t* filter,
+                             const int64_t f_shape[4], const uint16_t* bias, int stride_h, int stride_w,
+                             tfx_padding pad, tfx_activation act, uint16_t* y, void* stream);
+
 /* MobileNet v1 1.0 / 224 weights (Section 3.9, Table 1 workload), batch norm
  * already folded into the biases.  The struct lives in host memory; every
  * member is a device pointer owned by the caller.  Block i (0-based) has
@@ -202,6 +212,30 @@ size_t tfx_mobilenet_v1_variant_workspace_bytes(const tfx_mobilenet_v1_variant* 
 int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
                                      const tfx_mobilenet_v1_weights* weights, void* workspace,
                                      size_t workspace_bytes, float* probs, float* logits, void* stream);
+
+/* MobileNet v1 on 16-bit storage: the network of tfx_mobilenet_v1_variant_forward with
+ * every tensor (image, weights, biases, feature maps, pooled vector, logits,
+ * probabilities) stored as binary16 and every layer rounding its result once; the
+ * softmax is taken of the binary16 logits.  Members as in tfx_mobilenet_v1_weights. */
+typedef struct {
+  const uint16_t* conv0_w;
+  const uint16_t* conv0_b;
+  const uint16_t* dw_w[13];
+  const uint16_t* dw_b[13];
+  const uint16_t* pw_w[13];
+  const uint16_t* pw_b[13];
+  const uint16_t* fc_w;
+  const uint16_t* fc_b;
+} tfx_mobilenet_v1_weights_f16;
+
+/* Workspace bytes of tfx_mobilenet_v1_forward_f16 (0 if the variant or batch is invalid). */
+size_t tfx_mobilenet_v1_workspace_bytes_f16(const tfx_mobilenet_v1_variant* variant, int64_t batch);
+
+/* input: device [batch,image_size,image_size,3] binary16; probs / logits: device
+ * [batch,classes] binary16 (logits may be NULL); workspace as for the fp32 entry point. */
+int tfx_mobilenet_v1_forward_f16(const tfx_mobilenet_v1_variant* variant, const uint16_t* input, int64_t batch,
+                                 const tfx_mobilenet_v1_weights_f16* weights, void* workspace,
+                                 size_t workspace_bytes, uint16_t* probs, uint16_t* logits, void* stream);
 
 #ifdef __cplusplus
 }

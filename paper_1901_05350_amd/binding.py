@@ -19,6 +19,11 @@ class TfxWeights(ctypes.Structure):
                 ("fc_w", _VP), ("fc_b", _VP)]
 
 
+class TfxWeightsF16(ctypes.Structure):
+    """Mirror of tfx_mobilenet_v1_weights_f16 (same members, binary16 tensors)."""
+    _fields_ = TfxWeights._fields_
+
+
 class TfxVariant(ctypes.Structure):
     """Mirror of tfx_mobilenet_v1_variant."""
     _fields_ = [("image_size", ctypes.c_int64), ("width_quarters", ctypes.c_int64), ("classes", ctypes.c_int64)]
@@ -51,6 +56,14 @@ _SIGNATURES = {
     "tfx_add_f16": (ctypes.c_int, [_VP, _VP, ctypes.c_int64, _VP, _VP]),
     "tfx_batch_matmul_f16": (ctypes.c_int, [_VP, _I64P, _VP, _I64P, ctypes.c_int, ctypes.c_int, _VP, ctypes.c_int,
                                             _VP, _VP]),
+    "tfx_conv2d_f16": (ctypes.c_int, [_VP, _I64P, _VP, _I64P, _VP, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_int, _VP, _VP]),
+    "tfx_depthwise_conv2d_f16": (ctypes.c_int, [_VP, _I64P, _VP, _I64P, _VP, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                ctypes.c_int, _VP, _VP]),
+    "tfx_mobilenet_v1_workspace_bytes_f16": (ctypes.c_size_t, [ctypes.POINTER(TfxVariant), ctypes.c_int64]),
+    "tfx_mobilenet_v1_forward_f16": (ctypes.c_int, [ctypes.POINTER(TfxVariant), _VP, ctypes.c_int64,
+                                                    ctypes.POINTER(TfxWeightsF16), _VP, ctypes.c_size_t, _VP, _VP,
+                                                    _VP]),
     "tfx_mobilenet_v1_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64]),
     "tfx_mobilenet_v1_forward": (ctypes.c_int, [_VP, ctypes.c_int64, ctypes.POINTER(TfxWeights), _VP,
                                                 ctypes.c_size_t, _VP, _VP, _VP]),
@@ -202,14 +215,15 @@ def tfx_batch_matmul_f16(a, b, transpose_a=False, transpose_b=False, bias=None, 
     return c
 
 
-def _conv(fn_name, shape_fn, x, filt, bias, stride, pad, act, out):
+def _conv(fn_name, shape_fn, x, filt, bias, stride, pad, act, out, dtype=None):
     import torch
-    _dev(x, "x"), _dev(filt, "filter")
+    dtype = torch.float32 if dtype is None else dtype
+    _dev(x, "x", dtype), _dev(filt, "filter", dtype)
     if bias is not None:
-        _dev(bias, "bias")
+        _dev(bias, "bias", dtype)
     sh, sw = _pair(stride)
     oshape, _ = shape_fn(x.shape, filt.shape, (sh, sw), pad)
-    y = torch.empty(oshape, dtype=torch.float32, device=x.device) if out is None else _dev(out, "out")
+    y = torch.empty(oshape, dtype=dtype, device=x.device) if out is None else _dev(out, "out", dtype)
     fn = getattr(lib(), fn_name)
     _check(fn(x.data_ptr(), _shape(x.shape), filt.data_ptr(), _shape(filt.shape),
               None if bias is None else bias.data_ptr(), sh, sw, int(pad), int(act), y.data_ptr(), _stream(x)),
@@ -223,6 +237,17 @@ def tfx_conv2d(x, filt, bias=None, stride=1, pad=PAD_SAME, act=ACT_NONE, out=Non
 
 def tfx_depthwise_conv2d(x, filt, bias=None, stride=1, pad=PAD_SAME, act=ACT_NONE, out=None):
     return _conv("tfx_depthwise_conv2d", tfx_depthwise_conv2d_out_shape, x, filt, bias, stride, pad, act, out)
+
+
+def tfx_conv2d_f16(x, filt, bias=None, stride=1, pad=PAD_SAME, act=ACT_NONE, out=None):
+    import torch
+    return _conv("tfx_conv2d_f16", tfx_conv2d_out_shape, x, filt, bias, stride, pad, act, out, torch.float16)
+
+
+def tfx_depthwise_conv2d_f16(x, filt, bias=None, stride=1, pad=PAD_SAME, act=ACT_NONE, out=None):
+    import torch
+    return _conv("tfx_depthwise_conv2d_f16", tfx_depthwise_conv2d_out_shape, x, filt, bias, stride, pad, act, out,
+                 torch.float16)
 
 
 def tfx_mobilenet_v1_workspace_bytes(batch):
@@ -294,3 +319,42 @@ def tfx_mobilenet_v1_variant_forward(variant, image, weights_struct, workspace, 
                                                   None if logits is None else logits.data_ptr(), _stream(image)),
            "tfx_mobilenet_v1_variant_forward")
     return probs
+
+
+class MobileNetV1F16:
+    """Device-resident float16 MobileNet-v1 weights plus a workspace; calls tfx_mobilenet_v1_forward_f16."""
+
+    def __init__(self, weights, batch=1, device="cuda:0", image_size=224, width_quarters=4):
+        import torch
+        self.device = torch.device(device)
+        self.batch = int(batch)
+        up = lambda a: torch.as_tensor(a).to(torch.float16).contiguous().to(self.device)
+        self.tensors = {k: ([up(t) for t in v] if isinstance(v, (list, tuple)) else up(v)) for k, v in weights.items()}
+        self.struct = TfxWeightsF16()
+        for k in ("conv0_w", "conv0_b", "fc_w", "fc_b"):
+            setattr(self.struct, k, self.tensors[k].data_ptr())
+        for k in ("dw_w", "dw_b", "pw_w", "pw_b"):
+            arr = getattr(self.struct, k)
+            for i in range(13):
+                arr[i] = self.tensors[k][i].data_ptr()
+        classes = int(self.tensors["fc_w"].shape[1])
+        self.variant = TfxVariant(int(image_size), int(width_quarters), classes)
+        nbytes = int(lib().tfx_mobilenet_v1_workspace_bytes_f16(ctypes.byref(self.variant), self.batch))
+        if nbytes == 0:
+            raise ValueError("unsupported MobileNet-v1 variant or batch")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.probs = torch.empty((self.batch, classes), dtype=torch.float16, device=self.device)
+        self.logits = torch.empty((self.batch, classes), dtype=torch.float16, device=self.device)
+
+    def forward(self, image):
+        """Enqueue one forward pass on the current stream; returns (probs, logits) float16 device tensors."""
+        import torch
+        _dev(image, "image", torch.float16)
+        size = int(self.variant.image_size)
+        if tuple(image.shape) != (self.batch, size, size, 3):
+            raise TypeError("image must be [%d,%d,%d,3]" % (self.batch, size, size))
+        _check(lib().tfx_mobilenet_v1_forward_f16(ctypes.byref(self.variant), image.data_ptr(), self.batch,
+                                                  ctypes.byref(self.struct), self.workspace.data_ptr(),
+                                                  self.workspace.numel(), self.probs.data_ptr(), self.logits.data_ptr(),
+                                                  _stream(image)), "tfx_mobilenet_v1_forward_f16")
+        return self.probs, self.logits

@@ -101,7 +101,7 @@ bool valid_variant(const tfx_mobilenet_v1_variant* v) {
          v->classes >= 1 && v->classes <= 1024;
 }
 
-NetPlan plan_net(const tfx_mobilenet_v1_variant& v, int64_t batch) {
+NetPlan plan_net(const tfx_mobilenet_v1_variant& v, int64_t batch, size_t elem_bytes = sizeof(float)) {
   NetPlan p{};
   // largest feature map: the output of the first pointwise layer (half the image size, 64 alpha channels)
   const size_t half = (size_t)(v.image_size + 1) / 2;
@@ -109,7 +109,7 @@ NetPlan plan_net(const tfx_mobilenet_v1_variant& v, int64_t batch) {
   size_t off = 0;
   for (int i = 0; i < 2; ++i) {
     p.off_buf[i] = off;
-    off = align_up(off + p.act_floats * sizeof(float));
+    off = align_up(off + p.act_floats * elem_bytes);
   }
   p.off_partial = off;  // K-slice partial sums of the fully connected layer
   off = align_up(off + fc_partial_floats((int)batch, (int)(kFeatures * v.width_quarters / 4), (int)v.classes) * sizeof(float));
@@ -266,6 +266,43 @@ int tfx_batch_matmul_f16(const uint16_t* a, const int64_t a_shape[3], const uint
                          static_cast<hipStream_t>(stream));
 }
 
+int tfx_conv2d_f16(const uint16_t* x, const int64_t x_shape[4], const uint16_t* filter, const int64_t f_shape[4],
+                   const uint16_t* bias, int stride_h, int stride_w, tfx_padding pad, tfx_activation act, uint16_t* y,
+                   void* stream) {
+  if (!x || !filter || !y || !x_shape || !f_shape) return TFX_ERR_NULL;
+  if (!valid_act((int)act)) return TFX_ERR_ARG;
+  ConvGeom g;
+  int rc = conv_geometry(x_shape, f_shape, stride_h, stride_w, (int)pad, false, &g);
+  if (rc) return rc;
+  if (numel(x_shape, 4) < 0 || numel(f_shape, 4) < 0 || numel(g.out, 4) < 0) return TFX_ERR_UNSUPPORTED;
+  const int n = (int)x_shape[0], h = (int)x_shape[1], w = (int)x_shape[2], ci = (int)x_shape[3];
+  const int fh = (int)f_shape[0], fw = (int)f_shape[1], co = (int)f_shape[3];
+  const int oh = (int)g.out[1], ow = (int)g.out[2];
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // a 1x1 stride-1 convolution is the matMul of the pixel rows [n*h*w, ci] with the filter [ci, co]
+  if (fh == 1 && fw == 1 && stride_h == 1 && stride_w == 1)
+    return launch_gemm_f16(x, filter, y, bias, 1, n * h * w, co, ci, true, false, (int)act, s);
+  if (conv2d_stem_f16_supported(ci, fh, fw, co, y))
+    return launch_conv2d_stem_f16(x, filter, bias, y, n, h, w, co, oh, ow, stride_h, stride_w, (int)g.pad[0],
+                                  (int)g.pad[2], (int)act, s);
+  return launch_conv2d_direct_f16(x, filter, bias, y, n, h, w, ci, fh, fw, co, oh, ow, stride_h, stride_w,
+                                  (int)g.pad[0], (int)g.pad[2], (int)act, s);
+}
+
+int tfx_depthwise_conv2d_f16(const uint16_t* x, const int64_t x_shape[4], const uint16_t* filter,
+                             const int64_t f_shape[4], const uint16_t* bias, int stride_h, int stride_w,
+                             tfx_padding pad, tfx_activation act, uint16_t* y, void* stream) {
+  if (!x || !filter || !y || !x_shape || !f_shape) return TFX_ERR_NULL;
+  if (!valid_act((int)act)) return TFX_ERR_ARG;
+  ConvGeom g;
+  int rc = conv_geometry(x_shape, f_shape, stride_h, stride_w, (int)pad, true, &g);
+  if (rc) return rc;
+  if (numel(x_shape, 4) < 0 || numel(f_shape, 4) < 0 || numel(g.out, 4) < 0) return TFX_ERR_UNSUPPORTED;
+  return launch_depthwise_f16(x, filter, bias, y, (int)x_shape[0], (int)x_shape[1], (int)x_shape[2], (int)x_shape[3],
+                              (int)f_shape[0], (int)f_shape[1], (int)f_shape[3], (int)g.out[1], (int)g.out[2], stride_h,
+                              stride_w, (int)g.pad[0], (int)g.pad[2], (int)act, static_cast<hipStream_t>(stream));
+}
+
 size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch) {
   if (batch < 1 || batch > 1024) return 0;
   return plan_net(kBaseVariant, batch).bytes;
@@ -329,6 +366,59 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
   hipStream_t s = static_cast<hipStream_t>(stream);
   return launch_pool_fc_softmax(buf[cur], weights->fc_w, weights->fc_b, partial, logits, probs, (int)batch,
                                 (int)(shape[1] * shape[2]), (int)shape[3], (int)variant->classes, s);
+}
+
+size_t tfx_mobilenet_v1_workspace_bytes_f16(const tfx_mobilenet_v1_variant* variant, int64_t batch) {
+  if (!valid_variant(variant) || batch < 1 || batch > 1024) return 0;
+  return plan_net(*variant, batch, sizeof(uint16_t)).bytes;
+}
+
+int tfx_mobilenet_v1_forward_f16(const tfx_mobilenet_v1_variant* variant, const uint16_t* input, int64_t batch,
+                                 const tfx_mobilenet_v1_weights_f16* weights, void* workspace,
+                                 size_t workspace_bytes, uint16_t* probs, uint16_t* logits, void* stream) {
+  if (!variant || !input || !weights || !workspace || !probs) return TFX_ERR_NULL;
+  if (!weights->conv0_w || !weights->conv0_b || !weights->fc_w || !weights->fc_b) return TFX_ERR_NULL;
+  for (int i = 0; i < kBlocks; ++i)
+    if (!weights->dw_w[i] || !weights->dw_b[i] || !weights->pw_w[i] || !weights->pw_b[i]) return TFX_ERR_NULL;
+  if (!valid_variant(variant)) return TFX_ERR_ARG;
+  if (batch < 1) return TFX_ERR_SHAPE;
+  if (batch > 1024) return TFX_ERR_UNSUPPORTED;
+  const NetPlan plan = plan_net(*variant, batch, sizeof(uint16_t));
+  if (workspace_bytes < plan.bytes || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TFX_ERR_WORKSPACE;
+  const int q = (int)variant->width_quarters;
+
+  char* ws = static_cast<char*>(workspace);
+  uint16_t* buf[2] = {reinterpret_cast<uint16_t*>(ws + plan.off_buf[0]), reinterpret_cast<uint16_t*>(ws + plan.off_buf[1])};
+  float* partial = reinterpret_cast<float*>(ws + plan.off_partial);
+
+  int64_t shape[4] = {batch, variant->image_size, variant->image_size, 3};
+  const int64_t f0[4] = {3, 3, 3, kStemChannels * q / 4};
+  int rc = tfx_conv2d_f16(input, shape, weights->conv0_w, f0, weights->conv0_b, 2, 2, TFX_PAD_SAME, TFX_ACT_RELU6,
+                          buf[0], stream);
+  if (rc) return rc;
+  ConvGeom g;
+  conv_geometry(shape, f0, 2, 2, TFX_PAD_SAME, false, &g);
+  for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
+  int cur = 0;
+  for (int b = 0; b < kBlocks; ++b) {
+    const int64_t fd[4] = {3, 3, shape[3], 1};
+    rc = tfx_depthwise_conv2d_f16(buf[cur], shape, weights->dw_w[b], fd, weights->dw_b[b], kStrides[b], kStrides[b],
+                                  TFX_PAD_SAME, TFX_ACT_RELU6, buf[cur ^ 1], stream);
+    if (rc) return rc;
+    conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
+    for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
+    cur ^= 1;
+    const int64_t cout = kChannels[b] * q / 4;
+    const int64_t fp[4] = {1, 1, shape[3], cout};
+    rc = tfx_conv2d_f16(buf[cur], shape, weights->pw_w[b], fp, weights->pw_b[b], 1, 1, TFX_PAD_SAME, TFX_ACT_RELU6,
+                        buf[cur ^ 1], stream);
+    if (rc) return rc;
+    shape[3] = cout;
+    cur ^= 1;
+  }
+  return launch_pool_fc_softmax_f16(buf[cur], weights->fc_w, weights->fc_b, partial, logits, probs, (int)batch,
+                                    (int)(shape[1] * shape[2]), (int)shape[3], (int)variant->classes,
+                                    static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

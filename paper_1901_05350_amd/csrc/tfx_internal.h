@@ -76,6 +76,21 @@ int launch_add_f16(const uint16_t* a, const uint16_t* b, uint16_t* c, long long 
 int launch_gemm_f16(const uint16_t* a, const uint16_t* b, uint16_t* c, const uint16_t* bias, int batch, int m, int n,
                     int k, bool a_kc, bool b_kc, int act, hipStream_t stream);
 
+// conv2d, depthwiseConv2d and the MobileNet tail on IEEE binary16 storage (fp32 accumulation).
+int launch_conv2d_direct_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int n, int h,
+                             int wd, int ci, int fh, int fw, int co, int oh, int ow, int sh, int sw, int pt, int pl,
+                             int act, hipStream_t stream);
+bool conv2d_stem_f16_supported(int ci, int fh, int fw, int co, const void* y);
+int launch_conv2d_stem_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int n, int h,
+                           int wd, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act,
+                           hipStream_t stream);
+int launch_depthwise_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int n, int h, int wd,
+                         int c, int fh, int fw, int mult, int oh, int ow, int sh, int sw, int pt, int pl, int act,
+                         hipStream_t stream);
+int launch_pool_fc_softmax_f16(const uint16_t* a, const uint16_t* w, const uint16_t* bias, float* partial,
+                               uint16_t* logits, uint16_t* probs, int n, int hw, int k, int classes,
+                               hipStream_t stream);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? TFX_OK : TFX_ERR_LAUNCH; }
 
 }  // namespace tfx

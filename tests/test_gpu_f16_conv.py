@@ -1,0 +1,157 @@
+"""GPU parity on 16-bit float storage: conv2d, depthwiseConv2d and the MobileNet forward against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import ACT_NONE, ACT_RELU, ACT_RELU6, PAD_SAME, PAD_VALID
+from paper_1901_05350_amd import inputs
+from util import assert_close_f16, dev16, host
+
+pytestmark = pytest.mark.gpu
+
+
+def h(a):
+    return np.ascontiguousarray(a).astype(np.float16)
+
+
+def conv_case(seed, n, hh, ww, cin, cout, fh, fw):
+    d = inputs.conv_general(seed, n, hh, ww, cin, cout, fh, fw)
+    return h(d["x"]), h(d["filter"]), h(d["bias"] * 30)     # a bias large enough to matter in binary16
+
+
+@pytest.mark.parametrize("shape,stride,pad,act", [
+    ((2, 56, 56, 128, 128, 1, 1), 1, PAD_SAME, ACT_RELU6),      # pointwise: matMul path, B stored [K,N]
+    ((1, 14, 14, 512, 512, 1, 1), 1, PAD_SAME, ACT_RELU6),
+    ((3, 9, 7, 24, 40, 1, 1), 1, PAD_VALID, ACT_NONE),
+    ((2, 10, 10, 6, 10, 1, 1), 1, PAD_SAME, ACT_RELU),          # channel counts that are not multiples of 8
+    ((2, 224, 224, 3, 32, 3, 3), 2, PAD_SAME, ACT_RELU6),       # the stem
+    ((1, 97, 101, 3, 8, 3, 3), 2, PAD_SAME, ACT_RELU6),
+    ((1, 33, 35, 3, 24, 3, 3), 1, PAD_VALID, ACT_NONE),
+    ((2, 17, 19, 5, 7, 3, 3), 2, PAD_SAME, ACT_RELU6),          # general direct kernel
+    ((1, 12, 12, 16, 8, 5, 2), 3, PAD_VALID, ACT_RELU),
+    ((2, 8, 8, 32, 16, 1, 1), 2, PAD_SAME, ACT_NONE),           # 1x1 with stride 2 is not a plain matMul
+])
+def test_conv2d_f16(shape, stride, pad, act):
+    import paper_1901_05350_amd as tfx
+    n, hh, ww, cin, cout, fh, fw = shape
+    x, f, b = conv_case(100 + cin + cout, n, hh, ww, cin, cout, fh, fw)
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), dev16(b), stride, pad, act))
+    assert_close_f16(got, oracle.conv2d_f16(x, f, b, stride, pad, act), "conv2d_f16 %r s%d" % (shape, stride))
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), None, stride, pad, ACT_NONE))
+    assert_close_f16(got, oracle.conv2d_f16(x, f, None, stride, pad, ACT_NONE), "conv2d_f16 no bias %r" % (shape,))
+
+
+@pytest.mark.parametrize("shape,stride,pad,mult", [
+    ((2, 112, 112, 64), 1, PAD_SAME, 1), ((2, 112, 112, 64), 2, PAD_SAME, 1), ((64, 56, 56, 128), 1, PAD_SAME, 1),
+    ((1, 14, 14, 512), 1, PAD_SAME, 1), ((3, 7, 7, 1024), 1, PAD_SAME, 1), ((1, 14, 14, 512), 2, PAD_SAME, 1),
+    ((2, 13, 17, 16), 1, PAD_VALID, 1), ((2, 31, 29, 8), 2, PAD_SAME, 1), ((16, 28, 28, 256), 2, PAD_SAME, 1),
+    ((2, 9, 11, 12), 1, PAD_SAME, 1),          # C % 8 != 0: general kernel
+    ((1, 10, 10, 8), 1, PAD_SAME, 2), ((1, 12, 9, 5), 2, PAD_VALID, 3),
+])
+def test_depthwise_f16(shape, stride, pad, mult):
+    import paper_1901_05350_amd as tfx
+    n, hh, ww, c = shape
+    rng = np.random.default_rng(200 + c + stride)
+    x = h(rng.uniform(-1, 1, shape))
+    f = h(rng.standard_normal((3, 3, c, mult)) * (2.0 / 9) ** 0.5)
+    b = h(rng.standard_normal(c * mult) * 0.3)
+    xs = x if n <= 16 else x                      # the oracle handles these sizes in a few seconds
+    got = host(tfx.tfx_depthwise_conv2d_f16(dev16(xs), dev16(f), dev16(b), stride, pad, ACT_RELU6))
+    assert_close_f16(got, oracle.depthwise_conv2d_f16(xs, f, b, stride, pad, ACT_RELU6), "depthwise_f16 %r s%d" % (shape, stride))
+
+
+def test_f16_conv_rounds_once_and_handles_unaligned_buffers():
+    import torch
+    import paper_1901_05350_amd as tfx
+    # 2048 + 1 + 1 across three taps must give 2050 (a binary16 running sum would stay at 2048)
+    xs = np.array([2048, 1, 1], np.float16).reshape(1, 1, 3, 1)
+    ws = np.ones((1, 3, 1, 1), np.float16)
+    assert host(tfx.tfx_conv2d_f16(dev16(xs), dev16(ws), None, 1, PAD_VALID))[0, 0, 0, 0] == np.float16(2050)
+    assert host(tfx.tfx_depthwise_conv2d_f16(dev16(xs), dev16(ws), None, 1, PAD_VALID))[0, 0, 0, 0] == np.float16(2050)
+    # operands that start 2 bytes off a 16-byte boundary take the general paths
+    rng = np.random.default_rng(7)
+    x = h(rng.uniform(-1, 1, (1, 12, 12, 16)))
+    f = h(rng.standard_normal((3, 3, 16, 1)) * 0.4)
+    b = h(rng.standard_normal(16) * 0.1)
+    off = lambda a: dev16(np.concatenate([np.zeros(1, np.float16), a.ravel()]))[1:].view(a.shape)
+    got = host(tfx.tfx_depthwise_conv2d_f16(off(x), off(f), off(b), 1, PAD_SAME, ACT_RELU6))
+    assert_close_f16(got, oracle.depthwise_conv2d_f16(x, f, b, 1, PAD_SAME, ACT_RELU6), "unaligned depthwise_f16")
+    fp = h(rng.standard_normal((1, 1, 16, 24)) * 0.3)
+    bp = h(rng.standard_normal(24) * 0.1)
+    out = torch.zeros(12 * 12 * 24 + 2, dtype=torch.float16, device="cuda:0")
+    tfx.tfx_conv2d_f16(off(x), off(fp), off(bp), 1, PAD_SAME, ACT_RELU6, out=out[1:-1].view(1, 12, 12, 24))
+    o = host(out)
+    assert o[0] == 0 and o[-1] == 0
+    assert_close_f16(o[1:-1].reshape(1, 12, 12, 24), oracle.conv2d_f16(x, fp, bp, 1, PAD_SAME, ACT_RELU6), "unaligned pointwise f16")
+    with pytest.raises(TypeError):
+        tfx.tfx_conv2d_f16(dev16(x), dev16(fp).float(), None)
+
+
+@pytest.fixture(scope="module")
+def net16():
+    data = inputs.mobilenet_v1_f16(seed=4, batch=1)
+    probs, logits, acts = oracle.mobilenet_v1_forward_f16(data["image"], data["weights"], return_activations=True)
+    return data, probs, logits, acts
+
+
+def test_mobilenet_f16_layer_by_layer_each_fed_the_oracle_input(net16):
+    import paper_1901_05350_amd as tfx
+    data, probs, logits, acts = net16
+    w = data["weights"]
+    got = host(tfx.tfx_conv2d_f16(dev16(data["image"]), dev16(w["conv0_w"]), dev16(w["conv0_b"]), 2, PAD_SAME, ACT_RELU6))
+    assert_close_f16(got, acts[0], "f16 conv0")
+    for i in range(13):
+        s = oracle.MOBILENET_V1_STRIDES[i]
+        got = host(tfx.tfx_depthwise_conv2d_f16(dev16(acts[2 * i]), dev16(w["dw_w"][i]), dev16(w["dw_b"][i]), s, PAD_SAME, ACT_RELU6))
+        assert_close_f16(got, acts[2 * i + 1], "f16 dw%d" % (i + 1))
+        got = host(tfx.tfx_conv2d_f16(dev16(acts[2 * i + 1]), dev16(w["pw_w"][i]), dev16(w["pw_b"][i]), 1, PAD_SAME, ACT_RELU6))
+        assert_close_f16(got, acts[2 * i + 2], "f16 pw%d" % (i + 1))
+
+
+def end_to_end_bar(got, ref, what, steps):
+    """End to end, a one-step rounding difference in one layer's output moves the next layers' sums by a few
+    hundredths of a step each, so outputs may differ by a few binary16 steps; the exact bar applies layer by
+    layer (above).  Here: at most `steps` binary16 steps at the magnitude of the row's largest entry (a logit
+    near zero is a sum of terms of that magnitude)."""
+    g, r = got.astype(np.float64), ref.astype(np.float64)
+    bound = steps * np.spacing(np.abs(ref).max(axis=1, keepdims=True)).astype(np.float64)
+    assert np.isfinite(g).all() and (np.abs(g - r) <= bound).all(), (what, float(np.abs(g - r).max()), float(bound.min()))
+
+
+@pytest.mark.parametrize("size,q,classes,batch", [(224, 4, 1000, 1), (224, 4, 1000, 3), (128, 1, 10, 2), (160, 2, 100, 1),
+                                                  (192, 3, 1000, 1), (100, 2, 5, 2)])
+def test_mobilenet_f16_end_to_end(size, q, classes, batch):
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1_f16(seed=30 + q, batch=batch, image_size=size, width_quarters=q, classes=classes)
+    probs, logits = oracle.mobilenet_v1_forward_f16(data["image"], data["weights"])
+    model = tfx.MobileNetV1F16(data["weights"], batch=batch, image_size=size, width_quarters=q)
+    p, l = model.forward(dev16(data["image"]))
+    p, l = host(p).copy(), host(l).copy()
+    assert p.dtype == np.float16 and p.shape == (batch, classes)
+    end_to_end_bar(l, logits, "f16 logits", 8)
+    end_to_end_bar(p, probs, "f16 probs", 16)
+    assert np.array_equal(p.argmax(axis=1), probs.argmax(axis=1))
+    assert np.abs(p.astype(np.float64).sum(axis=1) - 1).max() < 2e-3
+    p2, l2 = model.forward(dev16(data["image"]))
+    assert np.array_equal(host(p2), p) and np.array_equal(host(l2), l)
+
+
+def test_mobilenet_f16_argument_checks():
+    import ctypes
+    import paper_1901_05350_amd as tfx
+    from paper_1901_05350_amd import binding
+    L = tfx.lib()
+    V = binding.TfxVariant
+    n32 = tfx.tfx_mobilenet_v1_variant_workspace_bytes(V(224, 4, 1000), 1)
+    n16 = int(L.tfx_mobilenet_v1_workspace_bytes_f16(ctypes.byref(V(224, 4, 1000)), 1))
+    assert 0 < n16 < n32 and n16 % 256 == 0
+    assert int(L.tfx_mobilenet_v1_workspace_bytes_f16(ctypes.byref(V(224, 9, 1000)), 1)) == 0
+    data = inputs.mobilenet_v1_f16(seed=4, batch=1, image_size=64, width_quarters=1, classes=10)
+    model = tfx.MobileNetV1F16(data["weights"], batch=1, image_size=64, width_quarters=1)
+    img = dev16(data["image"])
+    rc = L.tfx_mobilenet_v1_forward_f16(ctypes.byref(model.variant), img.data_ptr(), 1, ctypes.byref(model.struct),
+                                        model.workspace.data_ptr(), 16, model.probs.data_ptr(), None, None)
+    assert rc == -5
+    rc = L.tfx_mobilenet_v1_forward_f16(ctypes.byref(V(64, 0, 10)), img.data_ptr(), 1, ctypes.byref(model.struct),
+                                        model.workspace.data_ptr(), model.workspace.numel(), model.probs.data_ptr(), None, None)
+    assert rc == -3
