@@ -189,6 +189,28 @@ def main():
             return e
         return build
 
+    def op_depthwise_f16(n, s, copies):
+        """Depthwise 3x3 112x112x64 + bias + ReLU6 on 16-bit float storage (cold rotation as op_depthwise)."""
+        def build():
+            d = inputs.depthwise_conv(seed=2, n=n)
+            h16 = lambda a: dev(a).to(torch.float16)
+            ff, bb = h16(d["filter"]), h16(d["bias"])
+            xs = [h16(d["x"])]
+            for _ in range(copies - 1):
+                xs.append(xs[0].clone())
+            ys = [tfx.tfx_depthwise_conv2d_f16(xv, ff, bb, s, tfx.PAD_SAME, tfx.ACT_RELU6) for xv in xs]
+            nbytes = 2 * (xs[0].numel() + ys[0].numel() + 9 * 64 + 64)
+            state = {"i": 0}
+
+            def fn():
+                i = state["i"] = (state["i"] + 1) % copies
+                tfx.tfx_depthwise_conv2d_f16(xs[i], ff, bb, s, tfx.PAD_SAME, tfx.ACT_RELU6, out=ys[i])
+            t = time_loop(fn, max(reps, copies * 2), warmup=copies, inner=copies if copies > 1 else None)
+            return {"us": round(t * 1e6, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
+                    "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
+                                 "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
+        return build
+
     def op_copy():
         """Plain device-to-device copy of 205.5 MB (a framework elementwise kernel, not part of the library):
         the known-size reference that the HBM traffic counters are scaled by."""
@@ -272,6 +294,8 @@ def main():
     single_ops["batch_matmul_f16_1x4096x4096x4096"] = op_matmul_f16(1, 4096, 4096, 4096, tb=False)
     single_ops["pointwise_f16_64x56x56x128_to_128"] = op_pointwise_f16(64)
     single_ops["pointwise_f16_8x56x56x128_to_128"] = op_pointwise_f16(8)
+    single_ops["depthwise_f16_64x112x112x64_s1_cold_rotation"] = op_depthwise_f16(64, 1, 6)
+    single_ops["depthwise_f16_64x112x112x64_s2_cold_rotation"] = op_depthwise_f16(64, 2, 6)
     single_ops["add_f32_64M"] = op_add(1 << 26, False)
     single_ops["add_f16_64M"] = op_add(1 << 26, True)
     calibration_ops = {"copy_calibration_205MB": op_copy}
@@ -413,6 +437,18 @@ def main():
             family["%.2f_%d" % (q / 4, size)] = {"ms_per_inference": round(t * 1e3, 5)}
             del mv, img
         out["mobilenet_family_b1"] = family
+
+        # ---------------- the same network on 16-bit float storage (fp32 accumulation), batch 1 / 8 / 64 ----------
+        d16 = inputs.mobilenet_v1_f16(seed=4, batch=1)
+        half = {}
+        for nb in (1, 8, 64):
+            m16 = tfx.MobileNetV1F16(d16["weights"], batch=nb)
+            imgs = torch.empty((nb, 224, 224, 3), device="cuda:0").uniform_(-1, 1).to(torch.float16)
+            t = time_loop(lambda: m16.forward(imgs), max(20, reps // 4), warmup=3, inner=5)
+            half["batch_%d" % nb] = {"ms_per_batch": round(t * 1e3, 4), "images_per_s": round(nb / t, 1),
+                                     "TFLOPs": round(nb * 1.137480704e9 / t / 1e12, 3)}
+            del m16, imgs
+        out["mobilenet_f16"] = half
 
     # ---------------- CPU oracle on the host cores (baseline only) ----------------
     if not args.no_cpu_baseline:

@@ -461,6 +461,134 @@ int launch_cfg(const half_t* a, const half_t* b, half_t* c, const half_t* bias, 
   return check_launch();
 }
 
+// Small M x N (the 28x28 ... 7x7 pointwise layers of a batch-1 MobileNet: 49 ... 3136 rows): too few
+// 64 x 64 tiles for 256 CUs, and each tile is bound by memory latency, not by the matrix cores.
+// 16 x 32 tiles (v_mfma_f32_16x16x32_f16), a tile as deep as K up to 512 so that the whole K panel is
+// in flight in one memory round trip, the depth split over 8 wavefronts whose partial tiles are
+// added through LDS by the 512 threads that also apply the epilogue.  A stored [M,K], B stored
+// [K,N] (N % 8 == 0, K % 8 == 0, 16-byte aligned); B goes through the 4 x 8 register transpose
+// of the pipelined kernel.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(512) void gemm_f16_small_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
+                                                             half_t* __restrict__ C, const half_t* __restrict__ bias,
+                                                             int M, int N, int K, int tiles_m, int tiles_n,
+                                                             int total_blocks, long long strideA, long long strideB,
+                                                             long long strideC, int act) {
+  constexpr int BM = 16, BN = 32, BKS = 512, LD = BKS + 8, NT = 512, WAVES_K = 8;
+  __shared__ __align__(16) half_t lds[(BM + BN) * LD];
+  half_t* const lds_a = lds;
+  half_t* const lds_b = lds + BM * LD;
+
+  const int bid = blockIdx.x;
+  const int q8 = total_blocks / kXcds, rem = total_blocks % kXcds;
+  const int xcd = bid % kXcds;
+  const int vid = xcd * q8 + (xcd < rem ? xcd : rem) + bid / kXcds;
+  const int tiles = tiles_m * tiles_n;
+  const int batch = vid / tiles;
+  const int t = vid % tiles;
+  const int tile_m = t % tiles_m, tile_n = t / tiles_m;  // consecutive workgroups share a column panel of B
+
+  A += (size_t)batch * strideA;
+  B += (size_t)batch * strideB;
+  C += (size_t)batch * strideC;
+
+  const int tid = threadIdx.x;
+  const int wk = tid / 64, lane = tid % 64;
+  const int li = lane % 16, q = lane / 16;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // epilogue thread e owns the value of register v of lane l of column block j, e = (j * 4 + v) * 64 + l
+  const int ej = tid / 256, ev = (tid / 64) % 4, el = tid % 64;
+  const int erow = m0 + 4 * (el / 16) + ev, ecol = n0 + 16 * ej + el % 16;
+  float ebias = 0.f;
+  if (bias != nullptr && ecol < N) ebias = (float)bias[ecol];
+
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  // A: 2 slots per thread, slot s = tid + 512 i: row s / 64, halfs 8 (s % 64) ... + 7
+  // B: thread (kq = tid / 4, nb = tid % 4) owns k-rows 4 kq ... + 3 of columns 8 nb ... + 7
+  u32x4 ra[2], rb[4];
+  const int kq = tid / 4, nb = tid % 4;
+  const unsigned bcol = n0 + 8 * nb < N ? (unsigned)(n0 + 8 * nb) : 0u;
+  auto load = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int s = tid + i * NT;
+      const int row = min(m0 + s / 64, M - 1), k = k0 + 8 * (s % 64);
+      ra[i] = *reinterpret_cast<const u32x4*>(A + (size_t)((unsigned)row * (unsigned)K + (k < K ? (unsigned)k : 0u)));
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int k = k0 + 4 * kq + kk;
+      rb[kk] = *reinterpret_cast<const u32x4*>(B + (size_t)((k < K ? (unsigned)k : 0u) * (unsigned)N + bcol));
+    }
+  };
+  auto store = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int s = tid + i * NT;
+      const unsigned mask = k0 + 8 * (s % 64) < K ? 0xffffffffu : 0u;
+      *reinterpret_cast<u32x4*>(lds_a + (s / 64) * LD + 8 * (s % 64)) = ra[i] & mask;
+    }
+    h8 r[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const unsigned mask = k0 + 4 * kq + kk < K ? 0xffffffffu : 0u;
+      r[kk] = __builtin_bit_cast(h8, rb[kk] & mask);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const h4 o = {r[0][i], r[1][i], r[2][i], r[3][i]};
+      *reinterpret_cast<h4*>(lds_b + (8 * nb + i) * LD + 4 * kq) = o;
+    }
+  };
+
+  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  const int nk = (K + BKS - 1) / BKS;
+  load(0);
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt > 0) __syncthreads();  // everyone has finished reading the previous slice
+    store(kt * BKS);
+    __syncthreads();
+    if (kt + 1 < nk) load((kt + 1) * BKS);
+#pragma unroll
+    for (int s = 0; s < BKS / WAVES_K / 32; ++s) {
+      const int kb = wk * (BKS / WAVES_K) + 32 * s;  // this wavefront's 32 k of the slice
+      if (kt * BKS + kb >= K) break;                 // past the end of K: zeros
+      const h8 fa = *reinterpret_cast<const h8*>(lds_a + li * LD + kb + 8 * q);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const h8 fb = *reinterpret_cast<const h8*>(lds_b + (16 * j + li) * LD + kb + 8 * q);
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa, fb, acc[j], 0, 0, 0);
+      }
+    }
+  }
+
+  // add the 8 partial tiles through LDS: layout [wk][j][v][lane]
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(lds);
+  static_assert(WAVES_K * 2 * 4 * 64 * sizeof(float) <= sizeof(lds), "reduction reuses the slice buffers");
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[(wk * 8 + j * 4 + v) * 64 + lane] = acc[j][v];
+  __syncthreads();
+  float sum = ebias;
+#pragma unroll
+  for (int w = 0; w < WAVES_K; ++w) sum += red[w * 512 + tid];
+  if (erow < M && ecol < N) C[(size_t)erow * N + ecol] = (half_t)apply_act(sum, make_act(act));
+}
+
+int launch_small(const half_t* a, const half_t* b, half_t* c, const half_t* bias, int batch, int m, int n, int k,
+                 int act, hipStream_t stream) {
+  const int tiles_m = (m + 15) / 16, tiles_n = (n + 31) / 32;
+  const long long total = (long long)batch * tiles_m * tiles_n;
+  if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(gemm_f16_small_kernel, dim3((unsigned)total), dim3(512), 0, stream, a, b, c, bias, m, n, k,
+                     tiles_m, tiles_n, (int)total, (long long)m * k, (long long)n * k, (long long)m * n, act);
+  return check_launch();
+}
+
 }  // namespace
 
 int launch_gemm_f16(const uint16_t* a16, const uint16_t* b16, uint16_t* c16, const uint16_t* bias16, int batch, int m,
@@ -496,7 +624,9 @@ int launch_gemm_f16(const uint16_t* a16, const uint16_t* b16, uint16_t* c16, con
   if (vec_kn) {
     if (tiles(256, 256) >= 192 && fits(256, 256))
       return launch_pipe<2, 4, 4, 2, false>(a, b, c, bias, batch, m, n, k, true, false, act, stream);
-    return launch_pipe<2, 2, 2, 2, false>(a, b, c, bias, batch, m, n, k, true, false, act, stream);
+    if (tiles(128, 128) >= 128) return launch_pipe<2, 2, 2, 2, false>(a, b, c, bias, batch, m, n, k, true, false, act, stream);
+    if (tiles(64, 64) >= 128) return launch_pipe<2, 1, 1, 2, false>(a, b, c, bias, batch, m, n, k, true, false, act, stream);
+    return launch_small(a, b, c, bias, batch, m, n, k, act, stream);
   }
   if (tiles(128, 128) >= 256) return launch_cfg<2, 2, 2, 2>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, act, stream);
   return launch_cfg<2, 2, 1, 1>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, act, stream);

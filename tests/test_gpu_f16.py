@@ -96,7 +96,10 @@ def test_matmul_f16_layouts_and_ragged_shapes(ta, tb, shape):
                                          ((1, 4100, 4090, 136), False, True), ((2, 1, 1, 16), False, True),
                                          ((1, 2048, 2048, 72), False, False), ((2, 4096, 2048, 64), False, False),
                                          ((1, 3136, 128, 128), False, False), ((3, 100, 8, 8), False, False),
-                                         ((1, 4100, 4088, 136), False, False)])
+                                         ((1, 4100, 4088, 136), False, False),
+                                         ((1, 196, 512, 512), False, False), ((1, 49, 1024, 1024), False, False),
+                                         ((1, 3136, 128, 64), False, False), ((2, 50, 40, 72), False, False),
+                                         ((1, 12544, 64, 32), False, False), ((1, 700, 520, 1032), False, False)])
 def test_matmul_f16_tile_configurations(shape, ta, tb):
     """Each tile size of the 16-byte-load kernel (A [M,K], B stored [N,K]) and of the element-wise
     loader (other layouts), checked on sampled rows."""
