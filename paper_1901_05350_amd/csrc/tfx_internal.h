@@ -91,6 +91,11 @@ int launch_pool_fc_softmax_f16(const uint16_t* a, const uint16_t* w, const uint1
                                uint16_t* logits, uint16_t* probs, int n, int hw, int k, int classes,
                                hipStream_t stream);
 
+// Filter-stationary pointwise conv on binary16 storage for thin filters and large M.
+bool pointwise_stream_f16_supported(int m, int k, int n, const void* x, const void* w, const void* y);
+int launch_pointwise_stream_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int m, int k,
+                                int n, int act, hipStream_t stream);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? TFX_OK : TFX_ERR_LAUNCH; }
 
 }  // namespace tfx

@@ -21,6 +21,10 @@ def conv_case(seed, n, hh, ww, cin, cout, fh, fw):
 
 @pytest.mark.parametrize("shape,stride,pad,act", [
     ((2, 56, 56, 128, 128, 1, 1), 1, PAD_SAME, ACT_RELU6),      # pointwise: matMul path, B stored [K,N]
+    ((8, 56, 56, 128, 128, 1, 1), 1, PAD_SAME, ACT_RELU6),      # M >= 16384 with a thin filter: filter-stationary kernel
+    ((2, 112, 112, 32, 64, 1, 1), 1, PAD_SAME, ACT_RELU6),
+    ((7, 57, 53, 64, 128, 1, 1), 1, PAD_SAME, ACT_RELU),        # M = 21147: ragged last unit
+    ((6, 56, 56, 128, 256, 1, 1), 1, PAD_SAME, ACT_NONE),
     ((1, 14, 14, 512, 512, 1, 1), 1, PAD_SAME, ACT_RELU6),
     ((3, 9, 7, 24, 40, 1, 1), 1, PAD_VALID, ACT_NONE),
     ((2, 10, 10, 6, 10, 1, 1), 1, PAD_SAME, ACT_RELU),          # channel counts that are not multiples of 8
