@@ -29,16 +29,19 @@ PEAK_HBM = 8.0e12          # B/s
 # reading for a plain 205.5 MB copy (profiles/hbm_traffic_counters.txt).  Each entry names the kernel
 # source it was measured on; if that file has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100836282, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
-    "pointwise_64x56x56x128_to_128": (207517153, "pointwise.hip", "50947f4fbda77ef9c2f55bb75007539b43300bcfb9c65a85012606b202e1827a"),
-    "conv3x3_64x56x56x64_to_64": (104622642, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411117531, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (256968137, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235060799, "gemm_f16.hip", "6178f4ba44378dc7407c0835bb2b047efc3219e91974686e8d30e584105f7bb3"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50481321, "gemm_f16.hip", "6178f4ba44378dc7407c0835bb2b047efc3219e91974686e8d30e584105f7bb3"),
-    "add_f32_64M": (805263098, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
-    "add_f16_64M": (402651971, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
-    "mobilenet_b1_gemm_13_launches": (53651612, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
+    "batch_matmul_8x1024x1024x1024_tB": (100836248, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
+    "pointwise_64x56x56x128_to_128": (207507859, "pointwise.hip", "50947f4fbda77ef9c2f55bb75007539b43300bcfb9c65a85012606b202e1827a"),
+    "conv3x3_64x56x56x64_to_64": (104629381, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411117332, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (256969578, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235060813, "gemm_f16.hip", "3cfafa2edff0aad16fa05d59662181687afc393b0c5786e74170f7bc59d16b22"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50476187, "gemm_f16.hip", "3cfafa2edff0aad16fa05d59662181687afc393b0c5786e74170f7bc59d16b22"),
+    "pointwise_f16_64x56x56x128_to_128": (103141760, "pointwise_f16.hip", "0b7c2bf74c636322c00f99f09b8bf098c5c38aec4d922af8763a90d3f0e45c51"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205667919, "conv_f16.hip", "efc626efab45e2289bcd9a49a547526219b0f58877adad5696699d83053e4b0d"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (128533989, "conv_f16.hip", "efc626efab45e2289bcd9a49a547526219b0f58877adad5696699d83053e4b0d"),
+    "add_f32_64M": (805263048, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
+    "add_f16_64M": (402651729, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
+    "mobilenet_b1_gemm_13_launches": (53651638, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
 }
 
 
@@ -208,7 +211,8 @@ def main():
             t = time_loop(fn, max(reps, copies * 2), warmup=copies, inner=copies if copies > 1 else None)
             return {"us": round(t * 1e6, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
                     "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
-                                 "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
+                                 "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5),
+                                 "traffic": measured_traffic("depthwise_f16_%dx112x112x64_s%d_cold_rotation" % (n, s))}}
         return build
 
     def op_copy():
@@ -285,7 +289,8 @@ def main():
             return {"us": round(t * 1e6, 3), "TFLOPs": round(flop / t / 1e12, 3), "GBps": round(nbytes / t / 1e9, 1),
                     "algorithmic_bytes": nbytes,
                     "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
-                                 "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5), "traffic": None}}
+                                 "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5),
+                                 "traffic": measured_traffic("pointwise_f16_%dx56x56x128_to_128" % n)}}
         return build
 
     single_ops = {"matmul_64x128x64": op_matmul, "batch_matmul_8x1024x1024x1024_tB": op_batch_matmul}
