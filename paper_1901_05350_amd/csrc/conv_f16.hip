@@ -123,9 +123,10 @@ __global__ __launch_bounds__(256) void depthwise3x3_f16_kernel(const half_t* __r
     win[i][1] = (rok && in1) ? *reinterpret_cast<const h8*>(p + C) : z;
     win[i][2] = (rok && in2) ? *reinterpret_cast<const h8*>(p + 2 * C) : z;
   }
-  h8 wt[9];
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 wraw[9];
 #pragma unroll
-  for (int t = 0; t < 9; ++t) wt[t] = *reinterpret_cast<const h8*>(w + (size_t)t * C + 8 * c8);
+  for (int t = 0; t < 9; ++t) wraw[t] = *reinterpret_cast<const u32x4*>(w + (size_t)t * C + 8 * c8);
   h8 bv = z;
   if (bias) bv = *reinterpret_cast<const h8*>(bias + 8 * c8);
   const ActClamp clamp = make_act(act);
@@ -133,6 +134,14 @@ __global__ __launch_bounds__(256) void depthwise3x3_f16_kernel(const half_t* __r
 #pragma unroll
   for (int o = 0; o < RS; ++o) {
     if (oh0 + o >= OH) break;
+    // The filter stays packed (36 registers): the empty asm makes its value opaque per output row, so the
+    // binary16 -> fp32 conversions are not hoisted into 72 more registers; the mixed FMA reads binary16 directly.
+    h8 wt[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      asm volatile("" : "+v"(wraw[t]));
+      wt[t] = __builtin_bit_cast(h8, wraw[t]);
+    }
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = (float)bv[e];
