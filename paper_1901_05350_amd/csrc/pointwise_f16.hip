@@ -99,8 +99,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream_f16_kernel(const ha
       constexpr int PW = 16 * NBP, LS = PW + 8;            // columns per pass, strip row stride
       constexpr int LPR = PW / 8, RPI = 64 / LPR;          // lanes per row, rows per store instruction
       half_t* strip = stage + (tid / 64) * 16 * LS;
-#pragma unroll
-      for (int slab = 0; slab < 2; ++slab) {
+      auto emit = [&](const f32x4 (&acc)[NBP], int slab) {
 #pragma unroll
         for (int j = 0; j < NBP; ++j) {
           const int col = 16 * j + 4 * q;
@@ -111,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream_f16_kernel(const ha
           }
           h4 o;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (half_t)apply_act((slab ? acc1[j][e] : acc0[j][e]) + bv[e], clamp);
+          for (int e = 0; e < 4; ++e) o[e] = (half_t)apply_act(acc[j][e] + bv[e], clamp);
           *reinterpret_cast<h4*>(strip + li * LS + col) = o;
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -125,7 +124,9 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream_f16_kernel(const ha
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-      }
+      };
+      emit(acc0, 0);
+      emit(acc1, 1);
     }
   }
 }
