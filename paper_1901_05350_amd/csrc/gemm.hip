@@ -329,13 +329,8 @@ int launch_cfg(const float* a, const float* b, float* c, const float* bias, int 
   constexpr size_t lds_bytes = 2 * (TA::kFloats + TB::kFloats) * sizeof(float);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
   auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, A_KC, B_KC, VEC, CONV>;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
-      return TFX_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes, lds_allowed) != TFX_OK) return TFX_ERR_LAUNCH;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
   const long long total = (long long)batch * tiles_m * tiles_n;
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
@@ -502,13 +497,8 @@ int launch_m16_cfg(const float* a, const float* b, float* c, const float* bias, 
   constexpr size_t lds_bytes = (TA::kFloats + TB::kFloats) * sizeof(float);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
   auto kern = gemm_m16_kernel<TN, BK, WAVES_K, A_KC, B_KC, VEC>;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
-      return TFX_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes, lds_allowed) != TFX_OK) return TFX_ERR_LAUNCH;
   const int tiles_m = (m + 15) / 16, tiles_n = (n + 16 * TN - 1) / (16 * TN);
   const long long total = (long long)batch * tiles_m * tiles_n;
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;

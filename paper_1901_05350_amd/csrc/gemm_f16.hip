@@ -418,13 +418,8 @@ int launch_pipe(const half_t* a, const half_t* b, half_t* c, const half_t* bias,
   constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * kLd * sizeof(half_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
   auto kern = gemm_f16_pipe_kernel<WAVES_M, WAVES_N, TM, TN, B_KC>;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
-      return TFX_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes, lds_allowed) != TFX_OK) return TFX_ERR_LAUNCH;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
   const long long total = (long long)batch * tiles_m * tiles_n;
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
@@ -443,13 +438,8 @@ int launch_cfg(const half_t* a, const half_t* b, half_t* c, const half_t* bias, 
   constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * kLd * sizeof(half_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
   auto kern = gemm_f16_kernel<WAVES_M, WAVES_N, TM, TN>;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
-      return TFX_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes, lds_allowed) != TFX_OK) return TFX_ERR_LAUNCH;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
   const long long total = (long long)batch * tiles_m * tiles_n;
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;

@@ -110,13 +110,8 @@ int launch_stream16(const float* x, const float* w, const float* bias, float* y,
   constexpr size_t lds_bytes = (size_t)K * (N + 4) * sizeof(float);
   static_assert(lds_bytes <= 160 * 1024, "filter must fit in LDS");
   auto kern = pointwise_stream16_kernel<K, N>;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
-      return TFX_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes, lds_allowed) != TFX_OK) return TFX_ERR_LAUNCH;
   const int slabs = (m + 15) / 16;
   // as many workgroups as fit on the chip at once (two per CU when the filter takes <= 80 KB of LDS)
   int blocks = lds_bytes <= 80 * 1024 ? 512 : 256;

@@ -138,13 +138,8 @@ int launch_stream_f16(const half_t* x, const half_t* w, const half_t* bias, half
   constexpr size_t lds_bytes = ((size_t)N * (K + 8) + 8 * 16 * (16 * NBP + 8)) * sizeof(half_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
   auto kern = pointwise_stream_f16_kernel<K, N>;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
-      return TFX_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes, lds_allowed) != TFX_OK) return TFX_ERR_LAUNCH;
   const int units = (m + 31) / 32;
   int blocks = lds_bytes <= 80 * 1024 ? 512 : 256;  // two workgroups per CU when the filter and strips allow
   if (blocks > (units + 7) / 8) blocks = (units + 7) / 8;

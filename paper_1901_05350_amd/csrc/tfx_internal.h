@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/tfx.h"
 
 namespace tfx {
@@ -97,6 +99,21 @@ int launch_pointwise_stream_f16(const uint16_t* x, const uint16_t* w, const uint
                                 int n, int act, hipStream_t stream);
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? TFX_OK : TFX_ERR_LAUNCH; }
+
+// A kernel that uses more than 64 KB of dynamic LDS has to be allowed to, once per device (the attribute
+// belongs to the kernel's code object on the current device).  `done` is the caller's per-kernel bitmask of
+// the devices already set up; callers launch on the current device.  Safe to call from several threads.
+inline int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done) {
+  if (bytes <= 64 * 1024) return TFX_OK;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return TFX_ERR_LAUNCH;
+  const uint64_t bit = (dev >= 0 && dev < 64) ? (1ull << dev) : 0;  // devices past 63 are set up on every call
+  if (bit != 0 && (done.load(std::memory_order_acquire) & bit) != 0) return TFX_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+    return TFX_ERR_LAUNCH;
+  done.fetch_or(bit, std::memory_order_release);
+  return TFX_OK;
+}
 
 }  // namespace tfx
 

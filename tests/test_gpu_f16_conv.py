@@ -64,6 +64,40 @@ def test_depthwise_f16(shape, stride, pad, mult):
     assert_close_f16(got, oracle.depthwise_conv2d_f16(xs, f, b, stride, pad, ACT_RELU6), "depthwise_f16 %r s%d" % (shape, stride))
 
 
+def test_f16_benchmark_sizes_sampled_images():
+    """The sizes the benchmark times (batch 64), whole images checked by the oracle one at a time."""
+    import paper_1901_05350_amd as tfx
+    n = 64
+    x, f, b = conv_case(300, n, 56, 56, 128, 128, 1, 1)
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), dev16(b), 1, PAD_SAME, ACT_RELU6))
+    for img in (0, 37, n - 1):
+        assert_close_f16(got[img:img + 1], oracle.conv2d_f16(x[img:img + 1], f, b, 1, PAD_SAME, ACT_RELU6),
+                         "pointwise f16 batch 64 image %d" % img)
+    rng = np.random.default_rng(301)
+    x = h(rng.uniform(-1, 1, (n, 112, 112, 64)))
+    f = h(rng.standard_normal((3, 3, 64, 1)) * (2.0 / 9) ** 0.5)
+    b = h(rng.standard_normal(64) * 0.3)
+    for stride in (1, 2):
+        got = host(tfx.tfx_depthwise_conv2d_f16(dev16(x), dev16(f), dev16(b), stride, PAD_SAME, ACT_RELU6))
+        for img in (0, 22, n - 1):
+            assert_close_f16(got[img:img + 1], oracle.depthwise_conv2d_f16(x[img:img + 1], f, b, stride, PAD_SAME, ACT_RELU6),
+                             "depthwise f16 batch 64 s%d image %d" % (stride, img))
+
+
+@pytest.mark.parametrize("batch", [8, 64])
+def test_mobilenet_f16_benchmark_batches_sampled_images(batch):
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1_f16(seed=9, batch=batch)
+    model = tfx.MobileNetV1F16(data["weights"], batch=batch)
+    p, l = model.forward(dev16(data["image"]))
+    p, l = host(p).copy(), host(l).copy()
+    for img in sorted({0, batch // 3, batch - 1}):
+        probs, logits = oracle.mobilenet_v1_forward_f16(data["image"][img:img + 1], data["weights"])
+        end_to_end_bar(l[img:img + 1], logits, "f16 logits batch %d image %d" % (batch, img), 8)
+        end_to_end_bar(p[img:img + 1], probs, "f16 probs batch %d image %d" % (batch, img), 16)
+        assert np.array_equal(p[img:img + 1].argmax(axis=1), probs.argmax(axis=1))
+
+
 def test_f16_conv_rounds_once_and_handles_unaligned_buffers():
     import torch
     import paper_1901_05350_amd as tfx

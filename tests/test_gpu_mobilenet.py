@@ -61,6 +61,24 @@ def test_end_to_end_batch_3():
     assert_close(host(p), probs, "probs batch 3")
 
 
+@pytest.mark.parametrize("batch", [8, 64])
+def test_end_to_end_benchmark_batches_sampled_images(batch):
+    """The batched forward passes the benchmark times (other tile shapes and kernels than batch 1: filter-stationary
+    pointwise kernel, 128 x 128 tiles, several depthwise rows per lane).  Images are independent, so the oracle
+    checks a sample of them, each run alone."""
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1(seed=9, batch=batch)
+    model = tfx.MobileNetV1(data["weights"], batch=batch)
+    p, l = model.forward(dev(data["image"]))
+    p, l = host(p), host(l)
+    assert np.isfinite(p).all() and np.isfinite(l).all()
+    np.testing.assert_allclose(p.astype(np.float64).sum(axis=1), 1.0, atol=1e-5)
+    for img in sorted({0, batch // 3, batch - 1}):
+        probs, logits = oracle.mobilenet_v1_forward(data["image"][img:img + 1], data["weights"])
+        assert_close(l[img:img + 1], logits, "logits batch %d image %d" % (batch, img))
+        assert_close(p[img:img + 1], probs, "probs batch %d image %d" % (batch, img))
+
+
 @pytest.mark.parametrize("size,q,classes,batch", [(128, 1, 10, 2), (160, 2, 1000, 1), (192, 3, 1000, 1), (224, 4, 37, 1),
                                                   (100, 2, 5, 3), (256, 1, 1024, 1)])
 def test_family_variants_end_to_end(size, q, classes, batch):
