@@ -17,6 +17,44 @@ constexpr int kThreads = 512;  // 8 wavefronts share one copy of the filter
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Value held by the lane 8 places away within the lane's group of 16 (l % 16 <-> (l % 16) ^ 8): DPP row rotate by 8.
+__device__ __forceinline__ float swap8(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xf, 0xf, false));
+}
+
+// Bias + activation + store of NBLK 16-column blocks (NBLK even) of one 16-row slab.  After the MFMAs lane
+// (li = l % 16, q = l / 16) holds columns 16j + 4q .. + 3 of row li for every block j; stored like that, an
+// instruction would write 64-byte pieces of 16 rows (measured: half-line pieces cost 12 us of 72 on the
+// 32 -> 64 layer).  Lanes li and li ^ 8 therefore trade blocks 2h + 1 / 2h first, so that the lanes with
+// li < 8 hold block 2h of rows li and li + 8 and the others block 2h + 1 of rows li - 8 and li: two store
+// instructions per block pair, each writing whole 128-byte lines of 8 rows.  bv[h]: bias of the lane's 4
+// columns 32h + (li < 8 ? 0 : 16) + 4q .. + 3; yc: y + first column of block 0.
+template <int NBLK>
+__device__ __forceinline__ void store_slab(const floatx4 (&acc)[NBLK], const float4 (&bv)[NBLK / 2], float* yc, int n,
+                                           int row0, int M, int li, int q, const ActClamp& clamp) {
+  static_assert(NBLK % 2 == 0, "blocks are stored in pairs");
+  const bool lo = li < 8;
+  const int ra = row0 + (li & 7), rb = ra + 8;
+#pragma unroll
+  for (int h = 0; h < NBLK / 2; ++h) {
+    float got[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) got[v] = swap8(lo ? acc[2 * h + 1][v] : acc[2 * h][v]);
+    float4 oa, ob;
+    oa.x = apply_act((lo ? acc[2 * h][0] : got[0]) + bv[h].x, clamp);
+    oa.y = apply_act((lo ? acc[2 * h][1] : got[1]) + bv[h].y, clamp);
+    oa.z = apply_act((lo ? acc[2 * h][2] : got[2]) + bv[h].z, clamp);
+    oa.w = apply_act((lo ? acc[2 * h][3] : got[3]) + bv[h].w, clamp);
+    ob.x = apply_act((lo ? got[0] : acc[2 * h + 1][0]) + bv[h].x, clamp);
+    ob.y = apply_act((lo ? got[1] : acc[2 * h + 1][1]) + bv[h].y, clamp);
+    ob.z = apply_act((lo ? got[2] : acc[2 * h + 1][2]) + bv[h].z, clamp);
+    ob.w = apply_act((lo ? got[3] : acc[2 * h + 1][3]) + bv[h].w, clamp);
+    const int col = 32 * h + (lo ? 0 : 16) + 4 * q;
+    if (ra < M) *reinterpret_cast<float4*>(yc + (size_t)ra * n + col) = oa;
+    if (rb < M) *reinterpret_cast<float4*>(yc + (size_t)rb * n + col) = ob;
+  }
+}
+
 // The filter is the MFMA A operand (lane l: column n = l % 16 of a 16-column block, k = l / 16) and
 // the activations the B operand (lane l: row m = l % 16 of the slab, k = l / 16), so D[i = n][j = m]
 // leaves every lane with 4 consecutive output columns of its row per 16-column block: 128-bit
@@ -87,22 +125,87 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream16_kernel(const floa
         }
         __builtin_amdgcn_sched_barrier(0);  // keep later groups' LDS reads from being hoisted
       }
-      if (row < M) {
-        float* yp = y + (size_t)row * N + 16 * NBP * p + 4 * q;
+      float4 bv[NBP / 2];
 #pragma unroll
-        for (int j = 0; j < NBP; ++j) {
-          float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (bias) bv = *reinterpret_cast<const float4*>(bias + 16 * NBP * p + 16 * j + 4 * q);
-          float4 o;
-          o.x = apply_act(acc[j][0] + bv.x, clamp);
-          o.y = apply_act(acc[j][1] + bv.y, clamp);
-          o.z = apply_act(acc[j][2] + bv.z, clamp);
-          o.w = apply_act(acc[j][3] + bv.w, clamp);
-          *reinterpret_cast<float4*>(yp + 16 * j) = o;
-        }
-      }
+      for (int h = 0; h < NBP / 2; ++h)
+        bv[h] = bias ? *reinterpret_cast<const float4*>(bias + 16 * NBP * p + 32 * h + (li < 8 ? 0 : 16) + 4 * q)
+                     : make_float4(0.f, 0.f, 0.f, 0.f);
+      store_slab<NBP>(acc, bv, y + 16 * NBP * p, N, slab * 16, M, li, q, clamp);
     }
   }
+}
+
+// K = 32, N = 64 (MobileNet's first pointwise layer: 10.6 multiply-adds per byte, far below the ridge).
+// The whole filter is 32 registers per lane in the operand layout above (k = 16g + 4q + s, n = 16j + l % 16),
+// so it is loaded once per wavefront and the slab loop touches neither LDS nor a work counter: wavefront
+// number v of the grid takes slabs v, v + V, v + 2V, ... (all wavefronts advance along one front through x and
+// y) and fetches its next slab before multiplying the current one.
+constexpr int kThinThreads = 256;
+__global__ __launch_bounds__(kThinThreads) void pointwise_k32n64_kernel(const float* __restrict__ x,
+                                                                         const float* __restrict__ w,
+                                                                         const float* __restrict__ bias,
+                                                                         float* __restrict__ y, int M, int slabs, int act) {
+  constexpr int K = 32, N = 64, KG = 2, NB = 4;
+  const int lane = threadIdx.x % 64, li = lane % 16, q = lane / 16;
+  const int waves = gridDim.x * (kThinThreads / 64);
+  int slab = blockIdx.x * (kThinThreads / 64) + threadIdx.x / 64;
+  if (slab >= slabs) return;
+
+  float wr[KG][4][NB];
+#pragma unroll
+  for (int g = 0; g < KG; ++g)
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) wr[g][s][j] = w[(16 * g + 4 * q + s) * N + 16 * j + li];
+  float4 bv[NB / 2];  // bias of the columns this lane stores (see store_slab)
+#pragma unroll
+  for (int h = 0; h < NB / 2; ++h)
+    bv[h] = bias ? *reinterpret_cast<const float4*>(bias + 32 * h + (li < 8 ? 0 : 16) + 4 * q)
+                 : make_float4(0.f, 0.f, 0.f, 0.f);
+  const ActClamp clamp = make_act(act);
+
+  // a lane's operand values of one slab: its row (clamped: loaded, never stored), k = 16g + 4q .. + 3
+  auto slab_ptr = [&](int sl) {
+    const int row = sl * 16 + li;
+    return reinterpret_cast<const float4*>(x + (size_t)(row < M ? row : M - 1) * K + 4 * q);
+  };
+  const float4* xp = slab_ptr(slab);
+  float4 a0 = xp[0], a1 = xp[4], n0, n1;
+  for (;;) {
+    const int next = slab + waves;
+    xp = slab_ptr(next < slabs ? next : slab);  // the last round re-reads its own slab (in cache) instead of branching
+    n0 = xp[0];
+    n1 = xp[4];
+    const float4 a[KG] = {a0, a1};
+    floatx4 acc[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[j][v] = 0.f;
+#pragma unroll
+    for (int g = 0; g < KG; ++g) {
+      const float av[4] = {a[g].x, a[g].y, a[g].z, a[g].w};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[g][s][j], av[s], acc[j], 0, 0, 0);
+    }
+    store_slab<NB>(acc, bv, y, N, slab * 16, M, li, q, clamp);
+    if (next >= slabs) break;
+    slab = next;
+    a0 = n0;
+    a1 = n1;
+  }
+}
+
+int launch_k32n64(const float* x, const float* w, const float* bias, float* y, int m, int act, hipStream_t stream) {
+  const int slabs = (m + 15) / 16;
+  // 4 workgroups of 4 wavefronts per CU, all resident at once
+  int blocks = 256 * 4;
+  if (blocks > (slabs + 3) / 4) blocks = (slabs + 3) / 4;
+  hipLaunchKernelGGL(pointwise_k32n64_kernel, dim3(blocks), dim3(kThinThreads), 0, stream, x, w, bias, y, m, slabs, act);
+  return check_launch();
 }
 
 template <int K, int N>
@@ -132,7 +235,7 @@ bool pointwise_stream_supported(int m, int k, int n, const void* x, const void* 
 
 int launch_pointwise_stream(const float* x, const float* w, const float* bias, float* y, int m, int k, int n, int act,
                             hipStream_t stream) {
-  if (k == 32 && n == 64) return launch_stream16<32, 64>(x, w, bias, y, m, act, stream);
+  if (k == 32 && n == 64) return launch_k32n64(x, w, bias, y, m, act, stream);
   if (k == 64 && n == 128) return launch_stream16<64, 128>(x, w, bias, y, m, act, stream);
   if (k == 128 && n == 128) return launch_stream16<128, 128>(x, w, bias, y, m, act, stream);
   if (k == 128 && n == 256) return launch_stream16<128, 256>(x, w, bias, y, m, act, stream);
