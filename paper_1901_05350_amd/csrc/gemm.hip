@@ -17,6 +17,8 @@
 // That makes a lane's four steps one contiguous float4 in a K-contiguous LDS tile.
 #include "tfx_internal.h"
 
+#include <type_traits>
+
 namespace tfx {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -81,6 +83,33 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ g, int ld, i
     }
     reg[it] = v;
   }
+}
+
+// Branch-free variant for k-slices that lie entirely inside K (vector loads only).  A thread's slots keep a
+// pointer each, set up once: rows past the end of the operand are clamped to a valid row instead of masked --
+// they only feed output rows / columns that are never stored -- so a k-slice is NSLOT unconditional loads and
+// no other vector instruction (on this chip every vector-ALU instruction takes issue time away from the
+// matrix cores: the masked loader's compares, zero fills and branches cost ~10% of the main loop).
+template <int ROWS, int BK, bool KC, int NT, int NSLOT>
+__device__ __forceinline__ void slot_pointers(const float* __restrict__ g, int ld, int rows_total, int row0, int tid,
+                                              const float* (&ptr)[NSLOT]) {
+#pragma unroll
+  for (int it = 0; it < NSLOT; ++it) {
+    const int s = tid + it * NT;
+    if (KC) {
+      const int gr = min(row0 + s / (BK / 4), rows_total - 1);
+      ptr[it] = g + (size_t)gr * ld + 4 * (s % (BK / 4));
+    } else {
+      int gr = row0 + 4 * (s % (ROWS / 4));  // 4 consecutive rows, all inside or all outside (rows_total % 4 == 0)
+      if (gr >= rows_total) gr = 0;
+      ptr[it] = g + (size_t)(s / (ROWS / 4)) * ld + gr;
+    }
+  }
+}
+template <int NSLOT>
+__device__ __forceinline__ void load_tile_full(const float* (&ptr)[NSLOT], size_t k_offset, float4 (&reg)[NSLOT]) {
+#pragma unroll
+  for (int it = 0; it < NSLOT; ++it) reg[it] = *reinterpret_cast<const float4*>(ptr[it] + k_offset);
 }
 
 template <int ROWS, int BK, bool KC, int NT, int NSLOT>
@@ -253,21 +282,38 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
   const int nk = (K + BK - 1) / BK;
   ConvRow crow[CONV ? SA : 1];
   if constexpr (CONV) conv_rows<BM, BK, NT, SA>(cv, M, m0, tid, crow);
-  auto load_a = [&](int k0) {
-    if constexpr (CONV) load_tile_conv<BM, BK, VEC, NT, SA>(cv, K, k0, tid, crow, ra);
-    else load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, k0, tid, ra);
+  // k-slices that lie entirely inside K take the branch-free loaders (vector layouts only)
+  constexpr bool FAST_A = VEC && !CONV, FAST_B = VEC;
+  const int nk_full = K / BK;
+  const float* pa[SA];
+  const float* pb[SB];
+  if constexpr (FAST_A) slot_pointers<BM, BK, A_KC, NT, SA>(A, lda, M, m0, tid, pa);
+  if constexpr (FAST_B) slot_pointers<BN, BK, B_KC, NT, SB>(B, ldb, N, n0, tid, pb);
+  const size_t step_a = A_KC ? (size_t)BK : (size_t)BK * lda, step_b = B_KC ? (size_t)BK : (size_t)BK * ldb;
+  // FULL: k-slice kt is known to lie inside K
+  auto load_a = [&](int kt, auto full) {
+    if constexpr (CONV) load_tile_conv<BM, BK, VEC, NT, SA>(cv, K, kt * BK, tid, crow, ra);
+    else if constexpr (FAST_A && decltype(full)::value) load_tile_full<SA>(pa, kt * step_a, ra);
+    else load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, kt * BK, tid, ra);
   };
-  load_a(0);
-  load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, 0, tid, rb);
+  auto load_b = [&](int kt, auto full) {
+    if constexpr (FAST_B && decltype(full)::value) load_tile_full<SB>(pb, kt * step_b, rb);
+    else load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, kt * BK, tid, rb);
+  };
+  load_a(0, std::false_type{});
+  load_b(0, std::false_type{});
   store_tile<BM, BK, A_KC, NT, SA>(lds_a, tid, ra);
   store_tile<BN, BK, B_KC, NT, SB>(lds_b, tid, rb);
   __syncthreads();
 
-  for (int kt = 0; kt < nk; ++kt) {
+  // One k-slice: fetch slice kt + 1 into registers, multiply slice kt from LDS, hand the registers to the other
+  // LDS buffer.  NEXT_FULL: slice kt + 1 exists and lies inside K.
+  auto k_slice = [&](int kt, auto next_full) {
+    constexpr bool NEXT_FULL = decltype(next_full)::value;
     const int cur = kt & 1, nxt = cur ^ 1;
-    if (kt + 1 < nk) {
-      load_a((kt + 1) * BK);
-      load_tile<BN, BK, B_KC, VEC, NT, SB>(B, ldb, N, K, n0, (kt + 1) * BK, tid, rb);
+    if (NEXT_FULL || kt + 1 < nk) {
+      load_a(kt + 1, next_full);
+      load_b(kt + 1, next_full);
     }
     const float* la = lds_a + cur * TA::kFloats;
     const float* lb = lds_b + cur * TB::kFloats;
@@ -298,12 +344,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
                                                              0, 0, 0);
     }
     __builtin_amdgcn_s_setprio(0);
-    if (kt + 1 < nk) {
+    if (NEXT_FULL || kt + 1 < nk) {
       store_tile<BM, BK, A_KC, NT, SA>(lds_a + nxt * TA::kFloats, tid, ra);
       store_tile<BN, BK, B_KC, NT, SB>(lds_b + nxt * TB::kFloats, tid, rb);
     }
     __syncthreads();
-  }
+  };
+  int kt = 0;
+  for (; kt + 1 < nk_full; ++kt) k_slice(kt, std::true_type{});
+  for (; kt < nk; ++kt) k_slice(kt, std::false_type{});
   const ActClamp clamp = make_act(act);
   // Epilogue: bias[col] then activation, one dword per lane per register (two 128-byte rows per store).
 #pragma unroll

@@ -22,6 +22,11 @@ __device__ __forceinline__ float swap8(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xf, 0xf, false));
 }
 
+template <int KG>
+__device__ __forceinline__ void fetch_slab(const float4* __restrict__ xp, float4 (&a)[KG]) {
+#pragma unroll
+  for (int g = 0; g < KG; ++g) a[g] = xp[4 * g];
+}
 // Bias + activation + store of NBLK 16-column blocks (NBLK even) of one 16-row slab.  After the MFMAs lane
 // (li = l % 16, q = l / 16) holds columns 16j + 4q .. + 3 of row li for every block j; stored like that, an
 // instruction would write 64-byte pieces of 16 rows (measured: half-line pieces cost 12 us of 72 on the
@@ -29,7 +34,10 @@ __device__ __forceinline__ float swap8(float v) {
 // li < 8 hold block 2h of rows li and li + 8 and the others block 2h + 1 of rows li - 8 and li: two store
 // instructions per block pair, each writing whole 128-byte lines of 8 rows.  bv[h]: bias of the lane's 4
 // columns 32h + (li < 8 ? 0 : 16) + 4q .. + 3; yc: y + first column of block 0.
-template <int NBLK>
+// CHECK = false: all 16 rows exist; the stores are then unconditional, which also lets the compiler count them
+// when it waits for a later load (stores and loads share one in-order counter: behind stores it cannot count,
+// every wait for a load would also wait for all earlier stores to be acknowledged).
+template <int NBLK, bool CHECK>
 __device__ __forceinline__ void store_slab(const floatx4 (&acc)[NBLK], const float4 (&bv)[NBLK / 2], float* yc, int n,
                                            int row0, int M, int li, int q, const ActClamp& clamp) {
   static_assert(NBLK % 2 == 0, "blocks are stored in pairs");
@@ -50,8 +58,8 @@ __device__ __forceinline__ void store_slab(const floatx4 (&acc)[NBLK], const flo
     ob.z = apply_act((lo ? got[2] : acc[2 * h + 1][2]) + bv[h].z, clamp);
     ob.w = apply_act((lo ? got[3] : acc[2 * h + 1][3]) + bv[h].w, clamp);
     const int col = 32 * h + (lo ? 0 : 16) + 4 * q;
-    if (ra < M) *reinterpret_cast<float4*>(yc + (size_t)ra * n + col) = oa;
-    if (rb < M) *reinterpret_cast<float4*>(yc + (size_t)rb * n + col) = ob;
+    if (!CHECK || ra < M) *reinterpret_cast<float4*>(yc + (size_t)ra * n + col) = oa;
+    if (!CHECK || rb < M) *reinterpret_cast<float4*>(yc + (size_t)rb * n + col) = ob;
   }
 }
 
@@ -130,26 +138,33 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream16_kernel(const floa
       for (int h = 0; h < NBP / 2; ++h)
         bv[h] = bias ? *reinterpret_cast<const float4*>(bias + 16 * NBP * p + 32 * h + (li < 8 ? 0 : 16) + 4 * q)
                      : make_float4(0.f, 0.f, 0.f, 0.f);
-      store_slab<NBP>(acc, bv, y + 16 * NBP * p, N, slab * 16, M, li, q, clamp);
+      store_slab<NBP, true>(acc, bv, y + 16 * NBP * p, N, slab * 16, M, li, q, clamp);
     }
   }
 }
 
-// K = 32, N = 64 (MobileNet's first pointwise layer: 10.6 multiply-adds per byte, far below the ridge).
-// The whole filter is 32 registers per lane in the operand layout above (k = 16g + 4q + s, n = 16j + l % 16),
-// so it is loaded once per wavefront and the slab loop touches neither LDS nor a work counter: wavefront
-// number v of the grid takes slabs v, v + V, v + 2V, ... (all wavefronts advance along one front through x and
-// y) and fetches its next slab before multiplying the current one.
+// Filter in registers.  In the operand layout above a lane needs K/16 x 4 x NW/16 filter values for NW
+// output columns: 32 registers for K = 32 with NW = 64, K/2 registers with NW = 32.  A wavefront therefore
+// owns one group of NW columns for the whole launch, loads its part of the filter once and then walks
+// over slabs without touching LDS or a work counter: the N/NW wavefronts that share a slab are neighbours
+// in one workgroup (x comes from HBM once and from L1 for the others), wavefront group v of the grid takes
+// slabs v, v + V, v + 2V, ... (the whole grid advances along one front through x and y), and a wavefront
+// fetches its next slab before multiplying the current one.
 constexpr int kThinThreads = 256;
-__global__ __launch_bounds__(kThinThreads) void pointwise_k32n64_kernel(const float* __restrict__ x,
-                                                                         const float* __restrict__ w,
-                                                                         const float* __restrict__ bias,
-                                                                         float* __restrict__ y, int M, int slabs, int act) {
-  constexpr int K = 32, N = 64, KG = 2, NB = 4;
+template <int K, int N, int NW>
+__global__ __launch_bounds__(kThinThreads) void pointwise_regfilter_kernel(const float* __restrict__ x,
+                                                                            const float* __restrict__ w,
+                                                                            const float* __restrict__ bias,
+                                                                            float* __restrict__ y, int M, int slabs,
+                                                                            int act) {
+  constexpr int KG = K / 16, NB = NW / 16, CG = N / NW, WPB = kThinThreads / 64;
+  static_assert(N % NW == 0 && WPB % CG == 0 && NB % 2 == 0, "column groups share a workgroup");
   const int lane = threadIdx.x % 64, li = lane % 16, q = lane / 16;
-  const int waves = gridDim.x * (kThinThreads / 64);
-  int slab = blockIdx.x * (kThinThreads / 64) + threadIdx.x / 64;
-  if (slab >= slabs) return;
+  const int gw = blockIdx.x * WPB + threadIdx.x / 64;
+  const int col0 = (gw % CG) * NW;          // this wavefront's columns
+  const int stride = gridDim.x * WPB / CG;  // slabs between two slabs of one wavefront
+  const int group = gw / CG;  // wavefronts of one group share their slabs
+  if (group >= slabs) return;
 
   float wr[KG][4][NB];
 #pragma unroll
@@ -157,11 +172,11 @@ __global__ __launch_bounds__(kThinThreads) void pointwise_k32n64_kernel(const fl
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-      for (int j = 0; j < NB; ++j) wr[g][s][j] = w[(16 * g + 4 * q + s) * N + 16 * j + li];
+      for (int j = 0; j < NB; ++j) wr[g][s][j] = w[(16 * g + 4 * q + s) * N + col0 + 16 * j + li];
   float4 bv[NB / 2];  // bias of the columns this lane stores (see store_slab)
 #pragma unroll
   for (int h = 0; h < NB / 2; ++h)
-    bv[h] = bias ? *reinterpret_cast<const float4*>(bias + 32 * h + (li < 8 ? 0 : 16) + 4 * q)
+    bv[h] = bias ? *reinterpret_cast<const float4*>(bias + col0 + 32 * h + (li < 8 ? 0 : 16) + 4 * q)
                  : make_float4(0.f, 0.f, 0.f, 0.f);
   const ActClamp clamp = make_act(act);
 
@@ -170,15 +185,7 @@ __global__ __launch_bounds__(kThinThreads) void pointwise_k32n64_kernel(const fl
     const int row = sl * 16 + li;
     return reinterpret_cast<const float4*>(x + (size_t)(row < M ? row : M - 1) * K + 4 * q);
   };
-  const float4* xp = slab_ptr(slab);
-  float4 a0 = xp[0], a1 = xp[4], n0, n1;
-  for (;;) {
-    const int next = slab + waves;
-    xp = slab_ptr(next < slabs ? next : slab);  // the last round re-reads its own slab (in cache) instead of branching
-    n0 = xp[0];
-    n1 = xp[4];
-    const float4 a[KG] = {a0, a1};
-    floatx4 acc[NB];
+  auto multiply = [&](const float4 (&a)[KG], floatx4 (&acc)[NB]) {
 #pragma unroll
     for (int j = 0; j < NB; ++j)
 #pragma unroll
@@ -191,20 +198,68 @@ __global__ __launch_bounds__(kThinThreads) void pointwise_k32n64_kernel(const fl
 #pragma unroll
         for (int j = 0; j < NB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[g][s][j], av[s], acc[j], 0, 0, 0);
     }
-    store_slab<NB>(acc, bv, y, N, slab * 16, M, li, q, clamp);
-    if (next >= slabs) break;
-    slab = next;
-    a0 = n0;
-    a1 = n1;
+  };
+
+  const int full = M / 16;  // slabs with all 16 rows
+  float4 a[KG], an[KG];  // the slab being multiplied and the next one, in flight meanwhile
+  floatx4 acc[NB];
+  if (group < full) {
+    int slab = group;
+    fetch_slab<KG>(slab_ptr(slab), a);
+    // Wait for the first slab here (vmcnt(0)), not at the loop head: a wait at the loop head would also run on
+    // every later round, where it could only be met by waiting for the previous round's stores as well.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    // One basic block per round, fenced for the instruction scheduler: loads of the next slab, then the MFMAs and
+    // stores of this one, then the hand-over (the only place that waits for the loads).  Left to itself the
+    // compiler sinks the loads to their first use, which turns the prefetch into a stall per round.
+    for (;;) {
+      const int next = slab + stride;
+      const bool more = next < full;
+      fetch_slab<KG>(slab_ptr(more ? next : slab), an);  // the last round re-reads its own slab (in cache)
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(a, acc);
+      store_slab<NB, false>(acc, bv, y + col0, N, slab * 16, M, li, q, clamp);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < KG; ++g) a[g] = an[g];
+      slab = next;
+      if (!more) break;
+    }
+  }
+  // the ragged last slab (M % 16 rows), by the group whose turn it is
+  if (full < slabs && full % stride == group) {
+    fetch_slab<KG>(slab_ptr(full), a);
+    multiply(a, acc);
+    store_slab<NB, true>(acc, bv, y + col0, N, full * 16, M, li, q, clamp);
   }
 }
 
-int launch_k32n64(const float* x, const float* w, const float* bias, float* y, int m, int act, hipStream_t stream) {
+template <int K, int N, int NW>
+int launch_regfilter(const float* x, const float* w, const float* bias, float* y, int m, int act, hipStream_t stream) {
   const int slabs = (m + 15) / 16;
-  // 4 workgroups of 4 wavefronts per CU, all resident at once
-  int blocks = 256 * 4;
-  if (blocks > (slabs + 3) / 4) blocks = (slabs + 3) / 4;
-  hipLaunchKernelGGL(pointwise_k32n64_kernel, dim3(blocks), dim3(kThinThreads), 0, stream, x, w, bias, y, m, slabs, act);
+  constexpr int CG = N / NW, WPB = kThinThreads / 64;
+  // as many workgroups as are resident at once (slabs are dealt out statically, so a workgroup that had to
+  // wait for a free slot would finish last); the count depends only on the kernel's registers
+  static std::atomic<int> per_cu{0};
+  int resident = per_cu.load(std::memory_order_relaxed);
+  if (resident == 0) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, pointwise_regfilter_kernel<K, N, NW>, kThinThreads, 0) !=
+            hipSuccess || resident < 1)
+      return TFX_ERR_LAUNCH;
+    per_cu.store(resident, std::memory_order_relaxed);
+  }
+  int cus = 0;
+  {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+      return TFX_ERR_LAUNCH;
+  }
+  long long blocks = (long long)cus * resident;
+  const long long needed = ((long long)slabs * CG + WPB - 1) / WPB;
+  if (blocks > needed) blocks = needed;
+  hipLaunchKernelGGL((pointwise_regfilter_kernel<K, N, NW>), dim3((unsigned)blocks), dim3(kThinThreads), 0, stream, x, w,
+                     bias, y, m, slabs, act);
   return check_launch();
 }
 
@@ -235,7 +290,7 @@ bool pointwise_stream_supported(int m, int k, int n, const void* x, const void* 
 
 int launch_pointwise_stream(const float* x, const float* w, const float* bias, float* y, int m, int k, int n, int act,
                             hipStream_t stream) {
-  if (k == 32 && n == 64) return launch_k32n64(x, w, bias, y, m, act, stream);
+  if (k == 32 && n == 64) return launch_regfilter<32, 64, 64>(x, w, bias, y, m, act, stream);
   if (k == 64 && n == 128) return launch_stream16<64, 128>(x, w, bias, y, m, act, stream);
   if (k == 128 && n == 128) return launch_stream16<128, 128>(x, w, bias, y, m, act, stream);
   if (k == 128 && n == 256) return launch_stream16<128, 256>(x, w, bias, y, m, act, stream);
