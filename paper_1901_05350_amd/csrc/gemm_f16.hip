@@ -13,6 +13,8 @@
 // [M,K], B stored [N,K]) and a general one with an element-wise loader for everything else.
 #include "tfx_internal.h"
 
+#include <type_traits>
+
 namespace tfx {
 namespace {
 
@@ -247,44 +249,61 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_pipe_kernel(
   // columns, 4 consecutive k to the K-contiguous LDS row of that column.  The block is written when
   // its first slot comes up in the schedule, its slots are refilled one by one.
   u32x4 reg[SLOTS];
-  unsigned goff[SLOTS];  // K-contiguous operand: element offset of the slot's (clamped) row start
+  unsigned boff[SLOTS];  // byte offset of the slot at k0 = 0 from its operand's base (operands hold < 2^31 elements)
   const int kq = tid % 16, nb = tid / 16;
   const unsigned bcol = n0 + 8 * nb < N ? (unsigned)(n0 + 8 * nb) : 0u;  // past N: any valid column block
 #pragma unroll
   for (int w = 0; w < SLOTS; ++w) {
     const bool is_a = w < SA;
     const int i = is_a ? w : w - SA;
-    const int row = min((is_a ? m0 : n0) + srow + i * kRowStep, (is_a ? M : N) - 1);
-    goff[w] = (unsigned)row * (unsigned)K;
+    if (is_a || B_KC) {
+      const int row = min((is_a ? m0 : n0) + srow + i * kRowStep, (is_a ? M : N) - 1);
+      boff[w] = 2u * ((unsigned)row * (unsigned)K + (unsigned)scol);
+    } else {
+      boff[w] = 2u * ((unsigned)(4 * kq + i) * (unsigned)N + bcol);
+    }
   }
   const int nk = (K + kBK - 1) / kBK;
   const int k_last = (nk - 1) * kBK;
-  auto load_slot = [&](int w, int k0) {
+  // FULL: the slice starting at k0 lies inside K.  Then a load is the operand's base advanced by the slice
+  // (uniform, scalar registers) plus the slot's constant 32-bit offset, and a store needs no mask: no vector
+  // ALU instruction per slot (each one would take issue time from the matrix cores).
+  auto load_slot = [&](int w, int k0, auto full) {
+    const char* g = reinterpret_cast<const char*>(w < SA ? A : B);
     if (w < SA || B_KC) {
-      const half_t* g = w < SA ? A : B;
-      const unsigned kk = k0 + scol < K ? (unsigned)(k0 + scol) : 0u;  // past K: any valid address, zeroed later
-      reg[w] = *reinterpret_cast<const u32x4*>(g + (size_t)(goff[w] + kk));
+      if constexpr (decltype(full)::value) {
+        reg[w] = *reinterpret_cast<const u32x4*>(g + 2 * (size_t)k0 + boff[w]);
+      } else {
+        // past K: the start of the slot's row (a valid address), zeroed when stored
+        const unsigned off = k0 + scol < K ? boff[w] + 2u * (unsigned)k0 : boff[w] - 2u * (unsigned)scol;
+        reg[w] = *reinterpret_cast<const u32x4*>(g + off);
+      }
     } else {
-      const int k = k0 + 4 * kq + (w - SA);
-      const unsigned kk = k < K ? (unsigned)k : 0u;
-      reg[w] = *reinterpret_cast<const u32x4*>(B + (size_t)(kk * (unsigned)N + bcol));
+      if constexpr (decltype(full)::value) {
+        reg[w] = *reinterpret_cast<const u32x4*>(g + 2 * (size_t)k0 * (size_t)N + boff[w]);
+      } else {
+        const int k = k0 + 4 * kq + (w - SA);
+        const unsigned off = k < K ? boff[w] + 2u * (unsigned)k0 * (unsigned)N : 2u * bcol;  // past K: row 0
+        reg[w] = *reinterpret_cast<const u32x4*>(g + off);
+      }
     }
   };
   // k0: first k of the slice the registers hold; the zeroing of halfs past K happens here, when the
   // registers are consumed, so that nothing waits on a load right after issuing it
-  auto store_slot = [&](int w, int buf, int k0) {
+  auto store_slot = [&](int w, int buf, int k0, auto full) {
+    constexpr bool FULL = decltype(full)::value;
     if (w < SA || B_KC) {
       const bool is_a = w < SA;
       const int i = is_a ? w : w - SA;
       half_t* l = is_a ? lds_a + buf * kTileA : lds_b + buf * kTileB;
-      const unsigned mask = k0 + scol < K ? 0xffffffffu : 0u;
-      *reinterpret_cast<u32x4*>(l + (srow + i * kRowStep) * kLd + scol) = reg[w] & mask;
+      const unsigned mask = (FULL || k0 + scol < K) ? 0xffffffffu : 0u;
+      *reinterpret_cast<u32x4*>(l + (srow + i * kRowStep) * kLd + scol) = FULL ? reg[w] : reg[w] & mask;
     } else if (w == SA) {
       h8 r[4];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        const unsigned mask = k0 + 4 * kq + kk < K ? 0xffffffffu : 0u;
-        r[kk] = __builtin_bit_cast(h8, reg[SA + kk] & mask);
+        const unsigned mask = (FULL || k0 + 4 * kq + kk < K) ? 0xffffffffu : 0u;
+        r[kk] = __builtin_bit_cast(h8, FULL ? reg[SA + kk] : reg[SA + kk] & mask);
       }
       half_t* l = lds_b + buf * kTileB + (8 * nb) * kLd + 4 * kq;
 #pragma unroll
@@ -294,18 +313,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_pipe_kernel(
       }
     }
   };
+  constexpr std::false_type kMasked{};
 
 #pragma unroll
-  for (int w = 0; w < SLOTS; ++w) load_slot(w, 0);
+  for (int w = 0; w < SLOTS; ++w) load_slot(w, 0, kMasked);
 #pragma unroll
-  for (int w = 0; w < SLOTS; ++w) store_slot(w, 0, 0);
+  for (int w = 0; w < SLOTS; ++w) store_slot(w, 0, 0, kMasked);
 #pragma unroll
-  for (int w = 0; w < SLOTS; ++w) load_slot(w, min(kBK, k_last));
+  for (int w = 0; w < SLOTS; ++w) load_slot(w, min(kBK, k_last), kMasked);
   __syncthreads();
 
-  for (int kt = 0; kt < nk; ++kt) {
+  // One k-slice.  FULL: slices kt + 1 (stored) and kt + 2 (fetched) both lie inside K.
+  auto k_slice = [&](int kt, auto full) {
     const int cur = kt & 1;
-    const int k_next = min((kt + 2) * kBK, k_last);  // the last two iterations refetch the last slice (unused)
+    // the last two iterations refetch the last slice (unused)
+    const int k_next = decltype(full)::value ? (kt + 2) * kBK : min((kt + 2) * kBK, k_last);
     const half_t* la = lds_a + cur * kTileA + (wm0 + li) * kLd + 8 * hh;
     const half_t* lb = lds_b + cur * kTileB + (wn0 + li) * kLd + 8 * hh;
     h8 fa[2][TM], fb[2][TN];
@@ -334,15 +356,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_f16_pipe_kernel(
           const int p = s * MF + i * TN + j;
 #pragma unroll
           for (int w = p * SLOTS / ALL; w < (p + 1) * SLOTS / ALL; ++w) {
-            store_slot(w, cur ^ 1, (kt + 1) * kBK);
-            load_slot(w, k_next);
+            store_slot(w, cur ^ 1, (kt + 1) * kBK, full);
+            load_slot(w, k_next, full);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
     __syncthreads();
-  }
+  };
+  int kt = 0;
+  for (; (kt + 3) * kBK <= K; ++kt) k_slice(kt, std::true_type{});
+  for (; kt < nk; ++kt) k_slice(kt, kMasked);
 
   const ActClamp clamp = make_act(act);
   if (c_vec == 2) {
