@@ -22,6 +22,7 @@
 namespace tfx {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -197,6 +198,50 @@ __device__ __forceinline__ void load_tile_conv(const ConvA& cv, int K, int k0, i
   }
 }
 
+// Lean A-tile loader of the implicit GEMM for Ci % BK == 0 (vector loads, at most 32 filter taps): a k-slice
+// then lies inside one filter tap, so the tap (kh, kw) and the channel offset are the same for the whole
+// workgroup and live in scalar registers.  A slot keeps, from set-up, the address of its pixel's tap (0, 0) and
+// one validity bit per tap; per k-slice it adds the slice's uniform offset and, for a tap outside the image,
+// reads a zero quad instead: 5 vector-ALU instructions per slot where the general loader spends ~100 on
+// decoding and range checks (which take their issue time from the matrix cores).
+__device__ __align__(16) float kZeroQuad[4] = {0.f, 0.f, 0.f, 0.f};  // never written (not const: same address space as x)
+
+template <int BM, int BK, int NT, int NSLOT>
+__device__ __forceinline__ void conv_lean_rows(const ConvA& cv, int M, int K, int m0, int tid, const float* (&p0)[NSLOT],
+                                               unsigned (&ok)[NSLOT]) {
+  const int fh = K / (cv.fw * cv.Ci);
+#pragma unroll
+  for (int it = 0; it < NSLOT; ++it) {
+    const int r = min(m0 + (tid + it * NT) / (BK / 4), M - 1);  // rows past M repeat the last row (never stored)
+    const int ow = r % cv.OW;
+    const int t = r / cv.OW;
+    const int oh = t % cv.OH;
+    const int n = t / cv.OH;
+    const int ih0 = oh * cv.sh - cv.pt, iw0 = ow * cv.sw - cv.pl;
+    // address of tap (0, 0), channel 4 * (tid % (BK/4)); outside the image for border pixels, where only the taps
+    // whose bit is set are ever dereferenced
+    const long long e = (((long long)n * cv.H + ih0) * cv.W + iw0) * cv.Ci + 4 * (tid % (BK / 4));
+    p0[it] = cv.x + e;
+    unsigned bits = 0;
+    for (int kh = 0; kh < fh; ++kh)
+      for (int kw = 0; kw < cv.fw; ++kw)
+        if (ih0 + kh >= 0 && ih0 + kh < cv.H && iw0 + kw >= 0 && iw0 + kw < cv.W) bits |= 1u << (kh * cv.fw + kw);
+    ok[it] = bits;
+  }
+}
+
+template <int NSLOT>
+__device__ __forceinline__ void load_tile_conv_lean(const float* (&p0)[NSLOT], const unsigned (&ok)[NSLOT], int tap,
+                                                    long long slice_offset, float4 (&reg)[NSLOT]) {
+  const unsigned bit = 1u << tap;
+#pragma unroll
+  for (int it = 0; it < NSLOT; ++it) {
+    const float* p = (ok[it] & bit) ? p0[it] + slice_offset : kZeroQuad;
+    const floatx4 v = *reinterpret_cast<const floatx4*>(p);  // as a vector: a struct copy from a selected pointer stays in memory
+    reg[it] = make_float4(v[0], v[1], v[2], v[3]);
+  }
+}
+
 // MFMA operand of one 32-row sub-tile for k-group g: four steps' values for this lane.
 template <int ROWS, int BK, bool KC>
 __device__ __forceinline__ float4 read_frag(const float* __restrict__ lds, int row, int g, int h) {
@@ -216,12 +261,13 @@ __device__ __forceinline__ float f4_get(const float4& v, int s) {
 // Tiled kernel for medium and large problems: BM x BN tile, BK-deep k-slices double-buffered in LDS
 // (one barrier per slice), WAVES_M x WAVES_N wavefronts each owning a (BM/WAVES_M) x (BN/WAVES_N) sub-tile.
 // CONV: the A operand is the implicit im2col view `cv` of a convolution input instead of a matrix.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC, bool CONV>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC, bool CONV, bool LEAN>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, const float* __restrict__ bias,
     int M, int N, int K, int tiles_m, int tiles_n, int total_blocks, long long strideA, long long strideB,
     long long strideC, int act, int m_fastest, ConvA cv) {
   static_assert(!CONV || A_KC, "the im2col view is K-contiguous");
+  static_assert(!LEAN || (CONV && VEC), "the lean loader is the vector form of the convolution loader");
   constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -280,8 +326,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
 
   float4 ra[SA], rb[SB];
   const int nk = (K + BK - 1) / BK;
-  ConvRow crow[CONV ? SA : 1];
-  if constexpr (CONV) conv_rows<BM, BK, NT, SA>(cv, M, m0, tid, crow);
+  ConvRow crow[CONV && !LEAN ? SA : 1];
+  if constexpr (CONV && !LEAN) conv_rows<BM, BK, NT, SA>(cv, M, m0, tid, crow);
+  const float* cp0[SA];  // lean loader only
+  unsigned cok[SA];
+  // filter tap (kh, kw), its index and the channel offset of the next slice load_a is asked for (slices are
+  // requested in order 0, 1, 2, ...); uniform across the workgroup
+  int tap_c0 = 0, tap_kh = 0, tap_kw = 0, tap_idx = 0;
+  if constexpr (LEAN) conv_lean_rows<BM, BK, NT, SA>(cv, M, K, m0, tid, cp0, cok);
   // k-slices that lie entirely inside K take the branch-free loaders (vector layouts only)
   constexpr bool FAST_A = VEC && !CONV, FAST_B = VEC;
   const int nk_full = K / BK;
@@ -292,7 +344,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
   const size_t step_a = A_KC ? (size_t)BK : (size_t)BK * lda, step_b = B_KC ? (size_t)BK : (size_t)BK * ldb;
   // FULL: k-slice kt is known to lie inside K
   auto load_a = [&](int kt, auto full) {
-    if constexpr (CONV) load_tile_conv<BM, BK, VEC, NT, SA>(cv, K, kt * BK, tid, crow, ra);
+    if constexpr (LEAN) {
+      load_tile_conv_lean<SA>(cp0, cok, tap_idx, ((long long)tap_kh * cv.W + tap_kw) * cv.Ci + tap_c0, ra);
+      tap_c0 += BK;
+      if (tap_c0 >= cv.Ci) {
+        tap_c0 = 0;
+        ++tap_idx;
+        if (++tap_kw == cv.fw) {
+          tap_kw = 0;
+          ++tap_kh;
+        }
+      }
+    } else if constexpr (CONV) load_tile_conv<BM, BK, VEC, NT, SA>(cv, K, kt * BK, tid, crow, ra);
     else if constexpr (FAST_A && decltype(full)::value) load_tile_full<SA>(pa, kt * step_a, ra);
     else load_tile<BM, BK, A_KC, VEC, NT, SA>(A, lda, M, K, m0, kt * BK, tid, ra);
   };
@@ -370,14 +433,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(
   }
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC, bool CONV = false>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool VEC, bool CONV = false,
+          bool LEAN = false>
 int launch_cfg(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k, int act,
                hipStream_t stream, const ConvA& cv = ConvA{}) {
   using TA = Tile<BM, BK, A_KC>;
   using TB = Tile<BN, BK, B_KC>;
   constexpr size_t lds_bytes = 2 * (TA::kFloats + TB::kFloats) * sizeof(float);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
-  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, A_KC, B_KC, VEC, CONV>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, A_KC, B_KC, VEC, CONV, LEAN>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes, lds_allowed) != TFX_OK) return TFX_ERR_LAUNCH;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
@@ -417,7 +481,6 @@ int launch_layout(const float* a, const float* b, float* c, const float* bias, i
 // Layout of one MFMA 16x16x4 (wave64): A: lane l holds A[i = l % 16][k = l / 16]; B: lane l holds
 // B[k = l / 16][j = l % 16]; D: register v of lane l holds D[i = 4 * (l / 16) + v][j = l % 16].
 // Within a group of 16 consecutive k, lane quarter q = l / 16 takes k = 16g + 4q + s in step s.
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 template <int ROWS, int BK, bool KC>
 __device__ __forceinline__ float4 read_frag16(const float* __restrict__ lds, int row, int g, int q) {
@@ -632,6 +695,12 @@ int launch_conv2d_gemm(const float* x, const float* w, const float* bias, float*
   const ConvA cv{x, h, wd, ci, oh, ow, fw, sh, sw, pt, pl};
   const bool vec = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 &&
                    ci % 4 == 0 && co % 4 == 0;
+  // k-slices of 32 inside one filter tap, one validity bit per tap: the lean loader
+  const bool lean = vec && ci % 32 == 0 && fh * fw <= 32;
+  if (lean)
+    return prefer_128(1, m, co)
+               ? launch_cfg<128, 128, 32, 2, 2, true, false, true, true, true>(nullptr, w, y, bias, 1, (int)m, co, (int)k, act, stream, cv)
+               : launch_cfg<64, 64, 32, 2, 2, true, false, true, true, true>(nullptr, w, y, bias, 1, (int)m, co, (int)k, act, stream, cv);
   if (prefer_128(1, m, co)) {
     return vec ? launch_cfg<128, 128, 32, 2, 2, true, false, true, true>(nullptr, w, y, bias, 1, (int)m, co, (int)k, act, stream, cv)
                : launch_cfg<128, 128, 32, 2, 2, true, false, false, true>(nullptr, w, y, bias, 1, (int)m, co, (int)k, act, stream, cv);
