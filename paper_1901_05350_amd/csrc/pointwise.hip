@@ -284,8 +284,9 @@ bool pointwise_stream_supported(int m, int k, int n, const void* x, const void* 
   const bool shape = (k == 32 && n == 64) || (k == 64 && n == 128) || (k == 128 && n == 128) || (k == 128 && n == 256);
   const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 &&
                        reinterpret_cast<uintptr_t>(y) % 16 == 0 && reinterpret_cast<uintptr_t>(bias) % 16 == 0;  // a null bias passes
-  // worthwhile once every one of the 256 CUs gets a full workgroup of 8 slabs (measured: below that the tiled GEMM wins)
-  return shape && aligned && m >= 16384;
+  // worthwhile once every one of the 256 CUs gets a full workgroup of 8 slabs (measured: below that the tiled GEMM
+  // wins); the 128 KB filter leaves one workgroup per CU and needs 4 times as many rows to pay
+  return shape && aligned && m >= (k == 128 && n == 256 ? 65536 : 16384);
 }
 
 int launch_pointwise_stream(const float* x, const float* w, const float* bias, float* y, int m, int k, int n, int act,
