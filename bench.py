@@ -29,19 +29,19 @@ PEAK_HBM = 8.0e12          # B/s
 # reading for a plain 205.5 MB copy (profiles/hbm_traffic_counters.txt).  Each entry names the kernel
 # source it was measured on; if that file has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100836248, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
-    "pointwise_64x56x56x128_to_128": (207507859, "pointwise.hip", "50947f4fbda77ef9c2f55bb75007539b43300bcfb9c65a85012606b202e1827a"),
-    "conv3x3_64x56x56x64_to_64": (104629381, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411117332, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (256969578, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235060813, "gemm_f16.hip", "3cfafa2edff0aad16fa05d59662181687afc393b0c5786e74170f7bc59d16b22"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50476187, "gemm_f16.hip", "3cfafa2edff0aad16fa05d59662181687afc393b0c5786e74170f7bc59d16b22"),
-    "pointwise_f16_64x56x56x128_to_128": (103141760, "pointwise_f16.hip", "0b7c2bf74c636322c00f99f09b8bf098c5c38aec4d922af8763a90d3f0e45c51"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205667919, "conv_f16.hip", "efc626efab45e2289bcd9a49a547526219b0f58877adad5696699d83053e4b0d"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (128533989, "conv_f16.hip", "efc626efab45e2289bcd9a49a547526219b0f58877adad5696699d83053e4b0d"),
-    "add_f32_64M": (805263048, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
-    "add_f16_64M": (402651729, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
-    "mobilenet_b1_gemm_13_launches": (53651638, "gemm.hip", "63c2fa7d707dd8bb73b4595b26123302517f7efbf82604962cf45fabe6ed2628"),
+    "batch_matmul_8x1024x1024x1024_tB": (100843415, "gemm.hip", "ef76c2f9d76c5eac3e9a9cecdb1559e8b8e20643982db30e0783ffdf31f860e8"),
+    "pointwise_64x56x56x128_to_128": (206178151, "pointwise.hip", "23b1d84130711dfef1e8f63d292687a18ccdac496a9db232f6f4770c03ea2bfb"),
+    "conv3x3_64x56x56x64_to_64": (104501626, "gemm.hip", "ef76c2f9d76c5eac3e9a9cecdb1559e8b8e20643982db30e0783ffdf31f860e8"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411117208, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (256980010, "depthwise.hip", "19712e6d1d9c0bfe6726a16bf1066001650a7d19eb971b42a052113fe0ec2b2b"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235069815, "gemm_f16.hip", "54fd5820b9ce4de4f4ee13d8adf6330f797356f7585cabbfdb6a2b6e6f2b2bb9"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50489483, "gemm_f16.hip", "54fd5820b9ce4de4f4ee13d8adf6330f797356f7585cabbfdb6a2b6e6f2b2bb9"),
+    "pointwise_f16_64x56x56x128_to_128": (103141558, "pointwise_f16.hip", "cf4c2e12e5128b41a9520de40fd6d6562d9c0d441b35d4747031b2c3a0c7254e"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205674761, "conv_f16.hip", "8ca9932c5cc177c0de1bff4fa98cc4a79124cbd54b33c29dbb5a656f3509f013"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129328969, "conv_f16.hip", "8ca9932c5cc177c0de1bff4fa98cc4a79124cbd54b33c29dbb5a656f3509f013"),
+    "add_f32_64M": (805262957, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
+    "add_f16_64M": (402651516, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
+    "mobilenet_b1_gemm_13_launches": (53620897, "gemm.hip", "ef76c2f9d76c5eac3e9a9cecdb1559e8b8e20643982db30e0783ffdf31f860e8"),
 }
 
 
