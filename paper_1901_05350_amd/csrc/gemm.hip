@@ -678,10 +678,13 @@ int launch_gemm(const float* a, const float* b, float* c, const float* bias, int
   // throughput (measured on the MobileNet 28x28 .. 7x7 pointwise layers: 3.8-6.1 us each).
   const long long blocks16x32 = (long long)batch * ((m + 15) / 16) * ((n + 31) / 32);
   const bool wide = blocks16x32 >= 160;
-  if (k <= 128)
+  // more tiles than fit on the chip at once (one 512-deep tile per CU): 128-deep tiles, so that several
+  // workgroups share a CU and one's loads overlap another's MFMAs (M = 392, 512 -> 1024: 15.8 -> 11.2 us)
+  const int kcap = blocks16x32 > 512 ? 128 : 1 << 30;
+  if (k <= 128 || kcap <= 128)
     return wide ? launch_m16_layout<2, 128, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream)
                 : launch_m16_layout<1, 128, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
-  if (k <= 256)
+  if (k <= 256 || kcap <= 256)
     return wide ? launch_m16_layout<2, 256, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream)
                 : launch_m16_layout<1, 256, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
   return wide ? launch_m16_layout<2, 512, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream)
