@@ -620,6 +620,129 @@ int launch_m16_cfg(const float* a, const float* b, float* c, const float* bias, 
   return check_launch();
 }
 
+// 16-row tiles without operand staging, for A stored [M,K], B stored [K,N] (the pointwise-conv layout) and
+// K = 64 ... 1024 a power of two: the WAVES_K wavefronts of a workgroup split K into chunks of 16 ... 128, and every
+// wavefront loads the MFMA operands of its chunk straight into registers -- its row of A as 128-bit loads (4
+// consecutive k, the contraction order permuted inside groups of 16 as in the other kernels) and, for the same
+// k, TN adjacent columns of B as one load (TN = 2: 16 lanes read 128 contiguous bytes of a row of B; output
+// column 2c + j of the 32-column tile is then column c of MFMA column block j).  All loads of a wavefront are
+// issued before its first MFMA; there is no LDS fill and no barrier before the split-K reduction, which takes
+// 0.4-0.7 us off kernels that last 4-6 us (the batch-1 network's 56x56 ... 7x7 pointwise layers).
+template <int CHUNK, int WAVES_K, int TN>
+__global__ __launch_bounds__(64 * WAVES_K) void gemm_m16_direct_kernel(const float* __restrict__ A,
+                                                                       const float* __restrict__ B, float* __restrict__ C,
+                                                                       const float* __restrict__ bias, int M, int N, int K,
+                                                                       int tiles_m, int tiles_n, int total_blocks, int act,
+                                                                       int m_fastest) {
+  constexpr int G = CHUNK / 16;  // k-groups of 16 per wavefront
+  static_assert(CHUNK % 16 == 0 && CHUNK <= 128 && (TN == 1 || TN == 2) && 64 * WAVES_K >= 256, "shape");
+  __shared__ float red[WAVES_K * TN * 4 * 64];  // split-K partials: [wavefront][column block j][register v][lane]
+
+  const int bid = blockIdx.x;
+  const int q8 = total_blocks / kXcds, rem = total_blocks % kXcds;
+  const int xcd = bid % kXcds;
+  const int vid = xcd * q8 + (xcd < rem ? xcd : rem) + bid / kXcds;
+  const int tile_m = m_fastest ? vid % tiles_m : vid / tiles_n;
+  const int tile_n = m_fastest ? vid / tiles_m : vid % tiles_n;
+  const int tid = threadIdx.x, wk = tid / 64, lane = tid % 64, li = lane % 16, q = lane / 16;
+  const int m0 = tile_m * 16, n0 = tile_n * 16 * TN;
+
+  // operand addresses: rows / columns past the matrix are clamped (they only feed outputs that are not stored)
+  const int arow = min(m0 + li, M - 1);
+  const int bcol = min(n0 + TN * li, N - TN);
+  const float* ap = A + (size_t)arow * K + wk * CHUNK + 4 * q;
+  const float* bp = B + (size_t)(wk * CHUNK + 4 * q) * N + bcol;
+  float4 a[G];
+  float b[G][4][TN];
+#pragma unroll
+  for (int g = 0; g < G; ++g) a[g] = *reinterpret_cast<const float4*>(ap + 16 * g);
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const float* p = bp + (size_t)(16 * g + s) * N;
+      if constexpr (TN == 2) {
+        const float2 t = *reinterpret_cast<const float2*>(p);
+        b[g][s][0] = t.x;
+        b[g][s][1] = t.y;
+      } else {
+        b[g][s][0] = *p;
+      }
+    }
+
+  // epilogue thread e < 256 owns register v = e / 64 of lane l = e % 64: row 4 (l / 16) + v, columns
+  // TN (l % 16) ... + TN - 1; fetch its bias now
+  const int ev = tid / 64, el = tid % 64;
+  const int erow = m0 + 4 * (el / 16) + ev, ecol = n0 + TN * (el % 16);
+  float ebias[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) ebias[j] = (tid < 256 && bias != nullptr && ecol + j < N) ? bias[ecol + j] : 0.f;
+
+  floatx4 acc[2][TN];  // [chain][column block]
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[c][j][v] = 0.f;
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[s & 1][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(f4_get(a[g], s), b[g][s][j], acc[s & 1][j], 0, 0, 0);
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[((wk * TN + j) * 4 + v) * 64 + lane] = acc[0][j][v] + acc[1][j][v];
+  __syncthreads();
+  if (tid < 256 && erow < M) {
+    const ActClamp clamp = make_act(act);
+    float o[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      float sum = ebias[j];
+#pragma unroll
+      for (int w = 0; w < WAVES_K; ++w) sum += red[((w * TN + j) * 4 + ev) * 64 + el];
+      o[j] = apply_act(sum, clamp);
+    }
+    float* cp = C + (size_t)erow * N + ecol;
+    if constexpr (TN == 2) {
+      if (ecol + 1 < N) *reinterpret_cast<float2*>(cp) = make_float2(o[0], o[1]);
+    } else {
+      if (ecol < N) *cp = o[0];
+    }
+  }
+}
+
+// K a power of two in 64 ... 1024, N even, 16-byte aligned A (K % 4 == 0 holds), 8-byte aligned B, C and bias.
+bool m16_direct_supported(const float* a, const float* b, const float* c, const float* bias, int batch, int n, int k,
+                          bool a_kc, bool b_kc) {
+  const bool aligned = reinterpret_cast<uintptr_t>(a) % 16 == 0 && reinterpret_cast<uintptr_t>(b) % 8 == 0 &&
+                       reinterpret_cast<uintptr_t>(c) % 8 == 0 && reinterpret_cast<uintptr_t>(bias) % 8 == 0;
+  return batch == 1 && a_kc && !b_kc && aligned && n % 2 == 0 && n >= 2 &&
+         (k == 64 || k == 128 || k == 256 || k == 512 || k == 1024);
+}
+
+template <int TN>
+int launch_m16_direct(const float* a, const float* b, float* c, const float* bias, int m, int n, int k, int act,
+                      hipStream_t stream) {
+  const int tiles_m = (m + 15) / 16, tiles_n = (n + 16 * TN - 1) / (16 * TN);
+  const long long total = (long long)tiles_m * tiles_n;
+  if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
+#define TFX_DIRECT(CHUNK, WK)                                                                                      \
+  hipLaunchKernelGGL((gemm_m16_direct_kernel<CHUNK, WK, TN>), dim3((unsigned)total), dim3(64 * WK), 0, stream, a, b, c, \
+                     bias, m, n, k, tiles_m, tiles_n, (int)total, act, n > m ? 1 : 0)
+  if (k == 64) TFX_DIRECT(16, 4);
+  else if (k == 128) TFX_DIRECT(16, 8);
+  else if (k == 256) TFX_DIRECT(32, 8);
+  else if (k == 512) TFX_DIRECT(64, 8);
+  else TFX_DIRECT(128, 8);
+#undef TFX_DIRECT
+  return check_launch();
+}
+
 template <int TN, int BK, int WAVES_K>
 int launch_m16_layout(const float* a, const float* b, float* c, const float* bias, int batch, int m, int n, int k,
                       bool a_kc, bool b_kc, bool vec, int act, hipStream_t stream) {
@@ -678,6 +801,11 @@ int launch_gemm(const float* a, const float* b, float* c, const float* bias, int
   // throughput (measured on the MobileNet 28x28 .. 7x7 pointwise layers: 3.8-6.1 us each).
   const long long blocks16x32 = (long long)batch * ((m + 15) / 16) * ((n + 31) / 32);
   const bool wide = blocks16x32 >= 160;
+  // (with more tiles than the chip holds at once and K = 1024 the staged kernel's 128-deep tiles overlap better:
+  // M = 392, 1024 -> 1024: 18.6 us against 26.0)
+  if (m16_direct_supported(a, b, c, bias, batch, n, k, a_kc, b_kc) && (blocks16x32 <= 512 || k <= 512))
+    return wide ? launch_m16_direct<2>(a, b, c, bias, m, n, k, act, stream)
+                : launch_m16_direct<1>(a, b, c, bias, m, n, k, act, stream);
   // more tiles than fit on the chip at once (one 512-deep tile per CU): 128-deep tiles, so that several
   // workgroups share a CU and one's loads overlap another's MFMAs (M = 392, 512 -> 1024: 15.8 -> 11.2 us)
   const int kcap = blocks16x32 > 512 ? 128 : 1 << 30;

@@ -62,6 +62,35 @@ def test_shape_sweep_all_transposes(ta, tb):
         assert_close(got, ref, "matMul m=%d k=%d n=%d ta=%d tb=%d" % (m, k, n, ta, tb))
 
 
+def test_small_m_power_of_two_k_untransposed():
+    """A [M,K] times B [K,N] with K = 64 ... 1024 a power of two and few output tiles: the 16-row kernel that loads its
+    matrix-core operands straight from memory (no LDS staging; output columns interleaved between two column blocks).
+    One-hot products pin the row / column / k mapping exactly; random operands, ragged M and N that are not
+    multiples of the 32-column tile check the clamped loads and predicated stores; the pointwise-conv form adds
+    bias and clamp."""
+    import paper_1901_05350_amd as tfx
+    from oracle import ACT_RELU6, PAD_SAME
+    r = rng(77)
+    for k in (64, 128, 256, 512, 1024):
+        for (m, n) in ((196, 512), (49, 1024), (37, 130), (1, 2), (16, 34), (784, 256), (3136, 128), (200, 66)):
+            for _ in range(3):
+                i, kk, j = int(r.integers(m)), int(r.integers(k)), int(r.integers(n))
+                a = np.zeros((m, k), np.float32)
+                b = np.zeros((k, n), np.float32)
+                a[i, kk] = 1
+                b[kk, j] = 1
+                want = np.zeros((m, n), np.float32)
+                want[i, j] = 1
+                assert np.array_equal(run_matmul(a, b, False, False), want), (m, k, n, i, kk, j)
+            a = r.uniform(-1, 1, (m, k)).astype(np.float32)
+            b = (r.standard_normal((k, n)) * np.sqrt(2.0 / k)).astype(np.float32)
+            assert_close(run_matmul(a, b, False, False), oracle.matmul(a, b), "matMul m=%d k=%d n=%d" % (m, k, n))
+            bias = (r.standard_normal(n) * 0.5).astype(np.float32)
+            got = host(tfx.tfx_conv2d(dev(a.reshape(1, 1, m, k)), dev(b.reshape(1, 1, k, n)), dev(bias), 1, PAD_SAME, ACT_RELU6))
+            ref = oracle.conv2d(a.reshape(1, 1, m, k), b.reshape(1, 1, k, n), bias, 1, PAD_SAME, ACT_RELU6)
+            assert_close(got, ref, "pointwise m=%d k=%d n=%d" % (m, k, n))
+
+
 def test_all_ones_counts_k_exactly():
     for k in [1, 5, 127, 129, 1000]:
         got = run_matmul(np.ones((37, k), np.float32), np.ones((k, 41), np.float32), False, False)
