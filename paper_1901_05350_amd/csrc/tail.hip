@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void pool_fc_partial_kernel(const float* __res
 }
 
 __device__ __forceinline__ float block_reduce(float v, bool is_max, float* scratch) {
-  // wave reduction by shuffles, then across the 4 waves through LDS
+  // wave reduction by shuffles, then across the workgroup's waves through LDS
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     const float o = __shfl_xor(v, off, 64);
@@ -87,53 +87,35 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* scrat
   if (threadIdx.x % 64 == 0) scratch[wave] = v;
   __syncthreads();
   float r = scratch[0];
-  for (int i = 1; i < 4; ++i) r = is_max ? fmaxf(r, scratch[i]) : r + scratch[i];
+  for (int i = 1; i < (int)blockDim.x / 64; ++i) r = is_max ? fmaxf(r, scratch[i]) : r + scratch[i];
   return r;
 }
 
-// One workgroup per image: logits = bias + sum of the K-slice partials, then
-// probs = exp(l - max l) / sum exp(l - max l).
-constexpr int kMaxPerThread = 4;  // classes <= 256 * 4
-__global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ partial,
-                                                      const float* __restrict__ bias, float* __restrict__ logits,
-                                                      float* __restrict__ probs, int n, int classes) {
-  __shared__ float scratch[4];
+// One workgroup per image, one thread per class (all of a thread's 32 partial sums in flight at once):
+// logits = bias + sum of the K-slice partials, then probs = exp(l - max l) / sum exp(l - max l).
+constexpr int kSoftmaxThreads = 1024;  // classes <= 1024
+__global__ __launch_bounds__(kSoftmaxThreads) void softmax_kernel(const float* __restrict__ partial,
+                                                                  const float* __restrict__ bias,
+                                                                  float* __restrict__ logits, float* __restrict__ probs,
+                                                                  int n, int classes) {
+  __shared__ float scratch[kSoftmaxThreads / 64];
   const int img = blockIdx.x;
-  float l[kMaxPerThread];
-  float mx = -INFINITY;
+  const int j = threadIdx.x;
+  float l = -INFINITY;
+  if (j < classes) {
+    float part[kFcSlices];
 #pragma unroll
-  for (int i = 0; i < kMaxPerThread; ++i) {
-    const int j = threadIdx.x + 256 * i;
-    l[i] = -INFINITY;
-    if (j < classes) {
-      float part[kFcSlices];
+    for (int s = 0; s < kFcSlices; ++s) part[s] = partial[((size_t)s * n + img) * classes + j];
+    float v = bias ? bias[j] : 0.f;
 #pragma unroll
-      for (int s = 0; s < kFcSlices; ++s) part[s] = partial[((size_t)s * n + img) * classes + j];
-      float v = bias ? bias[j] : 0.f;
-#pragma unroll
-      for (int s = 0; s < kFcSlices; ++s) v += part[s];
-      if (logits) logits[(size_t)img * classes + j] = v;
-      l[i] = v;
-      mx = fmaxf(mx, v);
-    }
+    for (int s = 0; s < kFcSlices; ++s) v += part[s];
+    if (logits) logits[(size_t)img * classes + j] = v;
+    l = v;
   }
-  mx = block_reduce(mx, true, scratch);
-  float sum = 0.f;
-#pragma unroll
-  for (int i = 0; i < kMaxPerThread; ++i) {
-    const int j = threadIdx.x + 256 * i;
-    if (j < classes) {
-      l[i] = __expf(l[i] - mx);
-      sum += l[i];
-    }
-  }
-  sum = block_reduce(sum, false, scratch);
-  const float inv = 1.0f / sum;
-#pragma unroll
-  for (int i = 0; i < kMaxPerThread; ++i) {
-    const int j = threadIdx.x + 256 * i;
-    if (j < classes) probs[(size_t)img * classes + j] = l[i] * inv;
-  }
+  const float mx = block_reduce(l, true, scratch);
+  const float e = j < classes ? __expf(l - mx) : 0.f;
+  const float sum = block_reduce(e, false, scratch);
+  if (j < classes) probs[(size_t)img * classes + j] = e / sum;
 }
 
 }  // namespace
@@ -145,14 +127,14 @@ size_t fc_partial_floats(int n, int k, int classes) {
 
 int launch_pool_fc_softmax(const float* a, const float* w, const float* bias, float* partial, float* logits,
                            float* probs, int n, int hw, int k, int classes, hipStream_t stream) {
-  if (classes > 256 * kMaxPerThread) return TFX_ERR_UNSUPPORTED;
+  if (classes > kSoftmaxThreads) return TFX_ERR_UNSUPPORTED;
   const int kslice = (k + kFcSlices - 1) / kFcSlices;
   if (kslice > kFcKMax || hw > 64) return TFX_ERR_UNSUPPORTED;
   dim3 grid((classes + 255) / 256, kFcSlices, (n + kFcBatchMax - 1) / kFcBatchMax);
   hipLaunchKernelGGL(pool_fc_partial_kernel, grid, dim3(256), 0, stream, a, w, partial, n, hw, k, classes, kslice);
   int rc = check_launch();
   if (rc) return rc;
-  hipLaunchKernelGGL(softmax_kernel, dim3(n), dim3(256), 0, stream, (const float*)partial, bias, logits, probs, n,
+  hipLaunchKernelGGL(softmax_kernel, dim3(n), dim3(kSoftmaxThreads), 0, stream, (const float*)partial, bias, logits, probs, n,
                      classes);
   return check_launch();
 }
