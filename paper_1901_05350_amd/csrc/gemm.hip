@@ -621,7 +621,7 @@ int launch_m16_cfg(const float* a, const float* b, float* c, const float* bias, 
 }
 
 // 16-row tiles without operand staging, for A stored [M,K], B stored [K,N] (the pointwise-conv layout) and
-// K = 64 ... 1024 a power of two: the WAVES_K wavefronts of a workgroup split K into chunks of 16 ... 128, and every
+// K = 64 ... 1024 (a multiple of 16 per wavefront): the WAVES_K wavefronts of a workgroup split K into chunks of 16 ... 128, and every
 // wavefront loads the MFMA operands of its chunk straight into registers -- its row of A as 128-bit loads (4
 // consecutive k, the contraction order permuted inside groups of 16 as in the other kernels) and, for the same
 // k, TN adjacent columns of B as one load (TN = 2: 16 lanes read 128 contiguous bytes of a row of B; output
@@ -716,13 +716,13 @@ __global__ __launch_bounds__(64 * WAVES_K) void gemm_m16_direct_kernel(const flo
   }
 }
 
-// K a power of two in 64 ... 1024, N even, 16-byte aligned A (K % 4 == 0 holds), 8-byte aligned B, C and bias.
+// K one of the supported depths in 64 ... 1024, N even, 16-byte aligned A (K % 4 == 0 holds), 8-byte aligned B, C and bias.
 bool m16_direct_supported(const float* a, const float* b, const float* c, const float* bias, int batch, int n, int k,
                           bool a_kc, bool b_kc) {
   const bool aligned = reinterpret_cast<uintptr_t>(a) % 16 == 0 && reinterpret_cast<uintptr_t>(b) % 8 == 0 &&
                        reinterpret_cast<uintptr_t>(c) % 8 == 0 && reinterpret_cast<uintptr_t>(bias) % 8 == 0;
   return batch == 1 && a_kc && !b_kc && aligned && n % 2 == 0 && n >= 2 &&
-         (k == 64 || k == 128 || k == 256 || k == 512 || k == 1024);
+         (k == 64 || k == 96 || k == 128 || k == 192 || k == 256 || k == 384 || k == 512 || k == 768 || k == 1024);
 }
 
 template <int TN>
@@ -734,10 +734,15 @@ int launch_m16_direct(const float* a, const float* b, float* c, const float* bia
 #define TFX_DIRECT(CHUNK, WK)                                                                                      \
   hipLaunchKernelGGL((gemm_m16_direct_kernel<CHUNK, WK, TN>), dim3((unsigned)total), dim3(64 * WK), 0, stream, a, b, c, \
                      bias, m, n, k, tiles_m, tiles_n, (int)total, act, n > m ? 1 : 0)
+  // K = chunk x wavefronts (the channel counts of the MobileNet family at widths 0.5, 0.75 and 1)
   if (k == 64) TFX_DIRECT(16, 4);
+  else if (k == 96) TFX_DIRECT(16, 6);
   else if (k == 128) TFX_DIRECT(16, 8);
+  else if (k == 192) TFX_DIRECT(32, 6);
   else if (k == 256) TFX_DIRECT(32, 8);
+  else if (k == 384) TFX_DIRECT(48, 8);
   else if (k == 512) TFX_DIRECT(64, 8);
+  else if (k == 768) TFX_DIRECT(96, 8);
   else TFX_DIRECT(128, 8);
 #undef TFX_DIRECT
   return check_launch();

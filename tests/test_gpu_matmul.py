@@ -62,8 +62,8 @@ def test_shape_sweep_all_transposes(ta, tb):
         assert_close(got, ref, "matMul m=%d k=%d n=%d ta=%d tb=%d" % (m, k, n, ta, tb))
 
 
-def test_small_m_power_of_two_k_untransposed():
-    """A [M,K] times B [K,N] with K = 64 ... 1024 a power of two and few output tiles: the 16-row kernel that loads its
+def test_small_m_untransposed_direct_operand_depths():
+    """A [M,K] times B [K,N] with K one of 64, 96, 128, ..., 1024 and few output tiles: the 16-row kernel that loads its
     matrix-core operands straight from memory (no LDS staging; output columns interleaved between two column blocks).
     One-hot products pin the row / column / k mapping exactly; random operands, ragged M and N that are not
     multiples of the 32-column tile check the clamped loads and predicated stores; the pointwise-conv form adds
@@ -71,7 +71,7 @@ def test_small_m_power_of_two_k_untransposed():
     import paper_1901_05350_amd as tfx
     from oracle import ACT_RELU6, PAD_SAME
     r = rng(77)
-    for k in (64, 128, 256, 512, 1024):
+    for k in (64, 96, 128, 192, 256, 384, 512, 768, 1024):
         for (m, n) in ((196, 512), (49, 1024), (37, 130), (1, 2), (16, 34), (784, 256), (3136, 128), (200, 66)):
             for _ in range(3):
                 i, kk, j = int(r.integers(m)), int(r.integers(k)), int(r.integers(n))
