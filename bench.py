@@ -70,7 +70,7 @@ def main():
                                                "batch_matmul_8x1024x1024x1024_tB; 'list' prints the names")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
