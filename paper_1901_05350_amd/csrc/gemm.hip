@@ -628,12 +628,15 @@ int launch_m16_cfg(const float* a, const float* b, float* c, const float* bias, 
 // column 2c + j of the 32-column tile is then column c of MFMA column block j).  All loads of a wavefront are
 // issued before its first MFMA; there is no LDS fill and no barrier before the split-K reduction, which takes
 // 0.4-0.7 us off kernels that last 4-6 us (the batch-1 network's 56x56 ... 7x7 pointwise layers).
-template <int CHUNK, int WAVES_K, int TN>
+// CONV: A is the implicit-GEMM view of a convolution input with Ci = CHUNK channels and WAVES_K filter taps, one
+// tap per wavefront (K = taps x Ci): a lane's A operand is 4 consecutive channels of its output pixel's input
+// pixel under that tap, or zeros if the tap falls outside the image.
+template <int CHUNK, int WAVES_K, int TN, bool CONV = false>
 __global__ __launch_bounds__(64 * WAVES_K) void gemm_m16_direct_kernel(const float* __restrict__ A,
                                                                        const float* __restrict__ B, float* __restrict__ C,
                                                                        const float* __restrict__ bias, int M, int N, int K,
                                                                        int tiles_m, int tiles_n, int total_blocks, int act,
-                                                                       int m_fastest) {
+                                                                       int m_fastest, ConvA cv) {
   constexpr int G = CHUNK / 16;  // k-groups of 16 per wavefront
   static_assert(CHUNK % 16 == 0 && CHUNK <= 128 && (TN == 1 || TN == 2) && 64 * WAVES_K >= 256, "shape");
   __shared__ float red[WAVES_K * TN * 4 * 64];  // split-K partials: [wavefront][column block j][register v][lane]
@@ -650,12 +653,31 @@ __global__ __launch_bounds__(64 * WAVES_K) void gemm_m16_direct_kernel(const flo
   // operand addresses: rows / columns past the matrix are clamped (they only feed outputs that are not stored)
   const int arow = min(m0 + li, M - 1);
   const int bcol = min(n0 + TN * li, N - TN);
-  const float* ap = A + (size_t)arow * K + wk * CHUNK + 4 * q;
+  const float* ap;
+  bool inside = true;
+  if constexpr (CONV) {
+    const int ow = arow % cv.OW;
+    const int t = arow / cv.OW;
+    const int oh = t % cv.OH;
+    const int n = t / cv.OH;
+    const int ih = oh * cv.sh - cv.pt + wk / cv.fw, iw = ow * cv.sw - cv.pl + wk % cv.fw;
+    inside = ih >= 0 && ih < cv.H && iw >= 0 && iw < cv.W;
+    // outside the image: load from the (valid) clamped pixel, zero the values below
+    const int ihc = min(max(ih, 0), cv.H - 1), iwc = min(max(iw, 0), cv.W - 1);
+    ap = cv.x + (((size_t)n * cv.H + ihc) * cv.W + iwc) * CHUNK + 4 * q;
+  } else {
+    ap = A + (size_t)arow * K + wk * CHUNK + 4 * q;
+  }
   const float* bp = B + (size_t)(wk * CHUNK + 4 * q) * N + bcol;
   float4 a[G];
   float b[G][4][TN];
 #pragma unroll
   for (int g = 0; g < G; ++g) a[g] = *reinterpret_cast<const float4*>(ap + 16 * g);
+  if constexpr (CONV) {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      if (!inside) a[g] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
 #pragma unroll
   for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -733,7 +755,7 @@ int launch_m16_direct(const float* a, const float* b, float* c, const float* bia
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
 #define TFX_DIRECT(CHUNK, WK)                                                                                      \
   hipLaunchKernelGGL((gemm_m16_direct_kernel<CHUNK, WK, TN>), dim3((unsigned)total), dim3(64 * WK), 0, stream, a, b, c, \
-                     bias, m, n, k, tiles_m, tiles_n, (int)total, act, n > m ? 1 : 0)
+                     bias, m, n, k, tiles_m, tiles_n, (int)total, act, n > m ? 1 : 0, ConvA{})
   // K = chunk x wavefronts (the channel counts of the MobileNet family at widths 0.5, 0.75 and 1)
   if (k == 64) TFX_DIRECT(16, 4);
   else if (k == 96) TFX_DIRECT(16, 6);
@@ -824,6 +846,18 @@ int launch_gemm(const float* a, const float* b, float* c, const float* bias, int
               : launch_m16_layout<1, 512, 8>(a, b, c, bias, batch, m, n, k, a_kc, b_kc, vec, act, stream);
 }
 
+// 3x3 convolution of a small feature map (few 16 x 32 output tiles) with 16 / 32 / 64 / 128 input channels: one
+// filter tap per wavefront, operands straight from memory (gemm_m16_direct_kernel<..., CONV>).
+template <int CI>
+int launch_conv3x3_direct(const ConvA& cv, const float* w, const float* bias, float* y, int m, int co, int act,
+                          hipStream_t stream) {
+  const int tiles_m = (m + 15) / 16, tiles_n = (co + 31) / 32;
+  const int total = tiles_m * tiles_n;
+  hipLaunchKernelGGL((gemm_m16_direct_kernel<CI, 9, 2, true>), dim3((unsigned)total), dim3(64 * 9), 0, stream, nullptr, w, y,
+                     bias, m, co, 9 * CI, tiles_m, tiles_n, total, act, co > m ? 1 : 0, cv);
+  return check_launch();
+}
+
 int launch_conv2d_gemm(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int ci, int fh,
                        int fw, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream) {
   const long long m = (long long)n * oh * ow, k = (long long)fh * fw * ci;
@@ -831,6 +865,16 @@ int launch_conv2d_gemm(const float* x, const float* w, const float* bias, float*
   const ConvA cv{x, h, wd, ci, oh, ow, fw, sh, sw, pt, pl};
   const bool vec = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 &&
                    ci % 4 == 0 && co % 4 == 0;
+  // small maps (at most 512 tiles of 16 x 32: the tiled kernel would leave most CUs idle and run its 9 Ci / 32 k-slices
+  // one after the other on the rest)
+  const long long tiles16x32 = ((m + 15) / 16) * ((co + 31) / 32);
+  if (vec && fh == 3 && fw == 3 && tiles16x32 <= 512 && reinterpret_cast<uintptr_t>(y) % 8 == 0 &&
+      reinterpret_cast<uintptr_t>(bias) % 8 == 0) {
+    if (ci == 16) return launch_conv3x3_direct<16>(cv, w, bias, y, (int)m, co, act, stream);
+    if (ci == 32) return launch_conv3x3_direct<32>(cv, w, bias, y, (int)m, co, act, stream);
+    if (ci == 64) return launch_conv3x3_direct<64>(cv, w, bias, y, (int)m, co, act, stream);
+    if (ci == 128) return launch_conv3x3_direct<128>(cv, w, bias, y, (int)m, co, act, stream);
+  }
   // k-slices of 32 inside one filter tap, one validity bit per tap: the lean loader
   const bool lean = vec && ci % 32 == 0 && fh * fw <= 32;
   if (lean)

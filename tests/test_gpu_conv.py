@@ -134,6 +134,32 @@ def test_conv_implicit_gemm_sweep():
         assert_close(got, oracle.conv2d(x, f, b, st, pad, ACT_RELU6), "implicit gemm %r" % ((n, h, w, fh, fw, s, pad, ci, co),))
 
 
+def test_conv_3x3_small_maps_tap_per_wavefront():
+    """3x3 convolutions of small feature maps with 16 / 32 / 64 / 128 input channels (the kernel that gives every
+    filter tap a wavefront and loads the matrix-core operands straight from memory): both paddings, strides 1 and
+    2, borders everywhere (maps down to 1 x 1 ... 3 x 3), filter counts that are not multiples of the 32-column tile,
+    a one-hot filter that must copy a shifted input channel exactly, and the benchmark's 56 x 56 x 64 -> 64 layer."""
+    r = rng(61)
+    for ci, (n, h, w), co, s, pad in itertools.product(
+            [16, 32, 64, 128], [(1, 1, 1), (1, 3, 3), (2, 7, 5), (1, 14, 14), (3, 8, 9)], [4, 36, 64], [1, 2], [PAD_SAME, PAD_VALID]):
+        if pad == PAD_VALID and (h < 3 or w < 3):
+            continue
+        x = r.uniform(-1, 1, (n, h, w, ci)).astype(np.float32)
+        f = (r.standard_normal((3, 3, ci, co)) * np.sqrt(2.0 / (9 * ci))).astype(np.float32)
+        b = (r.standard_normal((co,)) * 0.5).astype(np.float32)
+        got = gpu_conv(x, f, b, s, pad, ACT_RELU6)
+        assert_close(got, oracle.conv2d(x, f, b, s, pad, ACT_RELU6), "conv3x3 small %r" % ((n, h, w, ci, co, s, pad),))
+        # one-hot filter: output channel j = input channel c under tap (kh, kw), shifted copy, bit-exact
+        kh, kw, c, j = int(r.integers(3)), int(r.integers(3)), int(r.integers(ci)), int(r.integers(co))
+        f1 = np.zeros((3, 3, ci, co), np.float32)
+        f1[kh, kw, c, j] = 1
+        got = gpu_conv(x, f1, None, s, pad, ACT_NONE)
+        assert np.array_equal(got, oracle.conv2d(x, f1, None, s, pad, ACT_NONE).astype(np.float32)), (n, h, w, ci, co, s, pad, kh, kw, c, j)
+    d = inputs.conv_general(36, 1, 56, 56, 64, 64, 3, 3)
+    got = gpu_conv(d["x"], d["filter"], d["bias"], 1, PAD_SAME, ACT_RELU6)
+    assert_close(got, oracle.conv2d(d["x"], d["filter"], d["bias"], 1, PAD_SAME, ACT_RELU6), "conv3x3 56x56x64->64")
+
+
 def test_conv_3x3_large_batches_sampled_images():
     # 3x3 convolutions at the sizes the benchmark times (128 x 128 tiles); the oracle checks whole images
     for (n, hw, ci, co, s) in [(8, 56, 64, 64, 1), (8, 56, 64, 128, 2), (4, 28, 128, 256, 1)]:
