@@ -20,6 +20,8 @@
  *     kernels on `stream` (a hipStream_t passed as void*, NULL = the default
  *     stream) and returns without synchronising, like the enqueue-and-return
  *     ops of Section 3.6 / 4.1.  The caller synchronises before reading.
+ *     The device that `stream` belongs to must be the calling thread's current
+ *     device.  Entry points may be called from several host threads.
  *   - Errors: the return value is a tfx_status.  Validation happens before any
  *     HIP call: a NULL pointer gives TFX_ERR_NULL; non-positive or mismatching
  *     dimensions, or a VALID convolution whose filter exceeds the image, give
