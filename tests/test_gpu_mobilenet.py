@@ -142,3 +142,26 @@ def test_forward_captured_in_a_graph_replays_identically(net):
         g.replay()
         assert np.array_equal(host(model.probs), p_eager)
         assert np.array_equal(host(model.logits), l_eager)
+
+
+def test_batched_forward_first_called_under_graph_capture():
+    """Batch 8 uses kernels batch 1 does not (filter-stationary pointwise kernels, which look up their residency and
+    set an LDS attribute on first use).  Here their first call in the process may happen while a graph is being
+    captured: the capture must succeed and the replay must match an eager run of the same model."""
+    import torch
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1(seed=11, batch=8, image_size=192, width_quarters=4)   # a size no other test uses at batch 8
+    model = tfx.MobileNetV1(data["weights"], batch=8, image_size=192, width_quarters=4)
+    image = dev(data["image"])
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        model.forward(image)
+    g.replay()
+    p_graph = host(model.probs).copy()
+    l_graph = host(model.logits).copy()
+    model.probs.zero_()
+    model.logits.zero_()
+    p_eager = host(model.forward(image)[0]).copy()
+    assert np.array_equal(p_graph, p_eager) and np.array_equal(l_graph, host(model.logits))
+    probs, logits = oracle.mobilenet_v1_forward(data["image"][5:6], data["weights"])
+    assert_close(l_graph[5:6], logits, "logits image 5 of 8 (192 x 192)")
