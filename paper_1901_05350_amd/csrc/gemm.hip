@@ -22,7 +22,6 @@
 namespace tfx {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 namespace {
 

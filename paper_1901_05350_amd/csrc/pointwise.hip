@@ -15,52 +15,11 @@ namespace {
 
 constexpr int kThreads = 512;  // 8 wavefronts share one copy of the filter
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-// Value held by the lane 8 places away within the lane's group of 16 (l % 16 <-> (l % 16) ^ 8): DPP row rotate by 8.
-__device__ __forceinline__ float swap8(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xf, 0xf, false));
-}
 
 template <int KG>
 __device__ __forceinline__ void fetch_slab(const float4* __restrict__ xp, float4 (&a)[KG]) {
 #pragma unroll
   for (int g = 0; g < KG; ++g) a[g] = xp[4 * g];
-}
-// Bias + activation + store of NBLK 16-column blocks (NBLK even) of one 16-row slab.  After the MFMAs lane
-// (li = l % 16, q = l / 16) holds columns 16j + 4q .. + 3 of row li for every block j; stored like that, an
-// instruction would write 64-byte pieces of 16 rows (measured: half-line pieces cost 12 us of 72 on the
-// 32 -> 64 layer).  Lanes li and li ^ 8 therefore trade blocks 2h + 1 / 2h first, so that the lanes with
-// li < 8 hold block 2h of rows li and li + 8 and the others block 2h + 1 of rows li - 8 and li: two store
-// instructions per block pair, each writing whole 128-byte lines of 8 rows.  bv[h]: bias of the lane's 4
-// columns 32h + (li < 8 ? 0 : 16) + 4q .. + 3; yc: y + first column of block 0.
-// CHECK = false: all 16 rows exist; the stores are then unconditional, which also lets the compiler count them
-// when it waits for a later load (stores and loads share one in-order counter: behind stores it cannot count,
-// every wait for a load would also wait for all earlier stores to be acknowledged).
-template <int NBLK, bool CHECK>
-__device__ __forceinline__ void store_slab(const floatx4 (&acc)[NBLK], const float4 (&bv)[NBLK / 2], float* yc, int n,
-                                           int row0, int M, int li, int q, const ActClamp& clamp) {
-  static_assert(NBLK % 2 == 0, "blocks are stored in pairs");
-  const bool lo = li < 8;
-  const int ra = row0 + (li & 7), rb = ra + 8;
-#pragma unroll
-  for (int h = 0; h < NBLK / 2; ++h) {
-    float got[4];
-#pragma unroll
-    for (int v = 0; v < 4; ++v) got[v] = swap8(lo ? acc[2 * h + 1][v] : acc[2 * h][v]);
-    float4 oa, ob;
-    oa.x = apply_act((lo ? acc[2 * h][0] : got[0]) + bv[h].x, clamp);
-    oa.y = apply_act((lo ? acc[2 * h][1] : got[1]) + bv[h].y, clamp);
-    oa.z = apply_act((lo ? acc[2 * h][2] : got[2]) + bv[h].z, clamp);
-    oa.w = apply_act((lo ? acc[2 * h][3] : got[3]) + bv[h].w, clamp);
-    ob.x = apply_act((lo ? got[0] : acc[2 * h + 1][0]) + bv[h].x, clamp);
-    ob.y = apply_act((lo ? got[1] : acc[2 * h + 1][1]) + bv[h].y, clamp);
-    ob.z = apply_act((lo ? got[2] : acc[2 * h + 1][2]) + bv[h].z, clamp);
-    ob.w = apply_act((lo ? got[3] : acc[2 * h + 1][3]) + bv[h].w, clamp);
-    const int col = 32 * h + (lo ? 0 : 16) + 4 * q;
-    if (!CHECK || ra < M) *reinterpret_cast<float4*>(yc + (size_t)ra * n + col) = oa;
-    if (!CHECK || rb < M) *reinterpret_cast<float4*>(yc + (size_t)rb * n + col) = ob;
-  }
 }
 
 // The filter is the MFMA A operand (lane l: column n = l % 16 of a 16-column block, k = l / 16) and

@@ -100,6 +100,27 @@ def test_stem_conv_small_and_ragged():
         assert_close(got, oracle.conv2d(x, f, b, s, pad, ACT_RELU6), "stem %r" % ((n, h, w, s, pad),))
 
 
+def test_stem_conv_matrix_core_form_slab_walk_and_borders():
+    """32 filters take the matrix-core stem kernel: 16-pixel slabs of an output row, interior slabs with
+    unconditional loads, border slabs with per-tap checks, a ragged last slab per row, and (batch 20 at 224 x 224:
+    15680 slabs for at most 8192 wavefronts) wavefronts that walk over several slabs, across row and image
+    boundaries.  Images are independent, so the oracle checks a sample of the large batch."""
+    r = rng(36)
+    f = r.standard_normal((3, 3, 3, 32)).astype(np.float32)
+    b = r.standard_normal((32,)).astype(np.float32)
+    for (n, h, w, s, pad, act, bias) in [(1, 40, 75, 2, PAD_SAME, ACT_RELU6, True), (2, 21, 53, 1, PAD_VALID, 0, False),
+                                         (1, 35, 130, (2, 1), PAD_SAME, ACT_RELU6, True), (3, 18, 34, 1, PAD_SAME, 0, True),
+                                         (1, 50, 64, (1, 2), PAD_VALID, ACT_RELU6, True)]:
+        x = r.uniform(-1, 1, (n, h, w, 3)).astype(np.float32)
+        got = gpu_conv(x, f, b if bias else None, s, pad, act)
+        assert_close(got, oracle.conv2d(x, f, b if bias else None, s, pad, act), "stem %r" % ((n, h, w, s, pad),))
+    x = r.uniform(-1, 1, (20, 224, 224, 3)).astype(np.float32)
+    got = gpu_conv(x, f, b, 2, PAD_SAME, ACT_RELU6)
+    assert got.shape == (20, 112, 112, 32)
+    for img in (0, 9, 10, 19):
+        assert_close(got[img:img + 1], oracle.conv2d(x[img:img + 1], f, b, 2, PAD_SAME, ACT_RELU6), "stem image %d of 20" % img)
+
+
 def test_general_conv_sweep():
     r = rng(33)
     hw = [(1, 1), (2, 3), (7, 7), (14, 15)]
