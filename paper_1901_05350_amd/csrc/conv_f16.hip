@@ -247,6 +247,111 @@ __global__ __launch_bounds__(256) void conv2d_stem_f16_kernel(const half_t* __re
   *reinterpret_cast<h8*>(y + (((size_t)n * OH + oh) * OW + ow) * CO + 8 * g) = out;
 }
 
+// The stem on the matrix cores for 32 filters: K = 27 padded to 32 is one v_mfma_f32_16x16x32_f16 per 16 output
+// channels and 16-pixel slab of an output row (channels as the first operand's rows, pixels as the second's
+// columns).  Lane (li = l % 16, q = l / 16) keeps filter values k = 8q .. 8q + 7 of channels li and 16 + li in
+// registers and loads input values k = 8q .. 8q + 7 of pixel li's 3 x 3 x 3 window (k = (kh * 3 + kw) * 3 + c)
+// straight from memory: slabs whose windows lie inside the image with unconditional loads at constant per-lane
+// offsets, slabs on a border with per-tap checks.  A wavefront walks over slabs with a scalar (n, oh, segment)
+// counter advanced with carries.  Its 16 x 32 results pass through a private LDS strip and leave as one 16-byte
+// store per lane (1 KB contiguous per slab).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void conv2d_stem_mfma_f16_kernel(const half_t* __restrict__ x,
+                                                                   const half_t* __restrict__ w,
+                                                                   const half_t* __restrict__ bias,
+                                                                   half_t* __restrict__ y, int N, int H, int W, int OH,
+                                                                   int OW, int sh, int sw, int pt, int pl, int act) {
+  constexpr int CO = 32, LS = CO + 8;
+  __shared__ __align__(16) half_t strips[4][16 * LS];
+  const int lane = threadIdx.x % 64, li = lane % 16, q = lane / 16;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / 64);
+  half_t* strip = strips[wave];
+  const int segs = (OW + 15) / 16;
+  const int stride = (int)gridDim.x * 4;
+  const int first = (int)blockIdx.x * 4 + wave;
+  int seg = first % segs, oh = (first / segs) % OH, n = first / segs / OH;
+  const int d_seg = stride % segs, d_oh = (stride / segs) % OH, d_n = stride / segs / OH;
+
+  int kh[8], kw[8], dk[8];
+  h8 wr[2];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const int k = 8 * q + t;
+    const bool valid = k < 27;
+    const int kc = valid ? k : 26;
+    kh[t] = kc / 9;
+    kw[t] = (kc % 9) / 3;
+    dk[t] = (kh[t] * W + kw[t]) * 3 + kc % 3;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const half_t v = w[kc * CO + 16 * j + li];
+      wr[j][t] = valid ? v : (half_t)0.f;
+    }
+  }
+  float bv[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bv[j][e] = bias ? (float)bias[16 * j + 4 * q + e] : 0.f;
+  const ActClamp clamp = make_act(act);
+
+  while (n < N) {
+    const long long row = (long long)n * OH + oh;
+    const int ow = min(seg * 16 + li, OW - 1);  // pixels past the row's end repeat the last one (not stored)
+    const int ih0 = oh * sh - pt, iw0 = ow * sw - pl;
+    const half_t* xb = x + (((long long)n * H + ih0) * W + iw0) * 3;  // tap (0, 0); outside x on a border
+    const int iw_first = seg * 16 * sw - pl, iw_last = min(seg * 16 + 15, OW - 1) * sw - pl + 2;
+    const bool interior = ih0 >= 0 && ih0 + 2 < H && iw_first >= 0 && iw_last < W;
+    h8 xv;
+    if (interior) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) xv[t] = xb[dk[t]];
+#pragma unroll
+      for (int t = 3; t < 8; ++t) xv[t] = q == 3 ? (half_t)0.f : xv[t];  // padding k = 27 .. 31: zero, not 0 * x
+    } else {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int ih = ih0 + kh[t], iw = iw0 + kw[t];
+        const bool ok = ih >= 0 && ih < H && iw >= 0 && iw < W && !(t >= 3 && q == 3);
+        const half_t v = *(ok ? xb + dk[t] : x);
+        xv[t] = ok ? v : (half_t)0.f;
+      }
+    }
+    f32x4 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wr[j], xv, zero, 0, 0, 0);
+    }
+    // lane (li, q) holds channels 16j + 4q .. + 3 of pixel li: through the strip to whole lines
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      h4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = to_half(apply_act(acc[j][e] + bv[j][e], clamp));
+      *reinterpret_cast<h4*>(strip + li * LS + 16 * j + 4 * q) = o;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    {
+      const int r = lane / 4, c = 8 * (lane % 4);
+      const h8 v = *reinterpret_cast<const h8*>(strip + r * LS + c);
+      if (seg * 16 + r < OW) *reinterpret_cast<h8*>(y + ((row * OW + seg * 16 + r) * CO + c)) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    seg += d_seg;
+    const int c1 = seg >= segs ? 1 : 0;
+    seg -= c1 * segs;
+    oh += d_oh + c1;
+    const int c2 = oh >= OH ? 1 : 0;
+    oh -= c2 * OH;
+    n += d_n + c2;
+  }
+}
+
 // ---- MobileNet tail: global average pool (rounded to binary16) fused into the fully connected
 // layer, split over K into fp32 partial sums; then bias, logits (binary16) and softmax of those --
 constexpr int kFcSlices = 32;
@@ -395,6 +500,15 @@ bool conv2d_stem_f16_supported(int ci, int fh, int fw, int co, const void* y) {
 int launch_conv2d_stem_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int n, int h,
                            int wd, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act,
                            hipStream_t stream) {
+  if (co == 32) {  // the matrix-core form (y is 16-byte aligned: conv2d_stem_f16_supported)
+    const long long slabs = (long long)n * oh * ((ow + 15) / 16);
+    if (slabs > 0x3fffffffLL) return TFX_ERR_UNSUPPORTED;
+    long long blocks = (slabs + 3) / 4;
+    if (blocks > 256 * 8) blocks = 256 * 8;  // 8 workgroups of 4 wavefronts per CU, then the slab loop
+    hipLaunchKernelGGL(conv2d_stem_mfma_f16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, H(x), H(w), H(bias),
+                       H(y), n, h, wd, oh, ow, sh, sw, pt, pl, act);
+    return check_launch();
+  }
   const long long total = (long long)n * oh * ow * (co / 8);
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
   const unsigned blocks = (unsigned)((total + 255) / 256);

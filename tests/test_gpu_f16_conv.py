@@ -30,6 +30,10 @@ def conv_case(seed, n, hh, ww, cin, cout, fh, fw):
     ((2, 10, 10, 6, 10, 1, 1), 1, PAD_SAME, ACT_RELU),          # channel counts that are not multiples of 8
     ((2, 224, 224, 3, 32, 3, 3), 2, PAD_SAME, ACT_RELU6),       # the stem
     ((1, 97, 101, 3, 8, 3, 3), 2, PAD_SAME, ACT_RELU6),
+    ((1, 40, 75, 3, 32, 3, 3), 2, PAD_SAME, ACT_RELU6),         # matrix-core stem: ragged last slab of a row, borders
+    ((2, 21, 53, 3, 32, 3, 3), 1, PAD_VALID, ACT_NONE),         # all slabs interior
+    ((3, 18, 34, 3, 32, 3, 3), 1, PAD_SAME, ACT_RELU),
+    ((1, 2, 2, 3, 32, 3, 3), 2, PAD_SAME, ACT_RELU6),
     ((1, 33, 35, 3, 24, 3, 3), 1, PAD_VALID, ACT_NONE),
     ((2, 17, 19, 5, 7, 3, 3), 2, PAD_SAME, ACT_RELU6),          # general direct kernel
     ((1, 12, 12, 16, 8, 5, 2), 3, PAD_VALID, ACT_RELU),
@@ -43,6 +47,18 @@ def test_conv2d_f16(shape, stride, pad, act):
     assert_close_f16(got, oracle.conv2d_f16(x, f, b, stride, pad, act), "conv2d_f16 %r s%d" % (shape, stride))
     got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), None, stride, pad, ACT_NONE))
     assert_close_f16(got, oracle.conv2d_f16(x, f, None, stride, pad, ACT_NONE), "conv2d_f16 no bias %r" % (shape,))
+
+
+def test_stem_f16_matrix_core_form_walks_over_several_slabs():
+    """Batch 20 at 224 x 224 is 15680 slabs for at most 8192 wavefronts: wavefronts move on across row and image
+    boundaries.  Images are independent, so the oracle checks a sample."""
+    import paper_1901_05350_amd as tfx
+    x, f, b = conv_case(77, 20, 224, 224, 3, 32, 3, 3)
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), dev16(b), 2, PAD_SAME, ACT_RELU6))
+    assert got.shape == (20, 112, 112, 32)
+    for img in (0, 9, 10, 19):
+        assert_close_f16(got[img:img + 1], oracle.conv2d_f16(x[img:img + 1], f, b, 2, PAD_SAME, ACT_RELU6),
+                         "stem f16 image %d of 20" % img)
 
 
 @pytest.mark.parametrize("shape,stride,pad,mult", [
