@@ -136,13 +136,16 @@ int launch_depthwise(const float* x, const float* w, const float* bias, float* y
   if (fh == 3 && fw == 3 && mult == 1 && c % 4 == 0 && sh == sw && (sh == 1 || sh == 2) && aligned) {
     const int c4 = c / 4;
     // Rows per thread: more rows = fewer halo re-reads and more bytes in flight per wavefront,
-    // fewer rows = more wavefronts.  Measured best at large sizes: 6 (stride 1), 2 (stride 2);
+    // fewer rows = more wavefronts.  Measured best at large sizes: 6 or, when it divides the height (every map
+    // of the 224-pixel network: no ragged last strip, a 7 x 7 map is a single strip), 7 (stride 1), 2 (stride 2);
     // small problems take fewer rows so that every CU still gets several wavefronts.
     const long long px = (long long)n * oh * ow * c4;  // threads at one row per thread
     const long long want = 256LL * 256 * 4;            // about 4 workgroups per CU
     if (sh == 1) {
+      if (oh % 7 == 0 && (px / 7 >= want * 3 / 4 || (oh == 7 && px / 7 >= want / 4)))
+        return launch_dw3x3<1, 7>(x, w, bias, y, n, h, wd, c4, oh, ow, pt, pl, act, stream);
       if (px / 6 >= want) return launch_dw3x3<1, 6>(x, w, bias, y, n, h, wd, c4, oh, ow, pt, pl, act, stream);
-      if (px / 4 >= want) return launch_dw3x3<1, 4>(x, w, bias, y, n, h, wd, c4, oh, ow, pt, pl, act, stream);
+      if (px / 4 >= want / 4) return launch_dw3x3<1, 4>(x, w, bias, y, n, h, wd, c4, oh, ow, pt, pl, act, stream);
       if (px / 2 >= want / 4) return launch_dw3x3<1, 2>(x, w, bias, y, n, h, wd, c4, oh, ow, pt, pl, act, stream);
       return launch_dw3x3<1, 1>(x, w, bias, y, n, h, wd, c4, oh, ow, pt, pl, act, stream);
     }

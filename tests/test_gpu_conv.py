@@ -231,9 +231,11 @@ def test_depthwise_benchmark_batches_sampled_images(n, stride):
 
 def test_depthwise_rows_per_thread_variants_ragged_heights():
     # output heights that are not multiples of the 2 / 4 / 6 rows a thread covers, at sizes that
-    # select each variant
+    # select each variant; heights that are multiples of 7 at sizes that select 7 rows per thread
+    # (several strips, and a 7-row map as a single strip)
     r = rng(44)
-    for (n, h, w, c) in [(16, 37, 45, 64), (44, 53, 61, 32), (200, 31, 33, 32), (4, 9, 200, 128)]:
+    for (n, h, w, c) in [(16, 37, 45, 64), (44, 53, 61, 32), (200, 31, 33, 32), (4, 9, 200, 128), (36, 28, 45, 128),
+                         (48, 7, 9, 1024)]:
         x = r.uniform(-1, 1, (n, h, w, c)).astype(np.float32)
         f = (r.standard_normal((3, 3, c, 1)) * np.sqrt(2.0 / 9)).astype(np.float32)
         b = (r.standard_normal((c,)) * 0.5).astype(np.float32)
