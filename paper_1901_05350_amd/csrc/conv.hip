@@ -126,8 +126,9 @@ __global__ __launch_bounds__(256) void conv2d_stem_kernel(const float* __restric
   *reinterpret_cast<float4*>(yp + 4) = o1;
 }
 
-// The stem on the matrix cores, for 16 or 32 filters.  K = 27 is thin, but the vector-ALU form above spends 27 x 8
-// FMAs plus 54 LDS reads per thread and is bound by that, not by its memory traffic; as a GEMM with
+// The stem on the matrix cores, for a multiple of 32 filters (32 is instantiated).  K = 27 is thin, but the
+// vector-ALU form above spends 27 x 8 FMAs plus 54 LDS reads per thread and is bound by that, not by its memory
+// traffic; as a GEMM with
 // v_mfma_f32_16x16x4_f32 (output channels as the A operand's rows, 16 output pixels as the B operand's columns, K
 // padded to 28) a 16-pixel slab costs 7 MFMAs per 16 channels.  A wavefront keeps its lanes' filter values in
 // registers (7 per column block) and walks over slabs of 16 consecutive pixels of one output row; lane
@@ -242,8 +243,8 @@ bool conv2d_stem_supported(int ci, int fh, int fw, int co, int sh, int sw) {
 
 int launch_conv2d_stem(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int co,
                        int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream) {
-  // 32 filters (any multiple of 32), 16-byte aligned y and bias: the matrix-core form
-  if (co % 32 == 0 && co == 32 && reinterpret_cast<uintptr_t>(y) % 16 == 0 && reinterpret_cast<uintptr_t>(bias) % 16 == 0) {
+  // 32 filters, 16-byte aligned y and bias: the matrix-core form
+  if (co == 32 && reinterpret_cast<uintptr_t>(y) % 16 == 0 && reinterpret_cast<uintptr_t>(bias) % 16 == 0) {
     const long long slabs = (long long)n * oh * ((ow + 15) / 16);
     if (slabs > 0x3fffffffLL) return TFX_ERR_UNSUPPORTED;
     long long blocks = (slabs + 3) / 4;
