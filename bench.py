@@ -293,12 +293,30 @@ def main():
                                  "traffic": measured_traffic("pointwise_f16_%dx56x56x128_to_128" % n)}}
         return build
 
+    def op_conv3x3_f16(n):
+        """3x3 conv2d 56x56x64 -> 64, stride 1, SAME, bias + ReLU6 on 16-bit storage (implicit GEMM, fp32 accumulation)."""
+        def build():
+            d = inputs.conv_general(5, n, 56, 56, 64, 64, 3, 3)
+            xx, ff, bb = (dev(d[k]).to(torch.float16) for k in ("x", "filter", "bias"))
+            yy = tfx.tfx_conv2d_f16(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6)
+            fn = lambda: tfx.tfx_conv2d_f16(xx, ff, bb, 1, tfx.PAD_SAME, tfx.ACT_RELU6, out=yy)
+            t = time_loop(fn, reps)
+            flop, nbytes = 2 * n * 56 * 56 * 64 * 64 * 9, 2 * (xx.numel() + yy.numel() + 9 * 64 * 64 + 64)
+            return {"us": round(t * 1e6, 3), "single_launch_us": round(time_single(fn) * 1e6, 2),
+                    "TFLOPs": round(flop / t / 1e12, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
+                    "roofline": {"bound": "mfma", "achieved": round(flop / t / 1e12, 3), "peak": PEAK_MFMA_F16 / 1e12,
+                                 "unit": "TFLOP/s", "frac": round(flop / t / PEAK_MFMA_F16, 5),
+                                 "traffic": measured_traffic("conv3x3_f16_%dx56x56x64_to_64" % n)}}
+        return build
+
     single_ops = {"matmul_64x128x64": op_matmul, "batch_matmul_8x1024x1024x1024_tB": op_batch_matmul}
     single_ops["batch_matmul_f16_8x1024x1024x1024_tB"] = op_matmul_f16(8, 1024, 1024, 1024)
     single_ops["batch_matmul_f16_1x4096x4096x4096_tB"] = op_matmul_f16(1, 4096, 4096, 4096)
     single_ops["batch_matmul_f16_1x4096x4096x4096"] = op_matmul_f16(1, 4096, 4096, 4096, tb=False)
     single_ops["pointwise_f16_64x56x56x128_to_128"] = op_pointwise_f16(64)
     single_ops["pointwise_f16_8x56x56x128_to_128"] = op_pointwise_f16(8)
+    single_ops["conv3x3_f16_64x56x56x64_to_64"] = op_conv3x3_f16(64)
+    single_ops["conv3x3_f16_8x56x56x64_to_64"] = op_conv3x3_f16(8)
     single_ops["depthwise_f16_64x112x112x64_s1_cold_rotation"] = op_depthwise_f16(64, 1, 6)
     single_ops["depthwise_f16_64x112x112x64_s2_cold_rotation"] = op_depthwise_f16(64, 2, 6)
     single_ops["add_f32_64M"] = op_add(1 << 26, False)

@@ -285,6 +285,9 @@ int tfx_conv2d_f16(const uint16_t* x, const int64_t x_shape[4], const uint16_t* 
   if (conv2d_stem_f16_supported(ci, fh, fw, co, y))
     return launch_conv2d_stem_f16(x, filter, bias, y, n, h, w, co, oh, ow, stride_h, stride_w, (int)g.pad[0],
                                   (int)g.pad[2], (int)act, s);
+  if (conv2d_gemm_f16_supported(x, filter, ci, fh, fw, co))
+    return launch_conv2d_gemm_f16(x, filter, bias, y, n, h, w, ci, fh, fw, co, oh, ow, stride_h, stride_w,
+                                  (int)g.pad[0], (int)g.pad[2], (int)act, s);
   return launch_conv2d_direct_f16(x, filter, bias, y, n, h, w, ci, fh, fw, co, oh, ow, stride_h, stride_w,
                                   (int)g.pad[0], (int)g.pad[2], (int)act, s);
 }

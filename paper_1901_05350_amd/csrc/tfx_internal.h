@@ -125,6 +125,12 @@ int launch_gemm_f16(const uint16_t* a, const uint16_t* b, uint16_t* c, const uin
 int launch_conv2d_direct_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int n, int h,
                              int wd, int ci, int fh, int fw, int co, int oh, int ow, int sh, int sw, int pt, int pl,
                              int act, hipStream_t stream);
+// conv2d on binary16 storage as an implicit GEMM on the matrix cores: channel counts multiples of 8, at most 32
+// filter taps, 16-byte aligned x and filter.
+bool conv2d_gemm_f16_supported(const void* x, const void* w, int ci, int fh, int fw, int co);
+int launch_conv2d_gemm_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int n, int h, int wd,
+                           int ci, int fh, int fw, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act,
+                           hipStream_t stream);
 bool conv2d_stem_f16_supported(int ci, int fh, int fw, int co, const void* y);
 int launch_conv2d_stem_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int n, int h,
                            int wd, int co, int oh, int ow, int sh, int sw, int pt, int pl, int act,

@@ -49,6 +49,58 @@ def test_conv2d_f16(shape, stride, pad, act):
     assert_close_f16(got, oracle.conv2d_f16(x, f, None, stride, pad, ACT_NONE), "conv2d_f16 no bias %r" % (shape,))
 
 
+@pytest.mark.parametrize("shape,stride,pad,act", [
+    ((2, 56, 56, 64, 64, 3, 3), 1, PAD_SAME, ACT_RELU6),        # several row tiles, every tap inside one 64-half slice
+    ((2, 56, 56, 64, 64, 3, 3), 2, PAD_SAME, ACT_RELU6),
+    ((1, 30, 29, 72, 136, 3, 3), 1, PAD_VALID, ACT_NONE),       # Ci not a divisor of 64, ragged column tile (136 = 128 + 8)
+    ((3, 19, 23, 24, 40, 3, 3), (2, 1), PAD_SAME, ACT_RELU),    # three tap carries per slice, ragged last slice (K = 216)
+    ((2, 21, 17, 8, 24, 5, 5), 1, PAD_SAME, ACT_RELU6),         # 8 channels: a slice spans 8 taps; 25 taps
+    ((1, 40, 33, 16, 8, 2, 7), (3, 2), PAD_SAME, ACT_NONE),
+    ((1, 9, 9, 128, 256, 4, 4), 1, PAD_VALID, ACT_RELU6),       # K = 2048: 32 slices, 36 rows (one ragged tile)
+    ((1, 1, 1, 64, 64, 3, 3), 1, PAD_SAME, ACT_NONE),           # a single pixel: 8 of 9 taps outside
+])
+def test_conv2d_f16_implicit_gemm(shape, stride, pad, act):
+    """Channel counts that are multiples of 8 take the matrix-core implicit GEMM."""
+    import paper_1901_05350_amd as tfx
+    n, hh, ww, cin, cout, fh, fw = shape
+    x, f, b = conv_case(400 + cin + cout + fh, n, hh, ww, cin, cout, fh, fw)
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), dev16(b), stride, pad, act))
+    assert_close_f16(got, oracle.conv2d_f16(x, f, b, stride, pad, act), "conv2d_f16 gemm %r" % (shape,))
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), None, stride, pad, ACT_NONE))
+    assert_close_f16(got, oracle.conv2d_f16(x, f, None, stride, pad, ACT_NONE), "conv2d_f16 gemm no bias %r" % (shape,))
+
+
+def test_conv2d_f16_implicit_gemm_one_hot_and_unaligned_output():
+    import torch
+    import paper_1901_05350_amd as tfx
+    # one-hot filters: output channel o copies input channel (o * 5) % 16 under tap (o % 3, (o // 3) % 3): every
+    # (tap, channel) position of the window is located exactly, borders included
+    rng = np.random.default_rng(11)
+    x = h(rng.uniform(-1, 1, (1, 7, 9, 16)))
+    f = np.zeros((3, 3, 16, 24), np.float16)
+    for o in range(24):
+        f[o % 3, (o // 3) % 3, (o * 5) % 16, o] = 1
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), None, 1, PAD_SAME, ACT_NONE))
+    assert np.array_equal(got, oracle.conv2d_f16(x, f, None, 1, PAD_SAME, ACT_NONE))
+    # an output buffer 2 bytes off a 16-byte boundary: element stores, nothing written outside
+    x, f, b = conv_case(412, 1, 10, 11, 16, 24, 3, 3)
+    out = torch.zeros(10 * 11 * 24 + 2, dtype=torch.float16, device="cuda:0")
+    tfx.tfx_conv2d_f16(dev16(x), dev16(f), dev16(b), 1, PAD_SAME, ACT_RELU6, out=out[1:-1].view(1, 10, 11, 24))
+    o = host(out)
+    assert o[0] == 0 and o[-1] == 0
+    assert_close_f16(o[1:-1].reshape(1, 10, 11, 24), oracle.conv2d_f16(x, f, b, 1, PAD_SAME, ACT_RELU6), "unaligned y")
+
+
+def test_conv2d_f16_3x3_benchmark_size_sampled_images():
+    import paper_1901_05350_amd as tfx
+    n = 64
+    x, f, b = conv_case(420, n, 56, 56, 64, 64, 3, 3)
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), dev16(b), 1, PAD_SAME, ACT_RELU6))
+    for img in (0, 41, n - 1):
+        assert_close_f16(got[img:img + 1], oracle.conv2d_f16(x[img:img + 1], f, b, 1, PAD_SAME, ACT_RELU6),
+                         "conv 3x3 f16 batch 64 image %d" % img)
+
+
 def test_stem_f16_matrix_core_form_walks_over_several_slabs():
     """Batch 20 at 224 x 224 is 15680 slabs for at most 8192 wavefronts: wavefronts move on across row and image
     boundaries.  Images are independent, so the oracle checks a sample."""
