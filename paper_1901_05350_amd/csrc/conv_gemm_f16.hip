@@ -33,7 +33,7 @@ constexpr int kSlots = 4;          // 16-byte slots per thread, operand and slic
 
 struct ConvGeomF16 {
   const half_t* x;
-  int H, W, Ci, OH, OW, fw, taps, sh, sw, pt, pl;
+  int H, W, Ci, OH, OW, fh, fw, taps, sh, sw, pt, pl;
 };
 
 // TN: 32-column MFMA blocks per wavefront (tile width 64 TN)
@@ -75,11 +75,12 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
     const int n = t / cv.OH;
     const int ih0 = oh * cv.sh - cv.pt, iw0 = ow * cv.sw - cv.pl;
     origin[i] = (((long long)n * cv.H + ih0) * cv.W + iw0) * cv.Ci;
-    unsigned ok = 0;
-    for (int tap = 0; tap < cv.taps; ++tap) {
-      const int ih = ih0 + tap / cv.fw, iw = iw0 + tap % cv.fw;
-      if (ih >= 0 && ih < cv.H && iw >= 0 && iw < cv.W) ok |= 1u << tap;
-    }
+    unsigned ok = 0, bit = 1u;
+    for (int fy = 0; fy < cv.fh; ++fy)
+      for (int fx = 0; fx < cv.fw; ++fx, bit <<= 1) {
+        const int ih = ih0 + fy, iw = iw0 + fx;
+        ok |= (ih >= 0 && ih < cv.H && iw >= 0 && iw < cv.W) ? bit : 0u;
+      }
     tap_ok[i] = ok;
   }
   // this thread's k position in the slice being fetched: tap (kh, kw) and channel c
@@ -279,7 +280,7 @@ int launch_conv2d_gemm_f16(const uint16_t* x, const uint16_t* w, const uint16_t*
                            hipStream_t stream) {
   const long long m = (long long)n * oh * ow, k = (long long)fh * fw * ci;
   if (m > 0x7fffffffLL || k > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
-  const ConvGeomF16 cv{reinterpret_cast<const half_t*>(x), h, wd, ci, oh, ow, fw, fh * fw, sh, sw, pt, pl};
+  const ConvGeomF16 cv{reinterpret_cast<const half_t*>(x), h, wd, ci, oh, ow, fh, fw, fh * fw, sh, sw, pt, pl};
   const half_t* wh = reinterpret_cast<const half_t*>(w);
   const half_t* bh = reinterpret_cast<const half_t*>(bias);
   half_t* yh = reinterpret_cast<half_t*>(y);
