@@ -7,8 +7,8 @@
 // tap falls outside the image.  Products are accumulated in fp32 (v_mfma_f32_32x32x16_f16), the result is
 // rounded once.
 //
-// A workgroup of 2 x 2 wavefronts computes a 128 x 128 tile (128 x 64 when that pads the output channels
-// less); k-slices of 64 halfs are double-buffered in LDS as K-contiguous rows of 144 bytes.  The slice kt + 1
+// A workgroup of 2 x 2 wavefronts computes a 128 x 128 tile (64 columns when that pads the output channels
+// less, 64 rows for small problems); k-slices of 64 halfs are double-buffered in LDS as K-contiguous rows of 144 bytes.  The slice kt + 1
 // is fetched into registers before the MFMAs of slice kt and written to LDS after them.  A thread's four A slots share their k position (8 halfs at k0 + 8 (tid % 8)),
 // so the tap and channel of that position are kept per thread and advanced by 64 per slice without a
 // division; each slot keeps its pixel's window origin and one validity bit per tap.  The filter is stored
@@ -27,22 +27,22 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kBK = 64;       // halfs per k-slice
 constexpr int kLd = kBK + 8;  // LDS row stride in halfs
 constexpr int kXcds = 8;
-constexpr int kBM = 128, kNT = 256;
-constexpr int kTileA = kBM * kLd;  // halfs per LDS buffer of A
-constexpr int kSlots = 4;          // 16-byte slots per thread, operand and slice
+constexpr int kNT = 256;
+constexpr int kSlots = 4;  // 16-byte filter slots per thread and slice
 
 struct ConvGeomF16 {
   const half_t* x;
   int H, W, Ci, OH, OW, fh, fw, taps, sh, sw, pt, pl;
 };
 
-// TN: 32-column MFMA blocks per wavefront (tile width 64 TN)
-template <int TN>
+// TM, TN: 32-row / 32-column MFMA blocks per wavefront (tile 64 TM x 64 TN)
+template <int TM, int TN>
 __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, const half_t* __restrict__ w,
                                                             const half_t* __restrict__ bias, half_t* __restrict__ y,
                                                             int M, int N, int K, int tiles_n, int total_blocks,
                                                             int wraps, int act, int c_vec) {
-  constexpr int kBN = 64 * TN, kTileB = kBN * kLd;
+  constexpr int kBM = 64 * TM, kBN = 64 * TN, kTileA = kBM * kLd, kTileB = kBN * kLd;
+  constexpr int kSlotsA = 2 * TM;  // 16-byte window slots per thread and slice
   extern __shared__ __align__(16) half_t smem_h[];
   half_t* const lds_a = smem_h;  // two A buffers, then two B buffers
   half_t* const lds_b = smem_h + 2 * kTileA;
@@ -58,16 +58,16 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
 
   const int tid = threadIdx.x;
   const int wave = tid / 64, lane = tid % 64;
-  const int wm0 = (wave / 2) * 64, wn0 = (wave % 2) * 32 * TN;
+  const int wm0 = (wave / 2) * 32 * TM, wn0 = (wave % 2) * 32 * TN;
   const int li = lane % 32, hh = lane / 32;
 
   // A slots: tile row srow + 32 i, halfs scol ... scol + 7 of the slice.  Per slot: element offset of the
   // window origin (oh * sh - pt, ow * sw - pl), which may lie outside the image, and a validity bit per tap.
   const int srow = tid / 8, scol = 8 * (tid % 8);
-  long long origin[kSlots];
-  unsigned tap_ok[kSlots];
+  long long origin[kSlotsA];
+  unsigned tap_ok[kSlotsA];
 #pragma unroll
-  for (int i = 0; i < kSlots; ++i) {
+  for (int i = 0; i < kSlotsA; ++i) {
     const int r = min(m0 + srow + 32 * i, M - 1);  // rows past M repeat the last one (never stored)
     const int ow = r % cv.OW;
     const int t = r / cv.OW;
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
   const bool has_b = 8 * nb < kBN;
   const int bcol = n0 + 8 * nb < N ? n0 + 8 * nb : 0;  // past N: any valid column block (feeds no stored output)
 
-  h8 ra[kSlots], rb[kSlots];
+  h8 ra[kSlotsA], rb[kSlots];
   unsigned a_ok = 0;  // bit i: A slot i of the fetched slice is inside the image and inside K
   const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   auto load = [&](int k0) {
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
     const long long tap_off = ((long long)kh * cv.W + kw) * cv.Ci + c;
     a_ok = 0;
 #pragma unroll
-    for (int i = 0; i < kSlots; ++i) {
+    for (int i = 0; i < kSlotsA; ++i) {
       const bool ok = k_in && ((tap_ok[i] >> tap) & 1u) != 0;
       const half_t* p = ok ? cv.x + (origin[i] + tap_off) : cv.x;  // unconditional load from a valid address
       ra[i] = *reinterpret_cast<const h8*>(p);
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
   auto store = [&](int buf) {
     half_t* la = lds_a + buf * kTileA + srow * kLd + scol;
 #pragma unroll
-    for (int i = 0; i < kSlots; ++i)
+    for (int i = 0; i < kSlotsA; ++i)
       *reinterpret_cast<h8*>(la + 32 * i * kLd) = ((a_ok >> i) & 1u) ? ra[i] : zero8;
     if (has_b) {
       half_t* lb = lds_b + buf * kTileB + (8 * nb) * kLd + 4 * kq;
@@ -142,9 +142,9 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
     }
   };
 
-  f32x16 acc[2][TN];
+  f32x16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -160,16 +160,16 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
     if (kt + 1 < nk) load((kt + 1) * kBK);
     const half_t* la = lds_a + cur * kTileA + (wm0 + li) * kLd + 8 * hh;
     const half_t* lb = lds_b + cur * kTileB + (wn0 + li) * kLd + 8 * hh;
-    h8 fa[2][2], fb[2][TN];
+    h8 fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) fa[0][i] = *reinterpret_cast<const h8*>(la + 32 * i * kLd);
+    for (int i = 0; i < TM; ++i) fa[0][i] = *reinterpret_cast<const h8*>(la + 32 * i * kLd);
 #pragma unroll
     for (int j = 0; j < TN; ++j) fb[0][j] = *reinterpret_cast<const h8*>(lb + 32 * j * kLd);
 #pragma unroll
     for (int s = 0; s < kBK / 16; ++s) {
       if (s + 1 < kBK / 16) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) fa[(s + 1) & 1][i] = *reinterpret_cast<const h8*>(la + 32 * i * kLd + 16 * (s + 1));
+        for (int i = 0; i < TM; ++i) fa[(s + 1) & 1][i] = *reinterpret_cast<const h8*>(la + 32 * i * kLd + 16 * (s + 1));
 #pragma unroll
         for (int j = 0; j < TN; ++j) fb[(s + 1) & 1][j] = *reinterpret_cast<const h8*>(lb + 32 * j * kLd + 16 * (s + 1));
       }
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
       // operands swapped (the filter's fragment first): a lane's registers then hold 4 consecutive output
       // columns of one row
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
@@ -189,12 +189,13 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
   // acc[i][j][v] is the output at row m0 + wm0 + 32 i + li, column n0 + wn0 + 32 j + 8 (v / 4) + 4 hh + v % 4
   const ActClamp clamp = make_act(act);
   if (c_vec == 2) {
-    // N % 8 == 0 and y 16-byte aligned: every wavefront converts its 64 x 32 TN block to binary16 in a private
+    // N % 8 == 0 and y 16-byte aligned: every wavefront converts its 32 TM x 32 TN block to binary16 in a private
     // LDS region (the slice buffers are free after the loop's last barrier), reads it back row-wise and
     // stores 16 bytes per lane, whole 128-byte lines per row
     constexpr int kWN = 32 * TN, kLs = kWN + 8;
-    static_assert(4 * 64 * kLs <= 2 * (kTileA + kTileB), "staging fits in the slice buffers");
-    half_t* stage = smem_h + wave * 64 * kLs;
+    constexpr int kWM = 32 * TM;
+    static_assert(4 * kWM * kLs <= 2 * (kTileA + kTileB), "staging fits in the slice buffers");
+    half_t* stage = smem_h + wave * kWM * kLs;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
 #pragma unroll
         for (int e = 0; e < 4; ++e) bv[e] = (bias != nullptr && col + e < N) ? (float)bias[col + e] : 0.f;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < TM; ++i) {
           h4 pk;
 #pragma unroll
           for (int e = 0; e < 4; ++e) pk[e] = (half_t)apply_act(acc[i][j][4 * g + e] + bv[e], clamp);
@@ -216,10 +217,11 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     constexpr int kLanesPerRow = kWN / 8, kRowsPerStep = 64 / kLanesPerRow;
+    static_assert(kWM % kRowsPerStep == 0, "store steps cover the block");
     const int rr = lane / kLanesPerRow, cc = 8 * (lane % kLanesPerRow);
     const int col = n0 + wn0 + cc;
 #pragma unroll
-    for (int r0 = 0; r0 < 64; r0 += kRowsPerStep) {
+    for (int r0 = 0; r0 < kWM; r0 += kRowsPerStep) {
       const int row = m0 + wm0 + r0 + rr;
       const h8 v = *reinterpret_cast<const h8*>(stage + (r0 + rr) * kLs + cc);
       if (row < M && col < N) *reinterpret_cast<h8*>(y + (size_t)row * N + col) = v;
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
     return;
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < TM; ++i) {
     const int row = m0 + wm0 + 32 * i + li;
     if (row >= M) continue;
     half_t* yrow = y + (size_t)row * N;
@@ -256,21 +258,21 @@ bool conv2d_gemm_f16_supported(const void* x, const void* w, int ci, int fh, int
 }
 
 namespace {
-template <int TN>
+template <int TM, int TN>
 int launch_tiles(const ConvGeomF16& cv, const half_t* w, const half_t* bias, half_t* y, long long m, int co, long long k,
                  int act, hipStream_t stream) {
-  constexpr int kBN = 64 * TN;
-  constexpr size_t lds_bytes = 2 * (size_t)(kTileA + kBN * kLd) * sizeof(half_t);
+  constexpr int kBM = 64 * TM, kBN = 64 * TN;
+  constexpr size_t lds_bytes = 2 * (size_t)(kBM + kBN) * kLd * sizeof(half_t);
   const long long tiles_m = (m + kBM - 1) / kBM, tiles_n = (co + kBN - 1) / kBN;
   if (tiles_m * tiles_n > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
   static std::atomic<uint64_t> lds_allowed{0};
-  if (allow_dynamic_lds(reinterpret_cast<const void*>(conv_f16_gemm_kernel<TN>), lds_bytes, lds_allowed) != TFX_OK)
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(conv_f16_gemm_kernel<TM, TN>), lds_bytes, lds_allowed) != TFX_OK)
     return TFX_ERR_LAUNCH;
   const int wraps = (kBK + cv.Ci - 1) / cv.Ci;  // tap carries per 64-half step
   const int c_vec = reinterpret_cast<uintptr_t>(y) % 16 == 0 ? 2 : 0;
   const int total = (int)(tiles_m * tiles_n);
-  hipLaunchKernelGGL(conv_f16_gemm_kernel<TN>, dim3((unsigned)total), dim3(kNT), lds_bytes, stream, cv, w, bias, y, (int)m,
-                     co, (int)k, (int)tiles_n, total, wraps, act, c_vec);
+  hipLaunchKernelGGL((conv_f16_gemm_kernel<TM, TN>), dim3((unsigned)total), dim3(kNT), lds_bytes, stream, cv, w, bias, y,
+                     (int)m, co, (int)k, (int)tiles_n, total, wraps, act, c_vec);
   return check_launch();
 }
 }  // namespace
@@ -284,10 +286,18 @@ int launch_conv2d_gemm_f16(const uint16_t* x, const uint16_t* w, const uint16_t*
   const half_t* wh = reinterpret_cast<const half_t*>(w);
   const half_t* bh = reinterpret_cast<const half_t*>(bias);
   half_t* yh = reinterpret_cast<half_t*>(y);
-  // 64-column tiles when they cover the output channels with less padding than 128-column tiles
+  // 64-column tiles when they cover the output channels with less padding than 128-column tiles.  64-row tiles
+  // with those, and whenever 128-row tiles would leave CUs without a workgroup: more, smaller workgroups per CU
+  // hide each other's memory latency (3x3, 56x56x64 -> 64 at batch 64: 70 -> 64 us; 28x28x256 -> 256 at batch 8:
+  // 56 -> 47 us), at the price of less operand reuse (same layer at batch 64: 140 -> 205 us).
   const bool narrow = (co + 63) / 64 * 64 < (co + 127) / 128 * 128;
-  return narrow ? launch_tiles<1>(cv, wh, bh, yh, m, co, k, act, stream)
-                : launch_tiles<2>(cv, wh, bh, yh, m, co, k, act, stream);
+  const long long tiles128 = ((m + 127) / 128) * ((co + (narrow ? 63 : 127)) / (narrow ? 64 : 128));
+  const bool low = narrow || tiles128 < 256;
+  if (low)
+    return narrow ? launch_tiles<1, 1>(cv, wh, bh, yh, m, co, k, act, stream)
+                  : launch_tiles<1, 2>(cv, wh, bh, yh, m, co, k, act, stream);
+  return narrow ? launch_tiles<2, 1>(cv, wh, bh, yh, m, co, k, act, stream)
+                : launch_tiles<2, 2>(cv, wh, bh, yh, m, co, k, act, stream);
 }
 
 }  // namespace tfx
