@@ -35,8 +35,11 @@ struct ConvGeomF16 {
   int H, W, Ci, OH, OW, fh, fw, taps, sh, sw, pt, pl;
 };
 
-// TM, TN: 32-row / 32-column MFMA blocks per wavefront (tile 64 TM x 64 TN)
-template <int TM, int TN>
+// TM, TN: 32-row / 32-column MFMA blocks per wavefront (tile 64 TM x 64 TN).
+// LEAN (Ci % 64 == 0, operands of fewer than 2^31 bytes): a k-slice lies inside one filter tap, the same for
+// every thread, so tap and channel are scalar state, a slot's address is a uniform base plus a 32-bit offset,
+// and no slice of the filter is ragged -- a fraction of the vector-ALU instructions of the general form.
+template <int TM, int TN, bool LEAN>
 __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, const half_t* __restrict__ w,
                                                             const half_t* __restrict__ bias, half_t* __restrict__ y,
                                                             int M, int N, int K, int tiles_n, int total_blocks,
@@ -65,6 +68,7 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
   // window origin (oh * sh - pt, ow * sw - pl), which may lie outside the image, and a validity bit per tap.
   const int srow = tid / 8, scol = 8 * (tid % 8);
   long long origin[kSlotsA];
+  unsigned origin_b[kSlotsA];  // LEAN: byte offset of (window origin, channel scol), modulo 2^32
   unsigned tap_ok[kSlotsA];
 #pragma unroll
   for (int i = 0; i < kSlotsA; ++i) {
@@ -75,6 +79,7 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
     const int n = t / cv.OH;
     const int ih0 = oh * cv.sh - cv.pt, iw0 = ow * cv.sw - cv.pl;
     origin[i] = (((long long)n * cv.H + ih0) * cv.W + iw0) * cv.Ci;
+    origin_b[i] = 2u * ((unsigned)(int)origin[i] + (unsigned)scol);
     unsigned ok = 0, bit = 1u;
     for (int fy = 0; fy < cv.fh; ++fy)
       for (int fx = 0; fx < cv.fw; ++fx, bit <<= 1) {
@@ -83,19 +88,50 @@ __global__ __launch_bounds__(kNT) void conv_f16_gemm_kernel(ConvGeomF16 cv, cons
       }
     tap_ok[i] = ok;
   }
-  // this thread's k position in the slice being fetched: tap (kh, kw) and channel c
-  int tap = scol / cv.Ci, c = scol % cv.Ci;
+  // this thread's k position in the slice being fetched: tap (kh, kw) and channel c (LEAN: the slice's first k,
+  // uniform)
+  int tap = LEAN ? 0 : scol / cv.Ci, c = LEAN ? 0 : scol % cv.Ci;
   int kh = tap / cv.fw, kw = tap % cv.fw;
 
   // B slots: k-rows 4 kq ... + 3 of the slice, columns n0 + 8 nb ... + 7 (threads with nb past the tile: none)
   const int kq = tid % 16, nb = tid / 16;
   const bool has_b = 8 * nb < kBN;
   const int bcol = n0 + 8 * nb < N ? n0 + 8 * nb : 0;  // past N: any valid column block (feeds no stored output)
+  unsigned boff_b[kSlots];  // LEAN: byte offset of the slot at k0 = 0
+#pragma unroll
+  for (int j = 0; j < kSlots; ++j) boff_b[j] = 2u * ((unsigned)(4 * kq + j) * (unsigned)N + (unsigned)bcol);
 
   h8 ra[kSlotsA], rb[kSlots];
   unsigned a_ok = 0;  // bit i: A slot i of the fetched slice is inside the image and inside K
   const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   auto load = [&](int k0) {
+    if constexpr (LEAN) {
+      const char* xb = reinterpret_cast<const char*>(cv.x);
+      const unsigned tap_off_b = 2u * (unsigned)((kh * cv.W + kw) * cv.Ci + c);  // uniform
+      a_ok = 0;
+#pragma unroll
+      for (int i = 0; i < kSlotsA; ++i) {
+        const bool ok = ((tap_ok[i] >> tap) & 1u) != 0;
+        const unsigned off = ok ? origin_b[i] + tap_off_b : 0u;  // inside the image: 0 <= offset < 2^32
+        ra[i] = *reinterpret_cast<const h8*>(xb + off);
+        a_ok |= ok ? 1u << i : 0u;
+      }
+      if (has_b) {
+        const char* wb = reinterpret_cast<const char*>(w) + 2 * (size_t)k0 * (size_t)N;  // uniform
+#pragma unroll
+        for (int j = 0; j < kSlots; ++j) rb[j] = *reinterpret_cast<const h8*>(wb + boff_b[j]);
+      }
+      c += kBK;
+      if (c >= cv.Ci) {
+        c = 0;
+        ++tap;
+        if (++kw >= cv.fw) {
+          kw = 0;
+          ++kh;
+        }
+      }
+      return;
+    }
     const bool k_in = tap < cv.taps;  // k0 + scol < K
     const long long tap_off = ((long long)kh * cv.W + kw) * cv.Ci + c;
     a_ok = 0;
@@ -258,7 +294,7 @@ bool conv2d_gemm_f16_supported(const void* x, const void* w, int ci, int fh, int
 }
 
 namespace {
-template <int TM, int TN>
+template <int TM, int TN, bool LEAN>
 int launch_tiles(const ConvGeomF16& cv, const half_t* w, const half_t* bias, half_t* y, long long m, int co, long long k,
                  int act, hipStream_t stream) {
   constexpr int kBM = 64 * TM, kBN = 64 * TN;
@@ -266,12 +302,12 @@ int launch_tiles(const ConvGeomF16& cv, const half_t* w, const half_t* bias, hal
   const long long tiles_m = (m + kBM - 1) / kBM, tiles_n = (co + kBN - 1) / kBN;
   if (tiles_m * tiles_n > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
   static std::atomic<uint64_t> lds_allowed{0};
-  if (allow_dynamic_lds(reinterpret_cast<const void*>(conv_f16_gemm_kernel<TM, TN>), lds_bytes, lds_allowed) != TFX_OK)
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(conv_f16_gemm_kernel<TM, TN, LEAN>), lds_bytes, lds_allowed) != TFX_OK)
     return TFX_ERR_LAUNCH;
   const int wraps = (kBK + cv.Ci - 1) / cv.Ci;  // tap carries per 64-half step
   const int c_vec = reinterpret_cast<uintptr_t>(y) % 16 == 0 ? 2 : 0;
   const int total = (int)(tiles_m * tiles_n);
-  hipLaunchKernelGGL((conv_f16_gemm_kernel<TM, TN>), dim3((unsigned)total), dim3(kNT), lds_bytes, stream, cv, w, bias, y,
+  hipLaunchKernelGGL((conv_f16_gemm_kernel<TM, TN, LEAN>), dim3((unsigned)total), dim3(kNT), lds_bytes, stream, cv, w, bias, y,
                      (int)m, co, (int)k, (int)tiles_n, total, wraps, act, c_vec);
   return check_launch();
 }
@@ -293,11 +329,14 @@ int launch_conv2d_gemm_f16(const uint16_t* x, const uint16_t* w, const uint16_t*
   const bool narrow = (co + 63) / 64 * 64 < (co + 127) / 128 * 128;
   const long long tiles128 = ((m + 127) / 128) * ((co + (narrow ? 63 : 127)) / (narrow ? 64 : 128));
   const bool low = narrow || tiles128 < 256;
-  if (low)
-    return narrow ? launch_tiles<1, 1>(cv, wh, bh, yh, m, co, k, act, stream)
-                  : launch_tiles<1, 2>(cv, wh, bh, yh, m, co, k, act, stream);
-  return narrow ? launch_tiles<2, 1>(cv, wh, bh, yh, m, co, k, act, stream)
-                : launch_tiles<2, 2>(cv, wh, bh, yh, m, co, k, act, stream);
+  // scalar tap state and 32-bit offsets: 64-channel multiples, x and filter below 2^31 bytes
+  const bool lean = ci % 64 == 0 && (long long)n * h * wd * ci < (1LL << 30) && k * co < (1LL << 30);
+#define TFX_CONV16(TM, TN)                                                                   \
+  (lean ? launch_tiles<TM, TN, true>(cv, wh, bh, yh, m, co, k, act, stream)                  \
+        : launch_tiles<TM, TN, false>(cv, wh, bh, yh, m, co, k, act, stream))
+  if (low) return narrow ? TFX_CONV16(1, 1) : TFX_CONV16(1, 2);
+  return narrow ? TFX_CONV16(2, 1) : TFX_CONV16(2, 2);
+#undef TFX_CONV16
 }
 
 }  // namespace tfx
