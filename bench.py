@@ -29,20 +29,20 @@ PEAK_HBM = 8.0e12          # B/s
 # reading for a plain 205.5 MB copy (profiles/hbm_traffic_counters.txt).  Each entry names the kernel
 # source it was measured on; if that file has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100844446, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
-    "pointwise_64x56x56x128_to_128": (206178087, "pointwise.hip", "1cca37ebed9cc6e9f04eec68e56ee5e10e3d9925ca61d49d80b2bc9ac3d8fa5a"),
-    "conv3x3_64x56x56x64_to_64": (104486449, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411136526, "depthwise.hip", "d0c8f0243a54a675029dc6f1640e6db7ee3f0dfefd34825c8c07514b9be676b1"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (257001200, "depthwise.hip", "d0c8f0243a54a675029dc6f1640e6db7ee3f0dfefd34825c8c07514b9be676b1"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235069809, "gemm_f16.hip", "54fd5820b9ce4de4f4ee13d8adf6330f797356f7585cabbfdb6a2b6e6f2b2bb9"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50489478, "gemm_f16.hip", "54fd5820b9ce4de4f4ee13d8adf6330f797356f7585cabbfdb6a2b6e6f2b2bb9"),
-    "pointwise_f16_64x56x56x128_to_128": (103141727, "pointwise_f16.hip", "cf4c2e12e5128b41a9520de40fd6d6562d9c0d441b35d4747031b2c3a0c7254e"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205674534, "conv_f16.hip", "1da80b607e0312d1634038566ab217a2c08dd99a0db058212dcfd5797d56795b"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (128535830, "conv_f16.hip", "1da80b607e0312d1634038566ab217a2c08dd99a0db058212dcfd5797d56795b"),
-    "conv3x3_f16_64x56x56x64_to_64": (52104093, "conv_gemm_f16.hip", "f4eda07d9effa7262ecb3513953bc703fe8e0705d8c8af8231ae6684137a3619"),
-    "add_f32_64M": (805262605, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
-    "add_f16_64M": (402651551, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
-    "mobilenet_b1_gemm_13_launches": (53068004, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
+    "batch_matmul_8x1024x1024x1024_tB": (100844399, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
+    "pointwise_64x56x56x128_to_128": (206178088, "pointwise.hip", "1cca37ebed9cc6e9f04eec68e56ee5e10e3d9925ca61d49d80b2bc9ac3d8fa5a"),
+    "conv3x3_64x56x56x64_to_64": (104505599, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411136548, "depthwise.hip", "d0c8f0243a54a675029dc6f1640e6db7ee3f0dfefd34825c8c07514b9be676b1"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (256999270, "depthwise.hip", "d0c8f0243a54a675029dc6f1640e6db7ee3f0dfefd34825c8c07514b9be676b1"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235069753, "gemm_f16.hip", "54fd5820b9ce4de4f4ee13d8adf6330f797356f7585cabbfdb6a2b6e6f2b2bb9"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50489470, "gemm_f16.hip", "54fd5820b9ce4de4f4ee13d8adf6330f797356f7585cabbfdb6a2b6e6f2b2bb9"),
+    "pointwise_f16_64x56x56x128_to_128": (103141721, "pointwise_f16.hip", "cf4c2e12e5128b41a9520de40fd6d6562d9c0d441b35d4747031b2c3a0c7254e"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205674357, "conv_f16.hip", "1da80b607e0312d1634038566ab217a2c08dd99a0db058212dcfd5797d56795b"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (128537295, "conv_f16.hip", "1da80b607e0312d1634038566ab217a2c08dd99a0db058212dcfd5797d56795b"),
+    "conv3x3_f16_64x56x56x64_to_64": (52068243, "conv_gemm_f16.hip", "0c434b66d6367e415ef2333183a421be78368ab414a1dedd278457301abe4bab"),
+    "add_f32_64M": (805262532, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
+    "add_f16_64M": (402651589, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
+    "mobilenet_b1_gemm_13_launches": (53067992, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
 }
 
 
