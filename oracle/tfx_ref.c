@@ -105,9 +105,13 @@ int tfx_ref_depthwise_conv2d_out_shape(const int64_t x_shape[4], const int64_t f
   return REF_OK;
 }
 
-/* bias first, then activation; relu6(v) = min(max(v,0),6). */
+/* bias first, then activation; relu(v) = max(v,0), relu6(v) = min(max(v,0),6).
+ * Both are written with comparisons that are false for a NaN, so a NaN comes out
+ * as a NaN under either activation (the convention of the library the paper's API
+ * follows, Section 3.1; the debug mode of Section 3.8 exists to find such values,
+ * so an activation must not erase them).  -inf gives 0, +inf the upper bound. */
 static double ref_activate(double v, int act) {
-  if (act == REF_ACT_RELU) return v > 0.0 ? v : 0.0;
+  if (act == REF_ACT_RELU) return v < 0.0 ? 0.0 : v;
   if (act == REF_ACT_RELU6) return v < 0.0 ? 0.0 : (v > 6.0 ? 6.0 : v);
   return v;
 }

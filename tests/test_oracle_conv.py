@@ -278,6 +278,30 @@ def test_bias_only_and_activation_table():
     assert tiny == np.float32(1e-8)
 
 
+def test_nan_and_inf_through_the_activations():
+    # a NaN survives relu and relu6 (it must not be erased by a clamp); -inf -> 0; +inf -> inf under relu, 6 under relu6
+    vals = np.array([np.nan, np.inf, -np.inf, 2.0], np.float32)
+    x = np.ones((1, 1, 1, 1), np.float32)
+    zero_f = np.zeros((1, 1, 1, 4), np.float32)
+    for fn, xx, ff in ((oracle.conv2d, x, zero_f), (oracle.depthwise_conv2d, np.ones((1, 1, 1, 4), np.float32), np.zeros((1, 1, 4, 1), np.float32))):
+        y = fn(xx, ff, vals, 1, PAD_SAME, ACT_NONE)[0, 0, 0]
+        assert np.isnan(y[0]) and y[1] == np.inf and y[2] == -np.inf and y[3] == 2
+        y = fn(xx, ff, vals, 1, PAD_SAME, ACT_RELU)[0, 0, 0]
+        assert np.isnan(y[0]) and y[1] == np.inf and y[2] == 0 and y[3] == 2
+        y = fn(xx, ff, vals, 1, PAD_SAME, ACT_RELU6)[0, 0, 0]
+        assert np.isnan(y[0]) and y[1] == 6 and y[2] == 0 and y[3] == 2
+    # a NaN in the input reaches exactly the outputs whose window holds it (3x3, SAME): a 3x3 patch of one channel
+    xi = np.zeros((1, 5, 5, 2), np.float32)
+    xi[0, 2, 2, 1] = np.nan
+    y = oracle.depthwise_conv2d(xi, np.ones((3, 3, 2, 1), np.float32), None, 1, PAD_SAME, ACT_RELU6)
+    want = np.zeros((5, 5), bool)
+    want[1:4, 1:4] = True
+    assert np.array_equal(np.isnan(y[0, :, :, 1]), want) and not np.isnan(y[0, :, :, 0]).any()
+    # in a conv2d the NaN of one input channel reaches every output channel of those pixels, under relu too
+    y = oracle.conv2d(xi, np.ones((3, 3, 2, 3), np.float32), None, 1, PAD_SAME, ACT_RELU)
+    assert np.array_equal(np.isnan(y[0]), np.repeat(want[:, :, None], 3, axis=2))
+
+
 def test_relu6_range_on_random_input():
     r = rng(20)
     x = r.uniform(-1, 1, (1, 9, 9, 8)).astype(np.float32)
