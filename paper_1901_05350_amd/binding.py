@@ -118,6 +118,20 @@ def _dev(t, name, dtype=None):
     return t
 
 
+def _rank(t, name, ranks):
+    """Shape checks come before the pointer is handed to the library: the C side reads exactly `rank` entries of the
+    host shape array and as many elements as the shapes say."""
+    shape = getattr(t, "shape", None)
+    if shape is None or len(shape) not in ranks:
+        raise TypeError("%s must have rank %s" % (name, " or ".join(str(r) for r in ranks)))
+    return tuple(int(d) for d in shape)
+
+
+def _expect_shape(t, name, shape):
+    if tuple(int(d) for d in getattr(t, "shape", ())) != tuple(int(d) for d in shape):
+        raise TypeError("%s must have shape %s" % (name, list(shape)))
+
+
 def _stream(t):
     import torch
     return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
@@ -152,8 +166,11 @@ def tfx_depthwise_conv2d_out_shape(x_shape, f_shape, stride, pad):
 
 def tfx_matmul(a, b, transpose_a=False, transpose_b=False, out=None):
     import torch
-    _dev(a, "a"), _dev(b, "b")
+    _rank(a, "a", (2,)), _rank(b, "b", (2,))
     m, n = tfx_matmul_out_shape(a.shape, b.shape, transpose_a, transpose_b)
+    if out is not None:
+        _expect_shape(out, "out", (m, n))
+    _dev(a, "a"), _dev(b, "b")
     c = torch.empty((m, n), dtype=torch.float32, device=a.device) if out is None else _dev(out, "out")
     _check(lib().tfx_matmul(a.data_ptr(), _shape(a.shape), b.data_ptr(), _shape(b.shape), int(transpose_a),
                             int(transpose_b), c.data_ptr(), _stream(a)), "tfx_matmul")
@@ -162,10 +179,11 @@ def tfx_matmul(a, b, transpose_a=False, transpose_b=False, out=None):
 
 def tfx_batch_matmul(a, b, transpose_a=False, transpose_b=False, out=None):
     import torch
-    _dev(a, "a"), _dev(b, "b")
-    if a.dim() != 3 or b.dim() != 3:
-        raise TypeError("batch_matmul operands must have rank 3")
+    _rank(a, "a", (3,)), _rank(b, "b", (3,))
     m, n = tfx_matmul_out_shape(a.shape[1:], b.shape[1:], transpose_a, transpose_b)
+    if out is not None:
+        _expect_shape(out, "out", (a.shape[0], m, n))
+    _dev(a, "a"), _dev(b, "b")
     c = torch.empty((a.shape[0], m, n), dtype=torch.float32, device=a.device) if out is None else _dev(out, "out")
     _check(lib().tfx_batch_matmul(a.data_ptr(), _shape(a.shape), b.data_ptr(), _shape(b.shape), int(transpose_a),
                                   int(transpose_b), c.data_ptr(), _stream(a)), "tfx_batch_matmul")
@@ -200,14 +218,15 @@ def tfx_batch_matmul_f16(a, b, transpose_a=False, transpose_b=False, bias=None, 
     """float16 [B,rows,cols] operands, float16 bias [N] or None, float16 result [B,M,N]."""
     import torch
     h = torch.float16
-    _dev(a, "a", h), _dev(b, "b", h)
-    if a.dim() != 3 or b.dim() != 3:
-        raise TypeError("batch_matmul operands must have rank 3")
+    _rank(a, "a", (3,)), _rank(b, "b", (3,))
     m, n = tfx_matmul_out_shape(a.shape[1:], b.shape[1:], transpose_a, transpose_b)
     if bias is not None:
+        _expect_shape(bias, "bias", (n,))
+    if out is not None:
+        _expect_shape(out, "out", (a.shape[0], m, n))
+    _dev(a, "a", h), _dev(b, "b", h)
+    if bias is not None:
         _dev(bias, "bias", h)
-        if tuple(bias.shape) != (n,):
-            raise TypeError("bias must have shape [%d]" % n)
     c = torch.empty((a.shape[0], m, n), dtype=h, device=a.device) if out is None else _dev(out, "out", h)
     _check(lib().tfx_batch_matmul_f16(a.data_ptr(), _shape(a.shape), b.data_ptr(), _shape(b.shape), int(transpose_a),
                                       int(transpose_b), None if bias is None else bias.data_ptr(), int(act),
@@ -218,11 +237,16 @@ def tfx_batch_matmul_f16(a, b, transpose_a=False, transpose_b=False, bias=None, 
 def _conv(fn_name, shape_fn, x, filt, bias, stride, pad, act, out, dtype=None):
     import torch
     dtype = torch.float32 if dtype is None else dtype
+    _rank(x, "x", (4,)), _rank(filt, "filter", (4,))
+    sh, sw = _pair(stride)
+    oshape, _ = shape_fn(x.shape, filt.shape, (sh, sw), pad)
+    if bias is not None:
+        _expect_shape(bias, "bias", (oshape[3],))
+    if out is not None:
+        _expect_shape(out, "out", oshape)
     _dev(x, "x", dtype), _dev(filt, "filter", dtype)
     if bias is not None:
         _dev(bias, "bias", dtype)
-    sh, sw = _pair(stride)
-    oshape, _ = shape_fn(x.shape, filt.shape, (sh, sw), pad)
     y = torch.empty(oshape, dtype=dtype, device=x.device) if out is None else _dev(out, "out", dtype)
     fn = getattr(lib(), fn_name)
     _check(fn(x.data_ptr(), _shape(x.shape), filt.data_ptr(), _shape(filt.shape),
@@ -258,6 +282,52 @@ def tfx_mobilenet_v1_variant_workspace_bytes(variant, batch):
     return int(lib().tfx_mobilenet_v1_variant_workspace_bytes(ctypes.byref(variant), int(batch)))
 
 
+_MOBILENET_CHANNELS = (64, 128, 128, 256, 256, 512, 512, 512, 512, 512, 512, 1024, 1024)
+
+
+def _check_mobilenet_weights(weights, image_size, width_quarters):
+    """Every weight tensor must have the shape the variant implies (include/tfx.h: channel counts are
+    alpha = width_quarters / 4 times 32, 64, 128, ..., 1024): the library reads that many elements of each."""
+    q = int(width_quarters)
+    if q not in (1, 2, 3, 4) or not 32 <= int(image_size) <= 256:
+        raise ValueError("unsupported MobileNet-v1 variant")
+    for k in ("conv0_w", "conv0_b", "dw_w", "dw_b", "pw_w", "pw_b", "fc_w", "fc_b"):
+        if k not in weights:
+            raise TypeError("weights lack %r" % k)
+    for k in ("dw_w", "dw_b", "pw_w", "pw_b"):
+        if not isinstance(weights[k], (list, tuple)) or len(weights[k]) != 13:
+            raise TypeError("weights[%r] must be a list of 13 tensors" % k)
+    c = 32 * q // 4
+    _expect_shape(weights["conv0_w"], "conv0_w", (3, 3, 3, c))
+    _expect_shape(weights["conv0_b"], "conv0_b", (c,))
+    for i, full in enumerate(_MOBILENET_CHANNELS):
+        co = full * q // 4
+        _expect_shape(weights["dw_w"][i], "dw_w[%d]" % i, (3, 3, c, 1))
+        _expect_shape(weights["dw_b"][i], "dw_b[%d]" % i, (c,))
+        _expect_shape(weights["pw_w"][i], "pw_w[%d]" % i, (1, 1, c, co))
+        _expect_shape(weights["pw_b"][i], "pw_b[%d]" % i, (co,))
+        c = co
+    classes = _rank(weights["fc_w"], "fc_w", (2,))[1]
+    _expect_shape(weights["fc_w"], "fc_w", (c, classes))
+    _expect_shape(weights["fc_b"], "fc_b", (classes,))
+    if not 1 <= classes <= 1024:
+        raise ValueError("unsupported number of classes")
+    return classes
+
+
+def _check_forward_buffers(image, workspace, probs, logits, batch, size, classes, dtype):
+    import torch
+    _expect_shape(image, "image", (batch, size, size, 3))
+    _expect_shape(probs, "probs", (batch, classes))
+    if logits is not None:
+        _expect_shape(logits, "logits", (batch, classes))
+    _dev(image, "image", dtype), _dev(probs, "probs", dtype)
+    if logits is not None:
+        _dev(logits, "logits", dtype)
+    if not isinstance(workspace, torch.Tensor) or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous tensor in GPU memory")
+
+
 class MobileNetV1:
     """Device-resident MobileNet-v1 weights plus a workspace.
 
@@ -267,6 +337,7 @@ class MobileNetV1:
 
     def __init__(self, weights, batch=1, device="cuda:0", image_size=224, width_quarters=4):
         import torch
+        _check_mobilenet_weights(weights, image_size, width_quarters)
         self.device = torch.device(device)
         self.batch = int(batch)
         up = lambda a: torch.as_tensor(a, dtype=torch.float32).contiguous().to(self.device)
@@ -303,7 +374,8 @@ class MobileNetV1:
 
 
 def tfx_mobilenet_v1_forward(image, weights_struct, workspace, probs, logits=None):
-    _dev(image, "image"), _dev(probs, "probs")
+    import torch
+    _check_forward_buffers(image, workspace, probs, logits, _rank(image, "image", (4,))[0], 224, 1000, torch.float32)
     _check(lib().tfx_mobilenet_v1_forward(image.data_ptr(), int(image.shape[0]), ctypes.byref(weights_struct),
                                           workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                           probs.data_ptr(), None if logits is None else logits.data_ptr(),
@@ -312,7 +384,9 @@ def tfx_mobilenet_v1_forward(image, weights_struct, workspace, probs, logits=Non
 
 
 def tfx_mobilenet_v1_variant_forward(variant, image, weights_struct, workspace, probs, logits=None):
-    _dev(image, "image"), _dev(probs, "probs")
+    import torch
+    _check_forward_buffers(image, workspace, probs, logits, _rank(image, "image", (4,))[0], int(variant.image_size),
+                           int(variant.classes), torch.float32)
     _check(lib().tfx_mobilenet_v1_variant_forward(ctypes.byref(variant), image.data_ptr(), int(image.shape[0]),
                                                   ctypes.byref(weights_struct), workspace.data_ptr(),
                                                   workspace.numel() * workspace.element_size(), probs.data_ptr(),
@@ -326,6 +400,7 @@ class MobileNetV1F16:
 
     def __init__(self, weights, batch=1, device="cuda:0", image_size=224, width_quarters=4):
         import torch
+        _check_mobilenet_weights(weights, image_size, width_quarters)
         self.device = torch.device(device)
         self.batch = int(batch)
         up = lambda a: torch.as_tensor(a).to(torch.float16).contiguous().to(self.device)
@@ -349,10 +424,8 @@ class MobileNetV1F16:
     def forward(self, image):
         """Enqueue one forward pass on the current stream; returns (probs, logits) float16 device tensors."""
         import torch
-        _dev(image, "image", torch.float16)
-        size = int(self.variant.image_size)
-        if tuple(image.shape) != (self.batch, size, size, 3):
-            raise TypeError("image must be [%d,%d,%d,3]" % (self.batch, size, size))
+        _check_forward_buffers(image, self.workspace, self.probs, self.logits, self.batch, int(self.variant.image_size),
+                               int(self.variant.classes), torch.float16)
         _check(lib().tfx_mobilenet_v1_forward_f16(ctypes.byref(self.variant), image.data_ptr(), self.batch,
                                                   ctypes.byref(self.struct), self.workspace.data_ptr(),
                                                   self.workspace.numel(), self.probs.data_ptr(), self.logits.data_ptr(),

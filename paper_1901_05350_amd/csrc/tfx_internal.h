@@ -14,7 +14,10 @@ namespace tfx {
 
 // Fused epilogue: bias first, then activation.  relu and relu6 are clamps ([0, +inf] and [0, 6]);
 // kernels turn the enum into an on/off flag and an upper bound once and apply max / min per
-// element.  With no activation the value passes through untouched (NaN and Inf included).
+// element.  With no activation the value passes through untouched (NaN and Inf included).  A NaN also
+// passes through relu and relu6 (the hardware's max / min would return the other operand, i.e. turn a NaN
+// into 0): an activation must not hide a poisoned value from the layers behind it, which is what the
+// debug mode of Section 3.8 looks for.  -Inf clamps to 0, +Inf to the upper bound.
 struct ActClamp {
   bool on;
   float hi;
@@ -27,7 +30,7 @@ __device__ __forceinline__ ActClamp make_act(int act) {
 }
 __device__ __forceinline__ float apply_act(float v, const ActClamp& c) {
   const float t = fminf(fmaxf(v, 0.0f), c.hi);
-  return c.on ? t : v;
+  return (c.on && v == v) ? t : v;
 }
 __device__ __forceinline__ float apply_act(float v, int act) { return apply_act(v, make_act(act)); }
 

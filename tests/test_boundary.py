@@ -74,6 +74,20 @@ def _sh(*d):
 FAKE = ctypes.c_void_p(0x1000)   # never dereferenced: every call below must fail validation first
 
 
+def _gpu_visible():
+    try:
+        import torch
+        return torch.cuda.is_available()
+    except Exception:
+        return False
+
+
+# The fake-pointer calls rely on validation failing first.  On a box with a GPU a validation regression would
+# enqueue kernels on address 0x1000, so there these tests do not run at all (they are CPU-suite tests).
+no_gpu_only = pytest.mark.skipif(_gpu_visible(), reason="fake device pointers are only passed where no GPU can be reached")
+
+
+@no_gpu_only
 def test_entry_points_validate_before_touching_the_gpu():
     L = tfx.lib()
     # null pointers
@@ -100,6 +114,7 @@ def test_entry_points_validate_before_touching_the_gpu():
     assert L.tfx_conv2d(FAKE, _sh(1 << 10, 1 << 10, 1 << 10, 8), FAKE, _sh(1, 1, 8, 8), None, 1, 1, 1, 0, FAKE, None) == -4
 
 
+@no_gpu_only
 def test_mobilenet_entry_point_validation():
     L = tfx.lib()
     w = binding.TfxWeights()
@@ -123,6 +138,7 @@ def test_mobilenet_entry_point_validation():
     assert L.tfx_mobilenet_v1_forward(FAKE, 1, ctypes.byref(w), FAKE, one, FAKE, None, None) == -1
 
 
+@no_gpu_only
 def test_mobilenet_variant_validation():
     L = tfx.lib()
     V = binding.TfxVariant
@@ -152,5 +168,68 @@ def test_mobilenet_variant_validation():
 
 def test_binding_refuses_host_tensors():
     import torch
-    with pytest.raises(TypeError):
+    with pytest.raises(TypeError, match="GPU memory"):
         tfx.tfx_matmul(torch.zeros(2, 2), torch.zeros(2, 2))
+    with pytest.raises(TypeError, match="GPU memory"):
+        tfx.tfx_conv2d(torch.zeros(1, 4, 4, 2), torch.zeros(3, 3, 2, 5), torch.zeros(5))
+
+
+def test_binding_checks_ranks_and_shapes_before_any_pointer_is_passed():
+    """The C side reads `rank` entries of each host shape array and as many elements of each buffer as the shapes
+    say, so the binding refuses a wrong rank, a bias or an output buffer of the wrong shape."""
+    import torch
+    z = torch.zeros
+    with pytest.raises(TypeError, match="a must have rank 2"):
+        tfx.tfx_matmul(z(6), z(6, 2))
+    with pytest.raises(TypeError, match="b must have rank 2"):
+        tfx.tfx_matmul(z(2, 6), z(1, 6, 2))
+    with pytest.raises(TypeError, match="out must have shape"):
+        tfx.tfx_matmul(z(2, 6), z(6, 3), out=z(2, 2))
+    with pytest.raises(TypeError, match="rank 3"):
+        tfx.tfx_batch_matmul(z(2, 6), z(6, 3))
+    with pytest.raises(TypeError, match="out must have shape"):
+        tfx.tfx_batch_matmul(z(4, 2, 6), z(4, 6, 3), out=z(3, 2, 3))
+    with pytest.raises(TypeError, match="rank 3"):
+        tfx.tfx_batch_matmul_f16(z(2, 6).half(), z(1, 6, 3).half())
+    with pytest.raises(TypeError, match="bias must have shape"):
+        tfx.tfx_batch_matmul_f16(z(1, 2, 6).half(), z(1, 6, 3).half(), bias=z(2).half())
+    for conv, f in ((tfx.tfx_conv2d, z(3, 3, 2, 5)), (tfx.tfx_depthwise_conv2d, z(3, 3, 2, 1)),
+                    (tfx.tfx_conv2d_f16, z(3, 3, 2, 5).half()), (tfx.tfx_depthwise_conv2d_f16, z(3, 3, 2, 1).half())):
+        x = z(1, 4, 4, 2).to(f.dtype)
+        co = f.shape[3] if conv in (tfx.tfx_conv2d, tfx.tfx_conv2d_f16) else 2
+        with pytest.raises(TypeError, match="x must have rank 4"):
+            conv(x[0], f)
+        with pytest.raises(TypeError, match="filter must have rank 4"):
+            conv(x, f[0])
+        with pytest.raises(TypeError, match="bias must have shape"):
+            conv(x, f, z(co + 1).to(f.dtype))
+        with pytest.raises(TypeError, match="bias must have shape"):
+            conv(x, f, z(1, co).to(f.dtype))
+        with pytest.raises(TypeError, match="out must have shape"):
+            conv(x, f, z(co).to(f.dtype), out=z(1, 4, 4, co - 1).to(f.dtype))
+        with pytest.raises(TypeError, match="out must have shape"):
+            conv(x, f, None, stride=2, out=z(1, 4, 4, co).to(f.dtype))
+
+
+def test_mobilenet_binding_checks_weight_shapes_against_the_variant():
+    from paper_1901_05350_amd import inputs
+    data = inputs.mobilenet_v1(seed=4, batch=1, image_size=64, width_quarters=1, classes=10)
+    w = data["weights"]
+    for ctor in (tfx.MobileNetV1, tfx.MobileNetV1F16):
+        with pytest.raises(TypeError, match="conv0_w must have shape"):
+            ctor(w, batch=1, image_size=64, width_quarters=2)          # weights of the 0.25 member given as 0.5
+        bad = dict(w)
+        bad["pw_w"] = list(w["pw_w"])
+        bad["pw_w"][6] = w["pw_w"][6][:, :, :, :-1]
+        with pytest.raises(TypeError, match=r"pw_w\[6\] must have shape"):
+            ctor(bad, batch=1, image_size=64, width_quarters=1)
+        bad = dict(w)
+        bad["fc_b"] = w["fc_b"][:-1]
+        with pytest.raises(TypeError, match="fc_b must have shape"):
+            ctor(bad, batch=1, image_size=64, width_quarters=1)
+        bad = dict(w)
+        bad["dw_b"] = list(w["dw_b"])[:12]
+        with pytest.raises(TypeError, match="list of 13"):
+            ctor(bad, batch=1, image_size=64, width_quarters=1)
+        with pytest.raises(ValueError):
+            ctor(w, batch=1, image_size=64, width_quarters=5)

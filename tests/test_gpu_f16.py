@@ -102,15 +102,13 @@ def test_matmul_f16_layouts_and_ragged_shapes(ta, tb, shape):
                                          ((1, 12544, 64, 32), False, False), ((1, 700, 520, 1032), False, False)])
 def test_matmul_f16_tile_configurations(shape, ta, tb):
     """Each tile size of the 16-byte-load kernel (A [M,K], B stored [N,K]) and of the element-wise
-    loader (other layouts), checked on sampled rows."""
+    loader (other layouts); every output is compared."""
     import paper_1901_05350_amd as tfx
     b, m, n, k = shape
     d = inputs.batch_matmul_f16(seed=40 + n, batch=b, m=m, n=n, k=k, transpose_a=ta, transpose_b=tb, bias=True)
     got = host(tfx.tfx_batch_matmul_f16(dev16(d["a"]), dev16(d["b"]), ta, tb, dev16(d["bias"]), oracle.ACT_RELU))
-    rows = np.unique(np.concatenate([np.arange(0, m, max(1, m // 37)), [m - 1, m // 2, min(m - 1, 255), min(m - 1, 256)]]))
-    a_rows = np.ascontiguousarray(d["a"][:, :, rows] if ta else d["a"][:, rows, :])
-    ref = oracle.batch_matmul_f16(a_rows, d["b"], ta, tb, d["bias"], oracle.ACT_RELU)
-    assert_close_f16(np.ascontiguousarray(got[:, rows, :]), ref, "f16 matmul %r" % (shape,))
+    ref = oracle.batch_matmul_f16(d["a"], d["b"], ta, tb, d["bias"], oracle.ACT_RELU)
+    assert_close_f16(got, ref, "f16 matmul %r" % (shape,))
 
 
 def test_matmul_f16_rounding_overflow_subnormals_and_nan():
@@ -161,12 +159,11 @@ def test_matmul_f16_unaligned_and_output_buffer():
     assert e.value.status == -2
 
 
-def test_matmul_f16_full_size_sampled_rows():
-    """8 x 1024^3 with transposeB, the configuration the benchmark times, on sampled rows of every batch."""
+def test_matmul_f16_full_size():
+    """8 x 1024^3 with transposeB, the configuration the benchmark times; every output is compared."""
     import paper_1901_05350_amd as tfx
     d = inputs.batch_matmul_f16(seed=6)
     got = host(tfx.tfx_batch_matmul_f16(dev16(d["a"]), dev16(d["b"]), False, True))
-    rows = np.array([0, 1, 31, 32, 127, 128, 255, 256, 511, 777, 1023])
-    ref = oracle.batch_matmul_f16(np.ascontiguousarray(d["a"][:, rows, :]), d["b"], False, True)
-    frac = assert_close_f16(np.ascontiguousarray(got[:, rows, :]), ref, "8x1024^3 f16")
+    ref = oracle.batch_matmul_f16(d["a"], d["b"], False, True)
+    frac = assert_close_f16(got, ref, "8x1024^3 f16")
     assert frac < 0.05   # only sums near a rounding boundary may land on the neighbouring binary16 value

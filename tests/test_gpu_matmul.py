@@ -125,6 +125,25 @@ def test_batch_matmul_small_and_no_leak():
     assert not got[3].any()
 
 
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("tb", [False, True])
+def test_batch_matmul_every_layout_with_batch_above_one(ta, tb):
+    # the batch stride of each stored layout: ragged small tiles, 64 x 64 tiles, 128 x 128 tiles (XCD-remapped
+    # order over batch x tiles) and the 16-row kernels; every batch differs, so a wrong stride shows
+    r = rng(12 + 2 * ta + tb)
+    for (bt, m, k, n) in [(5, 70, 33, 45), (3, 1, 1, 1), (7, 16, 64, 34), (6, 196, 128, 96), (12, 320, 96, 256),
+                          (9, 512, 200, 640), (4, 129, 1024, 130)]:
+        a = r.standard_normal((bt, m, k)).astype(np.float32)
+        b = r.standard_normal((bt, k, n)).astype(np.float32)
+        ref = np.stack([oracle.matmul(a[i], b[i]) for i in range(bt)])
+        a_in = np.ascontiguousarray(a.transpose(0, 2, 1)) if ta else a
+        b_in = np.ascontiguousarray(b.transpose(0, 2, 1)) if tb else b
+        import paper_1901_05350_amd as tfx
+        got = host(tfx.tfx_batch_matmul(dev(a_in), dev(b_in), ta, tb))
+        assert_close(got, ref, "batchMatMul b=%d m=%d k=%d n=%d ta=%d tb=%d" % (bt, m, k, n, ta, tb))
+        assert np.array_equal(oracle.batch_matmul(a_in, b_in, ta, tb), ref)
+
+
 def test_config_batch_matmul_full_size():
     import paper_1901_05350_amd as tfx
     d = inputs.batch_matmul(seed=3)

@@ -62,10 +62,10 @@ def test_end_to_end_batch_3():
 
 
 @pytest.mark.parametrize("batch", [8, 64])
-def test_end_to_end_benchmark_batches_sampled_images(batch):
+def test_end_to_end_benchmark_batches_every_image(batch):
     """The batched forward passes the benchmark times (other tile shapes and kernels than batch 1: filter-stationary
-    pointwise kernel, 128 x 128 tiles, several depthwise rows per lane).  Images are independent, so the oracle
-    checks a sample of them, each run alone."""
+    pointwise kernel, 128 x 128 tiles, several depthwise rows per lane).  Every image of the batch is compared with
+    the oracle's forward pass of the whole batch."""
     import paper_1901_05350_amd as tfx
     data = inputs.mobilenet_v1(seed=9, batch=batch)
     model = tfx.MobileNetV1(data["weights"], batch=batch)
@@ -73,10 +73,10 @@ def test_end_to_end_benchmark_batches_sampled_images(batch):
     p, l = host(p), host(l)
     assert np.isfinite(p).all() and np.isfinite(l).all()
     np.testing.assert_allclose(p.astype(np.float64).sum(axis=1), 1.0, atol=1e-5)
-    for img in sorted({0, batch // 3, batch - 1}):
-        probs, logits = oracle.mobilenet_v1_forward(data["image"][img:img + 1], data["weights"])
-        assert_close(l[img:img + 1], logits, "logits batch %d image %d" % (batch, img))
-        assert_close(p[img:img + 1], probs, "probs batch %d image %d" % (batch, img))
+    probs, logits = oracle.mobilenet_v1_forward(data["image"], data["weights"])
+    assert_close(l, logits, "logits batch %d" % batch)
+    assert_close(p, probs, "probs batch %d" % batch)
+    assert np.array_equal(p.argmax(axis=1), probs.argmax(axis=1))
 
 
 @pytest.mark.parametrize("size,q,classes,batch", [(128, 1, 10, 2), (160, 2, 1000, 1), (192, 3, 1000, 1), (224, 4, 37, 1),
@@ -163,5 +163,5 @@ def test_batched_forward_first_called_under_graph_capture():
     model.logits.zero_()
     p_eager = host(model.forward(image)[0]).copy()
     assert np.array_equal(p_graph, p_eager) and np.array_equal(l_graph, host(model.logits))
-    probs, logits = oracle.mobilenet_v1_forward(data["image"][5:6], data["weights"])
-    assert_close(l_graph[5:6], logits, "logits image 5 of 8 (192 x 192)")
+    probs, logits = oracle.mobilenet_v1_forward(data["image"], data["weights"])
+    assert_close(l_graph, logits, "logits batch 8 (192 x 192)")
