@@ -215,6 +215,27 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
                                      const tfx_mobilenet_v1_weights* weights, void* workspace,
                                      size_t workspace_bytes, float* probs, float* logits, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): tfx_mobilenet_v1_variant_forward with
+ * the workspace inside the library, a fixed array of
+ * tfx_mobilenet_v1_static_scratch_bytes() = 16 MiB of device memory that every GPU the
+ * library runs on holds until the process ends, from the moment the runtime loads the
+ * library's device code there (at the latest during the first call of this entry point
+ * on that GPU, which also looks up the array's device address once).  The call
+ * allocates and frees nothing.  {224, 4, 1000} fits at batch 1 and 2; a variant / batch whose
+ * tfx_mobilenet_v1_variant_workspace_bytes exceeds the array is refused with
+ * TFX_ERR_WORKSPACE (nothing enqueued).  Results are bit-identical to
+ * tfx_mobilenet_v1_variant_forward.  All calls on one GPU share the one array: calls that
+ * overlap in time on one GPU (different streams or host threads) race and give
+ * undefined results; calls ordered on one stream are fine.  Nothing in the array has to
+ * start at zero (each kernel writes what later kernels read), so its contents between
+ * calls do not matter.  Other arguments and errors as tfx_mobilenet_v1_variant_forward;
+ * TFX_ERR_LAUNCH also if the array's device address cannot be obtained. */
+size_t tfx_mobilenet_v1_static_scratch_bytes(void);
+int tfx_mobilenet_v1_variant_forward_static(const tfx_mobilenet_v1_variant* variant, const float* input,
+                                            int64_t batch, const tfx_mobilenet_v1_weights* weights, float* probs,
+                                            float* logits, void* stream);
+
 /* MobileNet v1 on 16-bit storage: the network of tfx_mobilenet_v1_variant_forward with
  * every tensor (image, weights, biases, feature maps, pooled vector, logits,
  * probabilities) stored as binary16 and every layer rounding its result once; the

@@ -68,6 +68,9 @@ _SIGNATURES = {
     "tfx_mobilenet_v1_forward": (ctypes.c_int, [_VP, ctypes.c_int64, ctypes.POINTER(TfxWeights), _VP,
                                                 ctypes.c_size_t, _VP, _VP, _VP]),
     "tfx_mobilenet_v1_variant_workspace_bytes": (ctypes.c_size_t, [ctypes.POINTER(TfxVariant), ctypes.c_int64]),
+    "tfx_mobilenet_v1_static_scratch_bytes": (ctypes.c_size_t, []),
+    "tfx_mobilenet_v1_variant_forward_static": (ctypes.c_int, [ctypes.POINTER(TfxVariant), _VP, ctypes.c_int64,
+                                                               ctypes.POINTER(TfxWeights), _VP, _VP, _VP]),
     "tfx_mobilenet_v1_variant_forward": (ctypes.c_int, [ctypes.POINTER(TfxVariant), _VP, ctypes.c_int64,
                                                         ctypes.POINTER(TfxWeights), _VP, ctypes.c_size_t, _VP, _VP,
                                                         _VP]),
@@ -392,6 +395,27 @@ def tfx_mobilenet_v1_variant_forward(variant, image, weights_struct, workspace, 
                                                   workspace.numel() * workspace.element_size(), probs.data_ptr(),
                                                   None if logits is None else logits.data_ptr(), _stream(image)),
            "tfx_mobilenet_v1_variant_forward")
+    return probs
+
+
+def tfx_mobilenet_v1_static_scratch_bytes():
+    return int(lib().tfx_mobilenet_v1_static_scratch_bytes())
+
+
+def tfx_mobilenet_v1_variant_forward_static(variant, image, weights_struct, probs, logits=None):
+    """The forward pass with the library's own fixed workspace: no allocation by the library or by this binding."""
+    import torch
+    batch = _rank(image, "image", (4,))[0]
+    _expect_shape(image, "image", (batch, int(variant.image_size), int(variant.image_size), 3))
+    _expect_shape(probs, "probs", (batch, int(variant.classes)))
+    if logits is not None:
+        _expect_shape(logits, "logits", (batch, int(variant.classes)))
+        _dev(logits, "logits")
+    _dev(image, "image"), _dev(probs, "probs")
+    _check(lib().tfx_mobilenet_v1_variant_forward_static(ctypes.byref(variant), image.data_ptr(), batch,
+                                                         ctypes.byref(weights_struct), probs.data_ptr(),
+                                                         None if logits is None else logits.data_ptr(),
+                                                         _stream(image)), "tfx_mobilenet_v1_variant_forward_static")
     return probs
 
 

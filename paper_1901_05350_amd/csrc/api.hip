@@ -119,6 +119,33 @@ NetPlan plan_net(const tfx_mobilenet_v1_variant& v, int64_t batch, size_t elem_b
 
 constexpr tfx_mobilenet_v1_variant kBaseVariant = {kImage, 4, kClasses};
 
+// Workspace of tfx_mobilenet_v1_variant_forward_static: it lives in the library's code object, one copy per
+// GPU, from the moment the library is loaded on that GPU until the process ends.
+constexpr size_t kStaticScratchBytes = size_t(16) << 20;
+constexpr int kMaxDevices = 64;
+
+}  // namespace
+}  // namespace tfx
+
+static __device__ __align__(256) unsigned char scratch[tfx::kStaticScratchBytes];
+
+namespace tfx {
+namespace {
+
+// Device address of `scratch` on the calling thread's current device.  In host code the array's name is only a
+// handle for the runtime; the address kernels can use is looked up once per device and kept.  Returns null if the
+// lookup fails.  Safe to call from several threads (the lookup is idempotent).
+void* static_scratch() {
+  static std::atomic<void*> ptr[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  ptr[dev].store(p, std::memory_order_release);
+  return p;
+}
+
 }  // namespace
 }  // namespace tfx
 
@@ -369,6 +396,24 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
   hipStream_t s = static_cast<hipStream_t>(stream);
   return launch_pool_fc_softmax(buf[cur], weights->fc_w, weights->fc_b, partial, logits, probs, (int)batch,
                                 (int)(shape[1] * shape[2]), (int)shape[3], (int)variant->classes, s);
+}
+
+size_t tfx_mobilenet_v1_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int tfx_mobilenet_v1_variant_forward_static(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
+                                            const tfx_mobilenet_v1_weights* weights, float* probs, float* logits,
+                                            void* stream) {
+  if (!variant || !input || !weights || !probs) return TFX_ERR_NULL;
+  if (!valid_variant(variant)) return TFX_ERR_ARG;
+  if (batch < 1) return TFX_ERR_SHAPE;
+  if (batch > 1024) return TFX_ERR_UNSUPPORTED;
+  if (plan_net(*variant, batch).bytes > kStaticScratchBytes) return TFX_ERR_WORKSPACE;
+  void* ws = static_scratch();
+  if (!ws) return TFX_ERR_LAUNCH;
+  // Every kernel of the forward pass writes the part of the workspace it later reads (feature maps, the fully
+  // connected layer's partial sums), so nothing has to be cleared between calls.
+  return tfx_mobilenet_v1_variant_forward(variant, input, batch, weights, ws, kStaticScratchBytes, probs, logits,
+                                          stream);
 }
 
 size_t tfx_mobilenet_v1_workspace_bytes_f16(const tfx_mobilenet_v1_variant* variant, int64_t batch) {
