@@ -348,6 +348,12 @@ def main():
         step()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # The interpreter's cyclic garbage collector is kept out of the timed region (as timeit does): a full
+    # collection takes tens of ms in a process that has imported torch, and when it falls into the K steps
+    # the GPU runs dry while the host is stopped (measured: 37 ms, twice the whole timed region).
+    import gc
+    gc.collect()
+    gc.disable()
     t0 = time.perf_counter()
     e0.record()
     for _ in range(args.steps):
@@ -355,6 +361,7 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    gc.enable()
     ms_per_step = wall * 1e3 / args.steps
     ms_events = e0.elapsed_time(e1) / args.steps
     probs = model.probs.cpu().numpy()

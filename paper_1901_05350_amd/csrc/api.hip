@@ -93,7 +93,8 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct NetPlan {
   size_t act_floats;  // per ping-pong buffer
-  size_t off_buf[2], off_partial, bytes;
+  size_t off_buf[2], off_partial, off_chain, bytes;
+  bool chain;         // the batch-1 full-width network: room for the chained small-map kernel (chain.hip)
 };
 
 bool valid_variant(const tfx_mobilenet_v1_variant* v) {
@@ -113,6 +114,9 @@ NetPlan plan_net(const tfx_mobilenet_v1_variant& v, int64_t batch, size_t elem_b
   }
   p.off_partial = off;  // K-slice partial sums of the fully connected layer
   off = align_up(off + fc_partial_floats((int)batch, (int)(kFeatures * v.width_quarters / 4), (int)v.classes) * sizeof(float));
+  p.off_chain = off;
+  p.chain = elem_bytes == sizeof(float) && chain_supported((int)v.image_size, (int)v.width_quarters, (int)v.classes, batch);
+  if (p.chain) off = align_up(off + chain_workspace_bytes((int)v.image_size, (int)v.classes));
   p.bytes = off;
   return p;
 }
@@ -367,17 +371,40 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
   float* buf[2] = {reinterpret_cast<float*>(ws + plan.off_buf[0]), reinterpret_cast<float*>(ws + plan.off_buf[1])};
   float* partial = reinterpret_cast<float*>(ws + plan.off_partial);
 
+  // Batch 1 at full width: the blocks from the 1/8-size maps on, the pool, the fully connected layer and the
+  // softmax run as one persistent kernel (chain.hip) when every pointer allows its vector loads and 256 of its
+  // workgroups are resident at once on this device; its task flags are cleared by the stem kernel.
+  bool chain = plan.chain;
+  if (chain) {
+    auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
+    chain = al16(input) && al16(weights->conv0_b) && al16(weights->fc_w) && al16(weights->fc_b);
+    for (int i = 0; i < kBlocks && chain; ++i)
+      chain = al16(weights->dw_w[i]) && al16(weights->dw_b[i]) && al16(weights->pw_w[i]) && al16(weights->pw_b[i]);
+    chain = chain && chain_resident();
+  }
+  void* chain_ws = ws + plan.off_chain;
+
   // stem: 3x3 stride-2 convolution to 32 alpha channels, then the 13 depthwise-separable blocks
   int64_t shape[4] = {batch, variant->image_size, variant->image_size, 3};
   const int64_t f0[4] = {3, 3, 3, kStemChannels * q / 4};
-  int rc = tfx_conv2d(input, shape, weights->conv0_w, f0, weights->conv0_b, 2, 2, TFX_PAD_SAME, TFX_ACT_RELU6, buf[0],
-                      stream);
-  if (rc) return rc;
   ConvGeom g;
   conv_geometry(shape, f0, 2, 2, TFX_PAD_SAME, false, &g);
+  int rc;
+  if (chain)
+    rc = launch_conv2d_stem(input, weights->conv0_w, weights->conv0_b, buf[0], 1, (int)shape[1], (int)shape[2],
+                            kStemChannels, (int)g.out[1], (int)g.out[2], 2, 2, (int)g.pad[0], (int)g.pad[2], TFX_ACT_RELU6,
+                            static_cast<hipStream_t>(stream), static_cast<int*>(chain_ws),
+                            chain_flag_words((int)variant->image_size, (int)variant->classes));
+  else
+    rc = tfx_conv2d(input, shape, weights->conv0_w, f0, weights->conv0_b, 2, 2, TFX_PAD_SAME, TFX_ACT_RELU6, buf[0],
+                    stream);
+  if (rc) return rc;
   for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
   int cur = 0;
   for (int b = 0; b < kBlocks; ++b) {
+    if (chain && b == 4)
+      return launch_chain(buf[cur], (int)shape[1], weights, chain_ws, probs, logits, (int)variant->classes,
+                          static_cast<hipStream_t>(stream));
     const int64_t fd[4] = {3, 3, shape[3], 1};
     rc = tfx_depthwise_conv2d(buf[cur], shape, weights->dw_w[b], fd, weights->dw_b[b], kStrides[b], kStrides[b],
                               TFX_PAD_SAME, TFX_ACT_RELU6, buf[cur ^ 1], stream);

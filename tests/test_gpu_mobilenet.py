@@ -165,3 +165,68 @@ def test_batched_forward_first_called_under_graph_capture():
     assert np.array_equal(p_graph, p_eager) and np.array_equal(l_graph, host(model.logits))
     probs, logits = oracle.mobilenet_v1_forward(data["image"], data["weights"])
     assert_close(l_graph, logits, "logits batch 8 (192 x 192)")
+
+
+# ---- the chained small-map kernel (batch 1, full width: blocks 5 .. 13, pool, fully connected, softmax in one launch) ----
+@pytest.mark.parametrize("size,classes", [(32, 3), (64, 1000), (100, 5), (128, 1024), (160, 37), (192, 1000), (250, 130),
+                                          (256, 1)])
+def test_chained_kernel_other_input_sizes_and_class_counts(size, classes):
+    """Full-width members at batch 1 take the chained kernel for every input size: maps from 32 x 32 down to 1 x 1,
+    ragged 16-pixel row tiles, both pointwise tile widths, class counts that are not multiples of 4 or 128."""
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1(seed=50 + size, batch=1, image_size=size, width_quarters=4, classes=classes)
+    probs, logits = oracle.mobilenet_v1_forward(data["image"], data["weights"])
+    model = tfx.MobileNetV1(data["weights"], batch=1, image_size=size, width_quarters=4)
+    p, l = model.forward(dev(data["image"]))
+    p, l = host(p).copy(), host(l).copy()
+    assert_close(l, logits, "logits 1.0/%d, %d classes" % (size, classes))
+    assert_close(p, probs, "probs 1.0/%d, %d classes" % (size, classes))
+    # the same bits on every call (the kernel's tasks run in a different order each time)
+    for _ in range(5):
+        p2, l2 = model.forward(dev(data["image"]))
+        assert np.array_equal(host(p2), p) and np.array_equal(host(l2), l)
+
+
+def test_chained_kernel_many_calls_back_to_back_give_the_same_bits(net):
+    import torch
+    import paper_1901_05350_amd as tfx
+    data, probs, logits, acts = net
+    model = tfx.MobileNetV1(data["weights"], batch=1)
+    image = dev(data["image"])
+    outs = [(torch.empty_like(model.probs), torch.empty_like(model.logits)) for _ in range(300)]
+    for p, l in outs:                      # no synchronisation in between: 300 forward passes queued on the stream
+        tfx.tfx_mobilenet_v1_forward(image, model.struct, model.workspace, p, l)
+    torch.cuda.synchronize()
+    p0, l0 = outs[0][0].cpu().numpy(), outs[0][1].cpu().numpy()
+    assert_close(l0, logits, "logits")
+    for p, l in outs[1:]:
+        assert np.array_equal(p.cpu().numpy(), p0) and np.array_equal(l.cpu().numpy(), l0)
+
+
+def test_chained_kernel_nan_in_the_image_reaches_every_output(net):
+    import paper_1901_05350_amd as tfx
+    data, *_ = net
+    img = data["image"].copy()
+    img[0, 100, 37, 1] = np.nan
+    probs, logits = oracle.mobilenet_v1_forward(img, data["weights"])
+    assert np.isnan(logits).all() and np.isnan(probs).all()
+    model = tfx.MobileNetV1(data["weights"], batch=1)
+    p, l = model.forward(dev(img))
+    assert np.isnan(host(p)).all() and np.isnan(host(l)).all()
+
+
+def test_chained_kernel_bounded_waits_give_up_and_report_nan(net, monkeypatch):
+    """Every wait inside the chained kernel is bounded.  With the limit forced down to one poll from the host, waits
+    give up before their producers are done: the kernel must still run to its end (no hang), flag the failure and
+    write NaN to every output instead of numbers computed from unfinished inputs; the next normal call is correct."""
+    import paper_1901_05350_amd as tfx
+    data, probs, logits, acts = net
+    model = tfx.MobileNetV1(data["weights"], batch=1)
+    image = dev(data["image"])
+    monkeypatch.setenv("TFX_CHAIN_SPIN_LIMIT", "1")
+    p, l = model.forward(image)
+    assert np.isnan(host(p)).all() and np.isnan(host(l)).all()
+    monkeypatch.delenv("TFX_CHAIN_SPIN_LIMIT")
+    p, l = model.forward(image)
+    assert_close(host(l), logits, "logits after a failed call")
+    assert_close(host(p), probs, "probs after a failed call")
