@@ -394,7 +394,7 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
     rc = launch_conv2d_stem(input, weights->conv0_w, weights->conv0_b, buf[0], 1, (int)shape[1], (int)shape[2],
                             kStemChannels, (int)g.out[1], (int)g.out[2], 2, 2, (int)g.pad[0], (int)g.pad[2], TFX_ACT_RELU6,
                             static_cast<hipStream_t>(stream), static_cast<int*>(chain_ws),
-                            chain_flag_words((int)variant->image_size, (int)variant->classes));
+                            chain_flag_words((int)variant->image_size, (int)variant->classes), chain_flag_stride());
   else
     rc = tfx_conv2d(input, shape, weights->conv0_w, f0, weights->conv0_b, 2, 2, TFX_PAD_SAME, TFX_ACT_RELU6, buf[0],
                     stream);

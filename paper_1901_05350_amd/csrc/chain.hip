@@ -36,14 +36,19 @@
 namespace tfx {
 namespace {
 
-constexpr int kChainThreads = 512;
-constexpr int kChainWaves = kChainThreads / 64;
+constexpr int kComputeThreads = 512;  // 8 wavefronts that compute
+constexpr int kComputeWaves = kComputeThreads / 64;
+constexpr int kChainThreads = kComputeThreads + 64;  // + one helper wavefront: polls flags, sets flags, warms L2
 constexpr int kChainGrid = 256;
 constexpr int kChainBlocks = 9;       // blocks 5 .. 13 of the network (0-based 4 .. 12)
 constexpr int kFirstChainBlock = 4;
 constexpr int kSpinLimit = 1 << 22;  // polls before a wait gives up (each poll is a memory round trip: seconds)
-constexpr int kFcSlices = 32;         // 32 input channels per fully connected task
+constexpr int kFcSlices = 8;          // slices of the fully connected layer's input channels, one per task
 constexpr int kFcColBlock = 128;      // classes per fully connected task
+constexpr int kFlagStride = 32;       // words between flags: one flag per 128-byte line.  Flags of neighbouring tasks
+                                      // are set by different CUs at almost the same time; packed into one line their
+                                      // write-throughs queue up behind each other (measured: 1.5 us until the last of
+                                      // 16 is visible, against 0.6 us with a line each)
 constexpr int kSc1 = 16;              // cache-policy operand of the buffer builtins: device-coherent access
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -67,7 +72,7 @@ struct ChainParams {
   unsigned in0_bytes;
   float* act;           // chain workspace: every step's output
   unsigned act_bytes;
-  int* flags;           // [0] failure word, then one word per task
+  int* flags;           // word 0: failure; task t's flag is word kFlagStride * t (t >= 1)
   const float *fc_w, *fc_b;
   unsigned partial_off; // float offset in act: [kFcSlices][classes] partial logits
   float *probs, *logits;
@@ -105,20 +110,24 @@ __device__ __forceinline__ void flag_store(int* f, int v) {
 }
 
 // Wait until the producer tasks (rows r_lo..r_hi) x (columns c_lo..c_hi) of a step with `tiles_n` column tiles
-// have set their flags.  One flag per thread; ends with a workgroup barrier.
+// have set their flags.  Only the helper wavefront polls, one flag per lane: loads return in order within a
+// wavefront, so a poll issued by a compute wavefront would wait behind that wavefront's filter loads.  Ends with a
+// workgroup barrier.
 __device__ __forceinline__ void wait_tiles(int* flags, int spin_limit, int first, int tiles_n, int r_lo, int r_hi,
                                            int c_lo, int c_hi) {
-  const int nc = c_hi - c_lo + 1, n = (r_hi - r_lo + 1) * nc;
-  for (int i = threadIdx.x; i < n; i += kChainThreads) {
-    const int* f = flags + first + (r_lo + i / nc) * tiles_n + c_lo + i % nc;
-    int spin = 0;
-    while (flag_load(f) == 0) {
-      if (++spin > spin_limit) {
-        flag_store(flags, 1);
-        break;
+  if (threadIdx.x >= kComputeThreads) {
+    const int nc = c_hi - c_lo + 1, n = (r_hi - r_lo + 1) * nc;
+    for (int i = threadIdx.x - kComputeThreads; i < n; i += 64) {
+      const int* f = flags + (size_t)(first + (r_lo + i / nc) * tiles_n + c_lo + i % nc) * kFlagStride;
+      int spin = 0;
+      while (flag_load(f) == 0) {
+        if (++spin > spin_limit) {
+          flag_store(flags, 1);
+          break;
+        }
+        if ((spin & 255) == 0 && flag_load(flags) != 0) break;
+        __builtin_amdgcn_s_sleep(1);
       }
-      if ((spin & 255) == 0 && flag_load(flags) != 0) break;
-      __builtin_amdgcn_s_sleep(1);
     }
   }
   __syncthreads();
@@ -128,21 +137,57 @@ __device__ __forceinline__ void wait_tiles(int* flags, int spin_limit, int first
 __device__ __forceinline__ void publish(int* flags, int index) {
   __builtin_amdgcn_s_waitcnt(0);  // vmcnt = expcnt = lgkmcnt = 0
   __syncthreads();
-  if (threadIdx.x == 0) flag_store(flags + index, 1);
+  if (threadIdx.x == kComputeThreads) flag_store(flags + (size_t)index * kFlagStride, 1);
 }
 
-// ---- depthwise 3x3 + bias + ReLU6: 16 output pixels x 32 channels, one output per thread ----
-__device__ __forceinline__ void dw_task(const ChainParams& P, const ChainBlock& B, int bi, int task,
+// Tasks of a step with tiles_m x tiles_c tiles are dealt to workgroups so that a row tile's tasks fall on
+// workgroups with the same id modulo 8, i.e. (workgroups are dealt to the 8 XCDs round robin) on one XCD -- or, with
+// 1, 2 or 4 row tiles, on 8, 4 or 2 XCDs, so that no XCD stays idle: the exchange between a row tile's depthwise
+// tasks and its pointwise tiles then stays inside an XCD's L2, which answers device-coherent accesses to lines it
+// owns faster than the memory side does (measured: 1.3 against 1.8 us per dependent step).  Correctness does not
+// depend on where workgroups run.  Workgroup w takes the virtual tasks vt = w, w + 256, ...; vt % 8 is the XCD.
+struct TaskMap {
+  int tiles_m, tiles_c, mode, f, count;
+};
+__device__ __forceinline__ TaskMap make_task_map(int tiles_m, int tiles_c) {
+  TaskMap m;
+  m.tiles_m = tiles_m;
+  m.tiles_c = tiles_c;
+  if (tiles_m >= 8) {
+    m.mode = 0, m.f = 1, m.count = 8 * ((tiles_m + 7) / 8) * tiles_c;  // vt = r % 8 + 8 ((r / 8) tiles_c + c)
+  } else if (tiles_m == 1 || tiles_m == 2 || tiles_m == 4) {
+    m.mode = 1, m.f = 8 / tiles_m, m.count = 8 * ((tiles_c + m.f - 1) / m.f);  // XCD = r f + c % f, slot = c / f
+  } else {
+    m.mode = 2, m.f = 1, m.count = tiles_m * tiles_c;  // plain order
+  }
+  return m;
+}
+__device__ __forceinline__ bool task_of(const TaskMap& m, int vt, int* r, int* c) {
+  if (m.mode == 0) {
+    *r = vt % 8 + 8 * ((vt / 8) / m.tiles_c);
+    *c = (vt / 8) % m.tiles_c;
+  } else if (m.mode == 1) {
+    *r = (vt % 8) / m.f;
+    *c = (vt / 8) * m.f + (vt % 8) % m.f;
+  } else {
+    *r = vt / m.tiles_c;
+    *c = vt % m.tiles_c;
+  }
+  return *r < m.tiles_m && *c < m.tiles_c;
+}
+
+// ---- depthwise 3x3 + bias + ReLU6: 16 output pixels x 32 channels, one output per compute thread ----
+__device__ __forceinline__ void dw_task(const ChainParams& P, const ChainBlock& B, int r, int c,
                                         __amdgpu_buffer_rsrc_t in, __amdgpu_buffer_rsrc_t act) {
   const int tiles_c = B.cin / 32;
-  const int r = task / tiles_c, c = task % tiles_c;
   const int m_out = B.out_hw * B.out_hw;
-  const int t = threadIdx.x, px = t / 32, ch = 32 * c + t % 32;
+  const int t = threadIdx.x, px = (t / 32) % 16, ch = 32 * c + t % 32;
+  const bool compute = t < kComputeThreads;
   // filter taps and bias first: they do not depend on anybody
   float w[9];
 #pragma unroll
-  for (int k = 0; k < 9; ++k) w[k] = B.dw_w[k * B.cin + ch];
-  const float bias = B.dw_b[ch];
+  for (int k = 0; k < 9; ++k) w[k] = compute ? B.dw_w[k * B.cin + ch] : 0.f;
+  const float bias = compute ? B.dw_b[ch] : 0.f;
 
   if (B.flag_in >= 0) {
     // input rows under the 16 output pixels, as whole rows of the input map -> producer row tiles of 16 pixels
@@ -153,60 +198,64 @@ __device__ __forceinline__ void dw_task(const ChainParams& P, const ChainBlock& 
     wait_tiles(P.flags, P.spin_limit, B.flag_in, B.cin / w16, iy_lo * B.in_hw / 16, (iy_hi * B.in_hw + B.in_hw - 1) / 16,
                32 * c / w16, (32 * c + 31) / w16);
   }
-  const int p = 16 * r + px;
-  const bool live = p < m_out;
-  const int oy = p / B.out_hw, ox = p % B.out_hw;
-  const int iy0 = oy * B.stride - B.pad, ix0 = ox * B.stride - B.pad;
-  float v[9];
-  bool ok[9];
+  if (compute) {
+    const int p = 16 * r + px;
+    const bool live = p < m_out;
+    const int oy = p / B.out_hw, ox = p % B.out_hw;
+    const int iy0 = oy * B.stride - B.pad, ix0 = ox * B.stride - B.pad;
+    float v[9];
+    bool ok[9];
 #pragma unroll
-  for (int kh = 0; kh < 3; ++kh)
+    for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
-    for (int kw = 0; kw < 3; ++kw) {
-      const int iy = iy0 + kh, ix = ix0 + kw;
-      ok[kh * 3 + kw] = live && iy >= 0 && iy < B.in_hw && ix >= 0 && ix < B.in_hw;
-      // a tap outside the image reads past the end of the buffer: the hardware returns 0, no branch
-      const unsigned off = ok[kh * 3 + kw] ? (B.in_off + (unsigned)((iy * B.in_hw + ix) * B.cin + ch)) * 4u : 0x80000000u;
-      v[kh * 3 + kw] = ld_f32(in, off);
-    }
-  float acc = bias;
+      for (int kw = 0; kw < 3; ++kw) {
+        const int iy = iy0 + kh, ix = ix0 + kw;
+        ok[kh * 3 + kw] = live && iy >= 0 && iy < B.in_hw && ix >= 0 && ix < B.in_hw;
+        // a tap outside the image reads past the end of the buffer: the hardware returns 0, no branch
+        const unsigned off =
+            ok[kh * 3 + kw] ? (B.in_off + (unsigned)((iy * B.in_hw + ix) * B.cin + ch)) * 4u : 0x80000000u;
+        v[kh * 3 + kw] = ld_f32(in, off);
+      }
+    float acc = bias;
 #pragma unroll
-  for (int k = 0; k < 9; ++k) acc = ok[k] ? fmaf(v[k], w[k], acc) : acc;
-  ActClamp clamp;
-  clamp.on = true;
-  clamp.hi = 6.0f;
-  if (live) st_f32(act, (B.mid_off + (unsigned)(p * B.cin + ch)) * 4u, apply_act(acc, clamp));
-  (void)bi;
-  publish(P.flags, B.flag_mid + task);
+    for (int k = 0; k < 9; ++k) acc = ok[k] ? fmaf(v[k], w[k], acc) : acc;
+    ActClamp clamp;
+    clamp.on = true;
+    clamp.hi = 6.0f;
+    if (live) st_f32(act, (B.mid_off + (unsigned)(p * B.cin + ch)) * 4u, apply_act(acc, clamp));
+  }
+  publish(P.flags, B.flag_mid + r * tiles_c + c);
 }
 
-// ---- pointwise 1x1 + bias + ReLU6: 16 x (16 TN) tile, K = 8 x CHUNK split over the wavefronts ----
+// ---- pointwise 1x1 + bias + ReLU6: 16 x (16 TN) tile, K = 8 x CHUNK split over the compute wavefronts ----
 template <int CHUNK, int TN>
-__device__ __forceinline__ void pw_task(const ChainParams& P, const ChainBlock& B, int task, __amdgpu_buffer_rsrc_t act,
-                                        float* red) {
+__device__ __forceinline__ void pw_task(const ChainParams& P, const ChainBlock& B, int tile_m, int tile_n,
+                                        __amdgpu_buffer_rsrc_t act, float* red) {
   constexpr int G = CHUNK / 16;
   const int K = B.cin, N = B.cout, M = B.out_hw * B.out_hw;
   const int tiles_n = N / (16 * TN);
-  const int tile_m = task / tiles_n, tile_n = task % tiles_n;
-  const int tid = threadIdx.x, wk = tid / 64, lane = tid % 64, li = lane % 16, q = lane / 16;
+  const int tid = threadIdx.x, wk = (tid / 64) % kComputeWaves, lane = tid % 64, li = lane % 16, q = lane / 16;
+  const bool compute = tid < kComputeThreads;
   const int m0 = 16 * tile_m, n0 = 16 * TN * tile_n;
 
   // filter columns and bias before the wait (ordinary cached loads)
   const float* bp = B.pw_w + (size_t)(wk * CHUNK + 4 * q) * N + n0 + TN * li;
   float b[G][4][TN];
+  if (compute) {
 #pragma unroll
-  for (int g = 0; g < G; ++g)
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const float* p = bp + (size_t)(16 * g + s) * N;
-      if constexpr (TN == 2) {
-        const float2 t2 = *reinterpret_cast<const float2*>(p);
-        b[g][s][0] = t2.x;
-        b[g][s][1] = t2.y;
-      } else {
-        b[g][s][0] = *p;
+      for (int s = 0; s < 4; ++s) {
+        const float* p = bp + (size_t)(16 * g + s) * N;
+        if constexpr (TN == 2) {
+          const float2 t2 = *reinterpret_cast<const float2*>(p);
+          b[g][s][0] = t2.x;
+          b[g][s][1] = t2.y;
+        } else {
+          b[g][s][0] = *p;
+        }
       }
-    }
+  }
   // epilogue thread e < 256 owns register v = e / 64 of lane l = e % 64: row 4 (l / 16) + v, columns TN (l % 16) ...
   const int ev = tid / 64, el = tid % 64;
   const int erow = m0 + 4 * (el / 16) + ev, ecol = n0 + TN * (el % 16);
@@ -217,32 +266,34 @@ __device__ __forceinline__ void pw_task(const ChainParams& P, const ChainBlock& 
   // the depthwise tasks of this row tile, all channel groups
   wait_tiles(P.flags, P.spin_limit, B.flag_mid, K / 32, tile_m, tile_m, 0, K / 32 - 1);
 
-  const int arow = min(m0 + li, M - 1);  // rows past M repeat the last one (they feed outputs that are not stored)
-  const unsigned a_off = (B.mid_off + (unsigned)(arow * K + wk * CHUNK + 4 * q)) * 4u;
-  float4 a[G];
+  if (compute) {
+    const int arow = min(m0 + li, M - 1);  // rows past M repeat the last one (they feed outputs that are not stored)
+    const unsigned a_off = (B.mid_off + (unsigned)(arow * K + wk * CHUNK + 4 * q)) * 4u;
+    float4 a[G];
 #pragma unroll
-  for (int g = 0; g < G; ++g) a[g] = ld_f32x4(act, a_off + 64u * g);
+    for (int g = 0; g < G; ++g) a[g] = ld_f32x4(act, a_off + 64u * g);
 
-  floatx4 acc[2][TN];
+    floatx4 acc[2][TN];
 #pragma unroll
-  for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[c][j][v] = 0.f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float av[4] = {a[g].x, a[g].y, a[g].z, a[g].w};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[s & 1][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s], b[g][s][j], acc[s & 1][j], 0, 0, 0);
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) acc[c][j][v] = 0.f;
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const float av[4] = {a[g].x, a[g].y, a[g].z, a[g].w};
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[s & 1][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s], b[g][s][j], acc[s & 1][j], 0, 0, 0);
+      for (int v = 0; v < 4; ++v) red[((wk * TN + j) * 4 + v) * 64 + lane] = acc[0][j][v] + acc[1][j][v];
   }
-#pragma unroll
-  for (int j = 0; j < TN; ++j)
-#pragma unroll
-    for (int v = 0; v < 4; ++v) red[((wk * TN + j) * 4 + v) * 64 + lane] = acc[0][j][v] + acc[1][j][v];
   __syncthreads();
   if (tid < 256 && erow < M) {
     ActClamp clamp;
@@ -253,14 +304,14 @@ __device__ __forceinline__ void pw_task(const ChainParams& P, const ChainBlock& 
     for (int j = 0; j < TN; ++j) {
       float sum = ebias[j];
 #pragma unroll
-      for (int w = 0; w < kChainWaves; ++w) sum += red[((w * TN + j) * 4 + ev) * 64 + el];
+      for (int w = 0; w < kComputeWaves; ++w) sum += red[((w * TN + j) * 4 + ev) * 64 + el];
       o[j] = apply_act(sum, clamp);
     }
     const unsigned off = (B.out_off + (unsigned)(erow * N + ecol)) * 4u;
     if constexpr (TN == 2) st_f32x2(act, off, o[0], o[1]);
     else st_f32(act, off, o[0]);
   }
-  publish(P.flags, B.flag_out + task);  // its barrier also protects `red` from the next task's writes
+  publish(P.flags, B.flag_out + tile_m * tiles_n + tile_n);  // its barrier also protects `red` from the next task's writes
 }
 
 __device__ __forceinline__ float block_sum_or_max(float v, bool is_max, float* scratch) {
@@ -274,28 +325,32 @@ __device__ __forceinline__ float block_sum_or_max(float v, bool is_max, float* s
   __syncthreads();
   float r = scratch[0];
 #pragma unroll
-  for (int i = 1; i < kChainWaves; ++i) r = is_max ? fmaxf(r, scratch[i]) : r + scratch[i];
+  for (int i = 1; i < kComputeWaves; ++i) r = is_max ? fmaxf(r, scratch[i]) : r + scratch[i];
   return r;
 }
 
 __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const ChainParams P) {
-  __shared__ float red[kChainWaves * 2 * 4 * 64];  // 16 KB: split-K partial tiles; reused by the tail
+  __shared__ float red[kComputeWaves * 2 * 4 * 64];  // 16 KB: split-K partial tiles; reused by the tail
   const int wg = blockIdx.x, tid = threadIdx.x;
+  const bool compute = tid < kComputeThreads;
   const __amdgpu_buffer_rsrc_t in0 = make_rsrc(P.in0, P.in0_bytes);
   const __amdgpu_buffer_rsrc_t act = make_rsrc(P.act, P.act_bytes);
 
-  // this workgroup's slice of the fully connected weights (32 input channels x 128 classes, 8 values per
-  // thread), fetched now: nothing in the kernel depends on it for the next 40 us
+  // this workgroup's slice of the fully connected weights (128 input channels x 128 classes, 32 values per
+  // compute thread), fetched now: nothing in the kernel depends on it for the next 50 us
   const int fc_tasks_c = (P.classes + kFcColBlock - 1) / kFcColBlock;
   const int fc_tasks = kFcSlices * fc_tasks_c;
-  float4 fw[2] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};
-  const int fks = wg / fc_tasks_c, fcb = wg % fc_tasks_c;   // task wg (tasks beyond the grid are fetched later)
-  const int fcol = kFcColBlock * fcb + 4 * (tid % 32), fk = (P.feat / kFcSlices) * fks + 2 * (tid / 32);
-  const bool fvec = P.classes % 4 == 0;
-  auto load_fc = [&](int ks_k, int col, float4 (&dst)[2]) {
+  const int kper = P.feat / kFcSlices;  // 128 input channels per task, 8 per thread
+  float4 fw[8];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const float* p = P.fc_w + (size_t)(ks_k + i) * P.classes + col;
+  for (int i = 0; i < 8; ++i) fw[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  const bool fvec = P.classes % 4 == 0;
+  auto load_fc = [&](int task, float4 (&dst)[8]) {
+    const int ks = task / fc_tasks_c, cb = task % fc_tasks_c;
+    const int col = kFcColBlock * cb + 4 * (tid % 32), k0 = kper * ks + 8 * ((tid / 32) % 16);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float* p = P.fc_w + (size_t)(k0 + i) * P.classes + col;
       if (fvec && col + 3 < P.classes) {
         dst[i] = *reinterpret_cast<const float4*>(p);
       } else {
@@ -306,64 +361,67 @@ __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const Ch
       }
     }
   };
-  if (wg < fc_tasks) load_fc(fk, fcol, fw);
-
+  if (wg < fc_tasks && compute) load_fc(wg, fw);
   for (int bi = 0; bi < kChainBlocks; ++bi) {
     const ChainBlock& B = P.blk[bi];
-    const int dw_tasks = ((B.out_hw * B.out_hw + 15) / 16) * (B.cin / 32);
-    for (int task = wg; task < dw_tasks; task += kChainGrid) dw_task(P, B, bi, task, bi == 0 ? in0 : act, act);
-    const int pw_tasks = ((B.out_hw * B.out_hw + 15) / 16) * (B.cout / (16 * B.tn));
-    for (int task = wg; task < pw_tasks; task += kChainGrid) {
-      if (B.cin == 256 && B.tn == 2) pw_task<32, 2>(P, B, task, act, red);
-      else if (B.cin == 256) pw_task<32, 1>(P, B, task, act, red);
-      else if (B.cin == 512 && B.tn == 2) pw_task<64, 2>(P, B, task, act, red);
-      else if (B.cin == 512) pw_task<64, 1>(P, B, task, act, red);
-      else pw_task<128, 1>(P, B, task, act, red);
+    const int tiles_m = (B.out_hw * B.out_hw + 15) / 16;
+    const TaskMap dw_map = make_task_map(tiles_m, B.cin / 32), pw_map = make_task_map(tiles_m, B.cout / (16 * B.tn));
+    for (int vt = wg; vt < dw_map.count; vt += kChainGrid) {
+      int r, c;
+      if (task_of(dw_map, vt, &r, &c)) dw_task(P, B, r, c, bi == 0 ? in0 : act, act);
+    }
+    for (int vt = wg; vt < pw_map.count; vt += kChainGrid) {
+      int r, c;
+      if (!task_of(pw_map, vt, &r, &c)) continue;
+      if (B.cin == 256 && B.tn == 2) pw_task<32, 2>(P, B, r, c, act, red);
+      else if (B.cin == 256) pw_task<32, 1>(P, B, r, c, act, red);
+      else if (B.cin == 512 && B.tn == 2) pw_task<64, 2>(P, B, r, c, act, red);
+      else if (B.cin == 512) pw_task<64, 1>(P, B, r, c, act, red);
+      else pw_task<128, 1>(P, B, r, c, act, red);
     }
   }
 
-  // ---- average pool + fully connected: task (ks, cb) = 32 input channels x 128 classes ----
+  // ---- average pool + fully connected: task (ks, cb) = 128 input channels x 128 classes ----
   const ChainBlock& L = P.blk[kChainBlocks - 1];
   const int hw2 = P.last_hw * P.last_hw;
-  const int kper = P.feat / kFcSlices;  // 32
   for (int task = wg; task < fc_tasks; task += kChainGrid) {
     const int ks = task / fc_tasks_c, cb = task % fc_tasks_c;
-    if (task != wg) load_fc(kper * ks + 2 * (tid / 32), kFcColBlock * cb + 4 * (tid % 32), fw);
-    // the last pointwise layer's tiles holding channels 32 ks .. 32 ks + 31, every pixel row tile
+    if (task != wg && compute) load_fc(task, fw);
+    // the last pointwise layer's tiles holding channels kper ks .. kper ks + kper - 1, every pixel row tile
     const int w16 = 16 * L.tn;
-    wait_tiles(P.flags, P.spin_limit, L.flag_out, L.cout / w16, 0, (hw2 + 15) / 16 - 1, kper * ks / w16, (kper * ks + kper - 1) / w16);
-    float* pooled = red;             // [32]
-    float* psum = red + 64;          // [16][32]
-    float* fsum = red + 64 + 512;    // [16][128]
-    {
-      const int chn = tid % 32, pg = tid / 32;  // 16 pixel groups
-      float s = 0.f;
-      float x[4];
+    wait_tiles(P.flags, P.spin_limit, L.flag_out, L.cout / w16, 0, (hw2 + 15) / 16 - 1, kper * ks / w16,
+               (kper * ks + kper - 1) / w16);
+    float* pooled = red;             // [128]
+    float* psum = red + 128;         // [4][128]
+    float* fsum = red + 128 + 512;   // [16][128]
+    if (compute) {
+      // thread (pixel group pg of 4, channel chn of 128) sums pixels pg, pg + 4, ... (at most 64 pixels)
+      const int chn = tid % 128, pg = tid / 128;
+      float x[16];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int p = pg + 16 * i;
+      for (int i = 0; i < 16; ++i) {
+        const int p = pg + 4 * i;
         x[i] = ld_f32(act, p < hw2 ? (L.out_off + (unsigned)(p * P.feat + kper * ks + chn)) * 4u : 0x80000000u);
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) s += x[i];
-      psum[pg * 32 + chn] = s;
-    }
-    __syncthreads();
-    if (tid < 32) {
       float s = 0.f;
 #pragma unroll
-      for (int g = 0; g < 16; ++g) s += psum[g * 32 + tid];
-      pooled[tid] = s / (float)hw2;
+      for (int i = 0; i < 16; ++i) s += x[i];
+      psum[pg * 128 + chn] = s;
     }
     __syncthreads();
-    {
+    if (tid < 128) pooled[tid] = (psum[tid] + psum[128 + tid] + psum[256 + tid] + psum[384 + tid]) / (float)hw2;
+    __syncthreads();
+    if (compute) {
       const int kq = tid / 32, c4 = tid % 32;
-      const float p0 = pooled[2 * kq], p1 = pooled[2 * kq + 1];
-      float4 s;
-      s.x = fmaf(p1, fw[1].x, p0 * fw[0].x);
-      s.y = fmaf(p1, fw[1].y, p0 * fw[0].y);
-      s.z = fmaf(p1, fw[1].z, p0 * fw[0].z);
-      s.w = fmaf(p1, fw[1].w, p0 * fw[0].w);
+      float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float pv = pooled[8 * kq + i];
+        s.x = fmaf(pv, fw[i].x, s.x);
+        s.y = fmaf(pv, fw[i].y, s.y);
+        s.z = fmaf(pv, fw[i].z, s.z);
+        s.w = fmaf(pv, fw[i].w, s.w);
+      }
       *reinterpret_cast<float4*>(fsum + kq * 128 + 4 * c4) = s;
     }
     __syncthreads();
@@ -377,32 +435,33 @@ __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const Ch
     publish(P.flags, P.flag_fc + task);
   }
 
-  // ---- bias + softmax: one task, two classes per thread ----
+  // ---- bias + softmax: one task, two classes per compute thread ----
   if (wg == 0) {
     wait_tiles(P.flags, P.spin_limit, P.flag_fc, fc_tasks_c, 0, kFcSlices - 1, 0, fc_tasks_c - 1);
     float l[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int j = tid + kChainThreads * h;
+      const int j = tid + kComputeThreads * h;
+      const bool in = compute && j < P.classes;
       float part[kFcSlices];
 #pragma unroll
       for (int s = 0; s < kFcSlices; ++s)
-        part[s] = ld_f32(act, j < P.classes ? (P.partial_off + (unsigned)(s * P.classes + j)) * 4u : 0x80000000u);
-      float v = j < P.classes ? P.fc_b[j] : 0.f;
+        part[s] = ld_f32(act, in ? (P.partial_off + (unsigned)(s * P.classes + j)) * 4u : 0x80000000u);
+      float v = in ? P.fc_b[j] : 0.f;
 #pragma unroll
       for (int s = 0; s < kFcSlices; ++s) v += part[s];
-      l[h] = j < P.classes ? v : -INFINITY;
+      l[h] = in ? v : -INFINITY;
     }
     const bool failed = flag_load(P.flags) != 0;
     const float mx = block_sum_or_max(fmaxf(l[0], l[1]), true, red);
     float e[2];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) e[h] = tid + kChainThreads * h < P.classes ? __expf(l[h] - mx) : 0.f;
-    const float sum = block_sum_or_max(e[0] + e[1], false, red);
+    for (int h = 0; h < 2; ++h) e[h] = (compute && tid + kComputeThreads * h < P.classes) ? __expf(l[h] - mx) : 0.f;
+    const float sum = block_sum_or_max(e[0] + e[1], false, red + 16);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int j = tid + kChainThreads * h;
-      if (j < P.classes) {
+      const int j = tid + kComputeThreads * h;
+      if (compute && j < P.classes) {
         const float nan = __uint_as_float(0x7fc00000u);
         if (P.logits) P.logits[j] = failed ? nan : l[h];
         P.probs[j] = failed ? nan : e[h] / sum;
@@ -492,15 +551,17 @@ ChainPlanHost chain_layout(int in_hw, int classes, ChainParams* P) {
 size_t chain_workspace_bytes(int image_size, int classes) {
   const int half = (image_size + 1) / 2, quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
   const ChainPlanHost h = chain_layout(eighth, classes, nullptr);
-  const size_t flag_bytes = ((size_t)h.flags * sizeof(int) + 255) / 256 * 256;
+  const size_t flag_bytes = (size_t)h.flags * kFlagStride * sizeof(int);
   return flag_bytes + (h.act_floats * sizeof(float) + 255) / 256 * 256;
 }
 
-// Number of flag words at the start of the chain workspace; they must be zero when the chain kernel starts.
+// The flags at the start of the chain workspace: `count` words, chain_flag_stride() words apart, that must be zero
+// when the chain kernel starts.
 int chain_flag_words(int image_size, int classes) {
   const int half = (image_size + 1) / 2, quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
   return chain_layout(eighth, classes, nullptr).flags;
 }
+int chain_flag_stride() { return kFlagStride; }
 
 int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, float* probs,
                  float* logits, int classes, hipStream_t stream) {
@@ -513,7 +574,7 @@ int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w,
     P.blk[bi].pw_w = w->pw_w[net];
     P.blk[bi].pw_b = w->pw_b[net];
   }
-  const size_t flag_bytes = ((size_t)h.flags * sizeof(int) + 255) / 256 * 256;
+  const size_t flag_bytes = (size_t)h.flags * kFlagStride * sizeof(int);
   P.in0 = in0;
   P.in0_bytes = (unsigned)((size_t)in_hw * in_hw * kNetChannels[kFirstChainBlock - 1] * sizeof(float));
   P.flags = static_cast<int*>(chain_ws);

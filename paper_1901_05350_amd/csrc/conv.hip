@@ -141,10 +141,11 @@ __global__ __launch_bounds__(256) void conv2d_stem_mfma_kernel(const float* __re
                                                                const float* __restrict__ bias, float* __restrict__ y,
                                                                int N, int H, int W, int OH, int OW, int sh, int sw, int pt,
                                                                int pl, int act, int* __restrict__ zero_words,
-                                                               int zero_count) {
+                                                               int zero_count, int zero_stride) {
   constexpr int NB = CO / 16;
   // optional: clear a small array of words for a later kernel of the same forward pass (its task flags)
-  for (int i = (int)(blockIdx.x * 256 + threadIdx.x); i < zero_count; i += (int)gridDim.x * 256) zero_words[i] = 0;
+  for (int i = (int)(blockIdx.x * 256 + threadIdx.x); i < zero_count; i += (int)gridDim.x * 256)
+    zero_words[(size_t)i * zero_stride] = 0;
   static_assert(CO % 32 == 0, "column blocks are stored in pairs");
   const int lane = threadIdx.x % 64, li = lane % 16, q = lane / 16;
   const int segs = (OW + 15) / 16;
@@ -246,7 +247,7 @@ bool conv2d_stem_supported(int ci, int fh, int fw, int co, int sh, int sw) {
 
 int launch_conv2d_stem(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int co,
                        int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream, int* zero_words,
-                       int zero_count) {
+                       int zero_count, int zero_stride) {
   // 32 filters, 16-byte aligned y and bias: the matrix-core form
   if (co == 32 && reinterpret_cast<uintptr_t>(y) % 16 == 0 && reinterpret_cast<uintptr_t>(bias) % 16 == 0) {
     const long long slabs = (long long)n * oh * ((ow + 15) / 16);
@@ -254,7 +255,7 @@ int launch_conv2d_stem(const float* x, const float* w, const float* bias, float*
     long long blocks = (slabs + 3) / 4;
     if (blocks > 256 * 8) blocks = 256 * 8;  // 8 workgroups of 4 wavefronts per CU, then the slab loop
     hipLaunchKernelGGL(conv2d_stem_mfma_kernel<32>, dim3((unsigned)blocks), dim3(256), 0, stream, x, w, bias, y, n, h, wd,
-                       oh, ow, sh, sw, pt, pl, act, zero_words, zero_count);
+                       oh, ow, sh, sw, pt, pl, act, zero_words, zero_count, zero_stride);
     return check_launch();
   }
   if (zero_count > 0) return TFX_ERR_UNSUPPORTED;  // only the matrix-core form clears words

@@ -102,19 +102,20 @@ int launch_conv2d_direct(const float* x, const float* w, const float* bias, floa
 
 // 3x3 stride-2 convolution with 3 input channels (the MobileNet stem).
 bool conv2d_stem_supported(int ci, int fh, int fw, int co, int sh, int sw);
-// zero_words / zero_count: optional array of 32-bit words that the kernel also clears (matrix-core form only:
-// 32 filters, 16-byte aligned y and bias).
+// zero_words / zero_count / zero_stride: optional: the kernel also clears zero_count 32-bit words, zero_stride
+// words apart (matrix-core form only: 32 filters, 16-byte aligned y and bias).
 int launch_conv2d_stem(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int co,
                        int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream,
-                       int* zero_words = nullptr, int zero_count = 0);
+                       int* zero_words = nullptr, int zero_count = 0, int zero_stride = 1);
 
 // The 28 x 28 ... 7 x 7 blocks, pool, fully connected layer and softmax of the batch-1, full-width network as one
-// persistent kernel (chain.hip).  chain_ws: chain_workspace_bytes() bytes, 256-byte aligned, whose first
-// chain_flag_words() 32-bit words are zero when the kernel starts.  in0: the output of block 4 (in_hw x in_hw x 256).
+// persistent kernel (chain.hip).  chain_ws: chain_workspace_bytes() bytes, 256-byte aligned; its first
+// chain_flag_words() words at a spacing of chain_flag_stride() words are zero when the kernel starts.  in0: the output of block 4 (in_hw x in_hw x 256).
 bool chain_supported(int image_size, int width_quarters, int classes, long long batch);
 bool chain_resident();
 size_t chain_workspace_bytes(int image_size, int classes);
 int chain_flag_words(int image_size, int classes);
+int chain_flag_stride();
 int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, float* probs,
                  float* logits, int classes, hipStream_t stream);
 
