@@ -12,8 +12,12 @@
  *     filters are HWIO [fh,fw,inC,outC], depthwise filters are [fh,fw,inC,mult].
  *   - Every data pointer is a DEVICE pointer.  Shape arrays and the weights
  *     struct are HOST memory and are read before the call returns.
- *   - Ownership: the caller owns every buffer.  The library allocates nothing,
- *     frees nothing and keeps no state between calls.  Inputs are never written
+ *   - Ownership: the caller owns every buffer.  The library allocates nothing
+ *     and frees nothing, and keeps no tensor state between calls.  What it does
+ *     keep, per process and per device, are launch attributes it has looked up
+ *     once (which kernels were allowed their dynamic LDS size, how many
+ *     workgroups of a kernel are resident at once); these never change a
+ *     result.  Inputs are never written
  *     (ops are functional, Section 3.7); the output must not overlap any input
  *     (overlap is not detected; the result is then undefined).
  *   - Asynchrony: a call validates its arguments on the host, enqueues its
@@ -21,7 +25,9 @@
  *     stream) and returns without synchronising, like the enqueue-and-return
  *     ops of Section 3.6 / 4.1.  The caller synchronises before reading.
  *     The device that `stream` belongs to must be the calling thread's current
- *     device.  Entry points may be called from several host threads.
+ *     device.  Entry points may be called from several host threads at once
+ *     (the caches above are atomics; calls that share an output or workspace
+ *     buffer must be ordered by the caller).
  *   - Errors: the return value is a tfx_status.  Validation happens before any
  *     HIP call: a NULL pointer gives TFX_ERR_NULL; non-positive or mismatching
  *     dimensions, or a VALID convolution whose filter exceeds the image, give
@@ -98,7 +104,10 @@ int tfx_matmul(const float* a, const int64_t a_shape[2], const float* b, const i
                int transpose_a, int transpose_b, float* c, void* stream);
 
 /* batchMatMul: tfx_matmul independently for each leading index.  a_shape and
- * b_shape are [B,rows,cols] with equal B (no broadcasting); c is [B,M,N]. */
+ * b_shape are [B,rows,cols] with equal B (no broadcasting); c is [B,M,N].
+ * The paper defines only the rank-2 product (Listing 2); the batched form follows
+ * the library its API is modelled on (Section 3.1): the same product per leading
+ * index. */
 int tfx_batch_matmul(const float* a, const int64_t a_shape[3], const float* b, const int64_t b_shape[3],
                      int transpose_a, int transpose_b, float* c, void* stream);
 
@@ -106,12 +115,18 @@ int tfx_batch_matmul(const float* a, const int64_t a_shape[3], const float* b, c
  * fused epilogue:
  *   y[n,oh,ow,o] = act( sum_{kh,kw,c} X(n, oh*sh - pt + kh, ow*sw - pl + kw, c) * filter[kh,kw,c,o] + bias[o] )
  * X is 0 outside the image.  bias is a device pointer to [outC] or NULL (= 0).
- * y: device, shape from tfx_conv2d_out_shape. */
+ * y: device, shape from tfx_conv2d_out_shape.
+ * Epilogue, here and in every fused op below: the bias is added first, then the
+ * activation: relu(v) = max(v, 0), relu6(v) = min(max(v, 0), 6).  A NaN passes
+ * through either activation unchanged, -Inf gives 0, +Inf gives +Inf (relu) or 6
+ * (relu6). */
 int tfx_conv2d(const float* x, const int64_t x_shape[4], const float* filter, const int64_t f_shape[4],
                const float* bias, int stride_h, int stride_w, tfx_padding pad, tfx_activation act,
                float* y, void* stream);
 
-/* depthwiseConv2d with fused epilogue:
+/* depthwiseConv2d with fused epilogue.  The paper names the op but gives no
+ * definition; this is the convention of the library its API is modelled on
+ * (Section 3.1), in the index order of the conv2d sampler of Section 4.1:
  *   y[n,oh,ow,c*mult+q] = act( sum_{kh,kw} X(n, oh*sh - pt + kh, ow*sw - pl + kw, c) * filter[kh,kw,c,q]
  *                              + bias[c*mult+q] )
  * bias is a device pointer to [C*mult] or NULL.  y: device, shape from
@@ -182,6 +197,11 @@ size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch);
 /* Full forward pass: 3x3 stride-2 conv to 32 channels, 13 x (depthwise 3x3 ->
  * pointwise 1x1), bias + ReLU6 after each of the 27 convolutions, SAME padding
  * throughout, global average pool, fully connected 1024 -> 1000, softmax.
+ * At batch 1 (and full width) the blocks from the 1/8-size maps on, the pool, the
+ * fully connected layer and the softmax run as one kernel whose workgroups hand
+ * results to each other through flags in the workspace; every wait in it is
+ * bounded, and if one ever gives up (a workgroup that never got to run) every
+ * output of the call is NaN rather than a number computed from unfinished data.
  * input: device [batch,224,224,3]; workspace: device, >= the size above, 256-byte
  * aligned, contents undefined before and after; probs: device [batch,1000];
  * logits: device [batch,1000] or NULL.  All kernels are enqueued on `stream`. */

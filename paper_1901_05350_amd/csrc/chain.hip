@@ -26,10 +26,14 @@
 // cached loads.  No location written inside the kernel is written twice (every step has its own
 // output region), so a slow reader can never see a later value.
 //
-// Every wait is bounded: a poll loop gives up after kSpinLimit rounds (seconds), sets a failure word
-// that makes every other wait give up too, and the softmax task then writes NaN to every output, so a
-// workgroup that was never scheduled cannot hang the GPU and cannot yield plausible numbers.
+// Every wait is bounded: a poll loop gives up after kSpinLimit rounds (seconds), sets a failure word that makes
+// every other wait give up too, and the softmax task then writes NaN to every output, so a workgroup that was
+// never scheduled cannot hang the GPU and cannot yield plausible numbers.  The grid (256 workgroups, one per CU) is
+// only launched where all of it is resident at once (chain_resident), and two such kernels never run side by side
+// in one process: launch_chain orders them across streams (see there), because two half-resident grids would wait
+// for workgroups that the other one keeps from being scheduled.
 #include <cstdlib>
+#include <mutex>
 
 #include "tfx_internal.h"
 
@@ -333,6 +337,16 @@ __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const Ch
   __shared__ float red[kComputeWaves * 2 * 4 * 64];  // 16 KB: split-K partial tiles; reused by the tail
   const int wg = blockIdx.x, tid = threadIdx.x;
   const bool compute = tid < kComputeThreads;
+  {
+    // The block descriptors are read at every block change, on the critical path, and the first touch of a line of
+    // the kernel argument segment misses the scalar cache: touch every line now.
+    typedef __attribute__((address_space(4))) const int* KernargInts;
+    KernargInts karg = (KernargInts)__builtin_amdgcn_kernarg_segment_ptr();
+    int warm = 0;
+#pragma unroll
+    for (int i = 0; i < (int)sizeof(ChainParams) / 4; i += 16) warm += karg[i];
+    asm volatile("" ::"s"(warm));
+  }
   const __amdgpu_buffer_rsrc_t in0 = make_rsrc(P.in0, P.in0_bytes);
   const __amdgpu_buffer_rsrc_t act = make_rsrc(P.act, P.act_bytes);
 
@@ -563,6 +577,39 @@ int chain_flag_words(int image_size, int classes) {
 }
 int chain_flag_stride() { return kFlagStride; }
 
+namespace {
+// Chain kernels of one process are kept from overlapping on a device.  The last stream that launched one is
+// remembered per device; a launch on another stream first records an event behind everything queued on that
+// stream and makes the new stream wait for it.  Launches that stay on one stream (the usual case) pay nothing.
+// A stream that is being captured into a graph is left alone (an event of another stream cannot be recorded into
+// the capture): replays of such graphs on several streams at once are the caller's to order.
+struct ChainOrder {
+  std::mutex lock;
+  hipStream_t last[64];
+  hipEvent_t event[64];
+  bool launched[64], have_event[64];
+};
+ChainOrder g_order;
+
+void order_after_other_streams(int dev, hipStream_t stream) {
+  hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &capturing) != hipSuccess || capturing != hipStreamCaptureStatusNone) {
+    (void)hipGetLastError();
+    return;
+  }
+  if (g_order.launched[dev] && g_order.last[dev] != stream) {
+    if (!g_order.have_event[dev])
+      g_order.have_event[dev] = hipEventCreateWithFlags(&g_order.event[dev], hipEventDisableTiming) == hipSuccess;
+    // a stream that has been destroyed since is refused by the runtime: nothing of it can still be running
+    if (g_order.have_event[dev] && hipEventRecord(g_order.event[dev], g_order.last[dev]) == hipSuccess)
+      (void)hipStreamWaitEvent(stream, g_order.event[dev], 0);
+    (void)hipGetLastError();
+  }
+  g_order.last[dev] = stream;
+  g_order.launched[dev] = true;
+}
+}  // namespace
+
 int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, float* probs,
                  float* logits, int classes, hipStream_t stream) {
   ChainParams P{};
@@ -591,6 +638,10 @@ int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w,
     const long v = strtol(e, nullptr, 10);
     if (v >= 1 && v <= kSpinLimit) P.spin_limit = (int)v;
   }
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return TFX_ERR_LAUNCH;
+  std::lock_guard<std::mutex> guard(g_order.lock);
+  order_after_other_streams(dev, stream);
   hipLaunchKernelGGL(mobilenet_chain_kernel, dim3(kChainGrid), dim3(kChainThreads), 0, stream, P);
   return check_launch();
 }

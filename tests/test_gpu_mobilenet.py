@@ -230,3 +230,33 @@ def test_chained_kernel_bounded_waits_give_up_and_report_nan(net, monkeypatch):
     p, l = model.forward(image)
     assert_close(host(l), logits, "logits after a failed call")
     assert_close(host(p), probs, "probs after a failed call")
+
+
+def test_two_chained_kernels_on_two_streams_at_once(net):
+    """Two batch-1 forward passes issued from two host threads on two streams: the chained kernels would compete for
+    the CUs (neither grid fully resident, each waiting for workgroups the other keeps out), so the library orders
+    them across streams.  All 60 results must have the right bits."""
+    import threading
+    import torch
+    import paper_1901_05350_amd as tfx
+    data, probs, logits, acts = net
+    models = [tfx.MobileNetV1(data["weights"], batch=1) for _ in range(2)]
+    image = dev(data["image"])
+    p0 = host(models[0].forward(image)[0]).copy()
+    outs = [[torch.zeros_like(m.probs) for _ in range(30)] for m in models]
+    streams = [torch.cuda.Stream() for _ in models]
+    torch.cuda.synchronize()
+
+    def worker(i):
+        with torch.cuda.stream(streams[i]):
+            for o in outs[i]:
+                tfx.tfx_mobilenet_v1_forward(image, models[i].struct, models[i].workspace, o, None)
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for i in range(2):
+        for o in outs[i]:
+            assert np.array_equal(o.cpu().numpy(), p0)
