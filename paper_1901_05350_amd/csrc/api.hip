@@ -406,13 +406,27 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
       return launch_chain(buf[cur], (int)shape[1], weights, chain_ws, probs, logits, (int)variant->classes,
                           static_cast<hipStream_t>(stream));
     const int64_t fd[4] = {3, 3, shape[3], 1};
+    const int64_t cout = kChannels[b] * q / 4;
+    // batch 1, thin block: depthwise and pointwise layer in one launch (block.hip)
+    if (separable_block_supported(batch, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, kStrides[b], buf[cur],
+                                  weights->dw_w[b], weights->dw_b[b], weights->pw_w[b], weights->pw_b[b], buf[cur ^ 1])) {
+      conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
+      rc = launch_separable_block(buf[cur], weights->dw_w[b], weights->dw_b[b], weights->pw_w[b], weights->pw_b[b],
+                                  buf[cur ^ 1], (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, (int)g.out[1],
+                                  (int)g.out[2], kStrides[b], (int)g.pad[0], (int)g.pad[2], TFX_ACT_RELU6, TFX_ACT_RELU6,
+                                  static_cast<hipStream_t>(stream));
+      if (rc) return rc;
+      for (int i = 0; i < 3; ++i) shape[i] = g.out[i];
+      shape[3] = cout;
+      cur ^= 1;
+      continue;
+    }
     rc = tfx_depthwise_conv2d(buf[cur], shape, weights->dw_w[b], fd, weights->dw_b[b], kStrides[b], kStrides[b],
                               TFX_PAD_SAME, TFX_ACT_RELU6, buf[cur ^ 1], stream);
     if (rc) return rc;
     conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
     for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
     cur ^= 1;
-    const int64_t cout = kChannels[b] * q / 4;
     const int64_t fp[4] = {1, 1, shape[3], cout};
     rc = tfx_conv2d(buf[cur], shape, weights->pw_w[b], fp, weights->pw_b[b], 1, 1, TFX_PAD_SAME, TFX_ACT_RELU6,
                     buf[cur ^ 1], stream);

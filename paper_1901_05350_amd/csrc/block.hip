@@ -1,0 +1,256 @@
+// One depthwise-separable block (depthwise 3x3 + bias + clamp, then pointwise 1x1 + bias + clamp) of a single
+// image as ONE kernel, for the early, thin blocks of the MobileNet of Section 5 / Table 1 at batch 1, where the two
+// layers are bound by being two dependent launches and not by traffic or arithmetic.
+//
+// A workgroup owns a 4 x 4 patch of output pixels (= one 16-row matrix-core tile) and NS output channels.  It first
+// copies the input window under the patch (6 x 6 or 9 x 9 pixels, all channels, zeros outside the image) into LDS,
+// each element fetched once: the reads of the previous layer's output are the one long-latency step of the kernel
+// (measured: they cost 3 us per block when every lane fetched its own 9 taps, 4 x redundantly, against 0.7 us for
+// everything else), so they are issued first and kept few.  The input channels are split over WK wavefronts; lane
+// (li, q) of such a wavefront computes the depthwise output of pixel li for the 4 channels that are exactly its A
+// operand of the 16x16x4 fp32 MFMA steps it issues, so the depthwise result goes from the filter arithmetic into the
+// matrix cores without a second trip through LDS or memory; then a split-K reduction of the WK partial tiles
+// through LDS with bias + clamp and the store.  The pointwise filter columns and the depthwise filter a lane needs
+// are loaded straight into registers while the window is on its way.
+//
+// Workgroups that cover the same patch (the NS-wide slices of N) each recompute its depthwise output: 9 x 16 x C
+// multiply-adds, nothing beside the 16 x C x NS of the pointwise product.
+#include "tfx_internal.h"
+
+namespace tfx {
+namespace {
+
+constexpr int kXcds = 8;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct BlockArgs {
+  const float* x;     // [H, W, C]
+  const float* dw_w;  // [3, 3, C]
+  const float* dw_b;  // [C]
+  const float* pw_w;  // [C, N]
+  const float* pw_b;  // [N]
+  float* y;           // [OH, OW, N]
+  int H, W, OH, OW, pt, pl, N;
+  int tiles_x, slices, total;
+  int dw_act, pw_act;
+  unsigned x_bytes;
+};
+
+__device__ __forceinline__ float f4_at(const float4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+
+// C input channels, split over WK wavefronts; WN wavefronts side by side over the columns, CB column blocks of 16
+// each: NS = 16 CB WN columns per workgroup.
+template <int C, int WK, int WN, int CB, int S>
+__global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const BlockArgs a) {
+  constexpr int NT = 64 * WK * WN;
+  constexpr int G = C / (16 * WK);  // groups of 16 channels per wavefront
+  constexpr int NS = 16 * CB * WN;
+  constexpr int EI = (256 * WN + NT - 1) / NT;  // epilogue items per thread
+  static_assert(C % (16 * WK) == 0 && (CB == 2 || CB == 4), "tile shape");
+  constexpr int WH = 3 * S + 3;             // window edge: 3 (S) + 3 input pixels under 4 output pixels
+  constexpr int P = C + 4;                   // floats between window pixels in LDS
+  constexpr int WQ = WH * WH * (C / 4);      // float4 elements of the window
+  constexpr int LI = (WQ + NT - 1) / NT;     // of which a thread copies at most LI
+  constexpr int kRed = WK * WN * CB * 4 * 64, kWin = WH * WH * P;
+  // the window, and after the MFMAs the partial tiles [wk][wn][j][v][lane]
+  __shared__ __align__(16) float lds[kRed > kWin ? kRed : kWin];
+  float* const red = lds;
+
+  // workgroups are dealt to the XCDs round robin: give every XCD a contiguous run of patches (shared halos and
+  // the slices of one patch then meet in one L2)
+  const int bid = blockIdx.x;
+  const int q8 = a.total / kXcds, rem = a.total % kXcds;
+  const int xcd = bid % kXcds;
+  const int vid = xcd * q8 + (xcd < rem ? xcd : rem) + bid / kXcds;
+  const int slice = vid % a.slices, tile = vid / a.slices;
+  const int ty = tile / a.tiles_x, tx = tile % a.tiles_x;
+
+  const int tid = threadIdx.x, wave = tid / 64, wk = wave % WK, wn = wave / WK;
+  const int lane = tid % 64, li = lane % 16, q = lane / 16;
+  const int N = a.N;
+  const int n0 = slice * NS;
+
+  // the input window: element i = (pixel i / (C/4) of the window, channel quad i % (C/4))
+  const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x), 0, (int)a.x_bytes, 0x00020000);
+  u32x4 win[LI];
+  {
+    const int wy0 = 4 * ty * S - a.pt, wx0 = 4 * tx * S - a.pl;
+#pragma unroll
+    for (int i = 0; i < LI; ++i) {
+      const int e = tid + i * NT, p = e / (C / 4), cq = e % (C / 4);
+      const int iy = wy0 + p / WH, ix = wx0 + p % WH;
+      // outside the image (or past the window): past the end of the buffer, the hardware returns 0
+      const bool in = e < WQ && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+      const unsigned off = in ? (unsigned)((iy * a.W + ix) * C + 4 * cq) * 4u : 0x80000000u;
+      win[i] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)off, 0, 0);
+    }
+  }
+
+  // pointwise filter columns of this lane: rows wk 16 G + 16 g + 4 q + s, columns n0 + 16 CB wn + CB li ...
+  float b[G][4][CB];
+  {
+    const float* bp = a.pw_w + (size_t)(wk * 16 * G + 4 * q) * N + n0 + 16 * CB * wn + CB * li;
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const float* p = bp + (size_t)(16 * g + s) * N;
+        if constexpr (CB == 4) {
+          const float4 t = *reinterpret_cast<const float4*>(p);
+          b[g][s][0] = t.x, b[g][s][1] = t.y, b[g][s][2] = t.z, b[g][s][3] = t.w;
+        } else {
+          const float2 t = *reinterpret_cast<const float2*>(p);
+          b[g][s][0] = t.x, b[g][s][1] = t.y;
+        }
+      }
+  }
+  // epilogue item e < 256 WN: register v = (e / 64) % 4 of lane l = e % 64 of column group e / 256:
+  // row 4 (l / 16) + v of the patch, columns n0 + 16 CB (e / 256) + CB (l % 16) ...
+  float ebias[EI][CB];
+#pragma unroll
+  for (int i = 0; i < EI; ++i) {
+    const int e = tid + i * NT;
+    const float* p = a.pw_b + n0 + 16 * CB * (e / 256) + CB * (e % 16);
+#pragma unroll
+    for (int j = 0; j < CB; ++j) ebias[i][j] = e < 256 * WN ? p[j] : 0.f;
+  }
+
+  // depthwise filter and bias of the lane's channels c4 + 16 g ... + 3
+  const int c4 = wk * 16 * G + 4 * q;
+  float4 dwf[G][9], dwb[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    dwb[g] = *reinterpret_cast<const float4*>(a.dw_b + c4 + 16 * g);
+#pragma unroll
+    for (int t = 0; t < 9; ++t) dwf[g][t] = *reinterpret_cast<const float4*>(a.dw_w + t * C + c4 + 16 * g);
+  }
+
+  // window -> LDS
+#pragma unroll
+  for (int i = 0; i < LI; ++i) {
+    const int e = tid + i * NT;
+    if (e < WQ) *reinterpret_cast<u32x4*>(lds + (e / (C / 4)) * P + 4 * (e % (C / 4))) = win[i];
+  }
+  __syncthreads();
+
+  // depthwise output of pixel li for the lane's channels
+  const int oy = 4 * ty + li / 4, ox = 4 * tx + li % 4;
+  const int iy0 = oy * S - a.pt, ix0 = ox * S - a.pl;
+  float4 tap[G][9];
+  bool ok[9];
+#pragma unroll
+  for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) {
+      const int iy = iy0 + kh, ix = ix0 + kw;
+      ok[kh * 3 + kw] = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+      const float* wp = lds + (((li / 4) * S + kh) * WH + (li % 4) * S + kw) * P + c4;
+#pragma unroll
+      for (int g = 0; g < G; ++g) tap[g][kh * 3 + kw] = *reinterpret_cast<const float4*>(wp + 16 * g);
+    }
+  // The filter is only used under the taps' in-image predicates; pinning it here keeps its loads where they
+  // are written, ahead of the taps and all in flight together, instead of inside per-tap branches.
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+      asm volatile("" : "+v"(dwf[g][t].x), "+v"(dwf[g][t].y), "+v"(dwf[g][t].z), "+v"(dwf[g][t].w));
+  const ActClamp dclamp = make_act(a.dw_act);
+  float4 av[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float4 acc = dwb[g];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      const float4 w = dwf[g][t];
+      acc.x = ok[t] ? fmaf(tap[g][t].x, w.x, acc.x) : acc.x;
+      acc.y = ok[t] ? fmaf(tap[g][t].y, w.y, acc.y) : acc.y;
+      acc.z = ok[t] ? fmaf(tap[g][t].z, w.z, acc.z) : acc.z;
+      acc.w = ok[t] ? fmaf(tap[g][t].w, w.w, acc.w) : acc.w;
+    }
+    av[g] = make_float4(apply_act(acc.x, dclamp), apply_act(acc.y, dclamp), apply_act(acc.z, dclamp), apply_act(acc.w, dclamp));
+  }
+
+  floatx4 acc[CB];
+#pragma unroll
+  for (int j = 0; j < CB; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[j][v] = 0.f;
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int j = 0; j < CB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(f4_at(av[g], s), b[g][s][j], acc[j], 0, 0, 0);
+
+  __syncthreads();  // everybody has read its taps: the window's LDS now takes the partial tiles
+#pragma unroll
+  for (int j = 0; j < CB; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[(((wk * WN + wn) * CB + j) * 4 + v) * 64 + lane] = acc[j][v];
+  __syncthreads();
+
+  const ActClamp pclamp = make_act(a.pw_act);
+#pragma unroll
+  for (int i = 0; i < EI; ++i) {
+    const int e = tid + i * NT;
+    if (e >= 256 * WN) break;
+    const int ewn = e / 256, ev = (e / 64) % 4, el = e % 64;
+    const int row = 4 * (el / 16) + ev;
+    const int py = 4 * ty + row / 4, px = 4 * tx + row % 4;
+    float o[CB];
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+      float sum = ebias[i][j];
+#pragma unroll
+      for (int w = 0; w < WK; ++w) sum += red[(((w * WN + ewn) * CB + j) * 4 + ev) * 64 + el];
+      o[j] = apply_act(sum, pclamp);
+    }
+    if (py < a.OH && px < a.OW) {
+      float* dst = a.y + (size_t)(py * a.OW + px) * N + n0 + 16 * CB * ewn + CB * (el % 16);
+      if constexpr (CB == 4) *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
+      else *reinterpret_cast<float2*>(dst) = make_float2(o[0], o[1]);
+    }
+  }
+}
+
+template <int C, int WK, int WN, int CB, int S>
+int launch_cfg(BlockArgs a, hipStream_t stream) {
+  constexpr int NS = 16 * CB * WN;
+  a.tiles_x = (a.OW + 3) / 4;
+  a.slices = a.N / NS;
+  a.total = a.tiles_x * ((a.OH + 3) / 4) * a.slices;
+  hipLaunchKernelGGL((separable_block_kernel<C, WK, WN, CB, S>), dim3((unsigned)a.total), dim3(64 * WK * WN), 0, stream, a);
+  return check_launch();
+}
+
+}  // namespace
+
+bool separable_block_supported(long long batch, int h, int w, int c, int n, int stride, const void* x, const void* dw_w,
+                               const void* dw_b, const void* pw_w, const void* pw_b, const void* y) {
+  auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
+  return batch == 1 && (c == 32 || c == 64 || c == 128) && n % 64 == 0 && n >= 64 && n <= 1024 &&
+         (stride == 1 || stride == 2) && h >= 1 && w >= 1 && (long long)h * w * c * 4 < (1ll << 31) && al16(x) &&
+         al16(dw_w) && al16(dw_b) && al16(pw_w) && al16(pw_b) && al16(y);
+}
+
+int launch_separable_block(const float* x, const float* dw_w, const float* dw_b, const float* pw_w, const float* pw_b,
+                           float* y, int h, int w, int c, int n, int oh, int ow, int stride, int pt, int pl, int dw_act,
+                           int pw_act, hipStream_t stream) {
+  BlockArgs a;
+  a.x = x, a.dw_w = dw_w, a.dw_b = dw_b, a.pw_w = pw_w, a.pw_b = pw_b, a.y = y;
+  a.H = h, a.W = w, a.OH = oh, a.OW = ow, a.pt = pt, a.pl = pl, a.N = n;
+  a.dw_act = dw_act, a.pw_act = pw_act;
+  a.x_bytes = (unsigned)((long long)h * w * c * 4);
+  a.tiles_x = a.slices = a.total = 0;
+#define TFX_BLOCK_CASE(CC, WK, WN, CB)                                       \
+  if (c == CC && stride == 1) return launch_cfg<CC, WK, WN, CB, 1>(a, stream); \
+  if (c == CC && stride == 2) return launch_cfg<CC, WK, WN, CB, 2>(a, stream);
+  TFX_BLOCK_CASE(32, 2, 2, 2)
+  TFX_BLOCK_CASE(64, 4, 1, 4)
+  TFX_BLOCK_CASE(128, 8, 1, 4)
+#undef TFX_BLOCK_CASE
+  return TFX_ERR_UNSUPPORTED;
+}
+
+}  // namespace tfx
