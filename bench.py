@@ -401,8 +401,9 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "MobileNet-v1 1.0/224 forward, batch 1, fp32 NHWC, random He-normal weights (seed 4), "
                                "input uniform[-1,1)",
-                   "launch": "stream enqueue, one C-ABI call per inference = 10 kernel launches (stem, 4 x (depthwise, "
-                             "pointwise), one chained kernel for blocks 5-13 + pool + FC + softmax)"},
+                   "launch": "stream enqueue, one C-ABI call per inference = 5 kernel launches (stem + block 1, blocks 2, "
+                             "3 and 4 each as one depthwise+pointwise kernel, one chained kernel for blocks 5-13 + pool + "
+                             "FC + softmax)"},
         "ms_per_step_hip_events": round(ms_events, 5),
         "graph_replay_ms_per_inference": None if graph_ms is None else round(graph_ms, 5),
         "paper_table1_ms": {"plain JS (MacBook Pro 2014)": 3426, "WebGL Intel Iris Pro": 49, "WebGL GTX 1080": 5,
@@ -438,30 +439,15 @@ def main():
         dw_bytes, dw_s = sum(l["bytes"] for l in dw), sum(l["us"] for l in dw) * 1e-6
 
         # The step's top kernel by time is mobilenet_chain_kernel (blocks 5-13, pool, fully connected layer, softmax
-        # in one launch: about 60 % of the step).  The C ABI enqueues it inside the forward call, so its duration is
+        # in one launch: about 70 % of the step).  The C ABI enqueues it inside the forward call, so its duration is
         # taken as the difference of two graph replays timed with HIP events on the launch stream: the whole forward
-        # pass (10 launches) minus the same 9 leading launches (stem, blocks 1-4) issued through the single-op entry
-        # points, which select the same kernels.
+        # pass (5 launches) minus its 4 leading launches (stem + block 1, blocks 2 - 4), which the C ABI runs on
+        # their own as tfx_mobilenet_v1_variant_features(end_block = 4).
         head_in = torch.empty((1, 224, 224, 3), device="cuda:0").uniform_(-1, 1)
-        head_bufs = []
-        hx = head_in
-        hy = tfx.tfx_conv2d(hx, w["conv0_w"], w["conv0_b"], 2, tfx.PAD_SAME, tfx.ACT_RELU6)
-        head_bufs.append(hy)
-        for i in range(4):
-            hx = hy
-            hy = tfx.tfx_depthwise_conv2d(hx, w["dw_w"][i], w["dw_b"][i], ST[i], tfx.PAD_SAME, tfx.ACT_RELU6)
-            head_bufs.append(hy)
-            hx = hy
-            hy = tfx.tfx_conv2d(hx, w["pw_w"][i], w["pw_b"][i], 1, tfx.PAD_SAME, tfx.ACT_RELU6)
-            head_bufs.append(hy)
+        head_out = model.features(head_in, 4)
 
         def head():
-            tfx.tfx_conv2d(head_in, w["conv0_w"], w["conv0_b"], 2, tfx.PAD_SAME, tfx.ACT_RELU6, out=head_bufs[0])
-            for i in range(4):
-                tfx.tfx_depthwise_conv2d(head_bufs[2 * i], w["dw_w"][i], w["dw_b"][i], ST[i], tfx.PAD_SAME, tfx.ACT_RELU6,
-                                         out=head_bufs[2 * i + 1])
-                tfx.tfx_conv2d(head_bufs[2 * i + 1], w["pw_w"][i], w["pw_b"][i], 1, tfx.PAD_SAME, tfx.ACT_RELU6,
-                               out=head_bufs[2 * i + 2])
+            model.features(head_in, 4, out=head_out)
         t_head = time_loop(head, reps, inner=10)
         t_full = time_loop(step, reps, inner=10)
         t_chain = max(t_full - t_head, 1e-9)
@@ -475,27 +461,32 @@ def main():
             "launches_per_step": 1, "avg_launch_us": round(t_chain * 1e6, 3),
             "algorithmic_flop": chain_flop, "algorithmic_bytes": chain_bytes,
             "hbm_frac_of_the_same_launch": round(chain_bytes / t_chain / PEAK_HBM, 5),
-            "how_timed": "graph replay of the whole forward pass (%.2f us) minus graph replay of its 9 leading launches "
+            "how_timed": "graph replay of the whole forward pass (%.2f us) minus graph replay of its 4 leading launches "
                          "(%.2f us), HIP events on the launch stream" % (t_full * 1e6, t_head * 1e6),
             "note": "18 dependent convolution layers + pool + FC + softmax at batch 1: bound by the latency of 20 "
                     "producer-consumer steps (1.3-1.8 us each on this GPU), not by a throughput roofline"}
-        head_pw = [l for l in pw if l["layer"] in ("pw1", "pw2", "pw3", "pw4")]
-        head_dw = [l for l in dw if l["layer"] in ("dw1", "dw2", "dw3", "dw4")]
+        head_layers = [l for l in layers if l["layer"] in ("conv0", "dw1", "pw1", "dw2", "pw2", "dw3", "pw3", "dw4", "pw4")]
+        head_flop = sum(l["flop"] for l in head_layers)
+        # algorithmic bytes of the 4 launches: the image in, each block's output written once and read once by the
+        # next launch (the last one only written), every filter and bias once; the stem's and the depthwise layers'
+        # outputs never leave the chip
+        head_bytes = 4 * (224 * 224 * 3 + 2 * (112 * 112 * 64 + 56 * 56 * 128 + 56 * 56 * 128) + 28 * 28 * 256 +
+                          (27 * 32 + 32) + sum(10 * c for c in (32, 64, 128, 128)) +
+                          sum(ci * co + co for ci, co in ((32, 64), (64, 128), (128, 128), (128, 256))))
         out["roofline_other_kernels_of_the_step"] = [
-            {"kernel": "gemm_mfma_kernel<64,64,32> (pw1), gemm_m16_direct_kernel (pw2-pw4): 4 launches", "bound": "mfma",
-             "achieved": round(sum(l["flop"] for l in head_pw) / (sum(l["us"] for l in head_pw) * 1e-6) / 1e12, 4),
-             "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
-             "frac": round(sum(l["flop"] for l in head_pw) / (sum(l["us"] for l in head_pw) * 1e-6) / PEAK_MFMA_F32, 5),
-             "avg_launch_us": round(sum(l["us"] for l in head_pw) / 4, 3)},
-            {"kernel": "depthwise3x3_kernel<1,1> / <2,1> (dw1-dw4): 4 launches", "bound": "hbm",
-             "achieved": round(sum(l["bytes"] for l in head_dw) / (sum(l["us"] for l in head_dw) * 1e-6) / 1e9, 1),
-             "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-             "frac": round(sum(l["bytes"] for l in head_dw) / (sum(l["us"] for l in head_dw) * 1e-6) / PEAK_HBM, 5),
-             "avg_launch_us": round(sum(l["us"] for l in head_dw) / 4, 3)},
-            {"kernel": "all 13 pointwise layers as single-op launches (the multi-kernel path of batch > 1)", "bound": "mfma",
+            {"kernel": "separable_block_kernel: stem + block 1, blocks 2, 3, 4 (4 launches, each a depthwise 3x3 and a "
+                       "pointwise layer)", "bound": "mfma",
+             "achieved": round(head_flop / t_head / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
+             "frac": round(head_flop / t_head / PEAK_MFMA_F32, 5), "avg_launch_us": round(t_head * 1e6 / 4, 3),
+             "algorithmic_flop": head_flop, "algorithmic_bytes": head_bytes,
+             "hbm_frac_of_the_same_launches": round(head_bytes / t_head / PEAK_HBM, 5),
+             "the_same_9_layers_as_single_op_launches_us": round(sum(l["us"] for l in head_layers), 2),
+             "note": "bound by four dependent launches (kernel-argument fetch, one round trip for the previous "
+                     "block's output, split-K reduction, store), not by a throughput roofline"},
+            {"kernel": "all 13 pointwise layers as single-op launches (the multi-kernel path of batch > 1; not part of the batch-1 step)", "bound": "mfma",
              "achieved": round(pw_flop / pw_s / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
              "frac": round(pw_flop / pw_s / PEAK_MFMA_F32, 5), "avg_launch_us": round(pw_s * 1e6 / 13, 3)},
-            {"kernel": "all 13 depthwise layers as single-op launches", "bound": "hbm",
+            {"kernel": "all 13 depthwise layers as single-op launches (not part of the batch-1 step)", "bound": "hbm",
              "achieved": round(dw_bytes / dw_s / 1e9, 1), "peak": PEAK_HBM / 1e9, "unit": "GB/s",
              "frac": round(dw_bytes / dw_s / PEAK_HBM, 5), "avg_launch_us": round(dw_s * 1e6 / 13, 3)}]
         out["mobilenet_layers"] = {

@@ -197,7 +197,8 @@ size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch);
 /* Full forward pass: 3x3 stride-2 conv to 32 channels, 13 x (depthwise 3x3 ->
  * pointwise 1x1), bias + ReLU6 after each of the 27 convolutions, SAME padding
  * throughout, global average pool, fully connected 1024 -> 1000, softmax.
- * At batch 1 (and full width) the blocks from the 1/8-size maps on, the pool, the
+ * At batch 1 the stem and the first block, and each of the next three blocks, are
+ * one kernel each; at batch 1 and full width the blocks from the 1/8-size maps on, the pool, the
  * fully connected layer and the softmax run as one kernel whose workgroups hand
  * results to each other through flags in the workspace; every wait in it is
  * bounded, and if one ever gives up (a workgroup that never got to run) every
@@ -234,6 +235,24 @@ size_t tfx_mobilenet_v1_variant_workspace_bytes(const tfx_mobilenet_v1_variant* 
 int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
                                      const tfx_mobilenet_v1_weights* weights, void* workspace,
                                      size_t workspace_bytes, float* probs, float* logits, void* stream);
+
+/* An internal activation of the network (Section 5.2 offers the hosted models to
+ * transfer learning, which trains a small model on such an activation): the
+ * output of depthwise-separable block `end_block` (1 ... 13, after its pointwise
+ * layer's bias + ReLU6), [batch, h, w, c] NHWC.  tfx_mobilenet_v1_variant_features_shape
+ * writes that shape (host-only): h = w = the image size halved by the stem and by each
+ * stride-2 block up to end_block (rounded up), c = alpha * that block's pointwise width.
+ * The layers up to that block run exactly as in tfx_mobilenet_v1_variant_forward (the
+ * batch-1 kernel that chains the last blocks is not used) and nothing after it runs.
+ * features: device, 16-byte aligned, written by the last kernel.  weights: the whole
+ * struct must be filled in.  workspace as for the forward pass.  TFX_ERR_ARG for an
+ * end_block outside 1 ... 13 or a misaligned features pointer; other errors as the
+ * forward pass. */
+int tfx_mobilenet_v1_variant_features_shape(const tfx_mobilenet_v1_variant* variant, int64_t batch, int end_block,
+                                            int64_t shape[4]);
+int tfx_mobilenet_v1_variant_features(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
+                                      const tfx_mobilenet_v1_weights* weights, void* workspace,
+                                      size_t workspace_bytes, int end_block, float* features, void* stream);
 
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): tfx_mobilenet_v1_variant_forward with

@@ -74,6 +74,11 @@ _SIGNATURES = {
     "tfx_mobilenet_v1_variant_forward": (ctypes.c_int, [ctypes.POINTER(TfxVariant), _VP, ctypes.c_int64,
                                                         ctypes.POINTER(TfxWeights), _VP, ctypes.c_size_t, _VP, _VP,
                                                         _VP]),
+    "tfx_mobilenet_v1_variant_features_shape": (ctypes.c_int, [ctypes.POINTER(TfxVariant), ctypes.c_int64, ctypes.c_int,
+                                                               _I64P]),
+    "tfx_mobilenet_v1_variant_features": (ctypes.c_int, [ctypes.POINTER(TfxVariant), _VP, ctypes.c_int64,
+                                                         ctypes.POINTER(TfxWeights), _VP, ctypes.c_size_t, ctypes.c_int,
+                                                         _VP, _VP]),
 }
 
 
@@ -375,6 +380,14 @@ class MobileNetV1:
             tfx_mobilenet_v1_variant_forward(self.variant, image, self.struct, self.workspace, self.probs, self.logits)
         return self.probs, self.logits
 
+    def features(self, image, end_block, out=None):
+        """Enqueue the layers up to depthwise-separable block `end_block` (1 ... 13); returns its output [N,h,w,c]."""
+        import torch
+        if out is None:
+            out = torch.empty(tfx_mobilenet_v1_variant_features_shape(self.variant, self.batch, end_block),
+                              dtype=torch.float32, device=self.device)
+        return tfx_mobilenet_v1_variant_features(self.variant, image, self.struct, self.workspace, end_block, out)
+
 
 def tfx_mobilenet_v1_forward(image, weights_struct, workspace, probs, logits=None):
     import torch
@@ -396,6 +409,30 @@ def tfx_mobilenet_v1_variant_forward(variant, image, weights_struct, workspace, 
                                                   None if logits is None else logits.data_ptr(), _stream(image)),
            "tfx_mobilenet_v1_variant_forward")
     return probs
+
+
+def tfx_mobilenet_v1_variant_features_shape(variant, batch, end_block):
+    out = (ctypes.c_int64 * 4)()
+    _check(lib().tfx_mobilenet_v1_variant_features_shape(ctypes.byref(variant), int(batch), int(end_block), out),
+           "tfx_mobilenet_v1_variant_features_shape")
+    return tuple(int(v) for v in out)
+
+
+def tfx_mobilenet_v1_variant_features(variant, image, weights_struct, workspace, end_block, features):
+    """The output of depthwise-separable block `end_block` (1 ... 13) into `features`; nothing after it runs."""
+    import torch
+    batch = _rank(image, "image", (4,))[0]
+    _expect_shape(image, "image", (batch, int(variant.image_size), int(variant.image_size), 3))
+    _expect_shape(features, "features", tfx_mobilenet_v1_variant_features_shape(variant, batch, end_block))
+    _dev(image, "image"), _dev(features, "features")
+    if not isinstance(workspace, torch.Tensor) or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous tensor in GPU memory")
+    _check(lib().tfx_mobilenet_v1_variant_features(ctypes.byref(variant), image.data_ptr(), batch,
+                                                   ctypes.byref(weights_struct), workspace.data_ptr(),
+                                                   workspace.numel() * workspace.element_size(), int(end_block),
+                                                   features.data_ptr(), _stream(image)),
+           "tfx_mobilenet_v1_variant_features")
+    return features
 
 
 def tfx_mobilenet_v1_static_scratch_bytes():

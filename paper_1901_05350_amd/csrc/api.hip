@@ -353,10 +353,14 @@ size_t tfx_mobilenet_v1_variant_workspace_bytes(const tfx_mobilenet_v1_variant* 
   return plan_net(*variant, batch).bytes;
 }
 
-int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
-                                     const tfx_mobilenet_v1_weights* weights, void* workspace,
-                                     size_t workspace_bytes, float* probs, float* logits, void* stream) {
-  if (!variant || !input || !weights || !workspace || !probs) return TFX_ERR_NULL;
+namespace {
+// The forward pass; end_block = 0: the whole network into probs / logits; end_block = 1 .. 13: stop after that
+// depthwise-separable block, whose output goes to `features` instead of the workspace.
+int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
+                 const tfx_mobilenet_v1_weights* weights, void* workspace, size_t workspace_bytes, float* probs,
+                 float* logits, int end_block, float* features, void* stream) {
+  if (!variant || !input || !weights || !workspace || !(end_block == 0 ? (const void*)probs : (const void*)features))
+    return TFX_ERR_NULL;
   if (!weights->conv0_w || !weights->conv0_b || !weights->fc_w || !weights->fc_b) return TFX_ERR_NULL;
   for (int i = 0; i < kBlocks; ++i)
     if (!weights->dw_w[i] || !weights->dw_b[i] || !weights->pw_w[i] || !weights->pw_b[i]) return TFX_ERR_NULL;
@@ -374,7 +378,7 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
   // Batch 1 at full width: the blocks from the 1/8-size maps on, the pool, the fully connected layer and the
   // softmax run as one persistent kernel (chain.hip) when every pointer allows its vector loads and 256 of its
   // workgroups are resident at once on this device; its task flags are cleared by the stem kernel.
-  bool chain = plan.chain;
+  bool chain = plan.chain && end_block == 0;
   if (chain) {
     auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
     chain = al16(input) && al16(weights->conv0_b) && al16(weights->fc_w) && al16(weights->fc_b);
@@ -390,7 +394,22 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
   ConvGeom g;
   conv_geometry(shape, f0, 2, 2, TFX_PAD_SAME, false, &g);
   int rc;
-  if (chain)
+  int first_block = 0;
+  const int64_t c0 = kChannels[0] * q / 4;
+  if (kStrides[0] == 1 &&
+      stem_block_supported(batch, (int)shape[1], (int)shape[2], (int)f0[3], (int)c0, input, weights->conv0_w,
+                           weights->conv0_b, weights->dw_w[0], weights->dw_b[0], weights->pw_w[0], weights->pw_b[0],
+                           end_block == 1 ? features : buf[0])) {
+    // batch 1: stem and first block in one launch (block.hip); it also clears the chain's task flags
+    rc = launch_stem_block(input, weights->conv0_w, weights->conv0_b, weights->dw_w[0], weights->dw_b[0],
+                           weights->pw_w[0], weights->pw_b[0], end_block == 1 ? features : buf[0], (int)shape[1],
+                           (int)shape[2], (int)g.out[1],
+                           (int)g.out[2], (int)g.pad[0], (int)g.pad[2], (int)c0, TFX_ACT_RELU6,
+                           static_cast<hipStream_t>(stream), chain ? static_cast<int*>(chain_ws) : nullptr,
+                           chain ? chain_flag_words((int)variant->image_size, (int)variant->classes) : 0,
+                           chain_flag_stride());
+    first_block = 1;
+  } else if (chain)
     rc = launch_conv2d_stem(input, weights->conv0_w, weights->conv0_b, buf[0], 1, (int)shape[1], (int)shape[2],
                             kStemChannels, (int)g.out[1], (int)g.out[2], 2, 2, (int)g.pad[0], (int)g.pad[2], TFX_ACT_RELU6,
                             static_cast<hipStream_t>(stream), static_cast<int*>(chain_ws),
@@ -400,8 +419,11 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
                     stream);
   if (rc) return rc;
   for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
+  if (first_block == 1) shape[3] = c0;
+  if (first_block == 1 && end_block == 1) return TFX_OK;
   int cur = 0;
-  for (int b = 0; b < kBlocks; ++b) {
+  for (int b = first_block; b < kBlocks; ++b) {
+    float* const block_out = end_block == b + 1 ? features : buf[cur ^ 1];
     if (chain && b == 4)
       return launch_chain(buf[cur], (int)shape[1], weights, chain_ws, probs, logits, (int)variant->classes,
                           static_cast<hipStream_t>(stream));
@@ -409,13 +431,14 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
     const int64_t cout = kChannels[b] * q / 4;
     // batch 1, thin block: depthwise and pointwise layer in one launch (block.hip)
     if (separable_block_supported(batch, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, kStrides[b], buf[cur],
-                                  weights->dw_w[b], weights->dw_b[b], weights->pw_w[b], weights->pw_b[b], buf[cur ^ 1])) {
+                                  weights->dw_w[b], weights->dw_b[b], weights->pw_w[b], weights->pw_b[b], block_out)) {
       conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
       rc = launch_separable_block(buf[cur], weights->dw_w[b], weights->dw_b[b], weights->pw_w[b], weights->pw_b[b],
-                                  buf[cur ^ 1], (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, (int)g.out[1],
+                                  block_out, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, (int)g.out[1],
                                   (int)g.out[2], kStrides[b], (int)g.pad[0], (int)g.pad[2], TFX_ACT_RELU6, TFX_ACT_RELU6,
                                   static_cast<hipStream_t>(stream));
       if (rc) return rc;
+      if (end_block == b + 1) return TFX_OK;
       for (int i = 0; i < 3; ++i) shape[i] = g.out[i];
       shape[3] = cout;
       cur ^= 1;
@@ -429,14 +452,42 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
     cur ^= 1;
     const int64_t fp[4] = {1, 1, shape[3], cout};
     rc = tfx_conv2d(buf[cur], shape, weights->pw_w[b], fp, weights->pw_b[b], 1, 1, TFX_PAD_SAME, TFX_ACT_RELU6,
-                    buf[cur ^ 1], stream);
+                    end_block == b + 1 ? features : buf[cur ^ 1], stream);
     if (rc) return rc;
+    if (end_block == b + 1) return TFX_OK;
     shape[3] = cout;
     cur ^= 1;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   return launch_pool_fc_softmax(buf[cur], weights->fc_w, weights->fc_b, partial, logits, probs, (int)batch,
                                 (int)(shape[1] * shape[2]), (int)shape[3], (int)variant->classes, s);
+}
+}  // namespace
+
+int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
+                                     const tfx_mobilenet_v1_weights* weights, void* workspace,
+                                     size_t workspace_bytes, float* probs, float* logits, void* stream) {
+  return forward_impl(variant, input, batch, weights, workspace, workspace_bytes, probs, logits, 0, nullptr, stream);
+}
+
+int tfx_mobilenet_v1_variant_features_shape(const tfx_mobilenet_v1_variant* variant, int64_t batch, int end_block,
+                                            int64_t shape[4]) {
+  if (!variant || !shape) return TFX_ERR_NULL;
+  if (!valid_variant(variant) || end_block < 1 || end_block > kBlocks) return TFX_ERR_ARG;
+  if (batch < 1) return TFX_ERR_SHAPE;
+  int64_t hw = (variant->image_size + 1) / 2;  // the stem halves the image (stride 2, SAME padding)
+  for (int b = 0; b < end_block; ++b) hw = (hw + kStrides[b] - 1) / kStrides[b];
+  shape[0] = batch, shape[1] = hw, shape[2] = hw, shape[3] = kChannels[end_block - 1] * variant->width_quarters / 4;
+  return TFX_OK;
+}
+
+int tfx_mobilenet_v1_variant_features(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
+                                      const tfx_mobilenet_v1_weights* weights, void* workspace, size_t workspace_bytes,
+                                      int end_block, float* features, void* stream) {
+  if (end_block < 1 || end_block > kBlocks) return variant && input && weights && workspace && features ? TFX_ERR_ARG : TFX_ERR_NULL;
+  if (features && reinterpret_cast<uintptr_t>(features) % 16 != 0) return TFX_ERR_ARG;
+  return forward_impl(variant, input, batch, weights, workspace, workspace_bytes, nullptr, nullptr, end_block, features,
+                      stream);
 }
 
 size_t tfx_mobilenet_v1_static_scratch_bytes(void) { return kStaticScratchBytes; }

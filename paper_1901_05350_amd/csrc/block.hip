@@ -34,19 +34,28 @@ struct BlockArgs {
   int tiles_x, slices, total;
   int dw_act, pw_act;
   unsigned x_bytes;
+  // STEM form: x is the image [IH, IW, 3]; the block's input [H, W, 32] is the 3x3 stride-2 convolution of the
+  // image with st_w [3, 3, 3, 32] + st_b, clamped, and exists only as windows in LDS
+  const float* st_w;
+  const float* st_b;
+  int IH, IW, st_pt, st_pl, st_act;
+  int* zero_words;  // optional: zero_count words, zero_stride words apart, cleared by this kernel
+  int zero_count, zero_stride;
 };
 
 __device__ __forceinline__ float f4_at(const float4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
 // C input channels, split over WK wavefronts; WN wavefronts side by side over the columns, CB column blocks of 16
 // each: NS = 16 CB WN columns per workgroup.
-template <int C, int WK, int WN, int CB, int S>
+// STEM: the block's input is computed from the image on the fly (see BlockArgs).
+template <int C, int WK, int WN, int CB, int S, bool STEM = false>
 __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const BlockArgs a) {
   constexpr int NT = 64 * WK * WN;
   constexpr int G = C / (16 * WK);  // groups of 16 channels per wavefront
   constexpr int NS = 16 * CB * WN;
   constexpr int EI = (256 * WN + NT - 1) / NT;  // epilogue items per thread
   static_assert(C % (16 * WK) == 0 && (CB == 2 || CB == 4), "tile shape");
+  static_assert(!STEM || (C == 32 && S == 1 && NT == 256), "the stem form feeds the first block");
   constexpr int WH = 3 * S + 3;             // window edge: 3 (S) + 3 input pixels under 4 output pixels
   constexpr int P = C + 4;                   // floats between window pixels in LDS
   constexpr int WQ = WH * WH * (C / 4);      // float4 elements of the window
@@ -73,7 +82,28 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
   // the input window: element i = (pixel i / (C/4) of the window, channel quad i % (C/4))
   const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x), 0, (int)a.x_bytes, 0x00020000);
   u32x4 win[LI];
-  {
+  // STEM: the 13 x 13 x 3 image pixels under the 6 x 6 window of stem outputs, rows of 39 floats; the stem filter
+  constexpr int kImgRow = 40, kImgFloats = 13 * 39;
+  __shared__ float img[STEM ? 13 * kImgRow : 1];
+  constexpr int kWstRow = 48;  // floats between filter rows in LDS: lanes q and q + 1 read rows 16 banks apart
+  __shared__ __align__(16) float wst[STEM ? 28 * kWstRow : 4];  // [27][32 of 48] filter, [32] bias
+  float iv[2];
+  float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int sy0 = 4 * ty - a.pt, sx0 = 4 * tx - a.pl;  // STEM: first row / column of the window in the stem's output
+  if constexpr (STEM) {
+    const int gy0 = 2 * sy0 - a.st_pt, gx0 = 2 * sx0 - a.st_pl;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int e = tid + i * NT, gy = gy0 + e / 39, gx = gx0 + (e % 39) / 3;
+      const bool in = e < kImgFloats && gy >= 0 && gy < a.IH && gx >= 0 && gx < a.IW;
+      const unsigned off = in ? (unsigned)((gy * a.IW + gx) * 3 + e % 3) * 4u : 0x80000000u;
+      iv[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(xr, (int)off, 0, 0));
+    }
+    if (tid < 27 * 8) wv = *reinterpret_cast<const float4*>(a.st_w + 4 * tid);
+    else if (tid < 28 * 8) wv = *reinterpret_cast<const float4*>(a.st_b + 4 * (tid - 27 * 8));
+    if (a.zero_count > 0)
+      for (int i = bid * NT + tid; i < a.zero_count; i += a.total * NT) a.zero_words[(size_t)i * a.zero_stride] = 0;
+  } else {
     const int wy0 = 4 * ty * S - a.pt, wx0 = 4 * tx * S - a.pl;
 #pragma unroll
     for (int i = 0; i < LI; ++i) {
@@ -85,6 +115,7 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
       win[i] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)off, 0, 0);
     }
   }
+  (void)win;
 
   // pointwise filter columns of this lane: rows wk 16 G + 16 g + 4 q + s, columns n0 + 16 CB wn + CB li ...
   float b[G][4][CB];
@@ -125,11 +156,58 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
     for (int t = 0; t < 9; ++t) dwf[g][t] = *reinterpret_cast<const float4*>(a.dw_w + t * C + c4 + 16 * g);
   }
 
-  // window -> LDS
+  if constexpr (STEM) {
+    // image pixels and stem filter -> LDS, then the stem's output for the window; window pixels outside the stem's
+    // output map are the depthwise layer's zero padding
 #pragma unroll
-  for (int i = 0; i < LI; ++i) {
-    const int e = tid + i * NT;
-    if (e < WQ) *reinterpret_cast<u32x4*>(lds + (e / (C / 4)) * P + 4 * (e % (C / 4))) = win[i];
+    for (int i = 0; i < 2; ++i) {
+      const int e = tid + i * NT;
+      if (e < kImgFloats) img[(e / 39) * kImgRow + e % 39] = iv[i];
+    }
+    if (tid < 28 * 8) *reinterpret_cast<float4*>(wst + (tid / 8) * kWstRow + 4 * (tid % 8)) = wv;
+    __syncthreads();
+    // the 36 window pixels x 32 filters as a [48 (36 used), 36 (27 used)] x [36, 32] product on the matrix cores.
+    // k = (kh, j): j runs along image row kh of the pixel's 3 x 3 x 3 patch (9 values), padded to 12 so that
+    // every address is a per-lane base plus a constant -- with 3 - 4 workgroups per CU this phase is bound by
+    // the number of instructions issued, not by the matrix cores.
+    const ActClamp sclamp = make_act(a.st_act);
+    const bool border = sy0 < 0 || sx0 < 0 || sy0 + WH > a.H || sx0 + WH > a.W;  // same for the whole workgroup
+    for (int t = wave; t < 6; t += NT / 64) {
+      const int rt = t % 3, cb = t / 3;
+      const int p = min(16 * rt + li, WH * WH - 1);
+      const float* ip = img + 2 * (p / WH) * kImgRow + 6 * (p % WH) + q;
+      const float* fp = wst + q * kWstRow + 16 * cb + li;
+      floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 9; ++kk) {
+        const int kh = kk / 3, j0 = 4 * (kk % 3);  // this lane's j = j0 + q: 8 + q > 8 is padding
+        float av = ip[kh * kImgRow + j0], bv = fp[(kh * 9 + j0) * kWstRow];
+        if (j0 == 8) av = q == 0 ? av : 0.f, bv = q == 0 ? bv : 0.f;
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc, 0, 0, 0);
+      }
+      const int c = 16 * cb + li;
+      const float sb = wst[27 * kWstRow + c];
+      if (rt < 2 || q == 0) {
+        float* dst = lds + (16 * rt + 4 * q) * P + c;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dst[v * P] = apply_act(acc[v] + sb, sclamp);
+        if (border) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int pp = 16 * rt + 4 * q + v;
+            const int sy = sy0 + pp / WH, sx = sx0 + pp % WH;
+            if (sy < 0 || sy >= a.H || sx < 0 || sx >= a.W) dst[v * P] = 0.f;
+          }
+        }
+      }
+    }
+  } else {
+    // window -> LDS
+#pragma unroll
+    for (int i = 0; i < LI; ++i) {
+      const int e = tid + i * NT;
+      if (e < WQ) *reinterpret_cast<u32x4*>(lds + (e / (C / 4)) * P + 4 * (e % (C / 4))) = win[i];
+    }
   }
   __syncthreads();
 
@@ -214,13 +292,13 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
   }
 }
 
-template <int C, int WK, int WN, int CB, int S>
+template <int C, int WK, int WN, int CB, int S, bool STEM = false>
 int launch_cfg(BlockArgs a, hipStream_t stream) {
   constexpr int NS = 16 * CB * WN;
   a.tiles_x = (a.OW + 3) / 4;
   a.slices = a.N / NS;
   a.total = a.tiles_x * ((a.OH + 3) / 4) * a.slices;
-  hipLaunchKernelGGL((separable_block_kernel<C, WK, WN, CB, S>), dim3((unsigned)a.total), dim3(64 * WK * WN), 0, stream, a);
+  hipLaunchKernelGGL((separable_block_kernel<C, WK, WN, CB, S, STEM>), dim3((unsigned)a.total), dim3(64 * WK * WN), 0, stream, a);
   return check_launch();
 }
 
@@ -243,6 +321,8 @@ int launch_separable_block(const float* x, const float* dw_w, const float* dw_b,
   a.dw_act = dw_act, a.pw_act = pw_act;
   a.x_bytes = (unsigned)((long long)h * w * c * 4);
   a.tiles_x = a.slices = a.total = 0;
+  a.st_w = a.st_b = nullptr, a.IH = a.IW = a.st_pt = a.st_pl = a.st_act = 0;
+  a.zero_words = nullptr, a.zero_count = 0, a.zero_stride = 1;
 #define TFX_BLOCK_CASE(CC, WK, WN, CB)                                       \
   if (c == CC && stride == 1) return launch_cfg<CC, WK, WN, CB, 1>(a, stream); \
   if (c == CC && stride == 2) return launch_cfg<CC, WK, WN, CB, 2>(a, stream);
@@ -251,6 +331,29 @@ int launch_separable_block(const float* x, const float* dw_w, const float* dw_b,
   TFX_BLOCK_CASE(128, 8, 1, 4)
 #undef TFX_BLOCK_CASE
   return TFX_ERR_UNSUPPORTED;
+}
+
+bool stem_block_supported(long long batch, int ih, int iw, int stem_filters, int n, const void* image, const void* st_w,
+                          const void* st_b, const void* dw_w, const void* dw_b, const void* pw_w, const void* pw_b,
+                          const void* y) {
+  auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
+  return batch == 1 && stem_filters == 32 && n == 64 && ih >= 1 && iw >= 1 && (long long)ih * iw * 3 * 4 < (1ll << 31) &&
+         al16(image) && al16(st_w) && al16(st_b) && al16(dw_w) && al16(dw_b) && al16(pw_w) && al16(pw_b) && al16(y);
+}
+
+int launch_stem_block(const float* image, const float* st_w, const float* st_b, const float* dw_w, const float* dw_b,
+                      const float* pw_w, const float* pw_b, float* y, int ih, int iw, int h, int w, int st_pt, int st_pl,
+                      int n, int act, hipStream_t stream, int* zero_words, int zero_count, int zero_stride) {
+  BlockArgs a;
+  a.x = image, a.dw_w = dw_w, a.dw_b = dw_b, a.pw_w = pw_w, a.pw_b = pw_b, a.y = y;
+  // the block: 3x3 stride-1 depthwise layer with SAME padding (one zero row / column before the map), then 32 -> n
+  a.H = h, a.W = w, a.OH = h, a.OW = w, a.pt = 1, a.pl = 1, a.N = n;
+  a.dw_act = act, a.pw_act = act;
+  a.x_bytes = (unsigned)((long long)ih * iw * 3 * 4);
+  a.tiles_x = a.slices = a.total = 0;
+  a.st_w = st_w, a.st_b = st_b, a.IH = ih, a.IW = iw, a.st_pt = st_pt, a.st_pl = st_pl, a.st_act = act;
+  a.zero_words = zero_words, a.zero_count = zero_count, a.zero_stride = zero_stride;
+  return launch_cfg<32, 2, 2, 2, 1, true>(a, stream);
 }
 
 }  // namespace tfx

@@ -167,6 +167,58 @@ def test_mobilenet_variant_validation():
     assert fwd(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes - 1, FAKE, None, None) == -5
 
 
+def test_features_shape_follows_the_strides_of_table_1():
+    """Host-only: map sizes worked by hand from the stride list of the MobileNet body (stem /2, blocks 2, 4, 6, 12
+    /2 each, SAME padding rounds up) and the pointwise widths scaled by alpha."""
+    V = binding.TfxVariant
+    shape = tfx.tfx_mobilenet_v1_variant_features_shape
+    base = V(224, 4, 1000)
+    assert shape(base, 1, 1) == (1, 112, 112, 64)
+    assert shape(base, 1, 2) == (1, 56, 56, 128)
+    assert shape(base, 1, 4) == (1, 28, 28, 256)
+    assert shape(base, 5, 6) == (5, 14, 14, 512)
+    assert shape(base, 1, 11) == (1, 14, 14, 512)
+    assert shape(base, 1, 13) == (1, 7, 7, 1024)
+    # 100 pixels: 50, 50, 25, 25, 13, 13, 7 ... 7, 4, 4; alpha 0.5
+    odd = V(100, 2, 10)
+    assert shape(odd, 2, 1) == (2, 50, 50, 32)
+    assert shape(odd, 2, 3) == (2, 25, 25, 64)
+    assert shape(odd, 2, 5) == (2, 13, 13, 128)
+    assert shape(odd, 2, 6) == (2, 7, 7, 256)
+    assert shape(odd, 2, 13) == (2, 4, 4, 512)
+    for bad in (0, 14, -1):
+        with pytest.raises(tfx.TfxError):
+            shape(base, 1, bad)
+    with pytest.raises(tfx.TfxError):
+        shape(V(224, 9, 1000), 1, 3)
+    with pytest.raises(tfx.TfxError):
+        shape(base, 0, 3)
+
+
+@no_gpu_only
+def test_features_entry_point_validation():
+    L = tfx.lib()
+    V = binding.TfxVariant
+    w = binding.TfxWeights()
+    for name in ("conv0_w", "conv0_b", "fc_w", "fc_b"):
+        setattr(w, name, 0x1000)
+    for name in ("dw_w", "dw_b", "pw_w", "pw_b"):
+        arr = getattr(w, name)
+        for i in range(13):
+            arr[i] = 0x1000
+    ok = V(160, 2, 100)
+    nbytes = tfx.tfx_mobilenet_v1_variant_workspace_bytes(ok, 1)
+    feat = L.tfx_mobilenet_v1_variant_features
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 0, FAKE, None) == -3
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 14, FAKE, None) == -3
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, None, None) == -1
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, 0x1004, None) == -3   # misaligned
+    assert feat(None, FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, FAKE, None) == -1
+    assert feat(ctypes.byref(ok), FAKE, 0, ctypes.byref(w), FAKE, nbytes, 3, FAKE, None) == -2
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes - 1, 3, FAKE, None) == -5
+    assert feat(ctypes.byref(V(224, 7, 1000)), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, FAKE, None) == -3
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError, match="GPU memory"):

@@ -96,6 +96,49 @@ def test_family_variants_end_to_end(size, q, classes, batch):
     np.testing.assert_allclose(p.astype(np.float64).sum(axis=1), 1.0, atol=1e-5)
 
 
+def test_internal_activations_of_every_block(net):
+    """tfx_mobilenet_v1_variant_features against the oracle's activation after each block's pointwise layer; at
+    batch 1 blocks 1 - 4 are the fused stem / depthwise / pointwise kernels, so this is their parity test too."""
+    import torch
+    import paper_1901_05350_amd as tfx
+    data, probs, logits, acts = net
+    model = tfx.MobileNetV1(data["weights"], batch=1)
+    img = dev(data["image"])
+    for k in range(1, 14):
+        want = acts[2 * k]
+        got = model.features(img, k)
+        assert tuple(got.shape) == want.shape
+        assert_close(host(got), want, "features after block %d" % k)
+    # into a caller's buffer, twice: same bits; the forward pass afterwards is unaffected
+    out = torch.full(acts[8].shape, -1.0, dtype=torch.float32, device="cuda:0")
+    model.features(img, 4, out=out)
+    first = host(out).copy()
+    model.features(img, 4, out=out)
+    assert np.array_equal(host(out), first)
+    assert_close(first, acts[8], "features after block 4")
+    p, l = model.forward(img)
+    assert_close(host(l), logits, "logits after features calls")
+    with pytest.raises(tfx.TfxError):
+        model.features(img, 14, out=out)
+    with pytest.raises(TypeError):
+        model.features(img, 6, out=out)   # wrong shape for block 6
+
+
+@pytest.mark.parametrize("size,q,batch,blocks", [(100, 4, 1, (1, 2, 3, 4, 7, 13)), (100, 2, 3, (1, 6, 13)),
+                                                 (160, 4, 2, (1, 4, 12)), (32, 4, 1, (1, 2, 3, 4, 5, 13))])
+def test_internal_activations_of_variants_and_batches(size, q, batch, blocks):
+    """Odd map sizes (ragged 4 x 4 patches of the fused batch-1 kernels), other widths and batches above one."""
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1(seed=40 + q, batch=batch, image_size=size, width_quarters=q, classes=10)
+    probs, logits, acts = oracle.mobilenet_v1_forward(data["image"], data["weights"], return_activations=True)
+    model = tfx.MobileNetV1(data["weights"], batch=batch, image_size=size, width_quarters=q)
+    img = dev(data["image"])
+    for k in blocks:
+        got = model.features(img, k)
+        assert tuple(got.shape) == acts[2 * k].shape
+        assert_close(host(got), acts[2 * k], "features %d/%d block %d" % (q, size, k))
+
+
 def test_base_variant_is_the_plain_entry_point(net):
     import torch
     import paper_1901_05350_amd as tfx
