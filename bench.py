@@ -27,7 +27,8 @@ PEAK_HBM = 8.0e12          # B/s
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters'
 # reading for a plain 205.5 MB copy (profiles/hbm_traffic_counters.txt).  Each entry names the kernel
-# source it was measured on; if that file has changed since, the entry is reported as null.
+# source it was measured on, with the digest of that file followed by the shared header csrc/tfx_internal.h;
+# if either has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
     "batch_matmul_8x1024x1024x1024_tB": (100844399, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
     "pointwise_64x56x56x128_to_128": (206178088, "pointwise.hip", "1cca37ebed9cc6e9f04eec68e56ee5e10e3d9925ca61d49d80b2bc9ac3d8fa5a"),
@@ -42,7 +43,7 @@ MEASURED_TRAFFIC = {
     "conv3x3_f16_64x56x56x64_to_64": (52068243, "conv_gemm_f16.hip", "0c434b66d6367e415ef2333183a421be78368ab414a1dedd278457301abe4bab"),
     "add_f32_64M": (805262532, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
     "add_f16_64M": (402651589, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
-    "mobilenet_b1_gemm_13_launches": (53067992, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
+    "mobilenet_chain_kernel": (0, "chain.hip", "0000000000000000000000000000000000000000000000000000000000000000"),
 }
 
 
@@ -52,10 +53,13 @@ def measured_traffic(name):
     if name not in MEASURED_TRAFFIC:
         return None
     nbytes, fname, digest = MEASURED_TRAFFIC[name]
-    path = os.path.join(ROOT, "paper_1901_05350_amd", "csrc", fname)
+    csrc = os.path.join(ROOT, "paper_1901_05350_amd", "csrc")
     try:
-        with open(path, "rb") as f:
-            return nbytes if hashlib.sha256(f.read()).hexdigest() == digest else None
+        h = hashlib.sha256()
+        for part in (fname, "tfx_internal.h"):
+            with open(os.path.join(csrc, part), "rb") as f:
+                h.update(f.read())
+        return nbytes if h.hexdigest() == digest else None
     except OSError:
         return None
 
