@@ -197,7 +197,7 @@ size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch);
 /* Full forward pass: 3x3 stride-2 conv to 32 channels, 13 x (depthwise 3x3 ->
  * pointwise 1x1), bias + ReLU6 after each of the 27 convolutions, SAME padding
  * throughout, global average pool, fully connected 1024 -> 1000, softmax.
- * At batch 1 the stem and the first block, and each of the next three blocks, are
+ * At batch 1 to 3 the stem and the first block, and each of the next three blocks, are
  * one kernel each; at batch 1 and full width the blocks from the 1/8-size maps on, the pool, the
  * fully connected layer and the softmax run as one kernel whose workgroups hand
  * results to each other through flags in the workspace; every wait in it is

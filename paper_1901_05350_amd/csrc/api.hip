@@ -377,7 +377,8 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
 
   // Batch 1 at full width: the blocks from the 1/8-size maps on, the pool, the fully connected layer and the
   // softmax run as one persistent kernel (chain.hip) when every pointer allows its vector loads and 256 of its
-  // workgroups are resident at once on this device; its task flags are cleared by the stem kernel.
+  // workgroups are resident at once on this device; its task flags are cleared by the first kernel of the pass
+  // (the stem, alone or fused with block 1).
   bool chain = plan.chain && end_block == 0;
   if (chain) {
     auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
@@ -400,9 +401,9 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
       stem_block_supported(batch, (int)shape[1], (int)shape[2], (int)f0[3], (int)c0, input, weights->conv0_w,
                            weights->conv0_b, weights->dw_w[0], weights->dw_b[0], weights->pw_w[0], weights->pw_b[0],
                            end_block == 1 ? features : buf[0])) {
-    // batch 1: stem and first block in one launch (block.hip); it also clears the chain's task flags
+    // batch 1 to 3: stem and first block in one launch (block.hip); it also clears the chain's task flags
     rc = launch_stem_block(input, weights->conv0_w, weights->conv0_b, weights->dw_w[0], weights->dw_b[0],
-                           weights->pw_w[0], weights->pw_b[0], end_block == 1 ? features : buf[0], (int)shape[1],
+                           weights->pw_w[0], weights->pw_b[0], end_block == 1 ? features : buf[0], (int)batch, (int)shape[1],
                            (int)shape[2], (int)g.out[1],
                            (int)g.out[2], (int)g.pad[0], (int)g.pad[2], (int)c0, TFX_ACT_RELU6,
                            static_cast<hipStream_t>(stream), chain ? static_cast<int*>(chain_ws) : nullptr,
@@ -429,12 +430,12 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
                           static_cast<hipStream_t>(stream));
     const int64_t fd[4] = {3, 3, shape[3], 1};
     const int64_t cout = kChannels[b] * q / 4;
-    // batch 1, thin block: depthwise and pointwise layer in one launch (block.hip)
+    // batch 1 to 3, thin block: depthwise and pointwise layer in one launch (block.hip)
     if (separable_block_supported(batch, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, kStrides[b], buf[cur],
                                   weights->dw_w[b], weights->dw_b[b], weights->pw_w[b], weights->pw_b[b], block_out)) {
       conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
       rc = launch_separable_block(buf[cur], weights->dw_w[b], weights->dw_b[b], weights->pw_w[b], weights->pw_b[b],
-                                  block_out, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, (int)g.out[1],
+                                  block_out, (int)batch, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, (int)g.out[1],
                                   (int)g.out[2], kStrides[b], (int)g.pad[0], (int)g.pad[2], TFX_ACT_RELU6, TFX_ACT_RELU6,
                                   static_cast<hipStream_t>(stream));
       if (rc) return rc;

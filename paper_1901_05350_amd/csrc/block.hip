@@ -1,12 +1,13 @@
-// One depthwise-separable block (depthwise 3x3 + bias + clamp, then pointwise 1x1 + bias + clamp) of a single
-// image as ONE kernel, for the early, thin blocks of the MobileNet of Section 5 / Table 1 at batch 1, where the two
-// layers are bound by being two dependent launches and not by traffic or arithmetic.
+// One depthwise-separable block (depthwise 3x3 + bias + clamp, then pointwise 1x1 + bias + clamp) of one to three
+// images as ONE kernel, for the early, thin blocks of the MobileNet v1 timed in Section 3.9 / Table 1 at batch 1, where
+// the two layers are bound by being two dependent launches and not by traffic or arithmetic.  A second form also
+// computes the network's stem inside the first block's kernel (STEM below).
 //
 // A workgroup owns a 4 x 4 patch of output pixels (= one 16-row matrix-core tile) and NS output channels.  It first
 // copies the input window under the patch (6 x 6 or 9 x 9 pixels, all channels, zeros outside the image) into LDS,
 // each element fetched once: the reads of the previous layer's output are the one long-latency step of the kernel
-// (measured: they cost 3 us per block when every lane fetched its own 9 taps, 4 x redundantly, against 0.7 us for
-// everything else), so they are issued first and kept few.  The input channels are split over WK wavefronts; lane
+// (measured: 3 us per block when every lane fetched its own 9 taps from memory, 4 x redundantly; 0.6 us this way),
+// so they are issued first and kept few.  The input channels are split over WK wavefronts; lane
 // (li, q) of such a wavefront computes the depthwise output of pixel li for the 4 channels that are exactly its A
 // operand of the 16x16x4 fp32 MFMA steps it issues, so the depthwise result goes from the filter arithmetic into the
 // matrix cores without a second trip through LDS or memory; then a split-K reduction of the WK partial tiles
@@ -21,6 +22,9 @@ namespace tfx {
 namespace {
 
 constexpr int kXcds = 8;
+// images per call up to which the fused kernels beat the two single-op kernels (measured on the whole network:
+// 6 us gained at batch 2 and 3, nothing at 4, a loss from 5 on, where the single-op kernels' larger tiles pay)
+constexpr int kMaxFusedBatch = 3;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct BlockArgs {
@@ -31,9 +35,11 @@ struct BlockArgs {
   const float* pw_b;  // [N]
   float* y;           // [OH, OW, N]
   int H, W, OH, OW, pt, pl, N;
-  int tiles_x, slices, total;
+  int tiles_x, tiles_img, slices, total;  // patches per row and per image, column slices, workgroups
+  long long x_img, y_img;                 // floats per input / output image
   int dw_act, pw_act;
-  unsigned x_bytes;
+  int batch;
+  unsigned x_bytes;                       // bytes of one input image
   // STEM form: x is the image [IH, IW, 3]; the block's input [H, W, 32] is the 3x3 stride-2 convolution of the
   // image with st_w [3, 3, 3, 32] + st_b, clamped, and exists only as windows in LDS
   const float* st_w;
@@ -72,7 +78,8 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
   const int xcd = bid % kXcds;
   const int vid = xcd * q8 + (xcd < rem ? xcd : rem) + bid / kXcds;
   const int slice = vid % a.slices, tile = vid / a.slices;
-  const int ty = tile / a.tiles_x, tx = tile % a.tiles_x;
+  const int img_n = tile / a.tiles_img, tile_i = tile % a.tiles_img;
+  const int ty = tile_i / a.tiles_x, tx = tile_i % a.tiles_x;
 
   const int tid = threadIdx.x, wave = tid / 64, wk = wave % WK, wn = wave / WK;
   const int lane = tid % 64, li = lane % 16, q = lane / 16;
@@ -80,7 +87,8 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
   const int n0 = slice * NS;
 
   // the input window: element i = (pixel i / (C/4) of the window, channel quad i % (C/4))
-  const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x), 0, (int)a.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t xr =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x + img_n * a.x_img), 0, (int)a.x_bytes, 0x00020000);
   u32x4 win[LI];
   // STEM: the 13 x 13 x 3 image pixels under the 6 x 6 window of stem outputs, rows of 39 floats; the stem filter
   constexpr int kImgRow = 40, kImgFloats = 13 * 39;
@@ -285,7 +293,7 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
       o[j] = apply_act(sum, pclamp);
     }
     if (py < a.OH && px < a.OW) {
-      float* dst = a.y + (size_t)(py * a.OW + px) * N + n0 + 16 * CB * ewn + CB * (el % 16);
+      float* dst = a.y + img_n * a.y_img + (size_t)(py * a.OW + px) * N + n0 + 16 * CB * ewn + CB * (el % 16);
       if constexpr (CB == 4) *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
       else *reinterpret_cast<float2*>(dst) = make_float2(o[0], o[1]);
     }
@@ -297,7 +305,11 @@ int launch_cfg(BlockArgs a, hipStream_t stream) {
   constexpr int NS = 16 * CB * WN;
   a.tiles_x = (a.OW + 3) / 4;
   a.slices = a.N / NS;
-  a.total = a.tiles_x * ((a.OH + 3) / 4) * a.slices;
+  a.tiles_img = a.tiles_x * ((a.OH + 3) / 4);
+  a.y_img = (long long)a.OH * a.OW * a.N;
+  const long long total = (long long)a.batch * a.tiles_img * a.slices;
+  if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
+  a.total = (int)total;
   hipLaunchKernelGGL((separable_block_kernel<C, WK, WN, CB, S, STEM>), dim3((unsigned)a.total), dim3(64 * WK * WN), 0, stream, a);
   return check_launch();
 }
@@ -307,20 +319,23 @@ int launch_cfg(BlockArgs a, hipStream_t stream) {
 bool separable_block_supported(long long batch, int h, int w, int c, int n, int stride, const void* x, const void* dw_w,
                                const void* dw_b, const void* pw_w, const void* pw_b, const void* y) {
   auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
-  return batch == 1 && (c == 32 || c == 64 || c == 128) && n % 64 == 0 && n >= 64 && n <= 1024 &&
+  return batch >= 1 && batch <= kMaxFusedBatch && (c == 32 || c == 64 || c == 128) && n % 64 == 0 && n >= 64 && n <= 1024 &&
          (stride == 1 || stride == 2) && h >= 1 && w >= 1 && (long long)h * w * c * 4 < (1ll << 31) && al16(x) &&
          al16(dw_w) && al16(dw_b) && al16(pw_w) && al16(pw_b) && al16(y);
 }
 
 int launch_separable_block(const float* x, const float* dw_w, const float* dw_b, const float* pw_w, const float* pw_b,
-                           float* y, int h, int w, int c, int n, int oh, int ow, int stride, int pt, int pl, int dw_act,
-                           int pw_act, hipStream_t stream) {
+                           float* y, int batch, int h, int w, int c, int n, int oh, int ow, int stride, int pt, int pl,
+                           int dw_act, int pw_act, hipStream_t stream) {
   BlockArgs a;
   a.x = x, a.dw_w = dw_w, a.dw_b = dw_b, a.pw_w = pw_w, a.pw_b = pw_b, a.y = y;
   a.H = h, a.W = w, a.OH = oh, a.OW = ow, a.pt = pt, a.pl = pl, a.N = n;
   a.dw_act = dw_act, a.pw_act = pw_act;
+  a.batch = batch;
   a.x_bytes = (unsigned)((long long)h * w * c * 4);
-  a.tiles_x = a.slices = a.total = 0;
+  a.x_img = (long long)h * w * c;
+  a.tiles_x = a.tiles_img = a.slices = a.total = 0;
+  a.y_img = 0;
   a.st_w = a.st_b = nullptr, a.IH = a.IW = a.st_pt = a.st_pl = a.st_act = 0;
   a.zero_words = nullptr, a.zero_count = 0, a.zero_stride = 1;
 #define TFX_BLOCK_CASE(CC, WK, WN, CB)                                       \
@@ -337,20 +352,23 @@ bool stem_block_supported(long long batch, int ih, int iw, int stem_filters, int
                           const void* st_b, const void* dw_w, const void* dw_b, const void* pw_w, const void* pw_b,
                           const void* y) {
   auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
-  return batch == 1 && stem_filters == 32 && n == 64 && ih >= 1 && iw >= 1 && (long long)ih * iw * 3 * 4 < (1ll << 31) &&
+  return batch >= 1 && batch <= kMaxFusedBatch && stem_filters == 32 && n == 64 && ih >= 1 && iw >= 1 && (long long)ih * iw * 3 * 4 < (1ll << 31) &&
          al16(image) && al16(st_w) && al16(st_b) && al16(dw_w) && al16(dw_b) && al16(pw_w) && al16(pw_b) && al16(y);
 }
 
 int launch_stem_block(const float* image, const float* st_w, const float* st_b, const float* dw_w, const float* dw_b,
-                      const float* pw_w, const float* pw_b, float* y, int ih, int iw, int h, int w, int st_pt, int st_pl,
-                      int n, int act, hipStream_t stream, int* zero_words, int zero_count, int zero_stride) {
+                      const float* pw_w, const float* pw_b, float* y, int batch, int ih, int iw, int h, int w, int st_pt,
+                      int st_pl, int n, int act, hipStream_t stream, int* zero_words, int zero_count, int zero_stride) {
   BlockArgs a;
   a.x = image, a.dw_w = dw_w, a.dw_b = dw_b, a.pw_w = pw_w, a.pw_b = pw_b, a.y = y;
   // the block: 3x3 stride-1 depthwise layer with SAME padding (one zero row / column before the map), then 32 -> n
   a.H = h, a.W = w, a.OH = h, a.OW = w, a.pt = 1, a.pl = 1, a.N = n;
   a.dw_act = act, a.pw_act = act;
+  a.batch = batch;
   a.x_bytes = (unsigned)((long long)ih * iw * 3 * 4);
-  a.tiles_x = a.slices = a.total = 0;
+  a.x_img = (long long)ih * iw * 3;
+  a.tiles_x = a.tiles_img = a.slices = a.total = 0;
+  a.y_img = 0;
   a.st_w = st_w, a.st_b = st_b, a.IH = ih, a.IW = iw, a.st_pt = st_pt, a.st_pl = st_pl, a.st_act = act;
   a.zero_words = zero_words, a.zero_count = zero_count, a.zero_stride = zero_stride;
   return launch_cfg<32, 2, 2, 2, 1, true>(a, stream);

@@ -119,23 +119,23 @@ int chain_flag_stride();
 int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, float* probs,
                  float* logits, int classes, hipStream_t stream);
 
-// One depthwise-separable block (depthwise 3x3 + bias + clamp, pointwise 1x1 + bias + clamp) of a single image in
+// One depthwise-separable block (depthwise 3x3 + bias + clamp, pointwise 1x1 + bias + clamp) of up to three images in
 // one launch (block.hip): 32, 64 or 128 input channels, n a multiple of 64, 16-byte aligned pointers.
 bool separable_block_supported(long long batch, int h, int w, int c, int n, int stride, const void* x, const void* dw_w,
                                const void* dw_b, const void* pw_w, const void* pw_b, const void* y);
 int launch_separable_block(const float* x, const float* dw_w, const float* dw_b, const float* pw_w, const float* pw_b,
-                           float* y, int h, int w, int c, int n, int oh, int ow, int stride, int pt, int pl, int dw_act,
-                           int pw_act, hipStream_t stream);
+                           float* y, int batch, int h, int w, int c, int n, int oh, int ow, int stride, int pt, int pl,
+                           int dw_act, int pw_act, hipStream_t stream);
 
 // The stem (3x3 stride-2 convolution of the image [ih, iw, 3] to 32 channels, [h, w, 32]) and the first
-// depthwise-separable block (stride 1, 32 -> n = 64 channels) of a single image in one launch; every layer with
+// depthwise-separable block (stride 1, 32 -> n = 64 channels) of up to three images in one launch; every layer with
 // bias + the activation `act`.  zero_words: as for launch_conv2d_stem.
 bool stem_block_supported(long long batch, int ih, int iw, int stem_filters, int n, const void* image, const void* st_w,
                           const void* st_b, const void* dw_w, const void* dw_b, const void* pw_w, const void* pw_b,
                           const void* y);
 int launch_stem_block(const float* image, const float* st_w, const float* st_b, const float* dw_w, const float* dw_b,
-                      const float* pw_w, const float* pw_b, float* y, int ih, int iw, int h, int w, int st_pt, int st_pl,
-                      int n, int act, hipStream_t stream, int* zero_words, int zero_count, int zero_stride);
+                      const float* pw_w, const float* pw_b, float* y, int batch, int ih, int iw, int h, int w, int st_pt,
+                      int st_pl, int n, int act, hipStream_t stream, int* zero_words, int zero_count, int zero_stride);
 
 // Depthwise convolution: generic kernel and the 3x3 / multiplier-1 / C%4==0 fast path.
 int launch_depthwise(const float* x, const float* w, const float* bias, float* y, int n, int h, int wd, int c,

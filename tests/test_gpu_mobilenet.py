@@ -125,9 +125,11 @@ def test_internal_activations_of_every_block(net):
 
 
 @pytest.mark.parametrize("size,q,batch,blocks", [(100, 4, 1, (1, 2, 3, 4, 7, 13)), (100, 2, 3, (1, 6, 13)),
-                                                 (160, 4, 2, (1, 4, 12)), (32, 4, 1, (1, 2, 3, 4, 5, 13))])
+                                                 (160, 4, 2, (1, 4, 12)), (32, 4, 1, (1, 2, 3, 4, 5, 13)),
+                                                 (72, 4, 3, (1, 2, 3, 4, 13)), (64, 4, 4, (1, 4))])
 def test_internal_activations_of_variants_and_batches(size, q, batch, blocks):
-    """Odd map sizes (ragged 4 x 4 patches of the fused batch-1 kernels), other widths and batches above one."""
+    """Odd map sizes (ragged 4 x 4 patches of the fused kernels, which serve batch 1 to 3), other widths, and batches
+    on both sides of that limit."""
     import paper_1901_05350_amd as tfx
     data = inputs.mobilenet_v1(seed=40 + q, batch=batch, image_size=size, width_quarters=q, classes=10)
     probs, logits, acts = oracle.mobilenet_v1_forward(data["image"], data["weights"], return_activations=True)
