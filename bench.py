@@ -405,9 +405,9 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "MobileNet-v1 1.0/224 forward, batch 1, fp32 NHWC, random He-normal weights (seed 4), "
                                "input uniform[-1,1)",
-                   "launch": "stream enqueue, one C-ABI call per inference = 5 kernel launches (stem + block 1, blocks 2, "
-                             "3 and 4 each as one depthwise+pointwise kernel, one chained kernel for blocks 5-13 + pool + "
-                             "FC + softmax)"},
+                   "launch": "stream enqueue, one C-ABI call per inference = 3 kernel launches (stem + block 1; blocks 2, "
+                             "3 and 4 as three stages of one launch; one chained kernel for blocks 5-13 + pool + FC + "
+                             "softmax)"},
         "ms_per_step_hip_events": round(ms_events, 5),
         "graph_replay_ms_per_inference": None if graph_ms is None else round(graph_ms, 5),
         "paper_table1_ms": {"plain JS (MacBook Pro 2014)": 3426, "WebGL Intel Iris Pro": 49, "WebGL GTX 1080": 5,
@@ -445,7 +445,7 @@ def main():
         # The step's top kernel by time is mobilenet_chain_kernel (blocks 5-13, pool, fully connected layer, softmax
         # in one launch: about 70 % of the step).  The C ABI enqueues it inside the forward call, so its duration is
         # taken as the difference of two graph replays timed with HIP events on the launch stream: the whole forward
-        # pass (5 launches) minus its 4 leading launches (stem + block 1, blocks 2 - 4), which the C ABI runs on
+        # pass (3 launches) minus its 2 leading launches (stem + block 1, blocks 2 - 4), which the C ABI runs on
         # their own as tfx_mobilenet_v1_variant_features(end_block = 4).
         head_in = torch.empty((1, 224, 224, 3), device="cuda:0").uniform_(-1, 1)
         head_out = model.features(head_in, 4)
@@ -465,7 +465,7 @@ def main():
             "launches_per_step": 1, "avg_launch_us": round(t_chain * 1e6, 3),
             "algorithmic_flop": chain_flop, "algorithmic_bytes": chain_bytes,
             "hbm_frac_of_the_same_launch": round(chain_bytes / t_chain / PEAK_HBM, 5),
-            "how_timed": "graph replay of the whole forward pass (%.2f us) minus graph replay of its 4 leading launches "
+            "how_timed": "graph replay of the whole forward pass (%.2f us) minus graph replay of its 2 leading launches "
                          "(%.2f us), HIP events on the launch stream" % (t_full * 1e6, t_head * 1e6),
             "note": "18 dependent convolution layers + pool + FC + softmax at batch 1: bound by the latency of 20 "
                     "producer-consumer steps (1.3-1.8 us each on this GPU), not by a throughput roofline"}
@@ -478,14 +478,14 @@ def main():
                           (27 * 32 + 32) + sum(10 * c for c in (32, 64, 128, 128)) +
                           sum(ci * co + co for ci, co in ((32, 64), (64, 128), (128, 128), (128, 256))))
         out["roofline_other_kernels_of_the_step"] = [
-            {"kernel": "separable_block_kernel: stem + block 1, blocks 2, 3, 4 (4 launches, each a depthwise 3x3 and a "
-                       "pointwise layer)", "bound": "mfma",
+            {"kernel": "separable_block_kernel (stem + block 1) and separable_chain_kernel (blocks 2, 3, 4 as three stages): "
+                       "2 launches, 9 layers", "bound": "mfma",
              "achieved": round(head_flop / t_head / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
-             "frac": round(head_flop / t_head / PEAK_MFMA_F32, 5), "avg_launch_us": round(t_head * 1e6 / 4, 3),
+             "frac": round(head_flop / t_head / PEAK_MFMA_F32, 5), "avg_launch_us": round(t_head * 1e6 / 2, 3),
              "algorithmic_flop": head_flop, "algorithmic_bytes": head_bytes,
              "hbm_frac_of_the_same_launches": round(head_bytes / t_head / PEAK_HBM, 5),
              "the_same_9_layers_as_single_op_launches_us": round(sum(l["us"] for l in head_layers), 2),
-             "note": "bound by four dependent launches (kernel-argument fetch, one round trip for the previous "
+             "note": "bound by four dependent steps (argument fetch or flag hand-over, one round trip for the previous "
                      "block's output, split-K reduction, store), not by a throughput roofline"},
             {"kernel": "all 13 pointwise layers as single-op launches (the multi-kernel path of batch > 1; not part of the batch-1 step)", "bound": "mfma",
              "achieved": round(pw_flop / pw_s / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",

@@ -198,7 +198,7 @@ size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch);
  * pointwise 1x1), bias + ReLU6 after each of the 27 convolutions, SAME padding
  * throughout, global average pool, fully connected 1024 -> 1000, softmax.
  * At batch 1 to 3 the stem and the first block, and each of the next three blocks, are
- * one kernel each; at batch 1 and full width the blocks from the 1/8-size maps on, the pool, the
+ * one kernel each (at batch 1 and full width the three share one launch); at batch 1 and full width the blocks from the 1/8-size maps on, the pool, the
  * fully connected layer and the softmax run as one kernel whose workgroups hand
  * results to each other through flags in the workspace; every wait in it is
  * bounded, and if one ever gives up (a workgroup that never got to run) every
@@ -244,7 +244,10 @@ int tfx_mobilenet_v1_variant_forward(const tfx_mobilenet_v1_variant* variant, co
  * stride-2 block up to end_block (rounded up), c = alpha * that block's pointwise width.
  * The layers up to that block run exactly as in tfx_mobilenet_v1_variant_forward (the
  * batch-1 kernel that chains the last blocks is not used) and nothing after it runs.
- * features: device, 16-byte aligned, written by the last kernel.  weights: the whole
+ * features: device, 16-byte aligned, written by the last kernel.  (Blocks 2 - 4 of the
+ * batch-1 full-width network run as stages of one launch whose workgroups wait for each
+ * other, every wait bounded: a stage that gives up writes NaN, which the later layers
+ * carry along, so an element of `features` is then NaN rather than a wrong number.)  weights: the whole
  * struct must be filled in.  workspace as for the forward pass.  TFX_ERR_ARG for an
  * end_block outside 1 ... 13 or a misaligned features pointer; other errors as the
  * forward pass. */

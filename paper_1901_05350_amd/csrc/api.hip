@@ -93,8 +93,9 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct NetPlan {
   size_t act_floats;  // per ping-pong buffer
-  size_t off_buf[2], off_partial, off_chain, bytes;
+  size_t off_buf[2], off_partial, off_chain, off_head, bytes;
   bool chain;         // the batch-1 full-width network: room for the chained small-map kernel (chain.hip)
+  bool head;          // and for blocks 2 - 4 as stages of one launch (block.hip): their three outputs at once
 };
 
 bool valid_variant(const tfx_mobilenet_v1_variant* v) {
@@ -117,6 +118,12 @@ NetPlan plan_net(const tfx_mobilenet_v1_variant& v, int64_t batch, size_t elem_b
   p.off_chain = off;
   p.chain = elem_bytes == sizeof(float) && chain_supported((int)v.image_size, (int)v.width_quarters, (int)v.classes, batch);
   if (p.chain) off = align_up(off + chain_workspace_bytes((int)v.image_size, (int)v.classes));
+  // blocks 2 - 4 in one launch: the outputs of blocks 2 and 3 share the second ping-pong buffer, the output of block 4
+  // (1/8-size map, 256 channels) gets a region of its own, because block 2 is still reading the first buffer
+  const size_t quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
+  p.off_head = off;
+  p.head = p.chain && 2 * quarter * quarter * 128 <= p.act_floats;
+  if (p.head) off = align_up(off + eighth * eighth * 256 * sizeof(float));
   p.bytes = off;
   return p;
 }
@@ -379,14 +386,17 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
   // softmax run as one persistent kernel (chain.hip) when every pointer allows its vector loads and 256 of its
   // workgroups are resident at once on this device; its task flags are cleared by the first kernel of the pass
   // (the stem, alone or fused with block 1).
-  bool chain = plan.chain && end_block == 0;
-  if (chain) {
+  bool flags_ok = plan.chain;  // the workspace has the flag region, and the kernels that use it may run
+  if (flags_ok) {
     auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
-    chain = al16(input) && al16(weights->conv0_b) && al16(weights->fc_w) && al16(weights->fc_b);
-    for (int i = 0; i < kBlocks && chain; ++i)
-      chain = al16(weights->dw_w[i]) && al16(weights->dw_b[i]) && al16(weights->pw_w[i]) && al16(weights->pw_b[i]);
-    chain = chain && chain_resident();
+    flags_ok = al16(input) && al16(weights->conv0_b) && al16(weights->fc_w) && al16(weights->fc_b);
+    for (int i = 0; i < kBlocks && flags_ok; ++i)
+      flags_ok = al16(weights->dw_w[i]) && al16(weights->dw_b[i]) && al16(weights->pw_w[i]) && al16(weights->pw_b[i]);
+    flags_ok = flags_ok && chain_resident();
   }
+  const bool chain = flags_ok && end_block == 0;
+  // blocks 2 - 4 as stages of one launch (block.hip): in the whole pass and when block 4's output is asked for
+  const bool head_chain = flags_ok && plan.head && (end_block == 0 || end_block == 4);
   void* chain_ws = ws + plan.off_chain;
 
   // stem: 3x3 stride-2 convolution to 32 alpha channels, then the 13 depthwise-separable blocks
@@ -406,8 +416,8 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
                            weights->pw_w[0], weights->pw_b[0], end_block == 1 ? features : buf[0], (int)batch, (int)shape[1],
                            (int)shape[2], (int)g.out[1],
                            (int)g.out[2], (int)g.pad[0], (int)g.pad[2], (int)c0, TFX_ACT_RELU6,
-                           static_cast<hipStream_t>(stream), chain ? static_cast<int*>(chain_ws) : nullptr,
-                           chain ? chain_flag_words((int)variant->image_size, (int)variant->classes) : 0,
+                           static_cast<hipStream_t>(stream), chain || head_chain ? static_cast<int*>(chain_ws) : nullptr,
+                           chain || head_chain ? chain_flag_words((int)variant->image_size, (int)variant->classes) : 0,
                            chain_flag_stride());
     first_block = 1;
   } else if (chain)
@@ -423,10 +433,39 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
   if (first_block == 1) shape[3] = c0;
   if (first_block == 1 && end_block == 1) return TFX_OK;
   int cur = 0;
+  const int head_flags = block_chain_flag_words((int)shape[1], (int)shape[2]);
+  if (head_chain && first_block == 1) {
+    // blocks 2 - 4 as three stages of one launch, then the chained kernel; flags (cleared by the first kernel) and
+    // failure word are shared with it
+    const size_t quarter = (size_t)((shape[1] + 1) / 2);
+    float* const b2_out = buf[1];
+    float* const b3_out = buf[1] + quarter * quarter * 128;
+    float* const b4_out = end_block == 4 ? features : reinterpret_cast<float*>(ws + plan.off_head);
+    if (block_chain_supported(buf[0], b2_out, b3_out, b4_out, weights)) {
+      struct Head {
+        const float* x;
+        float *b2, *b3, *b4;
+        int h, w;
+        const tfx_mobilenet_v1_weights* wt;
+        int* flags;
+        int flag_base;
+        hipStream_t stream;
+      } head{buf[0], b2_out, b3_out, b4_out, (int)shape[1], (int)shape[2], weights, static_cast<int*>(chain_ws),
+             chain_head_flag_base((int)variant->image_size, (int)variant->classes), static_cast<hipStream_t>(stream)};
+      auto launch_head = [](void* p) -> int {
+        const Head& a = *static_cast<const Head*>(p);
+        return launch_block_chain(a.x, a.b2, a.b3, a.b4, a.h, a.w, a.wt, a.flags, a.flag_base, chain_spin_limit(), a.stream);
+      };
+      if (end_block == 4) return launch_ordered(static_cast<hipStream_t>(stream), launch_head, &head);
+      const int eighth = (int)((quarter + 1) / 2);
+      return launch_chain(b4_out, eighth, weights, chain_ws, head_flags, probs, logits, (int)variant->classes,
+                          static_cast<hipStream_t>(stream), launch_head, &head);
+    }
+  }
   for (int b = first_block; b < kBlocks; ++b) {
     float* const block_out = end_block == b + 1 ? features : buf[cur ^ 1];
     if (chain && b == 4)
-      return launch_chain(buf[cur], (int)shape[1], weights, chain_ws, probs, logits, (int)variant->classes,
+      return launch_chain(buf[cur], (int)shape[1], weights, chain_ws, head_flags, probs, logits, (int)variant->classes,
                           static_cast<hipStream_t>(stream));
     const int64_t fd[4] = {3, 3, shape[3], 1};
     const int64_t cout = kChannels[b] * q / 4;

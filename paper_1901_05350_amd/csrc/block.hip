@@ -1,7 +1,8 @@
 // One depthwise-separable block (depthwise 3x3 + bias + clamp, then pointwise 1x1 + bias + clamp) of one to three
 // images as ONE kernel, for the early, thin blocks of the MobileNet v1 timed in Section 3.9 / Table 1 at batch 1, where
 // the two layers are bound by being two dependent launches and not by traffic or arithmetic.  A second form also
-// computes the network's stem inside the first block's kernel (STEM below).
+// computes the network's stem inside the first block's kernel (STEM below); and blocks 2 - 4 of the batch-1 network
+// run as three stages of one launch that hand their patches over through flags (separable_chain_kernel).
 //
 // A workgroup owns a 4 x 4 patch of output pixels (= one 16-row matrix-core tile) and NS output channels.  It first
 // copies the input window under the patch (6 x 6 or 9 x 9 pixels, all channels, zeros outside the image) into LDS,
@@ -25,6 +26,7 @@ constexpr int kXcds = 8;
 // images per call up to which the fused kernels beat the two single-op kernels (measured on the whole network:
 // 6 us gained at batch 2 and 3, nothing at 4, a loss from 5 on, where the single-op kernels' larger tiles pay)
 constexpr int kMaxFusedBatch = 3;
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct BlockArgs {
@@ -49,13 +51,38 @@ struct BlockArgs {
   int zero_count, zero_stride;
 };
 
+// Hand-over between blocks that run as stages of one launch (separable_chain_kernel): a workgroup's patch x slice
+// has a flag word, kLinkFlagStride words apart; the producer sets it after its stores are acknowledged, the consumer
+// polls the flags of the patches under its window.  Activations that move this way use device-coherent (sc1)
+// stores and loads, as in chain.hip.  flags[0] is the failure word shared with the chained kernel that follows.
+constexpr int kLinkFlagStride = 32;
+constexpr int kSc1 = 16;
+struct BlockLink {
+  int* flags;
+  int in_base, in_tiles_x, in_slices;  // producer stage: first flag, patches per row, column slices (in_base < 0: none)
+  int out_base;                        // this stage's first flag (< 0: nobody waits for it inside the launch)
+  int spin_limit;
+};
+
 __device__ __forceinline__ float f4_at(const float4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
 // C input channels, split over WK wavefronts; WN wavefronts side by side over the columns, CB column blocks of 16
 // each: NS = 16 CB WN columns per workgroup.
 // STEM: the block's input is computed from the image on the fly (see BlockArgs).
-template <int C, int WK, int WN, int CB, int S, bool STEM = false>
-__global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const BlockArgs a) {
+// LIN / LOUT: the input was written / the output will be read by another stage of the same launch (see BlockLink).
+// lds: max(kRed, kWin) floats (BlockShape); img, wst: STEM only.
+template <int C, int WK, int WN, int CB, int S>
+struct BlockShape {
+  static constexpr int WH = 3 * S + 3, P = C + 4;
+  static constexpr int kRed = WK * WN * CB * 4 * 64, kWin = WH * WH * P;
+  static constexpr int kLds = kRed > kWin ? kRed : kWin;
+};
+constexpr int kImgRow = 40, kImgFloats = 13 * 39;  // STEM: 13 x 13 x 3 image pixels under a window, rows of 39 floats
+constexpr int kWstRow = 48;  // STEM: floats between filter rows in LDS: lanes q and q + 1 read rows 16 banks apart
+
+template <int C, int WK, int WN, int CB, int S, bool STEM, bool LIN, bool LOUT>
+__device__ __forceinline__ void block_body(const BlockArgs& a, const int bid, float* const lds, float* const img,
+                                           float* const wst, const BlockLink& L, int* const gave_up) {
   constexpr int NT = 64 * WK * WN;
   constexpr int G = C / (16 * WK);  // groups of 16 channels per wavefront
   constexpr int NS = 16 * CB * WN;
@@ -66,14 +93,11 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
   constexpr int P = C + 4;                   // floats between window pixels in LDS
   constexpr int WQ = WH * WH * (C / 4);      // float4 elements of the window
   constexpr int LI = (WQ + NT - 1) / NT;     // of which a thread copies at most LI
-  constexpr int kRed = WK * WN * CB * 4 * 64, kWin = WH * WH * P;
-  // the window, and after the MFMAs the partial tiles [wk][wn][j][v][lane]
-  __shared__ __align__(16) float lds[kRed > kWin ? kRed : kWin];
-  float* const red = lds;
+  static_assert(!(STEM && LIN), "the stem form reads the image");
+  float* const red = lds;  // the window, and after the MFMAs the partial tiles [wk][wn][j][v][lane]
 
   // workgroups are dealt to the XCDs round robin: give every XCD a contiguous run of patches (shared halos and
   // the slices of one patch then meet in one L2)
-  const int bid = blockIdx.x;
   const int q8 = a.total / kXcds, rem = a.total % kXcds;
   const int xcd = bid % kXcds;
   const int vid = xcd * q8 + (xcd < rem ? xcd : rem) + bid / kXcds;
@@ -90,11 +114,6 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
   const __amdgpu_buffer_rsrc_t xr =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x + img_n * a.x_img), 0, (int)a.x_bytes, 0x00020000);
   u32x4 win[LI];
-  // STEM: the 13 x 13 x 3 image pixels under the 6 x 6 window of stem outputs, rows of 39 floats; the stem filter
-  constexpr int kImgRow = 40, kImgFloats = 13 * 39;
-  __shared__ float img[STEM ? 13 * kImgRow : 1];
-  constexpr int kWstRow = 48;  // floats between filter rows in LDS: lanes q and q + 1 read rows 16 banks apart
-  __shared__ __align__(16) float wst[STEM ? 28 * kWstRow : 4];  // [27][32 of 48] filter, [32] bias
   float iv[2];
   float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
   const int sy0 = 4 * ty - a.pt, sx0 = 4 * tx - a.pl;  // STEM: first row / column of the window in the stem's output
@@ -111,8 +130,9 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
     else if (tid < 28 * 8) wv = *reinterpret_cast<const float4*>(a.st_b + 4 * (tid - 27 * 8));
     if (a.zero_count > 0)
       for (int i = bid * NT + tid; i < a.zero_count; i += a.total * NT) a.zero_words[(size_t)i * a.zero_stride] = 0;
-  } else {
-    const int wy0 = 4 * ty * S - a.pt, wx0 = 4 * tx * S - a.pl;
+  }
+  const int wy0 = 4 * ty * S - a.pt, wx0 = 4 * tx * S - a.pl;
+  auto load_window = [&]() {
 #pragma unroll
     for (int i = 0; i < LI; ++i) {
       const int e = tid + i * NT, p = e / (C / 4), cq = e % (C / 4);
@@ -120,9 +140,10 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
       // outside the image (or past the window): past the end of the buffer, the hardware returns 0
       const bool in = e < WQ && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
       const unsigned off = in ? (unsigned)((iy * a.W + ix) * C + 4 * cq) * 4u : 0x80000000u;
-      win[i] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)off, 0, 0);
+      win[i] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)off, 0, LIN ? kSc1 : 0);
     }
-  }
+  };
+  if constexpr (!STEM && !LIN) load_window();  // first thing in flight; a linked stage fetches it after its wait
   (void)win;
 
   // pointwise filter columns of this lane: rows wk 16 G + 16 g + 4 q + s, columns n0 + 16 CB wn + CB li ...
@@ -163,6 +184,42 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
 #pragma unroll
     for (int t = 0; t < 9; ++t) dwf[g][t] = *reinterpret_cast<const float4*>(a.dw_w + t * C + c4 + 16 * g);
   }
+
+  if constexpr (LIN) {
+    // the producer patches under the window (its rows and columns inside the map), every column slice: one flag per
+    // lane of wavefront 0; bounded, a wait that gives up sets the failure word and ends every other wait
+    if (wave == 0) {
+      const int r_lo = max(wy0, 0) / 4, r_hi = min(wy0 + WH - 1, a.H - 1) / 4;
+      const int c_lo = max(wx0, 0) / 4, c_hi = min(wx0 + WH - 1, a.W - 1) / 4;
+      const int nc = c_hi - c_lo + 1, n = (r_hi - r_lo + 1) * nc * L.in_slices;
+      const int rows_in = (a.H + 3) / 4;
+      bool bad = false;
+      for (int i = lane; i < n; i += 64) {
+        const int r = r_lo + i / (nc * L.in_slices), c = c_lo + (i / L.in_slices) % nc, sl = i % L.in_slices;
+        const int* f = L.flags + (size_t)(L.in_base + ((img_n * rows_in + r) * L.in_tiles_x + c) * L.in_slices + sl) * kLinkFlagStride;
+        int spin = 0;
+        while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+          if (++spin > L.spin_limit) {
+            __hip_atomic_store(L.flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            bad = true;
+            break;
+          }
+          if ((spin & 255) == 0 && __hip_atomic_load(L.flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+            bad = true;
+            break;
+          }
+          __builtin_amdgcn_s_sleep(1);
+        }
+      }
+      const bool any_bad = __ballot(bad) != 0;
+      if (lane == 0) *gave_up = any_bad ? 1 : 0;
+    }
+    __syncthreads();
+    load_window();
+  }
+  // a stage that did not get all of its input writes NaN: every later layer then carries the NaN to the end of
+  // the network (the clamps pass NaN on), so an unfinished hand-over cannot yield plausible numbers
+  const bool poison = LIN ? *gave_up != 0 : false;
 
   if constexpr (STEM) {
     // image pixels and stem filter -> LDS, then the stem's output for the window; window pixels outside the stem's
@@ -290,14 +347,68 @@ __global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const Blo
       float sum = ebias[i][j];
 #pragma unroll
       for (int w = 0; w < WK; ++w) sum += red[(((w * WN + ewn) * CB + j) * 4 + ev) * 64 + el];
-      o[j] = apply_act(sum, pclamp);
+      o[j] = poison ? __uint_as_float(0x7fc00000u) : apply_act(sum, pclamp);
     }
     if (py < a.OH && px < a.OW) {
-      float* dst = a.y + img_n * a.y_img + (size_t)(py * a.OW + px) * N + n0 + 16 * CB * ewn + CB * (el % 16);
-      if constexpr (CB == 4) *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
-      else *reinterpret_cast<float2*>(dst) = make_float2(o[0], o[1]);
+      const size_t at = (size_t)(py * a.OW + px) * N + n0 + 16 * CB * ewn + CB * (el % 16);
+      float* dst = a.y + img_n * a.y_img + at;
+      if constexpr (LOUT) {
+        // device-coherent store (write-through: visible to the consumer's sc1 loads on any XCD)
+        const __amdgpu_buffer_rsrc_t yr =
+            __builtin_amdgcn_make_buffer_rsrc(a.y + img_n * a.y_img, 0, (int)(a.y_img * 4), 0x00020000);
+        if constexpr (CB == 4) {
+          u32x4 v;
+          v.x = __float_as_uint(o[0]), v.y = __float_as_uint(o[1]), v.z = __float_as_uint(o[2]), v.w = __float_as_uint(o[3]);
+          __builtin_amdgcn_raw_buffer_store_b128(v, yr, (int)(at * 4), 0, kSc1);
+        } else {
+          u32x2 v;
+          v.x = __float_as_uint(o[0]), v.y = __float_as_uint(o[1]);
+          __builtin_amdgcn_raw_buffer_store_b64(v, yr, (int)(at * 4), 0, kSc1);
+        }
+      } else {
+        if constexpr (CB == 4) *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
+        else *reinterpret_cast<float2*>(dst) = make_float2(o[0], o[1]);
+      }
     }
   }
+  if constexpr (LOUT) {
+    // stores acknowledged, everybody there, then the flag of (patch, slice)
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0)
+      __hip_atomic_store(L.flags + (size_t)(L.out_base + tile * a.slices + slice) * kLinkFlagStride, 1, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+template <int C, int WK, int WN, int CB, int S, bool STEM = false>
+__global__ __launch_bounds__(64 * WK * WN) void separable_block_kernel(const BlockArgs a) {
+  __shared__ __align__(16) float lds[BlockShape<C, WK, WN, CB, S>::kLds];
+  __shared__ float img[STEM ? 13 * kImgRow : 1];
+  __shared__ __align__(16) float wst[STEM ? 28 * kWstRow : 4];  // [27][32 of 48] filter, [32] bias
+  block_body<C, WK, WN, CB, S, STEM, false, false>(a, blockIdx.x, lds, img, wst, BlockLink{}, nullptr);
+}
+
+// Blocks 2, 3 and 4 of the batch-1 network (64 -> 128 at stride 2, 128 -> 128 at stride 1, 128 -> 256 at stride 2)
+// as three stages of one launch: workgroups [0, first[1]) are block 2's, [first[1], first[2]) block 3's, the rest
+// block 4's; a stage's workgroup waits for the flags of the patches under its window instead of for a kernel
+// boundary, and has fetched its arguments and filters by then.  Workgroups start in the order of their ids, so a
+// waiting workgroup never keeps its producers from starting; every wait is bounded all the same.
+struct BlockChainArgs {
+  BlockArgs blk[3];
+  BlockLink link[3];
+  int first[3];
+};
+constexpr int kChainLds = BlockShape<128, 8, 1, 4, 2>::kLds;
+static_assert(kChainLds >= BlockShape<64, 4, 2, 2, 2>::kLds && kChainLds >= BlockShape<128, 8, 1, 4, 1>::kLds, "LDS of the widest stage");
+__global__ __launch_bounds__(512) void separable_chain_kernel(const BlockChainArgs h) {
+  __shared__ __align__(16) float lds[kChainLds];
+  __shared__ int gave_up;
+  const int bid = blockIdx.x;
+  if (bid < h.first[1]) block_body<64, 4, 2, 2, 2, false, false, true>(h.blk[0], bid, lds, nullptr, nullptr, h.link[0], &gave_up);
+  else if (bid < h.first[2])
+    block_body<128, 8, 1, 4, 1, false, true, true>(h.blk[1], bid - h.first[1], lds, nullptr, nullptr, h.link[1], &gave_up);
+  else block_body<128, 8, 1, 4, 2, false, true, false>(h.blk[2], bid - h.first[2], lds, nullptr, nullptr, h.link[2], &gave_up);
 }
 
 template <int C, int WK, int WN, int CB, int S, bool STEM = false>
@@ -372,6 +483,68 @@ int launch_stem_block(const float* image, const float* st_w, const float* st_b, 
   a.st_w = st_w, a.st_b = st_b, a.IH = ih, a.IW = iw, a.st_pt = st_pt, a.st_pl = st_pl, a.st_act = act;
   a.zero_words = zero_words, a.zero_count = zero_count, a.zero_stride = zero_stride;
   return launch_cfg<32, 2, 2, 2, 1, true>(a, stream);
+}
+
+// ---- blocks 2 - 4 of a single full-width image as one launch ----
+namespace {
+BlockArgs plain_args(const float* x, const float* dw_w, const float* dw_b, const float* pw_w, const float* pw_b, float* y,
+                     int h, int w, int c, int n, int stride, int ns) {
+  BlockArgs a;
+  a.x = x, a.dw_w = dw_w, a.dw_b = dw_b, a.pw_w = pw_w, a.pw_b = pw_b, a.y = y;
+  a.H = h, a.W = w, a.OH = (h + stride - 1) / stride, a.OW = (w + stride - 1) / stride, a.N = n;
+  // SAME padding of a 3-tap filter: the odd unit goes after the map
+  const int need_h = (a.OH - 1) * stride + 3 - h, need_w = (a.OW - 1) * stride + 3 - w;
+  a.pt = need_h > 0 ? need_h / 2 : 0, a.pl = need_w > 0 ? need_w / 2 : 0;
+  a.dw_act = a.pw_act = TFX_ACT_RELU6;
+  a.batch = 1;
+  a.x_bytes = (unsigned)((long long)h * w * c * 4);
+  a.x_img = (long long)h * w * c;
+  a.tiles_x = (a.OW + 3) / 4;
+  a.tiles_img = a.tiles_x * ((a.OH + 3) / 4);
+  a.slices = n / ns;
+  a.total = a.tiles_img * a.slices;
+  a.y_img = (long long)a.OH * a.OW * n;
+  a.st_w = a.st_b = nullptr, a.IH = a.IW = a.st_pt = a.st_pl = a.st_act = 0;
+  a.zero_words = nullptr, a.zero_count = 0, a.zero_stride = 1;
+  return a;
+}
+}  // namespace
+
+int block_chain_flag_stride() { return kLinkFlagStride; }
+
+// Flags the chained launch needs for a first map of h x w pixels: one per (patch, slice) of its first two stages.
+int block_chain_flag_words(int h, int w) {
+  const int oh = (h + 1) / 2, ow = (w + 1) / 2;
+  return 2 * 2 * ((oh + 3) / 4) * ((ow + 3) / 4);
+}
+
+// x: [h, w, 64], the output of block 1; b2_out / b3_out: [ceil(h/2), ceil(w/2), 128]; y: the output of block 4,
+// [ceil(h/4), ceil(w/4), 256] (sizes rounded up at each halving).  flags: block_chain_flag_words() words from index
+// flag_base on, block_chain_flag_stride() words apart, zero when the kernel starts; word 0 is the failure word.
+bool block_chain_supported(const void* x, const void* b2_out, const void* b3_out, const void* y,
+                           const tfx_mobilenet_v1_weights* w) {
+  auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
+  bool ok = al16(x) && al16(b2_out) && al16(b3_out) && al16(y);
+  for (int i = 1; i <= 3 && ok; ++i) ok = al16(w->dw_w[i]) && al16(w->dw_b[i]) && al16(w->pw_w[i]) && al16(w->pw_b[i]);
+  return ok;
+}
+
+int launch_block_chain(const float* x, float* b2_out, float* b3_out, float* y, int h, int w,
+                       const tfx_mobilenet_v1_weights* wt, int* flags, int flag_base, int spin_limit,
+                       hipStream_t stream) {
+  BlockChainArgs c;
+  c.blk[0] = plain_args(x, wt->dw_w[1], wt->dw_b[1], wt->pw_w[1], wt->pw_b[1], b2_out, h, w, 64, 128, 2, 64);
+  const int h2 = c.blk[0].OH, w2 = c.blk[0].OW;
+  c.blk[1] = plain_args(b2_out, wt->dw_w[2], wt->dw_b[2], wt->pw_w[2], wt->pw_b[2], b3_out, h2, w2, 128, 128, 1, 64);
+  c.blk[2] = plain_args(b3_out, wt->dw_w[3], wt->dw_b[3], wt->pw_w[3], wt->pw_b[3], y, h2, w2, 128, 256, 2, 64);
+  c.first[0] = 0, c.first[1] = c.blk[0].total, c.first[2] = c.blk[0].total + c.blk[1].total;
+  const int f0 = flag_base, f1 = flag_base + c.blk[0].total;
+  c.link[0] = BlockLink{flags, -1, 0, 0, f0, spin_limit};
+  c.link[1] = BlockLink{flags, f0, c.blk[0].tiles_x, c.blk[0].slices, f1, spin_limit};
+  c.link[2] = BlockLink{flags, f1, c.blk[1].tiles_x, c.blk[1].slices, -1, spin_limit};
+  const int total = c.first[2] + c.blk[2].total;
+  hipLaunchKernelGGL(separable_chain_kernel, dim3((unsigned)total), dim3(512), 0, stream, c);
+  return check_launch();
 }
 
 }  // namespace tfx

@@ -565,15 +565,29 @@ ChainPlanHost chain_layout(int in_hw, int classes, ChainParams* P) {
 size_t chain_workspace_bytes(int image_size, int classes) {
   const int half = (image_size + 1) / 2, quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
   const ChainPlanHost h = chain_layout(eighth, classes, nullptr);
-  const size_t flag_bytes = (size_t)h.flags * kFlagStride * sizeof(int);
+  const size_t flag_bytes = (size_t)(h.flags + block_chain_flag_words(half, half)) * kFlagStride * sizeof(int);
   return flag_bytes + (h.act_floats * sizeof(float) + 255) / 256 * 256;
 }
 
 // The flags at the start of the chain workspace: `count` words, chain_flag_stride() words apart, that must be zero
-// when the chain kernel starts.
+// when the first kernel that uses them starts: the chain kernel's own (word 0 = failure word), then, from
+// chain_head_flag_base() on, those of the launch that runs blocks 2 - 4 as stages (block.hip).
 int chain_flag_words(int image_size, int classes) {
   const int half = (image_size + 1) / 2, quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
+  return chain_layout(eighth, classes, nullptr).flags + block_chain_flag_words(half, half);
+}
+int chain_head_flag_base(int image_size, int classes) {
+  const int half = (image_size + 1) / 2, quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
   return chain_layout(eighth, classes, nullptr).flags;
+}
+int chain_spin_limit() {
+  // Test hook: TFX_CHAIN_SPIN_LIMIT=<n> makes every wait give up after n polls, which exercises the failure
+  // path (all outputs NaN, the kernels still run to their end) without any workgroup actually missing.
+  if (const char* e = getenv("TFX_CHAIN_SPIN_LIMIT")) {
+    const long v = strtol(e, nullptr, 10);
+    if (v >= 1 && v <= kSpinLimit) return (int)v;
+  }
+  return kSpinLimit;
 }
 int chain_flag_stride() { return kFlagStride; }
 
@@ -610,8 +624,18 @@ void order_after_other_streams(int dev, hipStream_t stream) {
 }
 }  // namespace
 
-int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, float* probs,
-                 float* logits, int classes, hipStream_t stream) {
+// Runs fn(arg) -- which enqueues a kernel whose workgroups wait for each other -- once `stream` has been ordered behind
+// the last such kernel of any other stream.
+int launch_ordered(hipStream_t stream, int (*fn)(void*), void* arg) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return TFX_ERR_LAUNCH;
+  std::lock_guard<std::mutex> guard(g_order.lock);
+  order_after_other_streams(dev, stream);
+  return fn(arg);
+}
+
+int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, int head_flags,
+                 float* probs, float* logits, int classes, hipStream_t stream, int (*before)(void*), void* before_arg) {
   ChainParams P{};
   const ChainPlanHost h = chain_layout(in_hw, classes, &P);
   for (int bi = 0; bi < kChainBlocks; ++bi) {
@@ -621,7 +645,7 @@ int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w,
     P.blk[bi].pw_w = w->pw_w[net];
     P.blk[bi].pw_b = w->pw_b[net];
   }
-  const size_t flag_bytes = (size_t)h.flags * kFlagStride * sizeof(int);
+  const size_t flag_bytes = (size_t)(h.flags + head_flags) * kFlagStride * sizeof(int);
   P.in0 = in0;
   P.in0_bytes = (unsigned)((size_t)in_hw * in_hw * kNetChannels[kFirstChainBlock - 1] * sizeof(float));
   P.flags = static_cast<int*>(chain_ws);
@@ -631,17 +655,17 @@ int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w,
   P.fc_b = w->fc_b;
   P.probs = probs;
   P.logits = logits;
-  // Test hook: TFX_CHAIN_SPIN_LIMIT=<n> makes every wait give up after n polls, which exercises the failure
-  // path (all outputs NaN, the kernel still runs to its end) without any workgroup actually missing.
-  P.spin_limit = kSpinLimit;
-  if (const char* e = getenv("TFX_CHAIN_SPIN_LIMIT")) {
-    const long v = strtol(e, nullptr, 10);
-    if (v >= 1 && v <= kSpinLimit) P.spin_limit = (int)v;
-  }
+  P.spin_limit = chain_spin_limit();
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return TFX_ERR_LAUNCH;
   std::lock_guard<std::mutex> guard(g_order.lock);
   order_after_other_streams(dev, stream);
+  // a launch of waiting workgroups that belongs in front of this one (blocks 2 - 4 as stages, block.hip) is enqueued
+  // under the same lock, so that the pair is ordered against other streams' pairs as one
+  if (before != nullptr) {
+    const int rc = before(before_arg);
+    if (rc != TFX_OK) return rc;
+  }
   hipLaunchKernelGGL(mobilenet_chain_kernel, dim3(kChainGrid), dim3(kChainThreads), 0, stream, P);
   return check_launch();
 }

@@ -115,9 +115,29 @@ bool chain_supported(int image_size, int width_quarters, int classes, long long 
 bool chain_resident();
 size_t chain_workspace_bytes(int image_size, int classes);
 int chain_flag_words(int image_size, int classes);
+int chain_head_flag_base(int image_size, int classes);
 int chain_flag_stride();
-int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, float* probs,
-                 float* logits, int classes, hipStream_t stream);
+int chain_spin_limit();
+// head_flags: flag words behind the chain kernel's own at the start of chain_ws (block_chain_flag_words).
+// before(before_arg), if given, enqueues a launch that has to stay directly in front of the chain kernel on `stream`
+// (it is called once the stream has been ordered behind other streams' chain kernels) and returns a tfx_status.
+int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, int head_flags,
+                 float* probs, float* logits, int classes, hipStream_t stream, int (*before)(void*) = nullptr,
+                 void* before_arg = nullptr);
+// fn(arg) enqueues a kernel of waiting workgroups on `stream`; the stream is first ordered behind the last such
+// kernel of any other stream (two of them side by side could each hold the CUs the other's producers need).
+int launch_ordered(hipStream_t stream, int (*fn)(void*), void* arg);
+
+// Blocks 2 - 4 of a single full-width image (64 -> 128 /2, 128 -> 128, 128 -> 256 /2) as three stages of one launch
+// that hand results over through flags (block.hip).  x: [h, w, 64]; b2_out, b3_out: [ceil(h/2), ceil(w/2), 128];
+// y: [ceil(h/4), ceil(w/4), 256] (halvings round up).  flags: word 0 = failure word; block_chain_flag_words(h, w)
+// words from flag_base on, block_chain_flag_stride() words apart, zero when the kernel starts.
+int block_chain_flag_stride();
+int block_chain_flag_words(int h, int w);
+bool block_chain_supported(const void* x, const void* b2_out, const void* b3_out, const void* y,
+                           const tfx_mobilenet_v1_weights* w);
+int launch_block_chain(const float* x, float* b2_out, float* b3_out, float* y, int h, int w,
+                       const tfx_mobilenet_v1_weights* wt, int* flags, int flag_base, int spin_limit, hipStream_t stream);
 
 // One depthwise-separable block (depthwise 3x3 + bias + clamp, pointwise 1x1 + bias + clamp) of up to three images in
 // one launch (block.hip): 32, 64 or 128 input channels, n a multiple of 64, 16-byte aligned pointers.

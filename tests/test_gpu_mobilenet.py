@@ -277,6 +277,26 @@ def test_chained_kernel_bounded_waits_give_up_and_report_nan(net, monkeypatch):
     assert_close(host(p), probs, "probs after a failed call")
 
 
+def test_chained_blocks_that_give_up_write_nan_not_numbers(net, monkeypatch):
+    """Blocks 2 - 4 run as stages of one launch that wait for each other's patches.  With the waits cut to one poll,
+    a stage that went ahead without its input must write NaN: every element of block 4's output is then either
+    NaN or exactly the value of an undisturbed run, never a number computed from unfinished data."""
+    import paper_1901_05350_amd as tfx
+    data, probs, logits, acts = net
+    model = tfx.MobileNetV1(data["weights"], batch=1)
+    image = dev(data["image"])
+    good = host(model.features(image, 4)).copy()
+    assert_close(good, acts[8], "features after block 4")
+    monkeypatch.setenv("TFX_CHAIN_SPIN_LIMIT", "1")
+    cut = host(model.features(image, 4))
+    monkeypatch.delenv("TFX_CHAIN_SPIN_LIMIT")
+    bad = np.isnan(cut)
+    assert bad.any()
+    assert np.array_equal(cut[~bad], good[~bad])
+    again = host(model.features(image, 4))
+    assert np.array_equal(again, good)
+
+
 def test_two_chained_kernels_on_two_streams_at_once(net):
     """Two batch-1 forward passes issued from two host threads on two streams: the chained kernels would compete for
     the CUs (neither grid fully resident, each waiting for workgroups the other keeps out), so the library orders
