@@ -30,20 +30,20 @@ PEAK_HBM = 8.0e12          # B/s
 # source it was measured on, with the digest of that file followed by the shared header csrc/tfx_internal.h;
 # if either has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100844399, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
-    "pointwise_64x56x56x128_to_128": (206178088, "pointwise.hip", "1cca37ebed9cc6e9f04eec68e56ee5e10e3d9925ca61d49d80b2bc9ac3d8fa5a"),
-    "conv3x3_64x56x56x64_to_64": (104505599, "gemm.hip", "4fbcd682ca1f4892ebebc7c3db51e84cb91909a6116071a050ac4c7c5e144b1b"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411136548, "depthwise.hip", "d0c8f0243a54a675029dc6f1640e6db7ee3f0dfefd34825c8c07514b9be676b1"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (256999270, "depthwise.hip", "d0c8f0243a54a675029dc6f1640e6db7ee3f0dfefd34825c8c07514b9be676b1"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235069753, "gemm_f16.hip", "54fd5820b9ce4de4f4ee13d8adf6330f797356f7585cabbfdb6a2b6e6f2b2bb9"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50489470, "gemm_f16.hip", "54fd5820b9ce4de4f4ee13d8adf6330f797356f7585cabbfdb6a2b6e6f2b2bb9"),
-    "pointwise_f16_64x56x56x128_to_128": (103141721, "pointwise_f16.hip", "cf4c2e12e5128b41a9520de40fd6d6562d9c0d441b35d4747031b2c3a0c7254e"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205674357, "conv_f16.hip", "1da80b607e0312d1634038566ab217a2c08dd99a0db058212dcfd5797d56795b"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (128537295, "conv_f16.hip", "1da80b607e0312d1634038566ab217a2c08dd99a0db058212dcfd5797d56795b"),
-    "conv3x3_f16_64x56x56x64_to_64": (52068243, "conv_gemm_f16.hip", "0c434b66d6367e415ef2333183a421be78368ab414a1dedd278457301abe4bab"),
-    "add_f32_64M": (805262532, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
-    "add_f16_64M": (402651589, "elementwise.hip", "be3e80a4e0d81125abeb7ac79001cba32c98643cdc019fe43f28cedb2cff55fd"),
-    "mobilenet_chain_kernel": (0, "chain.hip", "0000000000000000000000000000000000000000000000000000000000000000"),
+    "batch_matmul_8x1024x1024x1024_tB": (100848608, "gemm.hip", "6b22134bf8be53a4344d54dce3d588ddc51705e551ff19499064e76916121455"),
+    "pointwise_64x56x56x128_to_128": (206184520, "pointwise.hip", "d14344ed633834dc66a8c26d14b0747f2648d97cbc1b2542660efe0ad92fbd7d"),
+    "conv3x3_64x56x56x64_to_64": (104544071, "gemm.hip", "6b22134bf8be53a4344d54dce3d588ddc51705e551ff19499064e76916121455"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411139371, "depthwise.hip", "21afbd7a8438f6a4e54cf88458a5cba73b8dba0d6e080412ab81bb029cf369fc"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (257142359, "depthwise.hip", "21afbd7a8438f6a4e54cf88458a5cba73b8dba0d6e080412ab81bb029cf369fc"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235078293, "gemm_f16.hip", "3916e946462eaf13407507e51350ec1d791da354dfe6f961891ac4039cfd9771"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50493682, "gemm_f16.hip", "3916e946462eaf13407507e51350ec1d791da354dfe6f961891ac4039cfd9771"),
+    "pointwise_f16_64x56x56x128_to_128": (103142592, "pointwise_f16.hip", "8e0f20fefbe9b93e62289716cfabf6a7a04ed04fba8f42aa60627afd9ee457b5"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205682028, "conv_f16.hip", "5df04c5c265a714b281a9a709d65faf265405e1c89e83500b4fda066825e0143"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129465370, "conv_f16.hip", "5df04c5c265a714b281a9a709d65faf265405e1c89e83500b4fda066825e0143"),
+    "conv3x3_f16_64x56x56x64_to_64": (52067283, "conv_gemm_f16.hip", "1139a888e5f8da4a856214969db4e3377fb03413ab18e1b1a7995ddeb8bcb48c"),
+    "add_f32_64M": (805263147, "elementwise.hip", "2f65a6b02bcffa69fbee6ad9a7b26e1833afa43a41ec5c0e818ae8ba1ed975ee"),
+    "add_f16_64M": (402651830, "elementwise.hip", "2f65a6b02bcffa69fbee6ad9a7b26e1833afa43a41ec5c0e818ae8ba1ed975ee"),
+    "mobilenet_chain_kernel": (129048187, "chain.hip", "6eea2273ccc08aadc8862665d1bf4577656b25a947107bb10644163dc196d1ea"),
 }
 
 
