@@ -30,20 +30,20 @@ PEAK_HBM = 8.0e12          # B/s
 # source it was measured on, with the digest of that file followed by the shared header csrc/tfx_internal.h;
 # if either has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100848608, "gemm.hip", "6b22134bf8be53a4344d54dce3d588ddc51705e551ff19499064e76916121455"),
-    "pointwise_64x56x56x128_to_128": (206184520, "pointwise.hip", "d14344ed633834dc66a8c26d14b0747f2648d97cbc1b2542660efe0ad92fbd7d"),
-    "conv3x3_64x56x56x64_to_64": (104544071, "gemm.hip", "6b22134bf8be53a4344d54dce3d588ddc51705e551ff19499064e76916121455"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411139371, "depthwise.hip", "21afbd7a8438f6a4e54cf88458a5cba73b8dba0d6e080412ab81bb029cf369fc"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (257142359, "depthwise.hip", "21afbd7a8438f6a4e54cf88458a5cba73b8dba0d6e080412ab81bb029cf369fc"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235078293, "gemm_f16.hip", "3916e946462eaf13407507e51350ec1d791da354dfe6f961891ac4039cfd9771"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50493682, "gemm_f16.hip", "3916e946462eaf13407507e51350ec1d791da354dfe6f961891ac4039cfd9771"),
-    "pointwise_f16_64x56x56x128_to_128": (103142592, "pointwise_f16.hip", "8e0f20fefbe9b93e62289716cfabf6a7a04ed04fba8f42aa60627afd9ee457b5"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205682028, "conv_f16.hip", "5df04c5c265a714b281a9a709d65faf265405e1c89e83500b4fda066825e0143"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129465370, "conv_f16.hip", "5df04c5c265a714b281a9a709d65faf265405e1c89e83500b4fda066825e0143"),
-    "conv3x3_f16_64x56x56x64_to_64": (52067283, "conv_gemm_f16.hip", "1139a888e5f8da4a856214969db4e3377fb03413ab18e1b1a7995ddeb8bcb48c"),
-    "add_f32_64M": (805263147, "elementwise.hip", "2f65a6b02bcffa69fbee6ad9a7b26e1833afa43a41ec5c0e818ae8ba1ed975ee"),
-    "add_f16_64M": (402651830, "elementwise.hip", "2f65a6b02bcffa69fbee6ad9a7b26e1833afa43a41ec5c0e818ae8ba1ed975ee"),
-    "mobilenet_chain_kernel": (129048187, "chain.hip", "6eea2273ccc08aadc8862665d1bf4577656b25a947107bb10644163dc196d1ea"),
+    "batch_matmul_8x1024x1024x1024_tB": (100848539, "gemm.hip", "3fa4fe7252aa5ee9b70ad6fffb6606e5bc3bfdfa35abf46537c5b4f8bf58eed3"),
+    "pointwise_64x56x56x128_to_128": (206184248, "pointwise.hip", "d29ff7ac20207d82db0222a405a62aa350d84727111a916456ea902730817a1d"),
+    "conv3x3_64x56x56x64_to_64": (104546322, "gemm.hip", "3fa4fe7252aa5ee9b70ad6fffb6606e5bc3bfdfa35abf46537c5b4f8bf58eed3"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411139607, "depthwise.hip", "aa1aeba44211fa898801c5afd4978534d78f5975686a5c208ba1642af7fd1c41"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (257118310, "depthwise.hip", "aa1aeba44211fa898801c5afd4978534d78f5975686a5c208ba1642af7fd1c41"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235078045, "gemm_f16.hip", "80aa83df2fd240f4f1fd0f7638f758b1c1abb7a0113ff8b09f40ad18172deb5f"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50493585, "gemm_f16.hip", "80aa83df2fd240f4f1fd0f7638f758b1c1abb7a0113ff8b09f40ad18172deb5f"),
+    "pointwise_f16_64x56x56x128_to_128": (103142521, "pointwise_f16.hip", "1856081f98a1d76163860cb4e20ff6f928268e86cd51ffa5d066932f03d3980b"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205682055, "conv_f16.hip", "ede4c45279dd7783bcd5846123d1372e2e7f064b7169dcc371c50a13f9ffffd3"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129310122, "conv_f16.hip", "ede4c45279dd7783bcd5846123d1372e2e7f064b7169dcc371c50a13f9ffffd3"),
+    "conv3x3_f16_64x56x56x64_to_64": (52067265, "conv_gemm_f16.hip", "bed8ce3dd5921dd131300d70423098bea6cb3c532bf49841b7fd8778284d423c"),
+    "add_f32_64M": (805262682, "elementwise.hip", "085f35045800c64ab32340bde100d08fabb0cbde23f7496b22b9014f58eba22f"),
+    "add_f16_64M": (402651813, "elementwise.hip", "085f35045800c64ab32340bde100d08fabb0cbde23f7496b22b9014f58eba22f"),
+    "mobilenet_chain_kernel": (121667068, "chain.hip", "39c2ecddb28a12c15d3ce41f5debc26b6e7c2583e9eda1fc657f146402c00ab3"),
 }
 
 
@@ -405,9 +405,9 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "MobileNet-v1 1.0/224 forward, batch 1, fp32 NHWC, random He-normal weights (seed 4), "
                                "input uniform[-1,1)",
-                   "launch": "stream enqueue, one C-ABI call per inference = 3 kernel launches (stem + block 1; blocks 2, "
-                             "3 and 4 as three stages of one launch; one chained kernel for blocks 5-13 + pool + FC + "
-                             "softmax)"},
+                   "launch": "stream enqueue, one C-ABI call per inference = 4 kernel launches (stem + block 1; blocks 2, "
+                             "3 and 4 as three stages of one launch; block 5; one chained kernel for blocks 6-13 + pool + "
+                             "FC + softmax)"},
         "ms_per_step_hip_events": round(ms_events, 5),
         "graph_replay_ms_per_inference": None if graph_ms is None else round(graph_ms, 5),
         "paper_table1_ms": {"plain JS (MacBook Pro 2014)": 3426, "WebGL Intel Iris Pro": 49, "WebGL GTX 1080": 5,
@@ -442,20 +442,20 @@ def main():
         pw_flop, pw_s = sum(l["flop"] for l in pw), sum(l["us"] for l in pw) * 1e-6
         dw_bytes, dw_s = sum(l["bytes"] for l in dw), sum(l["us"] for l in dw) * 1e-6
 
-        # The step's top kernel by time is mobilenet_chain_kernel (blocks 5-13, pool, fully connected layer, softmax
-        # in one launch: about 70 % of the step).  The C ABI enqueues it inside the forward call, so its duration is
+        # The step's top kernel by time is mobilenet_chain_kernel (blocks 6-13, pool, fully connected layer, softmax
+        # in one launch: about 65 % of the step).  The C ABI enqueues it inside the forward call, so its duration is
         # taken as the difference of two graph replays timed with HIP events on the launch stream: the whole forward
-        # pass (3 launches) minus its 2 leading launches (stem + block 1, blocks 2 - 4), which the C ABI runs on
-        # their own as tfx_mobilenet_v1_variant_features(end_block = 4).
+        # pass (4 launches) minus its 3 leading launches (stem + block 1, blocks 2 - 4, block 5), which the C ABI runs
+        # on their own as tfx_mobilenet_v1_variant_features(end_block = 5).
         head_in = torch.empty((1, 224, 224, 3), device="cuda:0").uniform_(-1, 1)
-        head_out = model.features(head_in, 4)
+        head_out = model.features(head_in, 5)
 
         def head():
-            model.features(head_in, 4, out=head_out)
+            model.features(head_in, 5, out=head_out)
         t_head = time_loop(head, reps, inner=10)
         t_full = time_loop(step, reps, inner=10)
         t_chain = max(t_full - t_head, 1e-9)
-        tail_layers = [l for l in layers if l["layer"] in ["dw%d" % i for i in range(5, 14)] + ["pw%d" % i for i in range(5, 14)]]
+        tail_layers = [l for l in layers if l["layer"] in ["dw%d" % i for i in range(6, 14)] + ["pw%d" % i for i in range(6, 14)]]
         chain_flop = sum(l["flop"] for l in tail_layers) + 2 * 1024 * 1000
         chain_bytes = sum(l["bytes"] for l in tail_layers) + 4 * (1024 * 1000 + 1000 + 1000 + 1000)
         out["roofline"] = {
@@ -465,27 +465,27 @@ def main():
             "launches_per_step": 1, "avg_launch_us": round(t_chain * 1e6, 3),
             "algorithmic_flop": chain_flop, "algorithmic_bytes": chain_bytes,
             "hbm_frac_of_the_same_launch": round(chain_bytes / t_chain / PEAK_HBM, 5),
-            "how_timed": "graph replay of the whole forward pass (%.2f us) minus graph replay of its 2 leading launches "
+            "how_timed": "graph replay of the whole forward pass (%.2f us) minus graph replay of its 3 leading launches "
                          "(%.2f us), HIP events on the launch stream" % (t_full * 1e6, t_head * 1e6),
-            "note": "18 dependent convolution layers + pool + FC + softmax at batch 1: bound by the latency of 20 "
+            "note": "16 dependent convolution layers + pool + FC + softmax at batch 1: bound by the latency of 18 "
                     "producer-consumer steps (1.3-1.8 us each on this GPU), not by a throughput roofline"}
-        head_layers = [l for l in layers if l["layer"] in ("conv0", "dw1", "pw1", "dw2", "pw2", "dw3", "pw3", "dw4", "pw4")]
+        head_layers = [l for l in layers if l["layer"] in ("conv0", "dw1", "pw1", "dw2", "pw2", "dw3", "pw3", "dw4", "pw4", "dw5", "pw5")]
         head_flop = sum(l["flop"] for l in head_layers)
         # algorithmic bytes of the 4 launches: the image in, each block's output written once and read once by the
         # next launch (the last one only written), every filter and bias once; the stem's and the depthwise layers'
         # outputs never leave the chip
-        head_bytes = 4 * (224 * 224 * 3 + 2 * (112 * 112 * 64 + 56 * 56 * 128 + 56 * 56 * 128) + 28 * 28 * 256 +
-                          (27 * 32 + 32) + sum(10 * c for c in (32, 64, 128, 128)) +
-                          sum(ci * co + co for ci, co in ((32, 64), (64, 128), (128, 128), (128, 256))))
+        head_bytes = 4 * (224 * 224 * 3 + 2 * (112 * 112 * 64 + 56 * 56 * 128 + 56 * 56 * 128 + 28 * 28 * 256) + 28 * 28 * 256 +
+                          (27 * 32 + 32) + sum(10 * c for c in (32, 64, 128, 128, 256)) +
+                          sum(ci * co + co for ci, co in ((32, 64), (64, 128), (128, 128), (128, 256), (256, 256))))
         out["roofline_other_kernels_of_the_step"] = [
-            {"kernel": "separable_block_kernel (stem + block 1) and separable_chain_kernel (blocks 2, 3, 4 as three stages): "
-                       "2 launches, 9 layers", "bound": "mfma",
+            {"kernel": "separable_block_kernel (stem + block 1; block 5) and separable_chain_kernel (blocks 2, 3, 4 as three "
+                       "stages): 3 launches, 11 layers", "bound": "mfma",
              "achieved": round(head_flop / t_head / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
-             "frac": round(head_flop / t_head / PEAK_MFMA_F32, 5), "avg_launch_us": round(t_head * 1e6 / 2, 3),
+             "frac": round(head_flop / t_head / PEAK_MFMA_F32, 5), "avg_launch_us": round(t_head * 1e6 / 3, 3),
              "algorithmic_flop": head_flop, "algorithmic_bytes": head_bytes,
              "hbm_frac_of_the_same_launches": round(head_bytes / t_head / PEAK_HBM, 5),
-             "the_same_9_layers_as_single_op_launches_us": round(sum(l["us"] for l in head_layers), 2),
-             "note": "bound by four dependent steps (argument fetch or flag hand-over, one round trip for the previous "
+             "the_same_11_layers_as_single_op_launches_us": round(sum(l["us"] for l in head_layers), 2),
+             "note": "bound by five dependent steps (argument fetch or flag hand-over, one round trip for the previous "
                      "block's output, split-K reduction, store), not by a throughput roofline"},
             {"kernel": "all 13 pointwise layers as single-op launches (the multi-kernel path of batch > 1; not part of the batch-1 step)", "bound": "mfma",
              "achieved": round(pw_flop / pw_s / 1e12, 4), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",

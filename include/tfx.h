@@ -197,12 +197,13 @@ size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch);
 /* Full forward pass: 3x3 stride-2 conv to 32 channels, 13 x (depthwise 3x3 ->
  * pointwise 1x1), bias + ReLU6 after each of the 27 convolutions, SAME padding
  * throughout, global average pool, fully connected 1024 -> 1000, softmax.
- * At batch 1 to 3 the stem and the first block, and each of the next three blocks, are
- * one kernel each (at batch 1 and full width the three share one launch); at batch 1 and full width the blocks from the 1/8-size maps on, the pool, the
- * fully connected layer and the softmax run as one kernel whose workgroups hand
- * results to each other through flags in the workspace; every wait in it is
- * bounded, and if one ever gives up (a workgroup that never got to run) every
- * output of the call is NaN rather than a number computed from unfinished data.
+ * At batch 1 to 3 the stem and the first block, and each of the next four blocks, are
+ * one kernel each.  At batch 1 and full width blocks 2 - 4 share one launch and the
+ * blocks from the sixth on, the pool, the fully connected layer and the softmax run
+ * as one kernel; the workgroups of these two kernels hand results to each other
+ * through flags in the workspace.  Every wait in them is bounded, and if one ever
+ * gives up (a workgroup that never got to run) every output of the call is NaN
+ * rather than a number computed from unfinished data.
  * input: device [batch,224,224,3]; workspace: device, >= the size above, 256-byte
  * aligned, contents undefined before and after; probs: device [batch,1000];
  * logits: device [batch,1000] or NULL.  All kernels are enqueued on `stream`. */

@@ -119,11 +119,12 @@ NetPlan plan_net(const tfx_mobilenet_v1_variant& v, int64_t batch, size_t elem_b
   p.chain = elem_bytes == sizeof(float) && chain_supported((int)v.image_size, (int)v.width_quarters, (int)v.classes, batch);
   if (p.chain) off = align_up(off + chain_workspace_bytes((int)v.image_size, (int)v.classes));
   // blocks 2 - 4 in one launch: the outputs of blocks 2 and 3 share the second ping-pong buffer, the output of block 4
-  // (1/8-size map, 256 channels) gets a region of its own, because block 2 is still reading the first buffer
+  // (1/8-size map, 256 channels) gets a region of its own, because block 2 is still reading the first buffer; the
+  // output of block 5 (a launch of its own) goes behind it
   const size_t quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
   p.off_head = off;
   p.head = p.chain && 2 * quarter * quarter * 128 <= p.act_floats;
-  if (p.head) off = align_up(off + eighth * eighth * 256 * sizeof(float));
+  if (p.head) off = align_up(off + 2 * eighth * eighth * 256 * sizeof(float));  // outputs of blocks 4 and 5
   p.bytes = off;
   return p;
 }
@@ -382,7 +383,7 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
   float* buf[2] = {reinterpret_cast<float*>(ws + plan.off_buf[0]), reinterpret_cast<float*>(ws + plan.off_buf[1])};
   float* partial = reinterpret_cast<float*>(ws + plan.off_partial);
 
-  // Batch 1 at full width: the blocks from the 1/8-size maps on, the pool, the fully connected layer and the
+  // Batch 1 at full width: the blocks from the last 1/8-size map on, the pool, the fully connected layer and the
   // softmax run as one persistent kernel (chain.hip) when every pointer allows its vector loads and 256 of its
   // workgroups are resident at once on this device; its task flags are cleared by the first kernel of the pass
   // (the stem, alone or fused with block 1).
@@ -395,8 +396,9 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
     flags_ok = flags_ok && chain_resident();
   }
   const bool chain = flags_ok && end_block == 0;
-  // blocks 2 - 4 as stages of one launch (block.hip): in the whole pass and when block 4's output is asked for
-  const bool head_chain = flags_ok && plan.head && (end_block == 0 || end_block == 4);
+  // blocks 2 - 4 as stages of one launch and block 5 as a launch (block.hip): in the whole pass and when block 4's
+  // or block 5's output is asked for
+  const bool head_chain = flags_ok && plan.head && (end_block == 0 || end_block == 4 || end_block == 5);
   void* chain_ws = ws + plan.off_chain;
 
   // stem: 3x3 stride-2 convolution to 32 alpha channels, then the 13 depthwise-separable blocks
@@ -435,31 +437,41 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
   int cur = 0;
   const int head_flags = block_chain_flag_words((int)shape[1], (int)shape[2]);
   if (head_chain && first_block == 1) {
-    // blocks 2 - 4 as three stages of one launch, then the chained kernel; flags (cleared by the first kernel) and
-    // failure word are shared with it
-    const size_t quarter = (size_t)((shape[1] + 1) / 2);
+    // blocks 2 - 4 as three stages of one launch, block 5 as a launch of its own, then the chained kernel from block 6
+    // on; flags (cleared by the first kernel) and failure word are shared with it
+    const size_t quarter = (size_t)((shape[1] + 1) / 2), eighth = (quarter + 1) / 2;
+    float* const region = reinterpret_cast<float*>(ws + plan.off_head);
     float* const b2_out = buf[1];
     float* const b3_out = buf[1] + quarter * quarter * 128;
-    float* const b4_out = end_block == 4 ? features : reinterpret_cast<float*>(ws + plan.off_head);
-    if (block_chain_supported(buf[0], b2_out, b3_out, b4_out, weights)) {
+    float* const b4_out = end_block == 4 ? features : region;
+    float* const b5_out = end_block == 5 ? features : region + eighth * eighth * 256;
+    const bool with_b5 = end_block != 4 && separable_block_supported(1, (int)eighth, (int)eighth, 256, 256, 1, b4_out,
+                                                                  weights->dw_w[4], weights->dw_b[4], weights->pw_w[4],
+                                                                  weights->pw_b[4], b5_out);
+    if (block_chain_supported(buf[0], b2_out, b3_out, b4_out, weights) && (with_b5 || end_block == 4)) {
       struct Head {
         const float* x;
-        float *b2, *b3, *b4;
-        int h, w;
+        float *b2, *b3, *b4, *b5;
+        int h, w, eighth;
+        bool with_b5;
         const tfx_mobilenet_v1_weights* wt;
         int* flags;
         int flag_base;
         hipStream_t stream;
-      } head{buf[0], b2_out, b3_out, b4_out, (int)shape[1], (int)shape[2], weights, static_cast<int*>(chain_ws),
-             chain_head_flag_base((int)variant->image_size, (int)variant->classes), static_cast<hipStream_t>(stream)};
+      } head{buf[0], b2_out, b3_out, b4_out, b5_out, (int)shape[1], (int)shape[2], (int)eighth, with_b5, weights,
+             static_cast<int*>(chain_ws), chain_head_flag_base((int)variant->image_size, (int)variant->classes),
+             static_cast<hipStream_t>(stream)};
       auto launch_head = [](void* p) -> int {
         const Head& a = *static_cast<const Head*>(p);
-        return launch_block_chain(a.x, a.b2, a.b3, a.b4, a.h, a.w, a.wt, a.flags, a.flag_base, chain_spin_limit(), a.stream);
+        const int rc = launch_block_chain(a.x, a.b2, a.b3, a.b4, a.h, a.w, a.wt, a.flags, a.flag_base, chain_spin_limit(), a.stream);
+        if (rc != TFX_OK || !a.with_b5) return rc;
+        // 28 x 28 x 256 -> 256, stride 1, SAME: one zero row / column before the map
+        return launch_separable_block(a.b4, a.wt->dw_w[4], a.wt->dw_b[4], a.wt->pw_w[4], a.wt->pw_b[4], a.b5, 1, a.eighth, a.eighth,
+                                      256, 256, a.eighth, a.eighth, 1, 1, 1, TFX_ACT_RELU6, TFX_ACT_RELU6, a.stream);
       };
-      if (end_block == 4) return launch_ordered(static_cast<hipStream_t>(stream), launch_head, &head);
-      const int eighth = (int)((quarter + 1) / 2);
-      return launch_chain(b4_out, eighth, weights, chain_ws, head_flags, probs, logits, (int)variant->classes,
-                          static_cast<hipStream_t>(stream), launch_head, &head);
+      if (end_block != 0) return launch_ordered(static_cast<hipStream_t>(stream), launch_head, &head);
+      return launch_chain(b5_out, (int)eighth, weights, chain_ws, head_flags, probs, logits, (int)variant->classes,
+                          static_cast<hipStream_t>(stream), launch_head, &head, 5);
     }
   }
   for (int b = first_block; b < kBlocks; ++b) {

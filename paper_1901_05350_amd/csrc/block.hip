@@ -430,7 +430,9 @@ int launch_cfg(BlockArgs a, hipStream_t stream) {
 bool separable_block_supported(long long batch, int h, int w, int c, int n, int stride, const void* x, const void* dw_w,
                                const void* dw_b, const void* pw_w, const void* pw_b, const void* y) {
   auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
-  return batch >= 1 && batch <= kMaxFusedBatch && (c == 32 || c == 64 || c == 128) && n % 64 == 0 && n >= 64 && n <= 1024 &&
+  // 256 channels: the 9 x 9 window of a stride-2 block would not fit the static LDS
+  return batch >= 1 && batch <= kMaxFusedBatch && (c == 32 || c == 64 || c == 128 || (c == 256 && stride == 1)) &&
+         n % 64 == 0 && n >= 64 && n <= 1024 &&
          (stride == 1 || stride == 2) && h >= 1 && w >= 1 && (long long)h * w * c * 4 < (1ll << 31) && al16(x) &&
          al16(dw_w) && al16(dw_b) && al16(pw_w) && al16(pw_b) && al16(y);
 }
@@ -456,6 +458,7 @@ int launch_separable_block(const float* x, const float* dw_w, const float* dw_b,
   TFX_BLOCK_CASE(64, 4, 1, 4)
   TFX_BLOCK_CASE(128, 8, 1, 4)
 #undef TFX_BLOCK_CASE
+  if (c == 256 && stride == 1) return launch_cfg<256, 8, 1, 4, 1>(a, stream);
   return TFX_ERR_UNSUPPORTED;
 }
 

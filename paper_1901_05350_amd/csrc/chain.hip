@@ -1,5 +1,5 @@
 // The small-map half of the batch-1 MobileNet v1 forward pass (Section 3.9, Table 1) as ONE kernel:
-// the depthwise-separable blocks from the 28 x 28 maps down to 7 x 7, the average pool, the fully
+// the depthwise-separable blocks from the last 28 x 28 one (or the one after it) down to 7 x 7, the average pool, the fully
 // connected layer and the softmax -- 20 dependent steps that, as 20 kernels of 3-6 us each, are
 // bound by kernel boundaries and by each kernel's own start-up, not by their arithmetic.
 //
@@ -44,8 +44,8 @@ constexpr int kComputeThreads = 512;  // 8 wavefronts that compute
 constexpr int kComputeWaves = kComputeThreads / 64;
 constexpr int kChainThreads = kComputeThreads + 64;  // + one helper wavefront: polls flags, sets flags, warms L2
 constexpr int kChainGrid = 256;
-constexpr int kChainBlocks = 9;       // blocks 5 .. 13 of the network (0-based 4 .. 12)
-constexpr int kFirstChainBlock = 4;
+constexpr int kChainBlocks = 9;       // at most blocks 5 .. 13 of the network (0-based 4 .. 12)
+constexpr int kFirstChainBlock = 4;   // a launch starts there or one block later (both read a 1/8-size map of 256 channels)
 constexpr int kSpinLimit = 1 << 22;  // polls before a wait gives up (each poll is a memory round trip: seconds)
 constexpr int kFcSlices = 8;          // slices of the fully connected layer's input channels, one per task
 constexpr int kFcColBlock = 128;      // classes per fully connected task
@@ -83,6 +83,7 @@ struct ChainParams {
   int classes, feat, last_hw;
   int flag_fc;          // first flag of the fully connected tasks
   int spin_limit;       // polls before a wait gives up
+  int nblocks;          // blocks in blk[]
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
@@ -376,7 +377,7 @@ __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const Ch
     }
   };
   if (wg < fc_tasks && compute) load_fc(wg, fw);
-  for (int bi = 0; bi < kChainBlocks; ++bi) {
+  for (int bi = 0; bi < P.nblocks; ++bi) {
     const ChainBlock& B = P.blk[bi];
     const int tiles_m = (B.out_hw * B.out_hw + 15) / 16;
     const TaskMap dw_map = make_task_map(tiles_m, B.cin / 32), pw_map = make_task_map(tiles_m, B.cout / (16 * B.tn));
@@ -396,7 +397,7 @@ __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const Ch
   }
 
   // ---- average pool + fully connected: task (ks, cb) = 128 input channels x 128 classes ----
-  const ChainBlock& L = P.blk[kChainBlocks - 1];
+  const ChainBlock& L = P.blk[P.nblocks - 1];
   const int hw2 = P.last_hw * P.last_hw;
   for (int task = wg; task < fc_tasks; task += kChainGrid) {
     const int ks = task / fc_tasks_c, cb = task % fc_tasks_c;
@@ -516,14 +517,15 @@ constexpr int kNetChannels[13] = {64, 128, 128, 256, 256, 512, 512, 512, 512, 51
 constexpr int kNetStrides[13] = {1, 2, 1, 2, 1, 2, 1, 1, 1, 1, 1, 2, 1};
 
 // Sizes of the chained part for an input map of in_hw x in_hw x 256 (the output of block 4).
-ChainPlanHost chain_layout(int in_hw, int classes, ChainParams* P) {
+ChainPlanHost chain_layout(int in_hw, int classes, ChainParams* P, int first = kFirstChainBlock) {
   ChainPlanHost h{};
   int flags = 1;  // [0] = failure word
   size_t off = 0;
-  int hw = in_hw, cin = kNetChannels[kFirstChainBlock - 1], prev_flags = -1, prev_tn = 2;
+  const int nblocks = 13 - first;
+  int hw = in_hw, cin = kNetChannels[first - 1], prev_flags = -1, prev_tn = 2;
   size_t prev_out = 0;
-  for (int bi = 0; bi < kChainBlocks; ++bi) {
-    const int net = kFirstChainBlock + bi, s = kNetStrides[net], cout = kNetChannels[net];
+  for (int bi = 0; bi < nblocks; ++bi) {
+    const int net = first + bi, s = kNetStrides[net], cout = kNetChannels[net];
     const int out_hw = (hw + s - 1) / s;
     const int need = (out_hw - 1) * s + 3 - hw;
     const int pad = need > 0 ? need / 2 : 0;
@@ -553,6 +555,7 @@ ChainPlanHost chain_layout(int in_hw, int classes, ChainParams* P) {
     P->last_hw = hw;
     P->feat = cin;
     P->classes = classes;
+    P->nblocks = nblocks;
   }
   flags += fc_tasks;
   off += (size_t)kFcSlices * classes;
@@ -635,11 +638,16 @@ int launch_ordered(hipStream_t stream, int (*fn)(void*), void* arg) {
 }
 
 int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, int head_flags,
-                 float* probs, float* logits, int classes, hipStream_t stream, int (*before)(void*), void* before_arg) {
+                 float* probs, float* logits, int classes, hipStream_t stream, int (*before)(void*), void* before_arg,
+                 int first_block) {
+  if (first_block != kFirstChainBlock && first_block != kFirstChainBlock + 1) return TFX_ERR_ARG;
   ChainParams P{};
-  const ChainPlanHost h = chain_layout(in_hw, classes, &P);
-  for (int bi = 0; bi < kChainBlocks; ++bi) {
-    const int net = kFirstChainBlock + bi;
+  // the workspace is laid out for the longer chain; a launch that starts one block later uses a part of it
+  const ChainPlanHost h = chain_layout(in_hw, classes, nullptr);
+  const ChainPlanHost used = chain_layout(in_hw, classes, &P, first_block);
+  if (used.flags > h.flags || used.act_floats > h.act_floats) return TFX_ERR_LAUNCH;
+  for (int bi = 0; bi < P.nblocks; ++bi) {
+    const int net = first_block + bi;
     P.blk[bi].dw_w = w->dw_w[net];
     P.blk[bi].dw_b = w->dw_b[net];
     P.blk[bi].pw_w = w->pw_w[net];
@@ -647,7 +655,7 @@ int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w,
   }
   const size_t flag_bytes = (size_t)(h.flags + head_flags) * kFlagStride * sizeof(int);
   P.in0 = in0;
-  P.in0_bytes = (unsigned)((size_t)in_hw * in_hw * kNetChannels[kFirstChainBlock - 1] * sizeof(float));
+  P.in0_bytes = (unsigned)((size_t)in_hw * in_hw * kNetChannels[first_block - 1] * sizeof(float));
   P.flags = static_cast<int*>(chain_ws);
   P.act = reinterpret_cast<float*>(static_cast<char*>(chain_ws) + flag_bytes);
   P.act_bytes = (unsigned)(h.act_floats * sizeof(float));

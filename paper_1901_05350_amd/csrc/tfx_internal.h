@@ -121,9 +121,10 @@ int chain_spin_limit();
 // head_flags: flag words behind the chain kernel's own at the start of chain_ws (block_chain_flag_words).
 // before(before_arg), if given, enqueues a launch that has to stay directly in front of the chain kernel on `stream`
 // (it is called once the stream has been ordered behind other streams' chain kernels) and returns a tfx_status.
+// first_block: 4 (the chain starts with block 5, in0 = the output of block 4) or 5 (block 6, in0 = output of block 5).
 int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, int head_flags,
                  float* probs, float* logits, int classes, hipStream_t stream, int (*before)(void*) = nullptr,
-                 void* before_arg = nullptr);
+                 void* before_arg = nullptr, int first_block = 4);
 // fn(arg) enqueues a kernel of waiting workgroups on `stream`; the stream is first ordered behind the last such
 // kernel of any other stream (two of them side by side could each hold the CUs the other's producers need).
 int launch_ordered(hipStream_t stream, int (*fn)(void*), void* arg);
@@ -140,7 +141,7 @@ int launch_block_chain(const float* x, float* b2_out, float* b3_out, float* y, i
                        const tfx_mobilenet_v1_weights* wt, int* flags, int flag_base, int spin_limit, hipStream_t stream);
 
 // One depthwise-separable block (depthwise 3x3 + bias + clamp, pointwise 1x1 + bias + clamp) of up to three images in
-// one launch (block.hip): 32, 64 or 128 input channels, n a multiple of 64, 16-byte aligned pointers.
+// one launch (block.hip): 32, 64 or 128 input channels (256 at stride 1), n a multiple of 64, 16-byte aligned pointers.
 bool separable_block_supported(long long batch, int h, int w, int c, int n, int stride, const void* x, const void* dw_w,
                                const void* dw_b, const void* pw_w, const void* pw_b, const void* y);
 int launch_separable_block(const float* x, const float* dw_w, const float* dw_b, const float* pw_w, const float* pw_b,

@@ -124,9 +124,9 @@ def test_internal_activations_of_every_block(net):
         model.features(img, 6, out=out)   # wrong shape for block 6
 
 
-@pytest.mark.parametrize("size,q,batch,blocks", [(100, 4, 1, (1, 2, 3, 4, 7, 13)), (100, 2, 3, (1, 6, 13)),
+@pytest.mark.parametrize("size,q,batch,blocks", [(100, 4, 1, (1, 2, 3, 4, 5, 7, 13)), (100, 2, 3, (1, 6, 13)),
                                                  (160, 4, 2, (1, 4, 12)), (32, 4, 1, (1, 2, 3, 4, 5, 13)),
-                                                 (72, 4, 3, (1, 2, 3, 4, 13)), (64, 4, 4, (1, 4))])
+                                                 (72, 4, 3, (1, 2, 3, 4, 5, 13)), (64, 4, 4, (1, 4))])
 def test_internal_activations_of_variants_and_batches(size, q, batch, blocks):
     """Odd map sizes (ragged 4 x 4 patches of the fused kernels, which serve batch 1 to 3), other widths, and batches
     on both sides of that limit."""
@@ -285,16 +285,17 @@ def test_chained_blocks_that_give_up_write_nan_not_numbers(net, monkeypatch):
     data, probs, logits, acts = net
     model = tfx.MobileNetV1(data["weights"], batch=1)
     image = dev(data["image"])
-    good = host(model.features(image, 4)).copy()
-    assert_close(good, acts[8], "features after block 4")
-    monkeypatch.setenv("TFX_CHAIN_SPIN_LIMIT", "1")
-    cut = host(model.features(image, 4))
-    monkeypatch.delenv("TFX_CHAIN_SPIN_LIMIT")
-    bad = np.isnan(cut)
-    assert bad.any()
-    assert np.array_equal(cut[~bad], good[~bad])
-    again = host(model.features(image, 4))
-    assert np.array_equal(again, good)
+    for k in (4, 5):   # the staged launch alone, and with block 5's kernel behind it
+        good = host(model.features(image, k)).copy()
+        assert_close(good, acts[2 * k], "features after block %d" % k)
+        monkeypatch.setenv("TFX_CHAIN_SPIN_LIMIT", "1")
+        cut = host(model.features(image, k))
+        monkeypatch.delenv("TFX_CHAIN_SPIN_LIMIT")
+        bad = np.isnan(cut)
+        assert bad.any()
+        assert np.array_equal(cut[~bad], good[~bad])
+        again = host(model.features(image, k))
+        assert np.array_equal(again, good)
 
 
 def test_two_chained_kernels_on_two_streams_at_once(net):
