@@ -324,6 +324,10 @@ int tfx_conv2d_f16(const uint16_t* x, const int64_t x_shape[4], const uint16_t* 
   if (conv2d_stem_f16_supported(ci, fh, fw, co, y))
     return launch_conv2d_stem_f16(x, filter, bias, y, n, h, w, co, oh, ow, stride_h, stride_w, (int)g.pad[0],
                                   (int)g.pad[2], (int)act, s);
+  if (conv3x3_stream_f16_supported((long long)n * oh * ow, numel(x_shape, 4), ci, fh, fw, co, stride_h, stride_w, x,
+                                   filter, y))
+    return launch_conv3x3_stream_f16(x, filter, bias, y, n, h, w, ci, co, oh, ow, (int)g.pad[0], (int)g.pad[2],
+                                     (int)act, s);
   if (conv2d_gemm_f16_supported(x, filter, ci, fh, fw, co))
     return launch_conv2d_gemm_f16(x, filter, bias, y, n, h, w, ci, fh, fw, co, oh, ow, stride_h, stride_w,
                                   (int)g.pad[0], (int)g.pad[2], (int)act, s);

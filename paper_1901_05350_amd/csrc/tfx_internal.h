@@ -203,6 +203,12 @@ bool pointwise_stream_f16_supported(int m, int k, int n, const void* x, const vo
 int launch_pointwise_stream_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int m, int k,
                                 int n, int act, hipStream_t stream);
 
+// 3x3 stride-1 conv2d on binary16 storage with the whole filter resident in LDS (few channels, many output pixels).
+bool conv3x3_stream_f16_supported(long long m, long long x_elems, int ci, int fh, int fw, int co, int sh, int sw,
+                                  const void* x, const void* w, const void* y);
+int launch_conv3x3_stream_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int n, int h,
+                              int wd, int ci, int co, int oh, int ow, int pt, int pl, int act, hipStream_t stream);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? TFX_OK : TFX_ERR_LAUNCH; }
 
 // A kernel that uses more than 64 KB of dynamic LDS has to be allowed to, once per device (the attribute

@@ -99,6 +99,41 @@ def test_conv2d_f16_3x3_benchmark_size_every_image():
     assert_close_f16(got, oracle.conv2d_f16(x, f, b, 1, PAD_SAME, ACT_RELU6), "conv 3x3 f16 batch 64")
 
 
+@pytest.mark.parametrize("shape,stride,pad,act", [
+    ((6, 56, 56, 64, 64, 3, 3), 1, PAD_SAME, ACT_RELU6),        # M = 18816, whole 4 x 8 patches
+    ((6, 57, 53, 32, 64, 3, 3), 1, PAD_SAME, ACT_RELU),         # ragged last patch row (1 of 4) and column (5 of 8)
+    ((9, 47, 45, 32, 128, 3, 3), 1, PAD_VALID, ACT_NONE),       # no tap outside the image; 45 x 43 outputs
+    ((10, 44, 41, 64, 32, 3, 3), 1, PAD_SAME, ACT_RELU6),
+    ((17, 33, 31, 32, 32, 3, 3), 1, PAD_SAME, ACT_NONE),
+    ((4, 150, 38, 64, 64, 3, 3), 1, PAD_VALID, ACT_RELU6),      # tall images: a workgroup's units cross image boundaries
+    ((9, 45, 47, 128, 32, 3, 3), 1, PAD_SAME, ACT_RELU6),       # 128 channels in: the tiled implicit GEMM
+    ((23, 57, 53, 32, 64, 3, 3), 2, PAD_SAME, ACT_RELU),        # stride 2: the tiled implicit GEMM
+])
+def test_conv2d_f16_filter_stationary(shape, stride, pad, act):
+    """Few channels, stride 1 and at least 16384 output pixels: the kernel that keeps the whole 3 x 3 filter in LDS."""
+    import paper_1901_05350_amd as tfx
+    n, hh, ww, cin, cout, fh, fw = shape
+    x, f, b = conv_case(500 + cin + cout, n, hh, ww, cin, cout, fh, fw)
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), dev16(b), stride, pad, act))
+    assert_close_f16(got, oracle.conv2d_f16(x, f, b, stride, pad, act), "conv2d_f16 stationary %r" % (shape,))
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), None, stride, pad, ACT_NONE))
+    assert_close_f16(got, oracle.conv2d_f16(x, f, None, stride, pad, ACT_NONE), "conv2d_f16 stationary no bias %r" % (shape,))
+
+
+def test_conv2d_f16_filter_stationary_one_hot():
+    """One-hot filters: output channel o copies input channel (o * 5) % 32 under tap (o % 3, (o // 3) % 3), so every
+    (tap, channel) position of the window is located exactly, image borders and image-to-image boundaries included."""
+    import paper_1901_05350_amd as tfx
+    rng = np.random.default_rng(12)
+    x = h(rng.uniform(-1, 1, (5, 60, 58, 32)))
+    f = np.zeros((3, 3, 32, 64), np.float16)
+    for o in range(64):
+        f[o % 3, (o // 3) % 3, (o * 5) % 32, o] = 1
+    got = host(tfx.tfx_conv2d_f16(dev16(x), dev16(f), None, 1, PAD_SAME, ACT_NONE))
+    assert got.shape[0] * got.shape[1] * got.shape[2] >= 16384
+    assert np.array_equal(got, oracle.conv2d_f16(x, f, None, 1, PAD_SAME, ACT_NONE))
+
+
 def test_stem_f16_matrix_core_form_walks_over_several_slabs():
     """Batch 20 at 224 x 224 is 15680 slabs for at most 8192 wavefronts: wavefronts move on across row and image
     boundaries.  Every image is compared."""
@@ -160,7 +195,7 @@ def test_mobilenet_f16_benchmark_batches_every_image(batch):
 def test_f16_nan_and_inf_through_the_fused_activations():
     """As on fp32 storage: a NaN passes through relu and relu6, -inf becomes 0, +inf the upper bound (or stays +inf
     under relu), and a NaN in the input reaches exactly the outputs whose window holds it.  Covers the tiled,
-    small-tile and filter-stationary pointwise kernels, the implicit GEMM, both stems, the direct kernel, both
+    small-tile and filter-stationary pointwise kernels, the implicit GEMM, the filter-stationary 3 x 3 kernel, both stems, the direct kernel, both
     depthwise kernels and the matMul epilogue."""
     import paper_1901_05350_amd as tfx
     rng = np.random.default_rng(46)
@@ -171,6 +206,7 @@ def test_f16_nan_and_inf_through_the_fused_activations():
 
     for (n, hh, ww, ci, co, fh, fw, s) in [(1, 14, 14, 64, 96, 1, 1, 1), (2, 56, 56, 128, 128, 1, 1, 1),
                                            (8, 56, 56, 128, 128, 1, 1, 1), (2, 20, 20, 32, 40, 3, 3, 1),
+                                           (6, 56, 56, 64, 64, 3, 3, 1), (6, 57, 53, 32, 64, 3, 3, 1),
                                            (1, 30, 30, 3, 32, 3, 3, 2), (1, 30, 30, 3, 16, 3, 3, 2), (1, 9, 9, 5, 4, 3, 3, 1)]:
         x, f, b = conv_case(500 + ci, n, hh, ww, ci, co, fh, fw)
         x[n - 1, hh // 2, ww // 3, ci - 1] = np.nan
