@@ -3,7 +3,7 @@
 //   y[M, N] = half(act(A[M, K] * w[K, N] + bias)),  M = n * oh * ow,  K = 9 * Ci,
 // where row m of A is the 3 x 3 x Ci window of output pixel m, never materialised.
 // With few channels the whole filter (K * N * 2 bytes, e.g. 74 KB for 64 -> 64) fits in LDS, and then the filter is
-// the stationary operand, as in pointwise_f16.hip: a workgroup transposes w into LDS once ([N][K + 16] halfs) and its
+// the stationary operand, as in pointwise_f16.hip: a workgroup transposes w into LDS once (stream_f16.h) and its
 // 8 wavefronts stream units of the output without meeting at a barrier again.  A unit is a 4 x 8 patch of output
 // pixels of one image (two v_mfma_f32_16x16x32_f16 slabs of 2 x 8 pixels).  The wavefront copies the patch's 6 x 10
 // input window into a private piece of LDS -- every input value crosses the vector memory path 1.9 times instead of
@@ -12,16 +12,12 @@
 // unit is on its way from memory into registers while the current one is multiplied.  The filter's columns are
 // stored in LDS in an order that leaves every lane with 8 consecutive output channels, so outputs go from the
 // accumulators to memory as 16-byte pieces.
-#include "tfx_internal.h"
+#include "stream_f16.h"
 
 namespace tfx {
 namespace {
 
-typedef _Float16 half_t;
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+using namespace f16s;
 
 constexpr int kThreads = 512, kWaves = kThreads / 64;
 constexpr int kPatchH = 4, kPatchW = 8;                      // output pixels of a unit
@@ -32,23 +28,6 @@ struct WindowGeom {
   int tiles_c, tiles_r;   // patches per output row and per output column
   unsigned x_bytes;
 };
-
-// ds_read_b128 serves 32 lanes at a time and is free of bank conflicts when their 16-byte pieces differ modulo 32
-// (measured on gfx950: such patterns read at twice the rate of ones that only differ modulo 16 within 16 lanes).
-// `piece(li, q)` is the piece index of lane (li = lane % 16, q = lane / 16) up to a constant.
-template <typename F>
-constexpr bool conflict_free(F piece) {
-  for (int half = 0; half < 2; ++half) {
-    unsigned seen = 0;
-    for (int li = 0; li < 16; ++li)
-      for (int q = 2 * half; q < 2 * half + 2; ++q) {
-        const unsigned bit = 1u << (piece(li, q) % 32);
-        if (seen & bit) return false;
-        seen |= bit;
-      }
-  }
-  return true;
-}
 
 // LDS layout of a window in 16-byte pieces: a pixel takes Ci/8 pieces plus two of padding and a row of the window
 // a multiple of 16 pieces that is not one of 32, which puts the 2 x 8 pixels of a slab, two k-groups each, into 32
@@ -68,14 +47,6 @@ struct WindowShape {
   static_assert(conflict_free(piece), "window layout");
 };
 
-// Filter rows in LDS: K halfs plus 16 of padding, i.e. an even number of pieces whose half is odd.
-template <int CI>
-struct FilterShape {
-  static constexpr int K = 9 * CI, LD = K + 16;
-  static constexpr int piece(int li, int q) { return li * (LD / 8) + q; }
-  static_assert(conflict_free(piece), "filter layout");
-};
-
 template <int CI, int N>
 __global__ __launch_bounds__(kThreads) void conv3x3_window_f16_kernel(const half_t* __restrict__ x,
                                                                       const half_t* __restrict__ w,
@@ -83,10 +54,11 @@ __global__ __launch_bounds__(kThreads) void conv3x3_window_f16_kernel(const half
                                                                       half_t* __restrict__ y, WindowGeom g, int units,
                                                                       int act) {
   using WS = WindowShape<CI>;
-  constexpr int K = 9 * CI, SPT = CI / 32, NB = N / 16, LD = FilterShape<CI>::LD;
+  using Stage = FilterStage<9 * CI, N, kThreads>;
+  constexpr int SPT = CI / 32, NB = N / 16, LD = Stage::LD;
   constexpr int Q = WS::Q, PS = WS::PS, RS = WS::RS, LI = WS::kLoads;
   static_assert(CI % 32 == 0 && N % 32 == 0 && NB <= 8, "filter shape");
-  extern __shared__ __align__(16) half_t wl[];  // [N][K + 16], then one window per wavefront
+  extern __shared__ __align__(16) half_t wl[];  // the filter, [N][LD], then one window per wavefront
   __shared__ int next_unit;
 
   const int tid = threadIdx.x;
@@ -121,58 +93,25 @@ __global__ __launch_bounds__(kThreads) void conv3x3_window_f16_kernel(const half
     }
   };
 
-  // Filter transpose, once per workgroup: block u covers k-rows 4 kq ... + 3 of columns 8 nb ... + 7
-  // (nb = u % (N/8) so that the lanes of a wavefront read whole rows of w); all 16-byte loads first, then a
-  // 4 x 8 transpose in registers and eight 8-byte LDS writes per block.  Column c of w goes to LDS row
-  // rho(c) = 32 (c / 32) + 16 (c % 8 / 4) + 4 (c % 32 / 8) + c % 4: with the MFMA's output layout (lane (li, q)
-  // holds rows 4 q ... 4 q + 3 of a 16-row block) a lane then owns channels 8 q ... 8 q + 7 of every 32, the
-  // first four in block 2 m and the rest in block 2 m + 1, and stores them as one 16-byte piece.
-  constexpr int BLOCKS = (K / 4) * (N / 8), PER = (BLOCKS + kThreads - 1) / kThreads;
-  h8 r[PER][4];
-#pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    // (no branch around the loads: a thread without a block in the last round reads block 0 again)
-    const int u = tid + i * kThreads < BLOCKS ? tid + i * kThreads : 0, nb = u % (N / 8), kq = u / (N / 8);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) r[i][kk] = *reinterpret_cast<const h8*>(w + (size_t)(4 * kq + kk) * N + 8 * nb);
-  }
-  // bias of this lane's channels, in the accumulators' layout: block j, rows 4 q ... 4 q + 3
-  // (loaded here, without a branch, and converted after the barrier below: nothing before it waits for them;
-  // with no bias the loads read the filter instead and their values are dropped)
-  const half_t* const bias_or_w = bias ? bias : w;
-  half_t braw[NB][4];
-#pragma unroll
-  for (int j = 0; j < NB; ++j)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) braw[j][e] = bias_or_w[32 * (j / 2) + 8 * q + 4 * (j % 2) + e];
+  // the filter's loads and the bias's first, so that they are on their way while the window's are set up
+  Stage stage;
+  stage.fetch(w, tid);
+  BiasRows<NB> bias_rows;
+  bias_rows.fetch(bias, w, q);
 
   // the first unit of each wavefront is fixed, and its window is in flight while the filter is staged; the rest
   // are handed out by a counter in LDS
   int cur = u0 + __builtin_amdgcn_readfirstlane(tid / 64);
   if (tid == 0) next_unit = kWaves;
   load_window(cur, cur < u1);
-#pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    const int u = tid + i * kThreads, nb = u % (N / 8), kq = u / (N / 8);
-    if (BLOCKS % kThreads == 0 || i + 1 < PER || u < BLOCKS) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const h4 o = {r[i][0][j], r[i][1][j], r[i][2][j], r[i][3][j]};
-        const int rho = 32 * (nb / 4) + 16 * (j / 4) + 4 * (nb % 4) + j % 4;
-        *reinterpret_cast<h4*>(wl + rho * LD + 4 * kq) = o;
-      }
-    }
-  }
+  stage.store(wl, tid);
   const ActClamp clamp = make_act(act);
   // this lane's MFMA operand inside a window: pixel (li / 8, li % 8) of a slab, pieces q, q + 4, ...
   const half_t* const a_base = win + ((li / 8) * RS + (li % 8) * PS + q) * 8;
   const half_t* const w_base = wl + li * LD + 8 * q;
   __syncthreads();
   f32x4 bv[NB];
-#pragma unroll
-  for (int j = 0; j < NB; ++j)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) bv[j][e] = bias ? (float)braw[j][e] : 0.f;
+  bias_rows.get(bias != nullptr, bv);
   auto draw = [&]() {
     int ticket = 0;
     if (lane == 0) ticket = atomicAdd(&next_unit, 1);
@@ -234,40 +173,14 @@ __global__ __launch_bounds__(kThreads) void conv3x3_window_f16_kernel(const half
     __builtin_amdgcn_sched_barrier(0);
 
     // Epilogue: activation, and one 16-byte store per lane, slab and 32 channels (a pixel's 4 lanes write
-    // 64 consecutive bytes).  The clamp is one median-of-three per value; that instruction, like max and min,
-    // drops a NaN, so NaNs are looked for on the side (a compare per pair of values, collected in scalar
-    // registers) and a wavefront that holds one takes the exact form, through which a NaN passes.
+    // 64 consecutive bytes).
     const int tc = cur % g.tiles_c, tq = cur / g.tiles_c, tr = tq % g.tiles_r, n = tq / g.tiles_r;
-    const float lo = clamp.on ? 0.f : -INFINITY;
     auto emit = [&](const f32x4 (&acc)[NB], int slab) {
       const int oh = kPatchH * tr + 2 * slab + li / 8, ow = kPatchW * tc + li % 8;
       half_t* const yp = y + ((size_t)(n * g.OH + oh) * g.OW + ow) * N + 8 * q;
-      const bool in = oh < g.OH && ow < g.OW;
       h8 o[NB / 2];
-      unsigned long long nan = 0;
-#pragma unroll
-      for (int m = 0; m < NB / 2; ++m) {
-        float v[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          v[e] = acc[2 * m][e];
-          v[4 + e] = acc[2 * m + 1][e];
-        }
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) nan |= __builtin_amdgcn_ballot_w64(__builtin_isunordered(v[e], v[e + 1]));
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[m][e] = (half_t)__builtin_amdgcn_fmed3f(v[e], lo, clamp.hi);
-      }
-      if (nan != 0) {
-#pragma unroll
-        for (int m = 0; m < NB / 2; ++m)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            o[m][e] = (half_t)apply_act(acc[2 * m][e], clamp);
-            o[m][4 + e] = (half_t)apply_act(acc[2 * m + 1][e], clamp);
-          }
-      }
-      if (in) {
+      activate_and_pack(acc, clamp, o);
+      if (oh < g.OH && ow < g.OW) {
 #pragma unroll
         for (int m = 0; m < NB / 2; ++m) *reinterpret_cast<h8*>(yp + 32 * m) = o[m];
       }
@@ -281,7 +194,7 @@ __global__ __launch_bounds__(kThreads) void conv3x3_window_f16_kernel(const half
 
 template <int CI, int N>
 constexpr size_t window_lds_bytes() {
-  return ((size_t)N * FilterShape<CI>::LD + (size_t)kWaves * WindowShape<CI>::kHalfs) * sizeof(half_t);
+  return ((size_t)N * filter_row_halfs(9 * CI) + (size_t)kWaves * WindowShape<CI>::kHalfs) * sizeof(half_t);
 }
 
 template <int CI, int N>

@@ -3,22 +3,20 @@
 //   the early pointwise layers of the Section 3.9 network at large batch).
 // At 2 bytes per element these layers move one byte per 1.5 ... 6 multiply-adds and are bound by
 // HBM, so the filter is the stationary operand: a workgroup transposes all of w into LDS once
-// ([N][K + 8] halfs, K-contiguous rows as the matrix cores want them) and its 8 wavefronts then
-// stream 32-row units of x: a lane loads its own v_mfma_f32_16x16x32_f16 operand (its row, 8
-// consecutive k per 16-byte load) straight from global memory, multiplies against the filter
-// fragments from LDS (each fragment read serves two 16-row slabs) and writes its outputs through a
-// private LDS strip so that they leave as whole 128-byte lines.  Units are handed out by a counter in LDS.
-#include "tfx_internal.h"
+// (stream_f16.h: K-contiguous rows as the matrix cores want them, padded against bank conflicts, in a row
+// order that leaves a lane with 8 consecutive output channels) and its 8 wavefronts then stream 32-row
+// units of x: a lane loads its own v_mfma_f32_16x16x32_f16 operand (its row, 8 consecutive k per 16-byte
+// load) straight from global memory, one unit ahead of the MFMAs that use it, multiplies against the filter
+// fragments from LDS (each fragment read serves two 16-row slabs) and stores its outputs as 16-byte pieces.
+// Units are handed out by a counter in LDS.
+#include "stream_f16.h"
 
 namespace tfx {
 namespace {
 
-typedef _Float16 half_t;
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
+using namespace f16s;
 
-constexpr int kThreads = 512;
+constexpr int kThreads = 512, kWaves = kThreads / 64;
 
 template <int K, int N>
 __global__ __launch_bounds__(kThreads) void pointwise_stream_f16_kernel(const half_t* __restrict__ x,
@@ -26,123 +24,131 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream_f16_kernel(const ha
                                                                         const half_t* __restrict__ bias,
                                                                         half_t* __restrict__ y, int M, int units,
                                                                         int act) {
-  constexpr int KS = K / 32, NB = N / 16, LD = K + 8;
-  constexpr int NBP = NB < 8 ? NB : 8;  // 16-channel blocks per pass
-  static_assert(K % 32 == 0 && N % 16 == 0, "filter shape");
-  extern __shared__ __align__(16) half_t wl[];  // [N][K + 8], then 8 wavefront-private output strips
-  half_t* const stage = wl + N * LD;
+  using Stage = FilterStage<K, N, kThreads>;
+  constexpr int KS = K / 32, NB = N / 16, LD = Stage::LD;
+  constexpr int NBP = NB < 8 ? NB : 8, PASSES = NB / NBP;  // 16-channel blocks per pass over the unit
+  static_assert(K % 32 == 0 && N % 32 == 0 && N <= kThreads, "filter shape");
+  extern __shared__ __align__(16) half_t wl[];  // the filter, [N][LD], then the bias as N floats in the same row order
+  float* const bias_l = reinterpret_cast<float*>(wl + N * LD);
   __shared__ int next_unit;
 
   const int tid = threadIdx.x;
-  if (tid == 0) next_unit = 0;
-  {
-    // Filter transpose, once per workgroup: block u covers k-rows 4 kq ... + 3 of columns 8 nb ... + 7
-    // (kq = u % (K/4) so that the lanes of a wavefront write consecutive 8-byte pieces of one LDS row);
-    // four 16-byte loads, a 4 x 8 transpose in registers, eight 8-byte LDS writes.
-    constexpr int BLOCKS = (K / 4) * (N / 8), PER = (BLOCKS + kThreads - 1) / kThreads;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int u = tid + i * kThreads;
-      if (u < BLOCKS) {
-        const int kq = u % (K / 4), nb = u / (K / 4);
-        h8 r[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) r[kk] = *reinterpret_cast<const h8*>(w + (size_t)(4 * kq + kk) * N + 8 * nb);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const h4 o = {r[0][j], r[1][j], r[2][j], r[3][j]};
-          *reinterpret_cast<h4*>(wl + (8 * nb + j) * LD + 4 * kq) = o;
-        }
-      }
-    }
-  }
-  __syncthreads();
-
   const int lane = tid % 64, li = lane % 16, q = lane / 16;
-  const ActClamp clamp = make_act(act);
   const int u0 = (int)((long long)units * blockIdx.x / gridDim.x);
   const int u1 = (int)((long long)units * (blockIdx.x + 1) / gridDim.x);
-  for (;;) {
+
+  // A unit's operands: this lane's two rows (li and li + 16 of the unit's 32), k-group q of every 32 k.
+  h8 a0[KS], a1[KS];
+  const half_t *xp0, *xp1;
+  auto locate = [&](int unit) {  // rows past M repeat the last one: loaded, never stored
+    const int row0 = unit * 32 + li, row1 = row0 + 16;
+    xp0 = x + (size_t)(row0 < M ? row0 : M - 1) * K + 8 * q;
+    xp1 = x + (size_t)(row1 < M ? row1 : M - 1) * K + 8 * q;
+  };
+  auto load_step = [&](int s) {
+    a0[s] = *reinterpret_cast<const h8*>(xp0 + 32 * s);
+    a1[s] = *reinterpret_cast<const h8*>(xp1 + 32 * s);
+  };
+
+  // The filter's loads first, then the operands of the wavefront's first unit (fixed; the rest are handed out by
+  // a counter in LDS): all of them are in flight while the filter is transposed.
+  Stage stage;
+  stage.fetch(w, tid);
+  const float bias_c = tid < N && bias ? (float)bias[tid] : 0.f;
+  int cur = u0 + __builtin_amdgcn_readfirstlane(tid / 64);
+  if (tid == 0) next_unit = kWaves;
+  locate(cur < u1 ? cur : u0);
+#pragma unroll
+  for (int s = 0; s < KS; ++s) load_step(s);
+  stage.store(wl, tid);
+  if (tid < N) bias_l[rho(tid)] = bias_c;
+  const ActClamp clamp = make_act(act);
+  const half_t* const w_base = wl + li * LD + 8 * q;
+  __syncthreads();
+  auto draw = [&]() {
     int ticket = 0;
     if (lane == 0) ticket = atomicAdd(&next_unit, 1);
-    const int unit = u0 + __builtin_amdgcn_readfirstlane(ticket);
-    if (unit >= u1) break;
-    const int row0 = unit * 32 + li, row1 = row0 + 16;
-    const int r0c = row0 < M ? row0 : M - 1, r1c = row1 < M ? row1 : M - 1;  // clamped: loaded, never stored
-    h8 a0[KS], a1[KS];
-    const half_t* xp0 = x + (size_t)r0c * K + 8 * q;
-    const half_t* xp1 = x + (size_t)r1c * K + 8 * q;
-#pragma unroll
-    for (int s = 0; s < KS; ++s) a0[s] = *reinterpret_cast<const h8*>(xp0 + 32 * s);
-#pragma unroll
-    for (int s = 0; s < KS; ++s) a1[s] = *reinterpret_cast<const h8*>(xp1 + 32 * s);
+    return ticket;
+  };
 
-#pragma unroll
-    for (int p = 0; p < NB / NBP; ++p) {
-      f32x4 acc0[NBP], acc1[NBP];
+  // Per pass: the MFMAs of unit `cur`, whose operands are in the registers; the registers of a k-step are
+  // refilled with the same step of unit `nxt` as soon as its last MFMAs have been issued, so a load has the time
+  // of a whole pass to arrive (a second unit in flight per wavefront was measured and is no faster).  The
+  // accumulators start from the bias.
+  int nxt = u0 + __builtin_amdgcn_readfirstlane(draw());
+  while (cur < u1) {
+    const int ticket = draw();  // the unit after `nxt`; its number is not needed before the end of the pass
+    locate(nxt < u1 ? nxt : cur);
+    // step t = KS p + s: k-step s of column pass p; its filter fragments are read from LDS one step ahead (the
+    // scheduling barriers keep the compiler from gathering all the reads of a pass in front of it, which spills,
+    // or from moving them back to where their values are used)
+    constexpr int STEPS = PASSES * KS;
+    h8 fw[2][NBP];
+    auto read_step = [&](int t, h8 (&f)[NBP]) {
 #pragma unroll
       for (int j = 0; j < NBP; ++j)
+        f[j] = *reinterpret_cast<const h8*>(w_base + 16 * (NBP * (t / KS) + j) * LD + 32 * (t % KS));
+    };
+    read_step(0, fw[0]);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) acc0[j][v] = acc1[j][v] = 0.f;
+    for (int p = 0; p < PASSES; ++p) {
+      f32x4 acc0[NBP], acc1[NBP];
+#pragma unroll
+      for (int j = 0; j < NBP; ++j) acc0[j] = acc1[j] = *reinterpret_cast<const f32x4*>(bias_l + 16 * (NBP * p + j) + 4 * q);
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
+        const int t = KS * p + s;
+        if (t + 1 < STEPS) read_step(t + 1, fw[(t + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < NBP; ++j) {
-          const h8 wf = *reinterpret_cast<const h8*>(wl + (16 * (NBP * p + j) + li) * LD + 32 * s + 8 * q);
-          acc0[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, a0[s], acc0[j], 0, 0, 0);
-          acc1[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, a1[s], acc1[j], 0, 0, 0);
+          acc0[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw[t & 1][j], a0[s], acc0[j], 0, 0, 0);
+          acc1[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw[t & 1][j], a1[s], acc1[j], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (p + 1 == PASSES) load_step(s);
       }
-      // Epilogue through a wavefront-private LDS strip: a lane's 4 consecutive channels (8 bytes) per block
-      // are written to [16 rows][PW + 8], read back as 16 bytes per lane along a row and stored as whole
-      // 128-byte lines (8-byte stores scattered over 16 rows cost more than the rest of the kernel).
-      constexpr int PW = 16 * NBP, LS = PW + 8;            // columns per pass, strip row stride
-      constexpr int LPR = PW / 8, RPI = 64 / LPR;          // lanes per row, rows per store instruction
-      half_t* strip = stage + (tid / 64) * 16 * LS;
+      // Epilogue: activation, and one 16-byte store per lane, slab and 32 channels (a row's 4 lanes write 64
+      // consecutive bytes).
       auto emit = [&](const f32x4 (&acc)[NBP], int slab) {
+        const int row = cur * 32 + 16 * slab + li;
+        h8 o[NBP / 2];
+        activate_and_pack(acc, clamp, o);
+        if (row < M) {
+          half_t* const yp = y + (size_t)row * N + 16 * NBP * p + 8 * q;
 #pragma unroll
-        for (int j = 0; j < NBP; ++j) {
-          const int col = 16 * j + 4 * q;
-          float bv[4] = {0.f, 0.f, 0.f, 0.f};
-          if (bias) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) bv[e] = (float)bias[PW * p + col + e];
-          }
-          h4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (half_t)apply_act(acc[j][e] + bv[e], clamp);
-          *reinterpret_cast<h4*>(strip + li * LS + col) = o;
+          for (int m = 0; m < NBP / 2; ++m) *reinterpret_cast<h8*>(yp + 32 * m) = o[m];
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int r0 = 0; r0 < 16; r0 += RPI) {
-          const int r = r0 + lane / LPR, c = 8 * (lane % LPR);
-          const h8 v = *reinterpret_cast<const h8*>(strip + r * LS + c);
-          const int row = unit * 32 + 16 * slab + r;
-          if (row < M) *reinterpret_cast<h8*>(y + (size_t)row * N + PW * p + c) = v;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
       };
       emit(acc0, 0);
       emit(acc1, 1);
     }
+    cur = nxt;
+    nxt = u0 + __builtin_amdgcn_readfirstlane(ticket);
   }
 }
 
 template <int K, int N>
 int launch_stream_f16(const half_t* x, const half_t* w, const half_t* bias, half_t* y, int m, int act,
                       hipStream_t stream) {
-  constexpr int NBP = N / 16 < 8 ? N / 16 : 8;
-  constexpr size_t lds_bytes = ((size_t)N * (K + 8) + 8 * 16 * (16 * NBP + 8)) * sizeof(half_t);
-  static_assert(lds_bytes <= 160 * 1024, "LDS budget per workgroup");
+  constexpr size_t lds_bytes = (size_t)N * filter_row_halfs(K) * sizeof(half_t) + N * sizeof(float);
+  static_assert(lds_bytes + 64 <= 160 * 1024, "LDS budget per workgroup");
   auto kern = pointwise_stream_f16_kernel<K, N>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes, lds_allowed) != TFX_OK) return TFX_ERR_LAUNCH;
+  // as many workgroups as are resident at once (one or two per CU, by registers and LDS): each transposes the
+  // filter once
+  static std::atomic<int> resident{0};
+  int per_cu = resident.load(std::memory_order_relaxed);
+  if (per_cu == 0) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, lds_bytes) != hipSuccess || per_cu < 1)
+      per_cu = 1;
+    if (per_cu > 2) per_cu = 2;
+    resident.store(per_cu, std::memory_order_relaxed);
+  }
   const int units = (m + 31) / 32;
-  int blocks = lds_bytes <= 80 * 1024 ? 512 : 256;  // two workgroups per CU when the filter and strips allow
-  if (blocks > (units + 7) / 8) blocks = (units + 7) / 8;
+  int blocks = 256 * per_cu;
+  if (blocks > (units + kWaves - 1) / kWaves) blocks = (units + kWaves - 1) / kWaves;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kThreads), lds_bytes, stream, x, w, bias, y, m, units, act);
   return check_launch();
 }

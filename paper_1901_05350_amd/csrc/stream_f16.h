@@ -1,0 +1,144 @@
+// Pieces shared by the filter-stationary kernels on 16-bit float storage (pointwise_f16.hip, conv_stream_f16.hip):
+// the filter's layout in LDS, its transpose from global memory, and the epilogue that turns accumulators into
+// 16-byte pieces of output.  All of it is written for v_mfma_f32_16x16x32_f16 with the filter as the first operand:
+// lane (li = lane % 16, q = lane / 16) supplies filter row li and k-group q, and receives rows 4 q ... 4 q + 3 of
+// the 16-row output block in its four accumulator registers.
+#pragma once
+#include "tfx_internal.h"
+
+namespace tfx {
+namespace f16s {
+
+typedef _Float16 half_t;
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// ds_read_b128 serves 32 lanes at a time and is free of bank conflicts when their 16-byte pieces differ modulo 32
+// (measured on gfx950: such patterns read at twice the rate of ones that only differ modulo 16 within 16 lanes).
+// `piece(li, q)` is the piece index of lane (li, q) up to a constant.
+template <typename F>
+constexpr bool conflict_free(F piece) {
+  for (int half = 0; half < 2; ++half) {
+    unsigned seen = 0;
+    for (int li = 0; li < 16; ++li)
+      for (int q = 2 * half; q < 2 * half + 2; ++q) {
+        const unsigned bit = 1u << (piece(li, q) % 32);
+        if (seen & bit) return false;
+        seen |= bit;
+      }
+  }
+  return true;
+}
+
+// Filter rows in LDS: K halfs (k-contiguous, as the matrix cores want them) plus the least padding, in 16-byte
+// pieces, that makes the fragment read of 16 consecutive rows free of conflicts.
+constexpr int filter_row_halfs(int K) {
+  for (int pieces = K / 8 + 1;; ++pieces) {
+    bool ok = true;
+    for (int half = 0; half < 2 && ok; ++half) {
+      unsigned seen = 0;
+      for (int li = 0; li < 16 && ok; ++li)
+        for (int q = 2 * half; q < 2 * half + 2; ++q) {
+          const unsigned bit = 1u << ((li * pieces + q) % 32);
+          if (seen & bit) ok = false;
+          seen |= bit;
+        }
+    }
+    if (ok) return pieces * 8;
+  }
+}
+
+// Column c of the filter goes to LDS row rho(c) = 32 (c / 32) + 16 (c % 8 / 4) + 4 (c % 32 / 8) + c % 4.  With the
+// MFMA's output layout a lane then owns channels 8 q ... 8 q + 7 of every 32 -- the first four in block 2 m, the
+// rest in block 2 m + 1 -- and stores them as one 16-byte piece.
+__device__ __forceinline__ constexpr int rho(int c) { return 32 * (c / 32) + 16 * (c % 8 / 4) + 4 * (c % 32 / 8) + c % 4; }
+
+// The filter w[K][N] moves to LDS as [N rows in rho order][LD halfs] in two steps, so that the caller can put other
+// loads between them: `filter_fetch` issues every 16-byte load of the thread (block u covers k-rows 4 kq ... + 3 of
+// columns 8 nb ... + 7, nb = u % (N/8), so the lanes of a wavefront read whole rows of w; no branch: a thread
+// without a block in the last round reads block 0 again), `filter_store` transposes each 4 x 8 block in registers
+// and writes eight 8-byte pieces.
+template <int K, int N, int NT>
+struct FilterStage {
+  static constexpr int BLOCKS = (K / 4) * (N / 8), PER = (BLOCKS + NT - 1) / NT, LD = filter_row_halfs(K);
+  h8 r[PER][4];
+  __device__ __forceinline__ void fetch(const half_t* __restrict__ w, int tid) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int u = tid + i * NT < BLOCKS ? tid + i * NT : 0, nb = u % (N / 8), kq = u / (N / 8);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) r[i][kk] = *reinterpret_cast<const h8*>(w + (size_t)(4 * kq + kk) * N + 8 * nb);
+    }
+  }
+  __device__ __forceinline__ void store(half_t* wl, int tid) const {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int u = tid + i * NT, nb = u % (N / 8), kq = u / (N / 8);
+      if (BLOCKS % NT == 0 || i + 1 < PER || u < BLOCKS) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const h4 o = {r[i][0][j], r[i][1][j], r[i][2][j], r[i][3][j]};
+          *reinterpret_cast<h4*>(wl + rho(8 * nb + j) * LD + 4 * kq) = o;
+        }
+      }
+    }
+  }
+};
+
+// Bias in the accumulators' layout (block j, rows 4 q ... 4 q + 3 = channels 32 (j / 2) + 8 q + 4 (j % 2) ...):
+// `fetch` issues the loads without a branch (with no bias they read `fallback`, any readable array of at least as
+// many halfs, and the values are dropped), `get` converts them; nothing between the two waits for the loads.
+template <int NB>
+struct BiasRows {
+  half_t raw[NB][4];
+  __device__ __forceinline__ void fetch(const half_t* __restrict__ bias, const half_t* __restrict__ fallback, int q) {
+    const half_t* const p = bias ? bias : fallback;
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) raw[j][e] = p[32 * (j / 2) + 8 * q + 4 * (j % 2) + e];
+  }
+  __device__ __forceinline__ void get(bool have, f32x4 (&bv)[NB]) const {
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bv[j][e] = have ? (float)raw[j][e] : 0.f;
+  }
+};
+
+// Activation and rounding of one 16-row slab: accumulator blocks 2 m and 2 m + 1 become the 8 halfs o[m].  The clamp
+// is one median-of-three per value; that instruction, like max and min, drops a NaN, so NaNs are looked for on the
+// side (a compare per pair of values, collected in scalar registers) and a wavefront that holds one takes the exact
+// form, through which a NaN passes.
+template <int NB>
+__device__ __forceinline__ void activate_and_pack(const f32x4 (&acc)[NB], const ActClamp& clamp, h8 (&o)[NB / 2]) {
+  const float lo = clamp.on ? 0.f : -INFINITY;
+  unsigned long long nan = 0;
+#pragma unroll
+  for (int m = 0; m < NB / 2; ++m) {
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[e] = acc[2 * m][e];
+      v[4 + e] = acc[2 * m + 1][e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) nan |= __builtin_amdgcn_ballot_w64(__builtin_isunordered(v[e], v[e + 1]));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[m][e] = (half_t)__builtin_amdgcn_fmed3f(v[e], lo, clamp.hi);
+  }
+  if (nan != 0) {
+#pragma unroll
+    for (int m = 0; m < NB / 2; ++m)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        o[m][e] = (half_t)apply_act(acc[2 * m][e], clamp);
+        o[m][4 + e] = (half_t)apply_act(acc[2 * m + 1][e], clamp);
+      }
+  }
+}
+
+}  // namespace f16s
+}  // namespace tfx
