@@ -27,23 +27,23 @@ PEAK_HBM = 8.0e12          # B/s
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same counters'
 # reading for a plain 205.5 MB copy (profiles/hbm_traffic_counters.txt).  Each entry names the kernel
-# source it was measured on, with the digest of that file followed by the shared header csrc/tfx_internal.h;
-# if either has changed since, the entry is reported as null.
+# source it was measured on, with the digest of that file followed by the shared headers csrc/tfx_internal.h and
+# csrc/stream_f16.h; if any of them has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100848539, "gemm.hip", "3fa4fe7252aa5ee9b70ad6fffb6606e5bc3bfdfa35abf46537c5b4f8bf58eed3"),
-    "pointwise_64x56x56x128_to_128": (206184248, "pointwise.hip", "d29ff7ac20207d82db0222a405a62aa350d84727111a916456ea902730817a1d"),
-    "conv3x3_64x56x56x64_to_64": (104546322, "gemm.hip", "3fa4fe7252aa5ee9b70ad6fffb6606e5bc3bfdfa35abf46537c5b4f8bf58eed3"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411139607, "depthwise.hip", "aa1aeba44211fa898801c5afd4978534d78f5975686a5c208ba1642af7fd1c41"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (257118310, "depthwise.hip", "aa1aeba44211fa898801c5afd4978534d78f5975686a5c208ba1642af7fd1c41"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235078045, "gemm_f16.hip", "80aa83df2fd240f4f1fd0f7638f758b1c1abb7a0113ff8b09f40ad18172deb5f"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50493585, "gemm_f16.hip", "80aa83df2fd240f4f1fd0f7638f758b1c1abb7a0113ff8b09f40ad18172deb5f"),
-    "pointwise_f16_64x56x56x128_to_128": (103142521, "pointwise_f16.hip", "1856081f98a1d76163860cb4e20ff6f928268e86cd51ffa5d066932f03d3980b"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205682055, "conv_f16.hip", "ede4c45279dd7783bcd5846123d1372e2e7f064b7169dcc371c50a13f9ffffd3"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129310122, "conv_f16.hip", "ede4c45279dd7783bcd5846123d1372e2e7f064b7169dcc371c50a13f9ffffd3"),
-    "conv3x3_f16_64x56x56x64_to_64": (52067265, "conv_gemm_f16.hip", "bed8ce3dd5921dd131300d70423098bea6cb3c532bf49841b7fd8778284d423c"),
-    "add_f32_64M": (805262682, "elementwise.hip", "085f35045800c64ab32340bde100d08fabb0cbde23f7496b22b9014f58eba22f"),
-    "add_f16_64M": (402651813, "elementwise.hip", "085f35045800c64ab32340bde100d08fabb0cbde23f7496b22b9014f58eba22f"),
-    "mobilenet_chain_kernel": (121667068, "chain.hip", "39c2ecddb28a12c15d3ce41f5debc26b6e7c2583e9eda1fc657f146402c00ab3"),
+    "batch_matmul_8x1024x1024x1024_tB": (100848560, "gemm.hip", "5812daa7fcc28f3e379e0e75b773d0dd0dade42527a6e1578f6554436ced57a9"),
+    "pointwise_64x56x56x128_to_128": (206184316, "pointwise.hip", "5357c3736c1d68178f35e52374abc9374f31f69f606e70a60c874d7cef439439"),
+    "conv3x3_64x56x56x64_to_64": (104539687, "gemm.hip", "5812daa7fcc28f3e379e0e75b773d0dd0dade42527a6e1578f6554436ced57a9"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411139145, "depthwise.hip", "e7145ca21cad0a1ce8dcebbd33a44e550bf90d9450529860520103b5b5847011"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (257101258, "depthwise.hip", "e7145ca21cad0a1ce8dcebbd33a44e550bf90d9450529860520103b5b5847011"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235078071, "gemm_f16.hip", "7989c0a413c6c219aff79387c25add87e5319d59946f92a8a2818bdce785b7d3"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50493589, "gemm_f16.hip", "7989c0a413c6c219aff79387c25add87e5319d59946f92a8a2818bdce785b7d3"),
+    "pointwise_f16_64x56x56x128_to_128": (104398427, "pointwise_f16.hip", "db4c9c454b245c7f2702bdc2696853ee9a1f21ae1eb26bb6612b8e58b467bf25"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205682025, "conv_f16.hip", "095e2db67d14849c6f4ae36fffa7a949bb0173952fa3502c759b717003b32f70"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129459127, "conv_f16.hip", "095e2db67d14849c6f4ae36fffa7a949bb0173952fa3502c759b717003b32f70"),
+    "conv3x3_f16_64x56x56x64_to_64": (55040793, "conv_stream_f16.hip", "f69d96fcaf15f7621e3026e3c9fd8810468014093a91720fecd495a60a391533"),
+    "add_f32_64M": (805262720, "elementwise.hip", "aad7cb000af0ae451b89b5009eed85617da85432d16843444e79b44ebcefad24"),
+    "add_f16_64M": (402651731, "elementwise.hip", "aad7cb000af0ae451b89b5009eed85617da85432d16843444e79b44ebcefad24"),
+    "mobilenet_chain_kernel": (121653062, "chain.hip", "55efe6105fe374418fd75d6f685a0f681469ca6544dee0694e540cef4f84e1ba"),
 }
 
 
@@ -56,7 +56,7 @@ def measured_traffic(name):
     csrc = os.path.join(ROOT, "paper_1901_05350_amd", "csrc")
     try:
         h = hashlib.sha256()
-        for part in (fname, "tfx_internal.h"):
+        for part in (fname, "tfx_internal.h", "stream_f16.h"):
             with open(os.path.join(csrc, part), "rb") as f:
                 h.update(f.read())
         return nbytes if h.hexdigest() == digest else None
