@@ -10,6 +10,8 @@
 // CU drift apart and loads, MFMAs and stores of different slabs overlap.
 #include "tfx_internal.h"
 
+#include <type_traits>
+
 namespace tfx {
 namespace {
 
@@ -29,6 +31,9 @@ __device__ __forceinline__ void fetch_slab(const float4* __restrict__ xp, float4
 // step s, i.e. one 128-bit load of its row per group.  LDS rows are padded by 4 floats so that the
 // four k rows read by one instruction fall into different banks.  Wavefronts of a workgroup take
 // the workgroup's slabs first come, first served (LDS counter).
+// The accumulators start from the bias (kept in LDS behind the filter).  Cutting the slabs left over after a
+// workgroup's last full round of 8 into column parts, so that the last round is short for everybody, was measured
+// and gained nothing: the workgroups end 15 us apart anyway, in the order in which memory served their first slabs.
 template <int K, int N>
 __global__ __launch_bounds__(kThreads) void pointwise_stream16_kernel(const float* __restrict__ x,
                                                                       const float* __restrict__ w,
@@ -36,8 +41,9 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream16_kernel(const floa
                                                                       float* __restrict__ y, int M, int slabs, int act) {
   constexpr int KG = K / 16, NB = N / 16, LD = N + 4;
   constexpr int NBP = NB < 8 ? NB : 8;  // 16-column blocks per pass
-  static_assert((K * N / 4) % kThreads == 0, "filter staging");
-  extern __shared__ __align__(16) float wl[];  // [K][N + 4]
+  static_assert((K * N / 4) % kThreads == 0 && N <= kThreads && NB % 2 == 0, "filter staging");
+  extern __shared__ __align__(16) float wl[];  // [K][N + 4], then the bias (N floats; zeros without one)
+  float* const bias_l = wl + K * LD;
   __shared__ int next_slab;                    // wavefronts of the workgroup take slabs first come, first served
 
   const int tid = threadIdx.x;
@@ -47,20 +53,41 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream16_kernel(const floa
     float4 t[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) t[i] = reinterpret_cast<const float4*>(w)[tid + i * kThreads];
+    const float bias_c = (bias ? bias : w)[tid < N ? tid : 0];
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       const int e = tid + i * kThreads;  // float4 index: row e / (N/4), column quad e % (N/4)
       *reinterpret_cast<float4*>(wl + (e / (N / 4)) * LD + 4 * (e % (N / 4))) = t[i];
     }
+    if (tid < N) bias_l[tid] = bias ? bias_c : 0.f;
   }
   __syncthreads();
 
   const int lane = tid % 64, li = lane % 16, q = lane / 16;
-  constexpr int waves = kThreads / 64;
   const ActClamp clamp = make_act(act);
   const int s0 = (int)((long long)slabs * blockIdx.x / gridDim.x);
   const int s1 = (int)((long long)slabs * (blockIdx.x + 1) / gridDim.x);
-  (void)waves;
+  // W blocks of 16 columns, starting at block jb, of one slab whose operand values are in a[]
+  auto columns = [&](auto wc, const float4 (&a)[KG], int slab, int jb) {
+    constexpr int W = decltype(wc)::value;
+    floatx4 acc[W];
+#pragma unroll
+    for (int j = 0; j < W; ++j) acc[j] = *reinterpret_cast<const floatx4*>(bias_l + 16 * (jb + j) + 4 * q);
+#pragma unroll
+    for (int g = 0; g < KG; ++g) {
+      const float av[4] = {a[g].x, a[g].y, a[g].z, a[g].w};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const float* wr = wl + (16 * g + 4 * q + s) * LD + 16 * jb + li;
+#pragma unroll
+        for (int j = 0; j < W; ++j)
+          acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[16 * j], av[s], acc[j], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // keep later groups' LDS reads from being hoisted
+    }
+    store_slab_biased<W, true>(acc, y + 16 * jb, N, slab * 16, M, li, q, clamp);
+  };
+
   for (;;) {
     int ticket = 0;
     if (lane == 0) ticket = atomicAdd(&next_slab, 1);
@@ -72,33 +99,9 @@ __global__ __launch_bounds__(kThreads) void pointwise_stream16_kernel(const floa
     const float* xp = x + (size_t)rowc * K + 4 * q;
 #pragma unroll
     for (int g = 0; g < KG; ++g) a[g] = *reinterpret_cast<const float4*>(xp + 16 * g);
-
 #pragma unroll
-    for (int p = 0; p < NB / NBP; ++p) {  // column passes of at most 128 columns keep the accumulators few
-      floatx4 acc[NBP];
-#pragma unroll
-      for (int j = 0; j < NBP; ++j)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) acc[j][v] = 0.f;
-#pragma unroll
-      for (int g = 0; g < KG; ++g) {
-        const float av[4] = {a[g].x, a[g].y, a[g].z, a[g].w};
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const float* wr = wl + (16 * g + 4 * q + s) * LD + 16 * NBP * p + li;
-#pragma unroll
-          for (int j = 0; j < NBP; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[16 * j], av[s], acc[j], 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);  // keep later groups' LDS reads from being hoisted
-      }
-      float4 bv[NBP / 2];
-#pragma unroll
-      for (int h = 0; h < NBP / 2; ++h)
-        bv[h] = bias ? *reinterpret_cast<const float4*>(bias + 16 * NBP * p + 32 * h + (li < 8 ? 0 : 16) + 4 * q)
-                     : make_float4(0.f, 0.f, 0.f, 0.f);
-      store_slab<NBP, true>(acc, bv, y + 16 * NBP * p, N, slab * 16, M, li, q, clamp);
-    }
+    for (int p = 0; p < NB / NBP; ++p)  // column passes of at most 128 columns keep the accumulators few
+      columns(std::integral_constant<int, NBP>{}, a, slab, NBP * p);
   }
 }
 
@@ -224,8 +227,8 @@ int launch_regfilter(const float* x, const float* w, const float* bias, float* y
 
 template <int K, int N>
 int launch_stream16(const float* x, const float* w, const float* bias, float* y, int m, int act, hipStream_t stream) {
-  constexpr size_t lds_bytes = (size_t)K * (N + 4) * sizeof(float);
-  static_assert(lds_bytes <= 160 * 1024, "filter must fit in LDS");
+  constexpr size_t lds_bytes = ((size_t)K * (N + 4) + N) * sizeof(float);
+  static_assert(lds_bytes + 64 <= 160 * 1024, "filter must fit in LDS");
   auto kern = pointwise_stream16_kernel<K, N>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes, lds_allowed) != TFX_OK) return TFX_ERR_LAUNCH;

@@ -77,6 +77,42 @@ __device__ __forceinline__ void store_slab(const floatx4 (&acc)[NBLK], const flo
   }
 }
 
+// The same store for accumulators that already hold the bias (they started from it).  The clamp is one
+// median-of-three per value; that instruction, like max and min, drops a NaN, so NaNs are looked for on the side
+// (one compare per pair of values, collected in scalar registers) and a block pair that holds one takes the exact
+// form, through which a NaN passes.
+template <int NBLK, bool CHECK>
+__device__ __forceinline__ void store_slab_biased(const floatx4 (&acc)[NBLK], float* yc, int n, int row0, int M, int li,
+                                                  int q, const ActClamp& clamp) {
+  static_assert(NBLK % 2 == 0, "blocks are stored in pairs");
+  const bool lo = li < 8;
+  const int ra = row0 + (li & 7), rb = ra + 8;
+  const float lo_bound = clamp.on ? 0.f : -INFINITY;
+  float a[NBLK / 2][4], b[NBLK / 2][4];
+  unsigned long long nan = 0;
+#pragma unroll
+  for (int h = 0; h < NBLK / 2; ++h)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float got = swap8(lo ? acc[2 * h + 1][v] : acc[2 * h][v]);
+      a[h][v] = lo ? acc[2 * h][v] : got;
+      b[h][v] = lo ? got : acc[2 * h + 1][v];
+      nan |= __builtin_amdgcn_ballot_w64(__builtin_isunordered(a[h][v], b[h][v]));
+    }
+  auto store = [&](auto act1) {
+#pragma unroll
+    for (int h = 0; h < NBLK / 2; ++h) {
+      const float4 oa = make_float4(act1(a[h][0]), act1(a[h][1]), act1(a[h][2]), act1(a[h][3]));
+      const float4 ob = make_float4(act1(b[h][0]), act1(b[h][1]), act1(b[h][2]), act1(b[h][3]));
+      const int col = 32 * h + (lo ? 0 : 16) + 4 * q;
+      if (!CHECK || ra < M) *reinterpret_cast<float4*>(yc + (size_t)ra * n + col) = oa;
+      if (!CHECK || rb < M) *reinterpret_cast<float4*>(yc + (size_t)rb * n + col) = ob;
+    }
+  };
+  if (nan == 0) store([&](float v) { return __builtin_amdgcn_fmed3f(v, lo_bound, clamp.hi); });
+  else store([&](float v) { return apply_act(v, clamp); });
+}
+
 // Shape rule of one spatial dimension (see include/tfx.h); returns a tfx_status.
 int out_extent(int64_t in, int64_t k, int64_t s, int pad, int64_t* out, int64_t* before, int64_t* after);
 
