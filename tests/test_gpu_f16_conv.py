@@ -106,6 +106,8 @@ def test_conv2d_f16_3x3_benchmark_size_every_image():
     ((10, 44, 41, 64, 32, 3, 3), 1, PAD_SAME, ACT_RELU6),
     ((17, 33, 31, 32, 32, 3, 3), 1, PAD_SAME, ACT_NONE),
     ((4, 150, 38, 64, 64, 3, 3), 1, PAD_VALID, ACT_RELU6),      # tall images: a workgroup's units cross image boundaries
+    ((1100, 3, 5, 32, 32, 3, 3), 1, PAD_SAME, ACT_RELU6),       # images smaller than a 4 x 8 patch: every window is mostly padding
+    ((50, 21, 20, 64, 64, 3, 3), 1, PAD_VALID, ACT_RELU),       # 19 x 18 outputs: 3 of 4 rows and 2 of 8 columns in the last patches
     ((9, 45, 47, 128, 32, 3, 3), 1, PAD_SAME, ACT_RELU6),       # 128 channels in: the tiled implicit GEMM
     ((23, 57, 53, 32, 64, 3, 3), 2, PAD_SAME, ACT_RELU),        # stride 2: the tiled implicit GEMM
 ])
