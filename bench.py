@@ -30,20 +30,20 @@ PEAK_HBM = 8.0e12          # B/s
 # source it was measured on, with the digest of that file followed by the shared headers csrc/tfx_internal.h and
 # csrc/stream_f16.h; if any of them has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100848560, "gemm.hip", "5812daa7fcc28f3e379e0e75b773d0dd0dade42527a6e1578f6554436ced57a9"),
-    "pointwise_64x56x56x128_to_128": (206184316, "pointwise.hip", "5357c3736c1d68178f35e52374abc9374f31f69f606e70a60c874d7cef439439"),
-    "conv3x3_64x56x56x64_to_64": (104539687, "gemm.hip", "5812daa7fcc28f3e379e0e75b773d0dd0dade42527a6e1578f6554436ced57a9"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411139145, "depthwise.hip", "e7145ca21cad0a1ce8dcebbd33a44e550bf90d9450529860520103b5b5847011"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (257101258, "depthwise.hip", "e7145ca21cad0a1ce8dcebbd33a44e550bf90d9450529860520103b5b5847011"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235078071, "gemm_f16.hip", "7989c0a413c6c219aff79387c25add87e5319d59946f92a8a2818bdce785b7d3"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50493589, "gemm_f16.hip", "7989c0a413c6c219aff79387c25add87e5319d59946f92a8a2818bdce785b7d3"),
-    "pointwise_f16_64x56x56x128_to_128": (104398427, "pointwise_f16.hip", "db4c9c454b245c7f2702bdc2696853ee9a1f21ae1eb26bb6612b8e58b467bf25"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205682025, "conv_f16.hip", "095e2db67d14849c6f4ae36fffa7a949bb0173952fa3502c759b717003b32f70"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129459127, "conv_f16.hip", "095e2db67d14849c6f4ae36fffa7a949bb0173952fa3502c759b717003b32f70"),
-    "conv3x3_f16_64x56x56x64_to_64": (55040793, "conv_stream_f16.hip", "f69d96fcaf15f7621e3026e3c9fd8810468014093a91720fecd495a60a391533"),
-    "add_f32_64M": (805262720, "elementwise.hip", "aad7cb000af0ae451b89b5009eed85617da85432d16843444e79b44ebcefad24"),
-    "add_f16_64M": (402651731, "elementwise.hip", "aad7cb000af0ae451b89b5009eed85617da85432d16843444e79b44ebcefad24"),
-    "mobilenet_chain_kernel": (121653062, "chain.hip", "55efe6105fe374418fd75d6f685a0f681469ca6544dee0694e540cef4f84e1ba"),
+    "batch_matmul_8x1024x1024x1024_tB": (100848644, "gemm.hip", "5070f643254ddcdf68189b70e4a70170098ddc5660bdc66bc8528366478629a9"),
+    "pointwise_64x56x56x128_to_128": (206181199, "pointwise.hip", "9ff3083131c438877e5c2b6f9c19a9d13a5d62611a1e3e6def76ecf98795b212"),
+    "conv3x3_64x56x56x64_to_64": (104548046, "gemm.hip", "5070f643254ddcdf68189b70e4a70170098ddc5660bdc66bc8528366478629a9"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411139482, "depthwise.hip", "318a4f1ae87d45856db39954fc26eb57f19d1d7d382924b414e7381103d37d0a"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (257166653, "depthwise.hip", "318a4f1ae87d45856db39954fc26eb57f19d1d7d382924b414e7381103d37d0a"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235078221, "gemm_f16.hip", "07b45ba15ffd07f664080f46b51ee959f2c8e18e0c965e7cf102085b9740b269"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50493620, "gemm_f16.hip", "07b45ba15ffd07f664080f46b51ee959f2c8e18e0c965e7cf102085b9740b269"),
+    "pointwise_f16_64x56x56x128_to_128": (104218020, "pointwise_f16.hip", "aef151b324b5bd955f49a0cee1cfd13dbede64f93ae464f704c0d0c630215d38"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205681939, "conv_f16.hip", "cb6f35036f7e9768d9db854cff0395c4992137fdc27248947ac962ff851e8cda"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129520583, "conv_f16.hip", "cb6f35036f7e9768d9db854cff0395c4992137fdc27248947ac962ff851e8cda"),
+    "conv3x3_f16_64x56x56x64_to_64": (55040849, "conv_stream_f16.hip", "5929df2173e5a34344a055430d4028da1372d4f6796ad6dbeea8d6681a1f1012"),
+    "add_f32_64M": (805263126, "elementwise.hip", "fb216fc7e663949b27aabc959a80de1d84323390c0197989ce399ceb4029cf56"),
+    "add_f16_64M": (402651694, "elementwise.hip", "fb216fc7e663949b27aabc959a80de1d84323390c0197989ce399ceb4029cf56"),
+    "mobilenet_chain_kernel": (121665685, "chain.hip", "03e3c2b81a655cebd11b7ba225a6c4bbc570786e0390249066473d79cf0b6249"),
 }
 
 
