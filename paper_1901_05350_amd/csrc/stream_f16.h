@@ -56,10 +56,10 @@ constexpr int filter_row_halfs(int K) {
 __device__ __forceinline__ constexpr int rho(int c) { return 32 * (c / 32) + 16 * (c % 8 / 4) + 4 * (c % 32 / 8) + c % 4; }
 
 // The filter w[K][N] moves to LDS as [N rows in rho order][LD halfs] in two steps, so that the caller can put other
-// loads between them: `filter_fetch` issues every 16-byte load of the thread (block u covers k-rows 4 kq ... + 3 of
+// loads between them: `fetch` issues every 16-byte load of the thread (block u covers k-rows 4 kq ... + 3 of
 // columns 8 nb ... + 7, nb = u % (N/8), so the lanes of a wavefront read whole rows of w; no branch: a thread
-// without a block in the last round reads block 0 again), `filter_store` transposes each 4 x 8 block in registers
-// and writes eight 8-byte pieces.
+// without a block in the last pass over the blocks reads block 0 again -- behind a guarded load the compiler waits
+// for every load still in flight), `store` transposes each 4 x 8 block in registers and writes eight 8-byte pieces.
 template <int K, int N, int NT>
 struct FilterStage {
   static constexpr int BLOCKS = (K / 4) * (N / 8), PER = (BLOCKS + NT - 1) / NT, LD = filter_row_halfs(K);
