@@ -30,20 +30,20 @@ PEAK_HBM = 8.0e12          # B/s
 # source it was measured on, with the digest of that file followed by the shared headers csrc/tfx_internal.h and
 # csrc/stream_f16.h; if any of them has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100848644, "gemm.hip", "5070f643254ddcdf68189b70e4a70170098ddc5660bdc66bc8528366478629a9"),
-    "pointwise_64x56x56x128_to_128": (206181199, "pointwise.hip", "9ff3083131c438877e5c2b6f9c19a9d13a5d62611a1e3e6def76ecf98795b212"),
-    "conv3x3_64x56x56x64_to_64": (104548046, "gemm.hip", "5070f643254ddcdf68189b70e4a70170098ddc5660bdc66bc8528366478629a9"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411139482, "depthwise.hip", "318a4f1ae87d45856db39954fc26eb57f19d1d7d382924b414e7381103d37d0a"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (257166653, "depthwise.hip", "318a4f1ae87d45856db39954fc26eb57f19d1d7d382924b414e7381103d37d0a"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235078221, "gemm_f16.hip", "07b45ba15ffd07f664080f46b51ee959f2c8e18e0c965e7cf102085b9740b269"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50493620, "gemm_f16.hip", "07b45ba15ffd07f664080f46b51ee959f2c8e18e0c965e7cf102085b9740b269"),
-    "pointwise_f16_64x56x56x128_to_128": (104218020, "pointwise_f16.hip", "aef151b324b5bd955f49a0cee1cfd13dbede64f93ae464f704c0d0c630215d38"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205681939, "conv_f16.hip", "cb6f35036f7e9768d9db854cff0395c4992137fdc27248947ac962ff851e8cda"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129520583, "conv_f16.hip", "cb6f35036f7e9768d9db854cff0395c4992137fdc27248947ac962ff851e8cda"),
-    "conv3x3_f16_64x56x56x64_to_64": (55040849, "conv_stream_f16.hip", "5929df2173e5a34344a055430d4028da1372d4f6796ad6dbeea8d6681a1f1012"),
-    "add_f32_64M": (805263126, "elementwise.hip", "fb216fc7e663949b27aabc959a80de1d84323390c0197989ce399ceb4029cf56"),
-    "add_f16_64M": (402651694, "elementwise.hip", "fb216fc7e663949b27aabc959a80de1d84323390c0197989ce399ceb4029cf56"),
-    "mobilenet_chain_kernel": (121665685, "chain.hip", "03e3c2b81a655cebd11b7ba225a6c4bbc570786e0390249066473d79cf0b6249"),
+    "batch_matmul_8x1024x1024x1024_tB": (100848644, "gemm.hip", "807829e18f0a615cbaae58e222a694f145f61bd709bfed5dbad3c23697225692"),
+    "pointwise_64x56x56x128_to_128": (206181199, "pointwise.hip", "1a65e2ea8c015f4691dc3b47fce26ad6019993ad200b66ccb449f41a26498961"),
+    "conv3x3_64x56x56x64_to_64": (104548046, "gemm.hip", "807829e18f0a615cbaae58e222a694f145f61bd709bfed5dbad3c23697225692"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411139482, "depthwise.hip", "3f1e0516ea4cb7432e3f0727a320a5ccb677ff79f5fbd7356c662489ca238ec8"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (257166653, "depthwise.hip", "3f1e0516ea4cb7432e3f0727a320a5ccb677ff79f5fbd7356c662489ca238ec8"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235078221, "gemm_f16.hip", "42e3f84717e37f74c750776d086088786e57ca701f7c42ea30c5a9892c44162a"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50493620, "gemm_f16.hip", "42e3f84717e37f74c750776d086088786e57ca701f7c42ea30c5a9892c44162a"),
+    "pointwise_f16_64x56x56x128_to_128": (104218020, "pointwise_f16.hip", "591e574ad4dbd62c1254be5484a309e1dbf98ecaaed7d27b58a16a425e43cd39"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205681939, "conv_f16.hip", "360dedc63e17afbfc734302766ff4041c879c63ccc5a9d4651fb87307d37d195"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129520583, "conv_f16.hip", "360dedc63e17afbfc734302766ff4041c879c63ccc5a9d4651fb87307d37d195"),
+    "conv3x3_f16_64x56x56x64_to_64": (55040849, "conv_stream_f16.hip", "f986ada394c7a8da79fd5b8bec95da8389a9a099c5a5458645b7a5054c75028a"),
+    "add_f32_64M": (805263126, "elementwise.hip", "07593e1330886dce69a08bd1930f778db73e34c77eddc422b82967e5eeeadcb9"),
+    "add_f16_64M": (402651694, "elementwise.hip", "07593e1330886dce69a08bd1930f778db73e34c77eddc422b82967e5eeeadcb9"),
+    "mobilenet_chain_kernel": (121665685, "chain.hip", "e3af06d21fa8899d7b147f277b0ebf10835b76e8553259d83616c59f2d404ed1"),
 }
 
 

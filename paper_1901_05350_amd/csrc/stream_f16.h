@@ -34,20 +34,13 @@ constexpr bool conflict_free(F piece) {
 
 // Filter rows in LDS: K halfs (k-contiguous, as the matrix cores want them) plus the least padding, in 16-byte
 // pieces, that makes the fragment read of 16 consecutive rows free of conflicts.
+struct FilterRowPieces {
+  int pieces;  // row stride in 16-byte pieces
+  constexpr int operator()(int li, int q) const { return li * pieces + q; }
+};
 constexpr int filter_row_halfs(int K) {
-  for (int pieces = K / 8 + 1;; ++pieces) {
-    bool ok = true;
-    for (int half = 0; half < 2 && ok; ++half) {
-      unsigned seen = 0;
-      for (int li = 0; li < 16 && ok; ++li)
-        for (int q = 2 * half; q < 2 * half + 2; ++q) {
-          const unsigned bit = 1u << ((li * pieces + q) % 32);
-          if (seen & bit) ok = false;
-          seen |= bit;
-        }
-    }
-    if (ok) return pieces * 8;
-  }
+  for (int pieces = K / 8 + 1;; ++pieces)
+    if (conflict_free(FilterRowPieces{pieces})) return pieces * 8;
 }
 
 // Column c of the filter goes to LDS row rho(c) = 32 (c / 32) + 16 (c % 8 / 4) + 4 (c % 32 / 8) + c % 4.  With the
