@@ -500,10 +500,25 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
       cur ^= 1;
       continue;
     }
+    // large batch, early block: depthwise and pointwise layer in one filter-stationary launch (block_stream.hip)
+    conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
+    if (separable_stream_supported((int)batch, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, kStrides[b],
+                                   (int)g.out[1], (int)g.out[2], buf[cur], weights->dw_w[b], weights->dw_b[b],
+                                   weights->pw_w[b], weights->pw_b[b], block_out)) {
+      rc = launch_separable_stream(buf[cur], weights->dw_w[b], weights->dw_b[b], weights->pw_w[b], weights->pw_b[b],
+                                   block_out, (int)batch, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout,
+                                   (int)g.out[1], (int)g.out[2], kStrides[b], (int)g.pad[0], (int)g.pad[2], TFX_ACT_RELU6,
+                                   TFX_ACT_RELU6, static_cast<hipStream_t>(stream));
+      if (rc) return rc;
+      if (end_block == b + 1) return TFX_OK;
+      for (int i = 0; i < 3; ++i) shape[i] = g.out[i];
+      shape[3] = cout;
+      cur ^= 1;
+      continue;
+    }
     rc = tfx_depthwise_conv2d(buf[cur], shape, weights->dw_w[b], fd, weights->dw_b[b], kStrides[b], kStrides[b],
                               TFX_PAD_SAME, TFX_ACT_RELU6, buf[cur ^ 1], stream);
     if (rc) return rc;
-    conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
     for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
     cur ^= 1;
     const int64_t fp[4] = {1, 1, shape[3], cout};

@@ -15,23 +15,6 @@ typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// ds_read_b128 serves 32 lanes at a time and is free of bank conflicts when their 16-byte pieces differ modulo 32
-// (measured on gfx950: such patterns read at twice the rate of ones that only differ modulo 16 within 16 lanes).
-// `piece(li, q)` is the piece index of lane (li, q) up to a constant.
-template <typename F>
-constexpr bool conflict_free(F piece) {
-  for (int half = 0; half < 2; ++half) {
-    unsigned seen = 0;
-    for (int li = 0; li < 16; ++li)
-      for (int q = 2 * half; q < 2 * half + 2; ++q) {
-        const unsigned bit = 1u << (piece(li, q) % 32);
-        if (seen & bit) return false;
-        seen |= bit;
-      }
-  }
-  return true;
-}
-
 // Filter rows in LDS: K halfs (k-contiguous, as the matrix cores want them) plus the least padding, in 16-byte
 // pieces, that makes the fragment read of 16 consecutive rows free of conflicts.
 struct FilterRowPieces {

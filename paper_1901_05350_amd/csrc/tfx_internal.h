@@ -81,12 +81,12 @@ __device__ __forceinline__ void store_slab(const floatx4 (&acc)[NBLK], const flo
 // median-of-three per value; that instruction, like max and min, drops a NaN, so NaNs are looked for on the side
 // (one compare per pair of values, collected in scalar registers) and a block pair that holds one takes the exact
 // form, through which a NaN passes.
-template <int NBLK, bool CHECK>
-__device__ __forceinline__ void store_slab_biased(const floatx4 (&acc)[NBLK], float* yc, int n, int row0, int M, int li,
-                                                  int q, const ActClamp& clamp) {
+// ya / yb: where this lane's two rows start (first column of block 0); oka / okb: whether they exist.
+template <int NBLK>
+__device__ __forceinline__ void store_rows_biased(const floatx4 (&acc)[NBLK], float* ya, float* yb, bool oka, bool okb,
+                                                  int li, int q, const ActClamp& clamp) {
   static_assert(NBLK % 2 == 0, "blocks are stored in pairs");
   const bool lo = li < 8;
-  const int ra = row0 + (li & 7), rb = ra + 8;
   const float lo_bound = clamp.on ? 0.f : -INFINITY;
   float a[NBLK / 2][4], b[NBLK / 2][4];
   unsigned long long nan = 0;
@@ -105,12 +105,36 @@ __device__ __forceinline__ void store_slab_biased(const floatx4 (&acc)[NBLK], fl
       const float4 oa = make_float4(act1(a[h][0]), act1(a[h][1]), act1(a[h][2]), act1(a[h][3]));
       const float4 ob = make_float4(act1(b[h][0]), act1(b[h][1]), act1(b[h][2]), act1(b[h][3]));
       const int col = 32 * h + (lo ? 0 : 16) + 4 * q;
-      if (!CHECK || ra < M) *reinterpret_cast<float4*>(yc + (size_t)ra * n + col) = oa;
-      if (!CHECK || rb < M) *reinterpret_cast<float4*>(yc + (size_t)rb * n + col) = ob;
+      if (oka) *reinterpret_cast<float4*>(ya + col) = oa;
+      if (okb) *reinterpret_cast<float4*>(yb + col) = ob;
     }
   };
   if (nan == 0) store([&](float v) { return __builtin_amdgcn_fmed3f(v, lo_bound, clamp.hi); });
   else store([&](float v) { return apply_act(v, clamp); });
+}
+template <int NBLK, bool CHECK>
+__device__ __forceinline__ void store_slab_biased(const floatx4 (&acc)[NBLK], float* yc, int n, int row0, int M, int li,
+                                                  int q, const ActClamp& clamp) {
+  const int ra = row0 + (li & 7), rb = ra + 8;
+  store_rows_biased<NBLK>(acc, yc + (size_t)ra * n, yc + (size_t)rb * n, !CHECK || ra < M, !CHECK || rb < M, li, q, clamp);
+}
+
+// ds_read_b128 serves 32 lanes at a time and is free of bank conflicts when their 16-byte pieces differ modulo 32
+// (measured on gfx950: such patterns read at twice the rate of ones that only differ modulo 16 within 16 lanes).
+// `piece(li, q)` is the piece index of lane (li = lane % 16, q = lane / 16) up to a constant: the fragment layouts of
+// the 16 x 16 MFMAs read one row or pixel per li and consecutive pieces per q.
+template <typename F>
+constexpr bool conflict_free(F piece) {
+  for (int half = 0; half < 2; ++half) {
+    unsigned seen = 0;
+    for (int li = 0; li < 16; ++li)
+      for (int q = 2 * half; q < 2 * half + 2; ++q) {
+        const unsigned bit = 1u << (piece(li, q) % 32);
+        if (seen & bit) return false;
+        seen |= bit;
+      }
+  }
+  return true;
 }
 
 // Shape rule of one spatial dimension (see include/tfx.h); returns a tfx_status.
@@ -244,6 +268,13 @@ bool conv3x3_stream_f16_supported(long long m, long long x_elems, int ci, int fh
                                   const void* x, const void* w, const void* y);
 int launch_conv3x3_stream_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int n, int h,
                               int wd, int ci, int co, int oh, int ow, int pt, int pl, int act, hipStream_t stream);
+
+// A depthwise-separable block at large batch as one filter-stationary kernel (block_stream.hip).
+bool separable_stream_supported(int batch, int h, int w, int c, int n, int stride, int oh, int ow, const void* x,
+                                const void* dw_w, const void* dw_b, const void* pw_w, const void* pw_b, const void* y);
+int launch_separable_stream(const float* x, const float* dw_w, const float* dw_b, const float* pw_w, const float* pw_b,
+                            float* y, int batch, int h, int w, int c, int n, int oh, int ow, int stride, int pt, int pl,
+                            int dw_act, int pw_act, hipStream_t stream);
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? TFX_OK : TFX_ERR_LAUNCH; }
 
