@@ -79,29 +79,6 @@ __global__ __launch_bounds__(kThreads) void separable_window_kernel(const float*
   const int tid = threadIdx.x;
   const int lane = tid % 64, li = lane % 16, q = lane / 16;
   float* const win = dwb_l + K + (tid / 64) * WL::kFloats;
-  if (tid == 0) next_unit = kWaves;
-  {
-    constexpr int PER = K * N / 4 / kThreads;
-    float4 t[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) t[i] = reinterpret_cast<const float4*>(pw_w)[tid + i * kThreads];
-    // (no branches around these loads: a thread past the end reads element 0 and its value is dropped)
-    const float4 dwv = reinterpret_cast<const float4*>(dw_w)[tid < 9 * K / 4 ? tid : 0];
-    const float pwb = (pw_b ? pw_b : pw_w)[tid < N ? tid : 0];
-    const float dwb = (dw_b ? dw_b : pw_w)[tid < K ? tid : 0];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int e = tid + i * kThreads;  // float4 index: row e / (N/4), column quad e % (N/4)
-      *reinterpret_cast<float4*>(wl + (e / (N / 4)) * LD + 4 * (e % (N / 4))) = t[i];
-    }
-    if (tid < 9 * K / 4) reinterpret_cast<float4*>(dww_l)[tid] = dwv;
-    if (tid < N) pwb_l[tid] = pw_b ? pwb : 0.f;
-    if (tid < K) dwb_l[tid] = dw_b ? dwb : 0.f;
-  }
-  __syncthreads();
-
-  const ActClamp dw_clamp = make_act(dw_act), pw_clamp = make_act(pw_act);
-  const float dw_lo = dw_clamp.on ? 0.f : -INFINITY;
   const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(x), 0, (int)g.x_bytes, 0x00020000);
   const int u0 = (int)((long long)units * blockIdx.x / gridDim.x);
   const int u1 = (int)((long long)units * (blockIdx.x + 1) / gridDim.x);
@@ -115,30 +92,6 @@ __global__ __launch_bounds__(kThreads) void separable_window_kernel(const float*
     goff[i] = ((wr * g.W + wc) * K + 4 * cq) * 4;
     loff[i] = (wr * RS + wc * PS + cq) * 4;
   }
-  // where this lane's taps start in a window: pixel (li / 8, li % 8) * S, piece q
-  const float* const tap0 = win + ((li / 8) * S * RS + (li % 8) * S * PS + q) * 4;
-
-  // W blocks of 16 columns, starting at block jb, of one unit whose operand values are in a[]
-  auto columns = [&](auto wc_, const float4 (&a)[KG], float* ya, float* yb, bool oka, bool okb, int jb) {
-    constexpr int W = decltype(wc_)::value;
-    floatx4 acc[W];
-#pragma unroll
-    for (int j = 0; j < W; ++j) acc[j] = *reinterpret_cast<const floatx4*>(pwb_l + 16 * (jb + j) + 4 * q);
-#pragma unroll
-    for (int gg = 0; gg < KG; ++gg) {
-      const float av[4] = {a[gg].x, a[gg].y, a[gg].z, a[gg].w};
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const float* wr = wl + (16 * gg + 4 * q + s) * LD + 16 * jb + li;
-#pragma unroll
-        for (int j = 0; j < W; ++j)
-          acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[16 * j], av[s], acc[j], 0, 0, 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);  // keep later groups' LDS reads from being hoisted
-    }
-    store_rows_biased<W>(acc, ya + 16 * jb, yb + 16 * jb, oka, okb, li, q, pw_clamp);
-  };
-
   // a unit's place: image, patch, and the byte offset of window pixel (0, 0), channel 0 (may lie outside x)
   struct Place {
     int n, tr, tc, ih0, iw0, base;
@@ -176,12 +129,60 @@ __global__ __launch_bounds__(kThreads) void separable_window_kernel(const float*
     for (int i = 0; i < LI; ++i) wreg[i] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)o.v[i], kChunk * 4 * ch, 0);
   };
 
-  // The first unit of a wavefront is fixed, the rest are handed out by the counter; the first chunk of a unit's
-  // window is requested before the MFMAs of the unit before it.
+  // The first unit of a wavefront is fixed (the rest are handed out by the counter) and the first chunk of its
+  // window is requested before the filters are staged.
+  if (tid == 0) next_unit = kWaves;
   int cur = u0 + __builtin_amdgcn_readfirstlane(tid / 64);
   Place pc = place_of(cur < u1 ? cur : u0);
   Offsets oc = offsets_of(pc, cur < u1);
   load_chunk(oc, 0);
+  {
+    constexpr int PER = K * N / 4 / kThreads;
+    float4 t[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) t[i] = reinterpret_cast<const float4*>(pw_w)[tid + i * kThreads];
+    // (no branches around these loads: a thread past the end reads element 0 and its value is dropped)
+    const float4 dwv = reinterpret_cast<const float4*>(dw_w)[tid < 9 * K / 4 ? tid : 0];
+    const float pwb = (pw_b ? pw_b : pw_w)[tid < N ? tid : 0];
+    const float dwb = (dw_b ? dw_b : pw_w)[tid < K ? tid : 0];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int e = tid + i * kThreads;  // float4 index: row e / (N/4), column quad e % (N/4)
+      *reinterpret_cast<float4*>(wl + (e / (N / 4)) * LD + 4 * (e % (N / 4))) = t[i];
+    }
+    if (tid < 9 * K / 4) reinterpret_cast<float4*>(dww_l)[tid] = dwv;
+    if (tid < N) pwb_l[tid] = pw_b ? pwb : 0.f;
+    if (tid < K) dwb_l[tid] = dw_b ? dwb : 0.f;
+  }
+  __syncthreads();
+
+  const ActClamp dw_clamp = make_act(dw_act), pw_clamp = make_act(pw_act);
+  const float dw_lo = dw_clamp.on ? 0.f : -INFINITY;
+  // where this lane's taps start in a window: pixel (li / 8, li % 8) * S, piece q
+  const float* const tap0 = win + ((li / 8) * S * RS + (li % 8) * S * PS + q) * 4;
+
+  // W blocks of 16 columns, starting at block jb, of one unit whose operand values are in a[]
+  auto columns = [&](auto wc_, const float4 (&a)[KG], float* ya, float* yb, bool oka, bool okb, int jb) {
+    constexpr int W = decltype(wc_)::value;
+    floatx4 acc[W];
+#pragma unroll
+    for (int j = 0; j < W; ++j) acc[j] = *reinterpret_cast<const floatx4*>(pwb_l + 16 * (jb + j) + 4 * q);
+#pragma unroll
+    for (int gg = 0; gg < KG; ++gg) {
+      const float av[4] = {a[gg].x, a[gg].y, a[gg].z, a[gg].w};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const float* wr = wl + (16 * gg + 4 * q + s) * LD + 16 * jb + li;
+#pragma unroll
+        for (int j = 0; j < W; ++j)
+          acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[16 * j], av[s], acc[j], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // keep later groups' LDS reads from being hoisted
+    }
+    store_rows_biased<W>(acc, ya + 16 * jb, yb + 16 * jb, oka, okb, li, q, pw_clamp);
+  };
+
+  // the first chunk of a unit's window is requested before the MFMAs of the unit before it
   while (cur < u1) {
     int ticket = 0;
     if (lane == 0) ticket = atomicAdd(&next_unit, 1);
@@ -281,7 +282,7 @@ bool separable_stream_supported(int batch, int h, int w, int c, int n, int strid
   bool aligned = true;
   for (const void* p : ptrs) aligned = aligned && reinterpret_cast<uintptr_t>(p) % 16 == 0;
   const long long m = (long long)batch * oh * ow, x_bytes = (long long)batch * h * w * c * 4;
-  return shape && aligned && m >= 32768 && m <= 0x3fffffffLL && x_bytes < (1ll << 31);
+  return shape && aligned && m >= 8192 && m <= 0x3fffffffLL && x_bytes < (1ll << 31);
 }
 
 int launch_separable_stream(const float* x, const float* dw_w, const float* dw_b, const float* pw_w, const float* pw_b,

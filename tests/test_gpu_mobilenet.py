@@ -141,11 +141,12 @@ def test_internal_activations_of_variants_and_batches(size, q, batch, blocks):
         assert_close(host(got), acts[2 * k], "features %d/%d block %d" % (q, size, k))
 
 
-@pytest.mark.parametrize("size,batch,blocks", [(224, 12, (2, 3)), (200, 16, (1, 2, 3)), (224, 44, (4, 5))])
+@pytest.mark.parametrize("size,batch,blocks", [(224, 5, (1, 2, 3, 4)), (224, 12, (2, 3)), (200, 16, (1, 2, 3)), (224, 44, (4, 5))])
 def test_internal_activations_at_large_batch(size, batch, blocks):
-    """Batches at which the early pointwise layers take the filter-stationary kernels (16384 rows and more) and the
-    depthwise layers their strip kernels; 200 x 200 images give 50 x 50 maps whose 16-row slabs straddle image rows
-    and images, and an odd padding under stride 2."""
+    """From 8192 output pixels on, blocks 1, 2 and 3 of the full-width network run as one filter-stationary launch
+    each (the depthwise result computed into the pointwise layer's MFMA operand from a window in LDS); the later
+    blocks take the single-op kernels.  200 x 200 images give 100 x 100 and 50 x 50 maps: ragged last patches and
+    an odd padding under stride 2."""
     import paper_1901_05350_amd as tfx
     data = inputs.mobilenet_v1(seed=47, batch=batch, image_size=size, width_quarters=4, classes=10)
     probs, logits, acts = oracle.mobilenet_v1_forward(data["image"], data["weights"], return_activations=True)
@@ -157,6 +158,27 @@ def test_internal_activations_at_large_batch(size, batch, blocks):
         assert_close(host(got), acts[2 * k], "features batch %d size %d block %d" % (batch, size, k))
     p, l = model.forward(img)
     assert_close(host(l), logits, "logits batch %d size %d" % (batch, size))
+
+
+def test_nan_and_inf_through_the_fused_blocks_at_large_batch():
+    """A NaN in one image reaches exactly the outputs whose windows hold it, block after block, and no other image;
+    +inf and -inf clamp as the oracle's relu6 does (the fused kernels clamp with a median of three and must notice
+    the NaN on the side)."""
+    import paper_1901_05350_amd as tfx
+    batch = 5
+    data = inputs.mobilenet_v1(seed=48, batch=batch, image_size=224, width_quarters=4, classes=10)
+    img = data["image"].copy()
+    img[3, 100, 37, 1] = np.nan
+    img[1, 5, 7, 0] = np.inf
+    img[4, 200, 220, 2] = -np.inf
+    probs, logits, acts = oracle.mobilenet_v1_forward(img, data["weights"], return_activations=True)
+    model = tfx.MobileNetV1(data["weights"], batch=batch, image_size=224, width_quarters=4)
+    for k in (1, 2, 3):
+        got, ref = host(model.features(dev(img), k)), acts[2 * k]
+        assert np.isnan(ref).any() and not np.isnan(ref[3]).all() and not np.isnan(ref[[0, 1, 2, 4]]).any()
+        assert np.array_equal(np.isnan(got), np.isnan(ref)), "NaN positions after block %d" % k
+        ok = ~np.isnan(ref)
+        assert_close(got[ok], ref[ok], "finite values after block %d" % k)
 
 
 def test_base_variant_is_the_plain_entry_point(net):
