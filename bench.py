@@ -30,20 +30,20 @@ PEAK_HBM = 8.0e12          # B/s
 # source it was measured on, with the digest of that file followed by the shared headers csrc/tfx_internal.h and
 # csrc/stream_f16.h; if any of them has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100848644, "gemm.hip", "807829e18f0a615cbaae58e222a694f145f61bd709bfed5dbad3c23697225692"),
-    "pointwise_64x56x56x128_to_128": (206181199, "pointwise.hip", "1a65e2ea8c015f4691dc3b47fce26ad6019993ad200b66ccb449f41a26498961"),
-    "conv3x3_64x56x56x64_to_64": (104548046, "gemm.hip", "807829e18f0a615cbaae58e222a694f145f61bd709bfed5dbad3c23697225692"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411139482, "depthwise.hip", "3f1e0516ea4cb7432e3f0727a320a5ccb677ff79f5fbd7356c662489ca238ec8"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (257166653, "depthwise.hip", "3f1e0516ea4cb7432e3f0727a320a5ccb677ff79f5fbd7356c662489ca238ec8"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235078221, "gemm_f16.hip", "42e3f84717e37f74c750776d086088786e57ca701f7c42ea30c5a9892c44162a"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50493620, "gemm_f16.hip", "42e3f84717e37f74c750776d086088786e57ca701f7c42ea30c5a9892c44162a"),
-    "pointwise_f16_64x56x56x128_to_128": (104218020, "pointwise_f16.hip", "591e574ad4dbd62c1254be5484a309e1dbf98ecaaed7d27b58a16a425e43cd39"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205681939, "conv_f16.hip", "360dedc63e17afbfc734302766ff4041c879c63ccc5a9d4651fb87307d37d195"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129520583, "conv_f16.hip", "360dedc63e17afbfc734302766ff4041c879c63ccc5a9d4651fb87307d37d195"),
-    "conv3x3_f16_64x56x56x64_to_64": (55040849, "conv_stream_f16.hip", "f986ada394c7a8da79fd5b8bec95da8389a9a099c5a5458645b7a5054c75028a"),
-    "add_f32_64M": (805263126, "elementwise.hip", "07593e1330886dce69a08bd1930f778db73e34c77eddc422b82967e5eeeadcb9"),
-    "add_f16_64M": (402651694, "elementwise.hip", "07593e1330886dce69a08bd1930f778db73e34c77eddc422b82967e5eeeadcb9"),
-    "mobilenet_chain_kernel": (121665685, "chain.hip", "e3af06d21fa8899d7b147f277b0ebf10835b76e8553259d83616c59f2d404ed1"),
+    "batch_matmul_8x1024x1024x1024_tB": (100848571, "gemm.hip", "3ab5c6a403c4e6aafee03c0313998835bde14a2a6c3ac550fe91e69181f5efd2"),
+    "pointwise_64x56x56x128_to_128": (206181208, "pointwise.hip", "70e26a5d662b22079fe3409ae52aa15025577fe33d5388021949cbaa213c2ef8"),
+    "conv3x3_64x56x56x64_to_64": (104544392, "gemm.hip", "3ab5c6a403c4e6aafee03c0313998835bde14a2a6c3ac550fe91e69181f5efd2"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411139388, "depthwise.hip", "5da620a6ccd4c30242611681bd2f7184658525366c61e78db0f3a5c2025cd97c"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (257110233, "depthwise.hip", "5da620a6ccd4c30242611681bd2f7184658525366c61e78db0f3a5c2025cd97c"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235078144, "gemm_f16.hip", "52b965dce64fddc7ff5c494d88e97f714faf64de32995732e75966efdd649057"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50493655, "gemm_f16.hip", "52b965dce64fddc7ff5c494d88e97f714faf64de32995732e75966efdd649057"),
+    "pointwise_f16_64x56x56x128_to_128": (104378788, "pointwise_f16.hip", "a8ecd84d7407b714cedfb1e4bd95cc44adba3f46f3299fe0d93b43e481c4739b"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205681787, "conv_f16.hip", "25dbb227fe16e327dd9e9148ff012044fcf936b7b19efc56b01d3fa93a5b7e69"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129445059, "conv_f16.hip", "25dbb227fe16e327dd9e9148ff012044fcf936b7b19efc56b01d3fa93a5b7e69"),
+    "conv3x3_f16_64x56x56x64_to_64": (55040849, "conv_stream_f16.hip", "585f19b79120be8c553d475c0b201104d2b9ecccdef37caaa43a99c86f56f338"),
+    "add_f32_64M": (805263146, "elementwise.hip", "5265e1e3f40c465d304eb54349f4a766f46e4d35a9fa395edbc5081acfe96ea1"),
+    "add_f16_64M": (402651912, "elementwise.hip", "5265e1e3f40c465d304eb54349f4a766f46e4d35a9fa395edbc5081acfe96ea1"),
+    "mobilenet_chain_kernel": (121663137, "chain.hip", "4e266b124962d34413a2136002f39377ba3af78dea1ca5aba7696550d0f26581"),
 }
 
 
