@@ -303,6 +303,14 @@ int tfx_mobilenet_v1_forward_f16(const tfx_mobilenet_v1_variant* variant, const 
                                  const tfx_mobilenet_v1_weights_f16* weights, void* workspace,
                                  size_t workspace_bytes, uint16_t* probs, uint16_t* logits, void* stream);
 
+/* tfx_mobilenet_v1_variant_features on 16-bit float storage: the output of block `end_block` (1 ... 13) as the
+ * layers of tfx_mobilenet_v1_forward_f16 compute it, binary16 [batch, h, w, c] with the shape
+ * tfx_mobilenet_v1_variant_features_shape gives; nothing after that block runs.  features: device, 16-byte
+ * aligned.  Errors as the fp32 call. */
+int tfx_mobilenet_v1_features_f16(const tfx_mobilenet_v1_variant* variant, const uint16_t* input, int64_t batch,
+                                  const tfx_mobilenet_v1_weights_f16* weights, void* workspace, size_t workspace_bytes,
+                                  int end_block, uint16_t* features, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

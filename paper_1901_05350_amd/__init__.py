@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     tfx_depthwise_conv2d_out_shape, tfx_matmul, tfx_matmul_out_shape, tfx_mobilenet_v1_forward,
     tfx_mobilenet_v1_variant_forward, tfx_mobilenet_v1_variant_workspace_bytes,
     tfx_mobilenet_v1_variant_forward_static, tfx_mobilenet_v1_static_scratch_bytes,
-    tfx_mobilenet_v1_variant_features, tfx_mobilenet_v1_variant_features_shape,
+    tfx_mobilenet_v1_variant_features, tfx_mobilenet_v1_variant_features_shape, tfx_mobilenet_v1_features_f16,
     tfx_mobilenet_v1_workspace_bytes, tfx_status_string,
 )

@@ -64,6 +64,9 @@ _SIGNATURES = {
     "tfx_mobilenet_v1_forward_f16": (ctypes.c_int, [ctypes.POINTER(TfxVariant), _VP, ctypes.c_int64,
                                                     ctypes.POINTER(TfxWeightsF16), _VP, ctypes.c_size_t, _VP, _VP,
                                                     _VP]),
+    "tfx_mobilenet_v1_features_f16": (ctypes.c_int, [ctypes.POINTER(TfxVariant), _VP, ctypes.c_int64,
+                                                     ctypes.POINTER(TfxWeightsF16), _VP, ctypes.c_size_t, ctypes.c_int,
+                                                     _VP, _VP]),
     "tfx_mobilenet_v1_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64]),
     "tfx_mobilenet_v1_forward": (ctypes.c_int, [_VP, ctypes.c_int64, ctypes.POINTER(TfxWeights), _VP,
                                                 ctypes.c_size_t, _VP, _VP, _VP]),
@@ -492,3 +495,28 @@ class MobileNetV1F16:
                                                   self.workspace.numel(), self.probs.data_ptr(), self.logits.data_ptr(),
                                                   _stream(image)), "tfx_mobilenet_v1_forward_f16")
         return self.probs, self.logits
+
+    def features(self, image, end_block, out=None):
+        """Enqueue the layers up to depthwise-separable block `end_block` (1 ... 13); returns its output [N,h,w,c]."""
+        import torch
+        if out is None:
+            out = torch.empty(tfx_mobilenet_v1_variant_features_shape(self.variant, self.batch, end_block),
+                              dtype=torch.float16, device=self.device)
+        return tfx_mobilenet_v1_features_f16(self.variant, image, self.struct, self.workspace, end_block, out)
+
+
+def tfx_mobilenet_v1_features_f16(variant, image, weights_struct, workspace, end_block, features):
+    """The float16 output of depthwise-separable block `end_block` (1 ... 13) into `features`; nothing after it runs."""
+    import torch
+    batch = _rank(image, "image", (4,))[0]
+    _expect_shape(image, "image", (batch, int(variant.image_size), int(variant.image_size), 3))
+    _expect_shape(features, "features", tfx_mobilenet_v1_variant_features_shape(variant, batch, end_block))
+    _dev(image, "image", torch.float16), _dev(features, "features", torch.float16)
+    if not isinstance(workspace, torch.Tensor) or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous tensor in GPU memory")
+    _check(lib().tfx_mobilenet_v1_features_f16(ctypes.byref(variant), image.data_ptr(), batch,
+                                               ctypes.byref(weights_struct), workspace.data_ptr(),
+                                               workspace.numel() * workspace.element_size(), int(end_block),
+                                               features.data_ptr(), _stream(image)),
+           "tfx_mobilenet_v1_features_f16")
+    return features

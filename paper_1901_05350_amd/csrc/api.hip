@@ -584,10 +584,15 @@ size_t tfx_mobilenet_v1_workspace_bytes_f16(const tfx_mobilenet_v1_variant* vari
   return plan_net(*variant, batch, sizeof(uint16_t)).bytes;
 }
 
-int tfx_mobilenet_v1_forward_f16(const tfx_mobilenet_v1_variant* variant, const uint16_t* input, int64_t batch,
-                                 const tfx_mobilenet_v1_weights_f16* weights, void* workspace,
-                                 size_t workspace_bytes, uint16_t* probs, uint16_t* logits, void* stream) {
-  if (!variant || !input || !weights || !workspace || !probs) return TFX_ERR_NULL;
+}  // extern "C"
+
+namespace {
+
+// end_block = 0: the whole network; else stop after that block and write its output to `features`
+int forward_f16_impl(const tfx_mobilenet_v1_variant* variant, const uint16_t* input, int64_t batch,
+                     const tfx_mobilenet_v1_weights_f16* weights, void* workspace, size_t workspace_bytes,
+                     uint16_t* probs, uint16_t* logits, int end_block, uint16_t* features, void* stream) {
+  if (!variant || !input || !weights || !workspace || !(end_block ? (void*)features : (void*)probs)) return TFX_ERR_NULL;
   if (!weights->conv0_w || !weights->conv0_b || !weights->fc_w || !weights->fc_b) return TFX_ERR_NULL;
   for (int i = 0; i < kBlocks; ++i)
     if (!weights->dw_w[i] || !weights->dw_b[i] || !weights->pw_w[i] || !weights->pw_b[i]) return TFX_ERR_NULL;
@@ -613,23 +618,59 @@ int tfx_mobilenet_v1_forward_f16(const tfx_mobilenet_v1_variant* variant, const 
   int cur = 0;
   for (int b = 0; b < kBlocks; ++b) {
     const int64_t fd[4] = {3, 3, shape[3], 1};
+    const int64_t cout = kChannels[b] * q / 4;
+    uint16_t* const block_out = end_block == b + 1 ? features : buf[cur ^ 1];
+    conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
+    // large batch, early block: depthwise and pointwise layer in one filter-stationary launch (block_stream_f16.hip)
+    if (separable_stream_f16_supported((int)batch, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout, kStrides[b],
+                                       (int)g.out[1], (int)g.out[2], buf[cur], weights->dw_w[b], weights->dw_b[b],
+                                       weights->pw_w[b], weights->pw_b[b], block_out)) {
+      rc = launch_separable_stream_f16(buf[cur], weights->dw_w[b], weights->dw_b[b], weights->pw_w[b], weights->pw_b[b],
+                                       block_out, (int)batch, (int)shape[1], (int)shape[2], (int)shape[3], (int)cout,
+                                       (int)g.out[1], (int)g.out[2], kStrides[b], (int)g.pad[0], (int)g.pad[2],
+                                       TFX_ACT_RELU6, TFX_ACT_RELU6, static_cast<hipStream_t>(stream));
+      if (rc) return rc;
+      if (end_block == b + 1) return TFX_OK;
+      for (int i = 0; i < 3; ++i) shape[i] = g.out[i];
+      shape[3] = cout;
+      cur ^= 1;
+      continue;
+    }
     rc = tfx_depthwise_conv2d_f16(buf[cur], shape, weights->dw_w[b], fd, weights->dw_b[b], kStrides[b], kStrides[b],
                                   TFX_PAD_SAME, TFX_ACT_RELU6, buf[cur ^ 1], stream);
     if (rc) return rc;
-    conv_geometry(shape, fd, kStrides[b], kStrides[b], TFX_PAD_SAME, true, &g);
     for (int i = 0; i < 4; ++i) shape[i] = g.out[i];
     cur ^= 1;
-    const int64_t cout = kChannels[b] * q / 4;
     const int64_t fp[4] = {1, 1, shape[3], cout};
     rc = tfx_conv2d_f16(buf[cur], shape, weights->pw_w[b], fp, weights->pw_b[b], 1, 1, TFX_PAD_SAME, TFX_ACT_RELU6,
-                        buf[cur ^ 1], stream);
+                        end_block == b + 1 ? features : buf[cur ^ 1], stream);
     if (rc) return rc;
+    if (end_block == b + 1) return TFX_OK;
     shape[3] = cout;
     cur ^= 1;
   }
   return launch_pool_fc_softmax_f16(buf[cur], weights->fc_w, weights->fc_b, partial, logits, probs, (int)batch,
                                     (int)(shape[1] * shape[2]), (int)shape[3], (int)variant->classes,
                                     static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+int tfx_mobilenet_v1_forward_f16(const tfx_mobilenet_v1_variant* variant, const uint16_t* input, int64_t batch,
+                                 const tfx_mobilenet_v1_weights_f16* weights, void* workspace,
+                                 size_t workspace_bytes, uint16_t* probs, uint16_t* logits, void* stream) {
+  return forward_f16_impl(variant, input, batch, weights, workspace, workspace_bytes, probs, logits, 0, nullptr, stream);
+}
+
+int tfx_mobilenet_v1_features_f16(const tfx_mobilenet_v1_variant* variant, const uint16_t* input, int64_t batch,
+                                  const tfx_mobilenet_v1_weights_f16* weights, void* workspace, size_t workspace_bytes,
+                                  int end_block, uint16_t* features, void* stream) {
+  if (end_block < 1 || end_block > kBlocks) return TFX_ERR_ARG;
+  if (features && reinterpret_cast<uintptr_t>(features) % 16 != 0) return TFX_ERR_ARG;
+  return forward_f16_impl(variant, input, batch, weights, workspace, workspace_bytes, nullptr, nullptr, end_block, features,
+                          stream);
 }
 
 }  // extern "C"

@@ -276,6 +276,14 @@ int launch_separable_stream(const float* x, const float* dw_w, const float* dw_b
                             float* y, int batch, int h, int w, int c, int n, int oh, int ow, int stride, int pt, int pl,
                             int dw_act, int pw_act, hipStream_t stream);
 
+// The same on binary16 storage (block_stream_f16.hip).
+bool separable_stream_f16_supported(int batch, int h, int w, int c, int n, int stride, int oh, int ow, const void* x,
+                                    const void* dw_w, const void* dw_b, const void* pw_w, const void* pw_b,
+                                    const void* y);
+int launch_separable_stream_f16(const uint16_t* x, const uint16_t* dw_w, const uint16_t* dw_b, const uint16_t* pw_w,
+                                const uint16_t* pw_b, uint16_t* y, int batch, int h, int w, int c, int n, int oh, int ow,
+                                int stride, int pt, int pl, int dw_act, int pw_act, hipStream_t stream);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? TFX_OK : TFX_ERR_LAUNCH; }
 
 // A kernel that uses more than 64 KB of dynamic LDS has to be allowed to, once per device (the attribute

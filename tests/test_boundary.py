@@ -219,6 +219,33 @@ def test_features_entry_point_validation():
     assert feat(ctypes.byref(V(224, 7, 1000)), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, FAKE, None) == -3
 
 
+@no_gpu_only
+def test_features_f16_entry_point_validation():
+    L = tfx.lib()
+    V = binding.TfxVariant
+    w = binding.TfxWeightsF16()
+    for name in ("conv0_w", "conv0_b", "fc_w", "fc_b"):
+        setattr(w, name, 0x1000)
+    for name in ("dw_w", "dw_b", "pw_w", "pw_b"):
+        arr = getattr(w, name)
+        for i in range(13):
+            arr[i] = 0x1000
+    ok = V(160, 2, 100)
+    nbytes = int(L.tfx_mobilenet_v1_workspace_bytes_f16(ctypes.byref(ok), 1))
+    assert nbytes > 0
+    feat = L.tfx_mobilenet_v1_features_f16
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 0, FAKE, None) == -3
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 14, FAKE, None) == -3
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, None, None) == -1
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, 0x1008, None) == -3   # misaligned
+    assert feat(None, FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, FAKE, None) == -1
+    assert feat(ctypes.byref(ok), FAKE, 0, ctypes.byref(w), FAKE, nbytes, 3, FAKE, None) == -2
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes - 1, 3, FAKE, None) == -5
+    assert feat(ctypes.byref(V(224, 7, 1000)), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, FAKE, None) == -3
+    w.pw_b[7] = 0
+    assert feat(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes, 3, FAKE, None) == -1
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError, match="GPU memory"):

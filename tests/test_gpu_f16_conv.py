@@ -292,7 +292,7 @@ def end_to_end_bar(got, ref, what, steps):
     layer (above).  Here: at most `steps` binary16 steps at the magnitude of the row's largest entry (a logit
     near zero is a sum of terms of that magnitude)."""
     g, r = got.astype(np.float64), ref.astype(np.float64)
-    bound = steps * np.spacing(np.abs(ref).max(axis=1, keepdims=True)).astype(np.float64)
+    bound = steps * np.spacing(np.abs(ref).max(axis=-1, keepdims=True)).astype(np.float64)
     assert np.isfinite(g).all() and (np.abs(g - r) <= bound).all(), (what, float(np.abs(g - r).max()), float(bound.min()))
 
 
@@ -312,6 +312,50 @@ def test_mobilenet_f16_end_to_end(size, q, classes, batch):
     assert np.abs(p.astype(np.float64).sum(axis=1) - 1).max() < 2e-3
     p2, l2 = model.forward(dev16(data["image"]))
     assert np.array_equal(host(p2), p) and np.array_equal(host(l2), l)
+
+
+@pytest.mark.parametrize("size,batch,blocks", [(224, 8, (1, 2, 3, 4)), (200, 12, (1, 2, 3)), (224, 3, (1, 2, 3, 5, 13))])
+def test_mobilenet_f16_internal_activations(size, batch, blocks):
+    """tfx_mobilenet_v1_features_f16 against the oracle's own feature maps.  From 16384 output pixels on, blocks 1, 2
+    and 3 of the full-width network run as one filter-stationary launch each (batch 8 and 12 here; 200 x 200 images
+    give 100 x 100 and 50 x 50 maps: ragged last patches, an odd padding under stride 2); batch 3 takes the single-op
+    kernels throughout.  The maps are the end of a chain of layers that each round once, so the end-to-end bar
+    applies (in steps at the pixel's largest channel), and in the first four blocks all but a small share of the
+    values -- growing with the depth -- must be the oracle's bit for bit."""
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1_f16(seed=52, batch=batch, image_size=size, width_quarters=4, classes=10)
+    probs, logits, acts = oracle.mobilenet_v1_forward_f16(data["image"], data["weights"], return_activations=True)
+    model = tfx.MobileNetV1F16(data["weights"], batch=batch, image_size=size, width_quarters=4)
+    img = dev16(data["image"])
+    for k in blocks:
+        got, ref = host(model.features(img, k)), acts[2 * k]
+        assert got.dtype == np.float16 and got.shape == ref.shape
+        end_to_end_bar(got, ref, "f16 features batch %d size %d block %d" % (batch, size, k), 4)
+        differ = float((got.view(np.uint16) != ref.view(np.uint16)).mean())
+        assert k > 4 or differ <= 0.005 * 4.0 ** (k - 1), (k, differ)
+    p, l = model.forward(img)
+    end_to_end_bar(host(l), logits, "f16 logits batch %d size %d" % (batch, size), 8)
+
+
+def test_mobilenet_f16_nan_and_inf_through_the_fused_blocks_at_large_batch():
+    """A NaN in one image reaches exactly the outputs whose windows hold it, block after block, and no other image;
+    +inf and -inf clamp as the oracle's relu6 does (the fused kernel clamps both layers with a median of three and
+    must notice the NaN on the side)."""
+    import paper_1901_05350_amd as tfx
+    batch = 8
+    data = inputs.mobilenet_v1_f16(seed=53, batch=batch, image_size=224, width_quarters=4, classes=10)
+    img = data["image"].copy()
+    img[3, 100, 37, 1] = np.nan
+    img[1, 5, 7, 0] = np.inf
+    img[6, 200, 220, 2] = -np.inf
+    probs, logits, acts = oracle.mobilenet_v1_forward_f16(img, data["weights"], return_activations=True)
+    model = tfx.MobileNetV1F16(data["weights"], batch=batch, image_size=224, width_quarters=4)
+    for k in (1, 2, 3):
+        got, ref = host(model.features(dev16(img), k)), acts[2 * k]
+        assert np.isnan(ref).any() and not np.isnan(ref[3]).all() and not np.isnan(np.delete(ref, 3, axis=0)).any()
+        assert np.array_equal(np.isnan(got), np.isnan(ref)), "NaN positions after block %d" % k
+        keep = ~np.isnan(ref).any(axis=-1)
+        end_to_end_bar(got[keep], ref[keep], "finite pixels after block %d" % k, 4)
 
 
 def test_mobilenet_f16_argument_checks():
