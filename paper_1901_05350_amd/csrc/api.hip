@@ -117,13 +117,13 @@ NetPlan plan_net(const tfx_mobilenet_v1_variant& v, int64_t batch, size_t elem_b
   off = align_up(off + fc_partial_floats((int)batch, (int)(kFeatures * v.width_quarters / 4), (int)v.classes) * sizeof(float));
   p.off_chain = off;
   p.chain = elem_bytes == sizeof(float) && chain_supported((int)v.image_size, (int)v.width_quarters, (int)v.classes, batch);
-  if (p.chain) off = align_up(off + chain_workspace_bytes((int)v.image_size, (int)v.classes));
+  if (p.chain) off = align_up(off + chain_workspace_bytes((int)v.image_size, (int)v.classes, (int)v.width_quarters));
   // blocks 2 - 4 in one launch: the outputs of blocks 2 and 3 share the second ping-pong buffer, the output of block 4
   // (1/8-size map, 256 channels) gets a region of its own, because block 2 is still reading the first buffer; the
   // output of block 5 (a launch of its own) goes behind it
   const size_t quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
   p.off_head = off;
-  p.head = p.chain && 2 * quarter * quarter * 128 <= p.act_floats;
+  p.head = p.chain && v.width_quarters == 4 && 2 * quarter * quarter * 128 <= p.act_floats;
   if (p.head) off = align_up(off + 2 * eighth * eighth * 256 * sizeof(float));  // outputs of blocks 4 and 5
   p.bytes = off;
   return p;
@@ -387,7 +387,7 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
   float* buf[2] = {reinterpret_cast<float*>(ws + plan.off_buf[0]), reinterpret_cast<float*>(ws + plan.off_buf[1])};
   float* partial = reinterpret_cast<float*>(ws + plan.off_partial);
 
-  // Batch 1 at full width: the blocks from the last 1/8-size map on, the pool, the fully connected layer and the
+  // Batch 1: the blocks from the last 1/8-size map on, the pool, the fully connected layer and the
   // softmax run as one persistent kernel (chain.hip) when every pointer allows its vector loads and 256 of its
   // workgroups are resident at once on this device; its task flags are cleared by the first kernel of the pass
   // (the stem, alone or fused with block 1).
@@ -397,7 +397,7 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
     flags_ok = al16(input) && al16(weights->conv0_b) && al16(weights->fc_w) && al16(weights->fc_b);
     for (int i = 0; i < kBlocks && flags_ok; ++i)
       flags_ok = al16(weights->dw_w[i]) && al16(weights->dw_b[i]) && al16(weights->pw_w[i]) && al16(weights->pw_b[i]);
-    flags_ok = flags_ok && chain_resident();
+    flags_ok = flags_ok && chain_resident(q);
   }
   const bool chain = flags_ok && end_block == 0;
   // blocks 2 - 4 as stages of one launch and block 5 as a launch (block.hip): in the whole pass and when block 4's
@@ -423,14 +423,14 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
                            (int)shape[2], (int)g.out[1],
                            (int)g.out[2], (int)g.pad[0], (int)g.pad[2], (int)c0, TFX_ACT_RELU6,
                            static_cast<hipStream_t>(stream), chain || head_chain ? static_cast<int*>(chain_ws) : nullptr,
-                           chain || head_chain ? chain_flag_words((int)variant->image_size, (int)variant->classes) : 0,
+                           chain || head_chain ? chain_flag_words((int)variant->image_size, (int)variant->classes, q) : 0,
                            chain_flag_stride());
     first_block = 1;
   } else if (chain)
     rc = launch_conv2d_stem(input, weights->conv0_w, weights->conv0_b, buf[0], 1, (int)shape[1], (int)shape[2],
-                            kStemChannels, (int)g.out[1], (int)g.out[2], 2, 2, (int)g.pad[0], (int)g.pad[2], TFX_ACT_RELU6,
+                            (int)f0[3], (int)g.out[1], (int)g.out[2], 2, 2, (int)g.pad[0], (int)g.pad[2], TFX_ACT_RELU6,
                             static_cast<hipStream_t>(stream), static_cast<int*>(chain_ws),
-                            chain_flag_words((int)variant->image_size, (int)variant->classes), chain_flag_stride());
+                            chain_flag_words((int)variant->image_size, (int)variant->classes, q), chain_flag_stride());
   else
     rc = tfx_conv2d(input, shape, weights->conv0_w, f0, weights->conv0_b, 2, 2, TFX_PAD_SAME, TFX_ACT_RELU6, buf[0],
                     stream);
@@ -474,14 +474,14 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
                                       256, 256, a.eighth, a.eighth, 1, 1, 1, TFX_ACT_RELU6, TFX_ACT_RELU6, a.stream);
       };
       if (end_block != 0) return launch_ordered(static_cast<hipStream_t>(stream), launch_head, &head);
-      return launch_chain(b5_out, (int)eighth, weights, chain_ws, head_flags, probs, logits, (int)variant->classes,
+      return launch_chain(b5_out, (int)eighth, weights, chain_ws, head_flags, probs, logits, (int)variant->classes, q,
                           static_cast<hipStream_t>(stream), launch_head, &head, 5);
     }
   }
   for (int b = first_block; b < kBlocks; ++b) {
     float* const block_out = end_block == b + 1 ? features : buf[cur ^ 1];
     if (chain && b == 4)
-      return launch_chain(buf[cur], (int)shape[1], weights, chain_ws, head_flags, probs, logits, (int)variant->classes,
+      return launch_chain(buf[cur], (int)shape[1], weights, chain_ws, head_flags, probs, logits, (int)variant->classes, q,
                           static_cast<hipStream_t>(stream));
     const int64_t fd[4] = {3, 3, shape[3], 1};
     const int64_t cout = kChannels[b] * q / 4;

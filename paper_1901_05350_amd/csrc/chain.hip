@@ -47,7 +47,7 @@ constexpr int kChainGrid = 256;
 constexpr int kChainBlocks = 9;       // at most blocks 5 .. 13 of the network (0-based 4 .. 12)
 constexpr int kFirstChainBlock = 4;   // a launch starts there or one block later (both read a 1/8-size map of 256 channels)
 constexpr int kSpinLimit = 1 << 22;  // polls before a wait gives up (each poll is a memory round trip: seconds)
-constexpr int kFcSlices = 8;          // slices of the fully connected layer's input channels, one per task
+constexpr int kFcSliceChannels = 128;  // input channels of the fully connected layer per task (2 to 8 slices)
 constexpr int kFcColBlock = 128;      // classes per fully connected task
 constexpr int kFlagStride = 32;       // words between flags: one flag per 128-byte line.  Flags of neighbouring tasks
                                       // are set by different CUs at almost the same time; packed into one line their
@@ -78,7 +78,7 @@ struct ChainParams {
   unsigned act_bytes;
   int* flags;           // word 0: failure; task t's flag is word kFlagStride * t (t >= 1)
   const float *fc_w, *fc_b;
-  unsigned partial_off; // float offset in act: [kFcSlices][classes] partial logits
+  unsigned partial_off; // float offset in act: [feat / 128][classes] partial logits
   float *probs, *logits;
   int classes, feat, last_hw;
   int flag_fc;          // first flag of the fully connected tasks
@@ -232,15 +232,16 @@ __device__ __forceinline__ void dw_task(const ChainParams& P, const ChainBlock& 
   publish(P.flags, B.flag_mid + r * tiles_c + c);
 }
 
-// ---- pointwise 1x1 + bias + ReLU6: 16 x (16 TN) tile, K = 8 x CHUNK split over the compute wavefronts ----
-template <int CHUNK, int TN>
+// ---- pointwise 1x1 + bias + ReLU6: 16 x (16 TN) tile, K = WAVES x CHUNK split over the first WAVES compute
+// wavefronts (all 8 where K is a multiple of 128; 4 for the K = 64 and K = 192 of the narrower networks) ----
+template <int CHUNK, int TN, int WAVES>
 __device__ __forceinline__ void pw_task(const ChainParams& P, const ChainBlock& B, int tile_m, int tile_n,
                                         __amdgpu_buffer_rsrc_t act, float* red) {
   constexpr int G = CHUNK / 16;
   const int K = B.cin, N = B.cout, M = B.out_hw * B.out_hw;
   const int tiles_n = N / (16 * TN);
   const int tid = threadIdx.x, wk = (tid / 64) % kComputeWaves, lane = tid % 64, li = lane % 16, q = lane / 16;
-  const bool compute = tid < kComputeThreads;
+  const bool compute = tid < 64 * WAVES;
   const int m0 = 16 * tile_m, n0 = 16 * TN * tile_n;
 
   // filter columns and bias before the wait (ordinary cached loads)
@@ -309,7 +310,7 @@ __device__ __forceinline__ void pw_task(const ChainParams& P, const ChainBlock& 
     for (int j = 0; j < TN; ++j) {
       float sum = ebias[j];
 #pragma unroll
-      for (int w = 0; w < kComputeWaves; ++w) sum += red[((w * TN + j) * 4 + ev) * 64 + el];
+      for (int w = 0; w < WAVES; ++w) sum += red[((w * TN + j) * 4 + ev) * 64 + el];
       o[j] = apply_act(sum, clamp);
     }
     const unsigned off = (B.out_off + (unsigned)(erow * N + ecol)) * 4u;
@@ -334,7 +335,23 @@ __device__ __forceinline__ float block_sum_or_max(float v, bool is_max, float* s
   return r;
 }
 
+// The pointwise task for a layer of K input channels: the K split, and 32-column tiles only below K = 1024.
+template <int K>
+__device__ __forceinline__ void pw_task_for(const ChainParams& P, const ChainBlock& B, int r, int c,
+                                            __amdgpu_buffer_rsrc_t act, float* red) {
+  constexpr int WAVES = K % 128 == 0 ? 8 : 4, CHUNK = K / WAVES;
+  static_assert(CHUNK % 16 == 0 && CHUNK <= 128, "a wavefront takes whole groups of 16 values of K");
+  if constexpr (K < 1024) {
+    if (B.tn == 2) return pw_task<CHUNK, 2, WAVES>(P, B, r, c, act, red);
+  }
+  pw_task<CHUNK, 1, WAVES>(P, B, r, c, act, red);
+}
+
+// Q = width multiplier in quarters: the chained blocks have 64 Q, 128 Q and 256 Q input channels, the fully
+// connected layer 256 Q = 2 Q slices of 128.
+template <int Q>
 __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const ChainParams P) {
+  constexpr int kSlices = 2 * Q;
   __shared__ float red[kComputeWaves * 2 * 4 * 64];  // 16 KB: split-K partial tiles; reused by the tail
   const int wg = blockIdx.x, tid = threadIdx.x;
   const bool compute = tid < kComputeThreads;
@@ -354,8 +371,8 @@ __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const Ch
   // this workgroup's slice of the fully connected weights (128 input channels x 128 classes, 32 values per
   // compute thread), fetched now: nothing in the kernel depends on it for the next 50 us
   const int fc_tasks_c = (P.classes + kFcColBlock - 1) / kFcColBlock;
-  const int fc_tasks = kFcSlices * fc_tasks_c;
-  const int kper = P.feat / kFcSlices;  // 128 input channels per task, 8 per thread
+  const int fc_tasks = kSlices * fc_tasks_c;
+  constexpr int kper = 128;  // input channels per task, 8 per thread
   float4 fw[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) fw[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -388,11 +405,9 @@ __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const Ch
     for (int vt = wg; vt < pw_map.count; vt += kChainGrid) {
       int r, c;
       if (!task_of(pw_map, vt, &r, &c)) continue;
-      if (B.cin == 256 && B.tn == 2) pw_task<32, 2>(P, B, r, c, act, red);
-      else if (B.cin == 256) pw_task<32, 1>(P, B, r, c, act, red);
-      else if (B.cin == 512 && B.tn == 2) pw_task<64, 2>(P, B, r, c, act, red);
-      else if (B.cin == 512) pw_task<64, 1>(P, B, r, c, act, red);
-      else pw_task<128, 1>(P, B, r, c, act, red);
+      if (B.cin == 64 * Q) pw_task_for<64 * Q>(P, B, r, c, act, red);
+      else if (B.cin == 128 * Q) pw_task_for<128 * Q>(P, B, r, c, act, red);
+      else pw_task_for<256 * Q>(P, B, r, c, act, red);
     }
   }
 
@@ -452,19 +467,19 @@ __global__ __launch_bounds__(kChainThreads) void mobilenet_chain_kernel(const Ch
 
   // ---- bias + softmax: one task, two classes per compute thread ----
   if (wg == 0) {
-    wait_tiles(P.flags, P.spin_limit, P.flag_fc, fc_tasks_c, 0, kFcSlices - 1, 0, fc_tasks_c - 1);
+    wait_tiles(P.flags, P.spin_limit, P.flag_fc, fc_tasks_c, 0, kSlices - 1, 0, fc_tasks_c - 1);
     float l[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int j = tid + kComputeThreads * h;
       const bool in = compute && j < P.classes;
-      float part[kFcSlices];
+      float part[kSlices];
 #pragma unroll
-      for (int s = 0; s < kFcSlices; ++s)
+      for (int s = 0; s < kSlices; ++s)
         part[s] = ld_f32(act, in ? (P.partial_off + (unsigned)(s * P.classes + j)) * 4u : 0x80000000u);
       float v = in ? P.fc_b[j] : 0.f;
 #pragma unroll
-      for (int s = 0; s < kFcSlices; ++s) v += part[s];
+      for (int s = 0; s < kSlices; ++s) v += part[s];
       l[h] = in ? v : -INFINITY;
     }
     const bool failed = flag_load(P.flags) != 0;
@@ -493,20 +508,34 @@ struct ChainPlanHost {
 }  // namespace
 
 bool chain_supported(int image_size, int width_quarters, int classes, long long batch) {
-  // full-width members whose 1/8-size map is what the first chained block reads; channel counts 256 / 512 / 1024
-  return batch == 1 && width_quarters == 4 && image_size >= 32 && image_size <= 256 && classes >= 1 && classes <= 1024;
+  // the 1/8-size map of 64 q channels is what the first chained block reads; channel counts 64 q / 128 q / 256 q
+  return batch == 1 && width_quarters >= 1 && width_quarters <= 4 && image_size >= 32 && image_size <= 256 &&
+         classes >= 1 && classes <= 1024;
 }
 
+namespace {
+typedef void (*ChainKernel)(const ChainParams);
+ChainKernel chain_kernel(int width_quarters) {
+  switch (width_quarters) {
+    case 1: return mobilenet_chain_kernel<1>;
+    case 2: return mobilenet_chain_kernel<2>;
+    case 3: return mobilenet_chain_kernel<3>;
+    default: return mobilenet_chain_kernel<4>;
+  }
+}
+}  // namespace
+
 // Whether 256 workgroups of the chain kernel are resident at once on the current device (looked up once per device).
-bool chain_resident() {
-  static std::atomic<int> state[64];  // 0 unknown, 1 yes, 2 no
+bool chain_resident(int width_quarters) {
+  static std::atomic<int> states[4][64];  // 0 unknown, 1 yes, 2 no
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+  if (width_quarters < 1 || width_quarters > 4 || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+  std::atomic<int>* const state = states[width_quarters - 1];
   const int s = state[dev].load(std::memory_order_acquire);
   if (s) return s == 1;
   int cus = 0, per_cu = 0;
   bool ok = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mobilenet_chain_kernel, kChainThreads, 0) == hipSuccess;
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel(width_quarters), kChainThreads, 0) == hipSuccess;
   ok = ok && (long long)cus * per_cu >= kChainGrid;
   state[dev].store(ok ? 1 : 2, std::memory_order_release);
   return ok;
@@ -516,16 +545,16 @@ namespace {
 constexpr int kNetChannels[13] = {64, 128, 128, 256, 256, 512, 512, 512, 512, 512, 512, 1024, 1024};
 constexpr int kNetStrides[13] = {1, 2, 1, 2, 1, 2, 1, 1, 1, 1, 1, 2, 1};
 
-// Sizes of the chained part for an input map of in_hw x in_hw x 256 (the output of block 4).
-ChainPlanHost chain_layout(int in_hw, int classes, ChainParams* P, int first = kFirstChainBlock) {
+// Sizes of the chained part for an input map of in_hw x in_hw x 64 q (the output of block 4) at width q / 4.
+ChainPlanHost chain_layout(int in_hw, int classes, int q, ChainParams* P, int first = kFirstChainBlock) {
   ChainPlanHost h{};
   int flags = 1;  // [0] = failure word
   size_t off = 0;
   const int nblocks = 13 - first;
-  int hw = in_hw, cin = kNetChannels[first - 1], prev_flags = -1, prev_tn = 2;
+  int hw = in_hw, cin = kNetChannels[first - 1] * q / 4, prev_flags = -1, prev_tn = 2;
   size_t prev_out = 0;
   for (int bi = 0; bi < nblocks; ++bi) {
-    const int net = first + bi, s = kNetStrides[net], cout = kNetChannels[net];
+    const int net = first + bi, s = kNetStrides[net], cout = kNetChannels[net] * q / 4;
     const int out_hw = (hw + s - 1) / s;
     const int need = (out_hw - 1) * s + 3 - hw;
     const int pad = need > 0 ? need / 2 : 0;
@@ -548,7 +577,8 @@ ChainPlanHost chain_layout(int in_hw, int classes, ChainParams* P, int first = k
     off += (size_t)m * cin + (size_t)m * cout;
     hw = out_hw, cin = cout, prev_tn = tn;
   }
-  const int fc_tasks = kFcSlices * ((classes + kFcColBlock - 1) / kFcColBlock);
+  const int slices = cin / kFcSliceChannels;
+  const int fc_tasks = slices * ((classes + kFcColBlock - 1) / kFcColBlock);
   if (P) {
     P->flag_fc = flags;
     P->partial_off = (unsigned)off;
@@ -558,16 +588,16 @@ ChainPlanHost chain_layout(int in_hw, int classes, ChainParams* P, int first = k
     P->nblocks = nblocks;
   }
   flags += fc_tasks;
-  off += (size_t)kFcSlices * classes;
+  off += (size_t)slices * classes;
   h.flags = flags;
   h.act_floats = off;
   return h;
 }
 }  // namespace
 
-size_t chain_workspace_bytes(int image_size, int classes) {
+size_t chain_workspace_bytes(int image_size, int classes, int width_quarters) {
   const int half = (image_size + 1) / 2, quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
-  const ChainPlanHost h = chain_layout(eighth, classes, nullptr);
+  const ChainPlanHost h = chain_layout(eighth, classes, width_quarters, nullptr);
   const size_t flag_bytes = (size_t)(h.flags + block_chain_flag_words(half, half)) * kFlagStride * sizeof(int);
   return flag_bytes + (h.act_floats * sizeof(float) + 255) / 256 * 256;
 }
@@ -575,13 +605,13 @@ size_t chain_workspace_bytes(int image_size, int classes) {
 // The flags at the start of the chain workspace: `count` words, chain_flag_stride() words apart, that must be zero
 // when the first kernel that uses them starts: the chain kernel's own (word 0 = failure word), then, from
 // chain_head_flag_base() on, those of the launch that runs blocks 2 - 4 as stages (block.hip).
-int chain_flag_words(int image_size, int classes) {
+int chain_flag_words(int image_size, int classes, int width_quarters) {
   const int half = (image_size + 1) / 2, quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
-  return chain_layout(eighth, classes, nullptr).flags + block_chain_flag_words(half, half);
+  return chain_layout(eighth, classes, width_quarters, nullptr).flags + block_chain_flag_words(half, half);
 }
 int chain_head_flag_base(int image_size, int classes) {
   const int half = (image_size + 1) / 2, quarter = (half + 1) / 2, eighth = (quarter + 1) / 2;
-  return chain_layout(eighth, classes, nullptr).flags;
+  return chain_layout(eighth, classes, 4, nullptr).flags;
 }
 int chain_spin_limit() {
   // Test hook: TFX_CHAIN_SPIN_LIMIT=<n> makes every wait give up after n polls, which exercises the failure
@@ -638,13 +668,14 @@ int launch_ordered(hipStream_t stream, int (*fn)(void*), void* arg) {
 }
 
 int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, int head_flags,
-                 float* probs, float* logits, int classes, hipStream_t stream, int (*before)(void*), void* before_arg,
-                 int first_block) {
+                 float* probs, float* logits, int classes, int width_quarters, hipStream_t stream, int (*before)(void*),
+                 void* before_arg, int first_block) {
   if (first_block != kFirstChainBlock && first_block != kFirstChainBlock + 1) return TFX_ERR_ARG;
+  if (width_quarters < 1 || width_quarters > 4) return TFX_ERR_ARG;
   ChainParams P{};
   // the workspace is laid out for the longer chain; a launch that starts one block later uses a part of it
-  const ChainPlanHost h = chain_layout(in_hw, classes, nullptr);
-  const ChainPlanHost used = chain_layout(in_hw, classes, &P, first_block);
+  const ChainPlanHost h = chain_layout(in_hw, classes, width_quarters, nullptr);
+  const ChainPlanHost used = chain_layout(in_hw, classes, width_quarters, &P, first_block);
   if (used.flags > h.flags || used.act_floats > h.act_floats) return TFX_ERR_LAUNCH;
   for (int bi = 0; bi < P.nblocks; ++bi) {
     const int net = first_block + bi;
@@ -655,7 +686,7 @@ int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w,
   }
   const size_t flag_bytes = (size_t)(h.flags + head_flags) * kFlagStride * sizeof(int);
   P.in0 = in0;
-  P.in0_bytes = (unsigned)((size_t)in_hw * in_hw * kNetChannels[first_block - 1] * sizeof(float));
+  P.in0_bytes = (unsigned)((size_t)in_hw * in_hw * (kNetChannels[first_block - 1] * width_quarters / 4) * sizeof(float));
   P.flags = static_cast<int*>(chain_ws);
   P.act = reinterpret_cast<float*>(static_cast<char*>(chain_ws) + flag_bytes);
   P.act_bytes = (unsigned)(h.act_floats * sizeof(float));
@@ -674,7 +705,7 @@ int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w,
     const int rc = before(before_arg);
     if (rc != TFX_OK) return rc;
   }
-  hipLaunchKernelGGL(mobilenet_chain_kernel, dim3(kChainGrid), dim3(kChainThreads), 0, stream, P);
+  hipLaunchKernelGGL(chain_kernel(width_quarters), dim3(kChainGrid), dim3(kChainThreads), 0, stream, P);
   return check_launch();
 }
 

@@ -49,7 +49,11 @@ template <int CO>
 __global__ __launch_bounds__(256) void conv2d_stem_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                           const float* __restrict__ bias, float* __restrict__ y, int N,
                                                           int H, int W, int OH, int OW, int sh, int sw, int pt, int pl,
-                                                          int act, int total) {
+                                                          int act, int total, int* __restrict__ zero_words,
+                                                          int zero_count, int zero_stride) {
+  // optional: clear a small array of words for a later kernel of the same forward pass (its task flags)
+  for (int i = (int)(blockIdx.x * 256 + threadIdx.x); i < zero_count; i += (int)gridDim.x * 256)
+    zero_words[(size_t)i * zero_stride] = 0;
   constexpr int G = CO / 8;
   constexpr int WPT = (27 * CO + 255) / 256;  // filter floats staged per thread
   __shared__ __align__(16) float wl[27 * CO];
@@ -258,13 +262,12 @@ int launch_conv2d_stem(const float* x, const float* w, const float* bias, float*
                        oh, ow, sh, sw, pt, pl, act, zero_words, zero_count, zero_stride);
     return check_launch();
   }
-  if (zero_count > 0) return TFX_ERR_UNSUPPORTED;  // only the matrix-core form clears words
   const long long total = (long long)n * oh * ow * (co / 8);
   if (total > 0x7fffffffLL) return TFX_ERR_UNSUPPORTED;
   const unsigned blocks = (unsigned)((total + 255) / 256);
 #define TFX_STEM(CO)                                                                                              \
   hipLaunchKernelGGL(conv2d_stem_kernel<CO>, dim3(blocks), dim3(256), 0, stream, x, w, bias, y, n, h, wd, oh, ow, \
-                     sh, sw, pt, pl, act, (int)total)
+                     sh, sw, pt, pl, act, (int)total, zero_words, zero_count, zero_stride)
   switch (co) {
     case 8: TFX_STEM(8); break;
     case 16: TFX_STEM(16); break;

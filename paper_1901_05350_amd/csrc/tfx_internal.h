@@ -168,14 +168,15 @@ int launch_conv2d_stem(const float* x, const float* w, const float* bias, float*
                        int oh, int ow, int sh, int sw, int pt, int pl, int act, hipStream_t stream,
                        int* zero_words = nullptr, int zero_count = 0, int zero_stride = 1);
 
-// The 28 x 28 ... 7 x 7 blocks, pool, fully connected layer and softmax of the batch-1, full-width network as one
-// persistent kernel (chain.hip).  chain_ws: chain_workspace_bytes() bytes, 256-byte aligned; its first
-// chain_flag_words() words at a spacing of chain_flag_stride() words are zero when the kernel starts.  in0: the output of block 4 (in_hw x in_hw x 256).
+// The 28 x 28 ... 7 x 7 blocks, pool, fully connected layer and softmax of the batch-1 network (any of the four
+// widths) as one persistent kernel (chain.hip).  chain_ws: chain_workspace_bytes() bytes, 256-byte aligned; its first
+// chain_flag_words() words at a spacing of chain_flag_stride() words are zero when the kernel starts.  in0: the
+// output of block 4 (in_hw x in_hw x 64 width_quarters).
 bool chain_supported(int image_size, int width_quarters, int classes, long long batch);
-bool chain_resident();
-size_t chain_workspace_bytes(int image_size, int classes);
-int chain_flag_words(int image_size, int classes);
-int chain_head_flag_base(int image_size, int classes);
+bool chain_resident(int width_quarters);
+size_t chain_workspace_bytes(int image_size, int classes, int width_quarters);
+int chain_flag_words(int image_size, int classes, int width_quarters);
+int chain_head_flag_base(int image_size, int classes);  // full width only: where the flags of blocks 2 - 4 as stages begin
 int chain_flag_stride();
 int chain_spin_limit();
 // head_flags: flag words behind the chain kernel's own at the start of chain_ws (block_chain_flag_words).
@@ -183,8 +184,8 @@ int chain_spin_limit();
 // (it is called once the stream has been ordered behind other streams' chain kernels) and returns a tfx_status.
 // first_block: 4 (the chain starts with block 5, in0 = the output of block 4) or 5 (block 6, in0 = output of block 5).
 int launch_chain(const float* in0, int in_hw, const tfx_mobilenet_v1_weights* w, void* chain_ws, int head_flags,
-                 float* probs, float* logits, int classes, hipStream_t stream, int (*before)(void*) = nullptr,
-                 void* before_arg = nullptr, int first_block = 4);
+                 float* probs, float* logits, int classes, int width_quarters, hipStream_t stream,
+                 int (*before)(void*) = nullptr, void* before_arg = nullptr, int first_block = 4);
 // fn(arg) enqueues a kernel of waiting workgroups on `stream`; the stream is first ordered behind the last such
 // kernel of any other stream (two of them side by side could each hold the CUs the other's producers need).
 int launch_ordered(hipStream_t stream, int (*fn)(void*), void* arg);
@@ -262,6 +263,11 @@ int launch_pool_fc_softmax_f16(const uint16_t* a, const uint16_t* w, const uint1
 bool pointwise_stream_f16_supported(int m, int k, int n, const void* x, const void* w, const void* y);
 int launch_pointwise_stream_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int m, int k,
                                 int n, int act, hipStream_t stream);
+// The same with a filter too large for LDS (K = 256 or 512; N = 2, 4, 8 or 16 slabs of 128 columns): a workgroup keeps
+// one column slab (pointwise_slab_f16.hip).
+bool pointwise_slab_f16_supported(int m, int k, int n, const void* x, const void* w, const void* y);
+int launch_pointwise_slab_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int m, int k,
+                              int n, int act, hipStream_t stream);
 
 // 3x3 stride-1 conv2d on binary16 storage with the whole filter resident in LDS (few channels, many output pixels).
 bool conv3x3_stream_f16_supported(long long m, long long x_elems, int ci, int fh, int fw, int co, int sh, int sw,

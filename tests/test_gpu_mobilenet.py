@@ -272,6 +272,44 @@ def test_chained_kernel_other_input_sizes_and_class_counts(size, classes):
         assert np.array_equal(host(p2), p) and np.array_equal(host(l2), l)
 
 
+@pytest.mark.parametrize("size,q,classes", [(128, 1, 1000), (32, 1, 3), (224, 1, 10), (160, 2, 37), (96, 2, 1024),
+                                            (192, 3, 1000), (224, 3, 130), (250, 3, 5)])
+def test_chained_kernel_other_widths(size, q, classes):
+    """The narrower members at batch 1 take the chained kernel from block 5 on: 64 q / 128 q / 256 q channels, i.e. a K
+    split over 4 wavefronts for K = 64 and 192, 2 q slices of the fully connected layer; the stem kernel for 8 q
+    filters clears the task flags."""
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1(seed=70 + size + q, batch=1, image_size=size, width_quarters=q, classes=classes)
+    probs, logits, acts = oracle.mobilenet_v1_forward(data["image"], data["weights"], return_activations=True)
+    model = tfx.MobileNetV1(data["weights"], batch=1, image_size=size, width_quarters=q)
+    image = dev(data["image"])
+    p, l = model.forward(image)
+    p, l = host(p).copy(), host(l).copy()
+    assert_close(l, logits, "logits %d/4 width, %d, %d classes" % (q, size, classes))
+    assert_close(p, probs, "probs %d/4 width, %d, %d classes" % (q, size, classes))
+    for _ in range(5):
+        p2, l2 = model.forward(image)
+        assert np.array_equal(host(p2), p) and np.array_equal(host(l2), l)
+    # the layers in front of the chain, and the same blocks as single kernels
+    for k in (4, 5, 13):
+        assert_close(host(model.features(image, k)), acts[2 * k], "features %d/4 width, %d, block %d" % (q, size, k))
+
+
+def test_chained_kernel_of_a_narrow_member_that_gives_up_writes_nan(monkeypatch):
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1(seed=77, batch=1, image_size=160, width_quarters=2, classes=100)
+    probs, logits = oracle.mobilenet_v1_forward(data["image"], data["weights"])
+    model = tfx.MobileNetV1(data["weights"], batch=1, image_size=160, width_quarters=2)
+    image = dev(data["image"])
+    monkeypatch.setenv("TFX_CHAIN_SPIN_LIMIT", "1")
+    p, l = model.forward(image)
+    assert np.isnan(host(p)).all() and np.isnan(host(l)).all()
+    monkeypatch.delenv("TFX_CHAIN_SPIN_LIMIT")
+    p, l = model.forward(image)
+    assert_close(host(l), logits, "logits after a failed call")
+    assert_close(host(p), probs, "probs after a failed call")
+
+
 def test_chained_kernel_many_calls_back_to_back_give_the_same_bits(net):
     import torch
     import paper_1901_05350_amd as tfx
