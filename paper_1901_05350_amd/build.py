@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtfx.so")
-SOURCES = ["api.hip", "gemm.hip", "pointwise.hip", "conv.hip", "depthwise.hip", "tail.hip", "elementwise.hip", "gemm_f16.hip", "conv_f16.hip", "pointwise_f16.hip", "conv_gemm_f16.hip", "conv_stream_f16.hip", "chain.hip", "block.hip", "block_stream.hip", "block_stream_f16.hip"]
+SOURCES = ["api.hip", "gemm.hip", "pointwise.hip", "conv.hip", "depthwise.hip", "tail.hip", "elementwise.hip", "gemm_f16.hip", "conv_f16.hip", "pointwise_f16.hip", "pointwise_slab_f16.hip", "conv_gemm_f16.hip", "conv_stream_f16.hip", "chain.hip", "block.hip", "block_stream.hip", "block_stream_f16.hip"]
 HEADERS = [os.path.join(CSRC, "tfx_internal.h"), os.path.join(CSRC, "stream_f16.h"), os.path.join(HERE, "..", "include", "tfx.h")]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU ops are kept off on this target

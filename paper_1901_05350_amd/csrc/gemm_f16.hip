@@ -638,6 +638,8 @@ int launch_gemm_f16(const uint16_t* a16, const uint16_t* b16, uint16_t* c16, con
   }
   if (batch == 1 && a_kc && !b_kc && pointwise_stream_f16_supported(m, k, n, a, b, c))
     return launch_pointwise_stream_f16(a16, b16, bias16, c16, m, k, n, act, stream);
+  if (batch == 1 && a_kc && !b_kc && pointwise_slab_f16_supported(m, k, n, a, b, c))
+    return launch_pointwise_slab_f16(a16, b16, bias16, c16, m, k, n, act, stream);
   if (vec_kn) {
     if (tiles(256, 256) >= 192 && fits(256, 256))
       return launch_pipe<2, 4, 4, 2, false>(a, b, c, bias, batch, m, n, k, true, false, act, stream);

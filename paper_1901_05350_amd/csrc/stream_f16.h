@@ -33,25 +33,46 @@ __device__ __forceinline__ constexpr int rho(int c) { return 32 * (c / 32) + 16 
 
 // The filter w[K][N] moves to LDS as [N rows in rho order][LD halfs] in two steps, so that the caller can put other
 // loads between them: `fetch` issues every 16-byte load of the thread (block u covers k-rows 4 kq ... + 3 of
-// columns 8 nb ... + 7, nb = u % (N/8), so the lanes of a wavefront read whole rows of w; no branch: a thread
+// columns 8 nb ... + 7; no branch: a thread
 // without a block in the last pass over the blocks reads block 0 again -- behind a guarded load the compiler waits
-// for every load still in flight), `store` transposes each 4 x 8 block in registers and writes eight 8-byte pieces.
+// for every load still in flight; `row_halfs` is the length of w's rows where the N columns are a slab of a wider
+// filter), `store` transposes each 4 x 8 block in registers and writes eight 8-byte pieces.
 template <int K, int N, int NT>
 struct FilterStage {
   static constexpr int BLOCKS = (K / 4) * (N / 8), PER = (BLOCKS + NT - 1) / NT, LD = filter_row_halfs(K);
+  // Block u -> (column block nb, k-group kq).  The 8-byte LDS writes of a wavefront go to row rho(8 nb + j) at
+  // half 4 kq.  A row is an odd multiple of 32 bytes long, so the rows of column blocks nb, nb + 1, nb + 2, nb + 3
+  // (4 rows apart) start at the four multiples of 128 bytes modulo 512.  Where K allows it (64 k = 16 k-groups per
+  // wavefront) the 64 blocks of a wavefront are therefore 4 neighbouring column blocks x 16 k-groups: 4 x 128
+  // consecutive bytes, every bank once, and the loads still read 64 consecutive bytes of each row of w.
+  // Otherwise: the column blocks of whole rows of w (several writes per bank; only small filters take this form).
+  static constexpr bool kByGroups = K % 64 == 0 && N % 32 == 0;
+  __device__ __forceinline__ static void place(int u, int* nb, int* kq) {
+    if constexpr (kByGroups) {
+      const int g = u / 64, l = u % 64;
+      *nb = 4 * (g % (N / 32)) + l % 4;
+      *kq = 16 * (g / (N / 32)) + l / 4;
+    } else {
+      *nb = u % (N / 8);
+      *kq = u / (N / 8);
+    }
+  }
   h8 r[PER][4];
-  __device__ __forceinline__ void fetch(const half_t* __restrict__ w, int tid) {
+  __device__ __forceinline__ void fetch(const half_t* __restrict__ w, int tid, int row_halfs = N) {
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      const int u = tid + i * NT < BLOCKS ? tid + i * NT : 0, nb = u % (N / 8), kq = u / (N / 8);
+      int nb, kq;
+      place(tid + i * NT < BLOCKS ? tid + i * NT : 0, &nb, &kq);
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) r[i][kk] = *reinterpret_cast<const h8*>(w + (size_t)(4 * kq + kk) * N + 8 * nb);
+      for (int kk = 0; kk < 4; ++kk) r[i][kk] = *reinterpret_cast<const h8*>(w + (size_t)(4 * kq + kk) * row_halfs + 8 * nb);
     }
   }
   __device__ __forceinline__ void store(half_t* wl, int tid) const {
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      const int u = tid + i * NT, nb = u % (N / 8), kq = u / (N / 8);
+      const int u = tid + i * NT;
+      int nb, kq;
+      place(u, &nb, &kq);
       if (BLOCKS % NT == 0 || i + 1 < PER || u < BLOCKS) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
