@@ -432,10 +432,52 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* scrat
   return r;
 }
 
+// Global average pool alone, for batches where the fully connected layer is worth a GEMM of its own: workgroup
+// (image, 256 channels), thread (pixel group p0 of 8, 8 channels): 16-byte loads, fp32 sums, one rounding.
+__global__ __launch_bounds__(256) void pool_f16_kernel(const half_t* __restrict__ a, half_t* __restrict__ pooled, int hw,
+                                                       int k) {
+  typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+  __shared__ float red[8][32][8];
+  const int img = blockIdx.y, c8 = threadIdx.x % 32, p0 = threadIdx.x / 32;
+  const int ch = 256 * blockIdx.x + 8 * c8;
+  const bool live = ch < k;  // k % 8 == 0
+  const half_t* const ap = a + (size_t)img * hw * k + (live ? ch : 0);
+  h8 v[8];  // hw <= 64
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int p = p0 + 8 * i;
+    v[i] = *reinterpret_cast<const h8*>(ap + (size_t)(p < hw ? p : hw - 1) * k);
+  }
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    if (p0 + 8 * i < hw) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s[e] += (float)v[i][e];
+    }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[p0][c8][e] = s[e];
+  __syncthreads();
+  if (p0 == 0 && live) {
+    h8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float t = 0.f;
+#pragma unroll
+      for (int g = 0; g < 8; ++g) t += red[g][c8][e];
+      o[e] = to_half(t / (float)hw);
+    }
+    *reinterpret_cast<h8*>(pooled + (size_t)img * k + ch) = o;
+  }
+}
+
 constexpr int kMaxPerThread = 4;  // classes <= 1024
+// logits_in == nullptr: the logits are the sum of the K-slice partial sums plus the bias, rounded to binary16 (and
+// written to `logits` if asked for); otherwise they are read from logits_in.
 __global__ __launch_bounds__(256) void softmax_f16_kernel(const float* __restrict__ partial,
                                                           const half_t* __restrict__ bias, half_t* __restrict__ logits,
-                                                          half_t* __restrict__ probs, int n, int classes) {
+                                                          half_t* __restrict__ probs, int n, int classes,
+                                                          const half_t* __restrict__ logits_in) {
   __shared__ float scratch[4];
   const int img = blockIdx.x;
   float l[kMaxPerThread];
@@ -444,7 +486,10 @@ __global__ __launch_bounds__(256) void softmax_f16_kernel(const float* __restric
   for (int i = 0; i < kMaxPerThread; ++i) {
     const int j = threadIdx.x + 256 * i;
     l[i] = -INFINITY;
-    if (j < classes) {
+    if (j < classes && logits_in != nullptr) {
+      l[i] = (float)logits_in[(size_t)img * classes + j];
+      mx = fmaxf(mx, l[i]);
+    } else if (j < classes) {
       float part[kFcSlices];
 #pragma unroll
       for (int s = 0; s < kFcSlices; ++s) part[s] = partial[((size_t)s * n + img) * classes + j];
@@ -559,6 +604,23 @@ int launch_pool_fc_softmax_f16(const uint16_t* a, const uint16_t* w, const uint1
                                uint16_t* logits, uint16_t* probs, int n, int hw, int k, int classes,
                                hipStream_t stream) {
   if (classes > 256 * kMaxPerThread) return TFX_ERR_UNSUPPORTED;
+  // From 16 images on the fully connected layer is a matrix product worth its own launch: pool, then the GEMM (bias
+  // and the rounding of the logits in its epilogue), then the softmax of the stored logits.  The pooled vectors,
+  // and the logits if the caller does not ask for them, live where the partial sums would (32 n classes floats).
+  const size_t partial_bytes = (size_t)kFcSlices * n * classes * sizeof(float);
+  if (n >= 16 && hw <= 64 && k % 8 == 0 && classes % 8 == 0 && reinterpret_cast<uintptr_t>(a) % 16 == 0 &&
+      ((size_t)n * k + 127) / 128 * 256 + (size_t)n * classes * 2 <= partial_bytes) {
+    uint16_t* const pooled = reinterpret_cast<uint16_t*>(partial);
+    uint16_t* const lg = logits ? logits : pooled + (((size_t)n * k + 127) / 128) * 128;
+    hipLaunchKernelGGL(pool_f16_kernel, dim3((k + 255) / 256, n), dim3(256), 0, stream, H(a), H(pooled), hw, k);
+    int rc = check_launch();
+    if (rc) return rc;
+    rc = launch_gemm_f16(pooled, w, lg, bias, 1, n, classes, k, true, false, TFX_ACT_NONE, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(softmax_f16_kernel, dim3(n), dim3(256), 0, stream, (const float*)nullptr, (const half_t*)nullptr,
+                       (half_t*)nullptr, H(probs), n, classes, H(lg));
+    return check_launch();
+  }
   const int kslice = (k + kFcSlices - 1) / kFcSlices;
   if (kslice > kFcKMax || hw > 64) return TFX_ERR_UNSUPPORTED;
   dim3 grid((classes + 255) / 256, kFcSlices, (n + kFcBatchMax - 1) / kFcBatchMax);
@@ -567,7 +629,7 @@ int launch_pool_fc_softmax_f16(const uint16_t* a, const uint16_t* w, const uint1
   int rc = check_launch();
   if (rc) return rc;
   hipLaunchKernelGGL(softmax_f16_kernel, dim3(n), dim3(256), 0, stream, (const float*)partial, H(bias), H(logits),
-                     H(probs), n, classes);
+                     H(probs), n, classes, (const half_t*)nullptr);
   return check_launch();
 }
 
