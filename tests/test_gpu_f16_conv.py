@@ -394,6 +394,30 @@ def test_mobilenet_f16_nan_and_inf_through_the_fused_blocks_at_large_batch():
         end_to_end_bar(got[keep], ref[keep], "finite pixels after block %d" % k, 4)
 
 
+@pytest.mark.parametrize("size,q,classes,batch", [(64, 1, 40, 16), (96, 2, 1000, 17), (64, 4, 8, 40), (64, 1, 37, 16)])
+def test_mobilenet_f16_tail_at_large_batch(size, q, classes, batch):
+    """From 16 images on (class count a multiple of 8) the tail is pool, GEMM, softmax as three launches, with the
+    pooled vectors -- and the logits, if the caller passes no buffer for them -- in the workspace; 37 classes take the
+    fused tail.  With and without a logits buffer the probabilities have the same bits."""
+    import ctypes
+    import torch
+    import paper_1901_05350_amd as tfx
+    data = inputs.mobilenet_v1_f16(seed=60 + classes, batch=batch, image_size=size, width_quarters=q, classes=classes)
+    probs, logits = oracle.mobilenet_v1_forward_f16(data["image"], data["weights"])
+    model = tfx.MobileNetV1F16(data["weights"], batch=batch, image_size=size, width_quarters=q)
+    img = dev16(data["image"])
+    p, l = model.forward(img)
+    p, l = host(p).copy(), host(l).copy()
+    end_to_end_bar(l, logits, "f16 logits", 8)
+    end_to_end_bar(p, probs, "f16 probs", 16)
+    assert np.array_equal(p.argmax(axis=1), probs.argmax(axis=1))
+    p2 = torch.zeros_like(model.probs)
+    rc = tfx.lib().tfx_mobilenet_v1_forward_f16(ctypes.byref(model.variant), img.data_ptr(), batch, ctypes.byref(model.struct),
+                                                model.workspace.data_ptr(), model.workspace.numel(), p2.data_ptr(), None, None)
+    assert rc == 0
+    assert np.array_equal(host(p2), p)
+
+
 def test_mobilenet_f16_argument_checks():
     import ctypes
     import paper_1901_05350_amd as tfx
