@@ -30,20 +30,21 @@ PEAK_HBM = 8.0e12          # B/s
 # source it was measured on, with the digest of that file followed by the shared headers csrc/tfx_internal.h and
 # csrc/stream_f16.h; if any of them has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100848571, "gemm.hip", "3ab5c6a403c4e6aafee03c0313998835bde14a2a6c3ac550fe91e69181f5efd2"),
-    "pointwise_64x56x56x128_to_128": (206181208, "pointwise.hip", "70e26a5d662b22079fe3409ae52aa15025577fe33d5388021949cbaa213c2ef8"),
-    "conv3x3_64x56x56x64_to_64": (104544392, "gemm.hip", "3ab5c6a403c4e6aafee03c0313998835bde14a2a6c3ac550fe91e69181f5efd2"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411139388, "depthwise.hip", "5da620a6ccd4c30242611681bd2f7184658525366c61e78db0f3a5c2025cd97c"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (257110233, "depthwise.hip", "5da620a6ccd4c30242611681bd2f7184658525366c61e78db0f3a5c2025cd97c"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235078144, "gemm_f16.hip", "52b965dce64fddc7ff5c494d88e97f714faf64de32995732e75966efdd649057"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50493655, "gemm_f16.hip", "52b965dce64fddc7ff5c494d88e97f714faf64de32995732e75966efdd649057"),
-    "pointwise_f16_64x56x56x128_to_128": (104378788, "pointwise_f16.hip", "a8ecd84d7407b714cedfb1e4bd95cc44adba3f46f3299fe0d93b43e481c4739b"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205681787, "conv_f16.hip", "25dbb227fe16e327dd9e9148ff012044fcf936b7b19efc56b01d3fa93a5b7e69"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (129445059, "conv_f16.hip", "25dbb227fe16e327dd9e9148ff012044fcf936b7b19efc56b01d3fa93a5b7e69"),
-    "conv3x3_f16_64x56x56x64_to_64": (55040849, "conv_stream_f16.hip", "585f19b79120be8c553d475c0b201104d2b9ecccdef37caaa43a99c86f56f338"),
-    "add_f32_64M": (805263146, "elementwise.hip", "5265e1e3f40c465d304eb54349f4a766f46e4d35a9fa395edbc5081acfe96ea1"),
-    "add_f16_64M": (402651912, "elementwise.hip", "5265e1e3f40c465d304eb54349f4a766f46e4d35a9fa395edbc5081acfe96ea1"),
-    "mobilenet_chain_kernel": (121663137, "chain.hip", "4e266b124962d34413a2136002f39377ba3af78dea1ca5aba7696550d0f26581"),
+    "batch_matmul_8x1024x1024x1024_tB": (100848582, "gemm.hip", "24059a96a79970d4752d83254a15fd3476a327be5e60be76f13425610c45c2b1"),
+    "pointwise_64x56x56x128_to_128": (206181192, "pointwise.hip", "283a3b4c53b264dcd0cf1fec36ea618620277b877cc4888541b0877a7b9b7af5"),
+    "conv3x3_64x56x56x64_to_64": (104550019, "gemm.hip", "24059a96a79970d4752d83254a15fd3476a327be5e60be76f13425610c45c2b1"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411140035, "depthwise.hip", "439fb12e0d03a35f81ce4faf03d7389951693b8e2c0265850998cc85fe88c49b"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (257091597, "depthwise.hip", "439fb12e0d03a35f81ce4faf03d7389951693b8e2c0265850998cc85fe88c49b"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235078068, "gemm_f16.hip", "edd4b947bb3fd0914372bef292338980e17bfc02c2e59d5dee6cb664ed22fcb8"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50493625, "gemm_f16.hip", "edd4b947bb3fd0914372bef292338980e17bfc02c2e59d5dee6cb664ed22fcb8"),
+    "pointwise_f16_64x56x56x128_to_128": (104406861, "pointwise_f16.hip", "20ec0ee6f5f1a008b3519a0bf4c99ba5c193e50cde7c632a6916cdf20aada08c"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205681926, "conv_f16.hip", "2470ce6f05843cca0d96735ea95472f2224cda0398feea675b06aad9e8136030"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (128551961, "conv_f16.hip", "2470ce6f05843cca0d96735ea95472f2224cda0398feea675b06aad9e8136030"),
+    "pointwise_f16_64x14x14x512_to_512": (30220399, "pointwise_slab_f16.hip", "cc17782f570159b83f2aba58422fffabc3bf75e81a5c34eb98d5648d480b6abd"),
+    "conv3x3_f16_64x56x56x64_to_64": (55026497, "conv_stream_f16.hip", "71cec29631279f2156c9e5148d545d594cb163208b4cad9fd934064ebac98613"),
+    "add_f32_64M": (805262999, "elementwise.hip", "dfb0348f8009736271297f64c6dc51b922843799aa9dd6c3d0f0c6d6e2f1f7d9"),
+    "add_f16_64M": (402651870, "elementwise.hip", "dfb0348f8009736271297f64c6dc51b922843799aa9dd6c3d0f0c6d6e2f1f7d9"),
+    "mobilenet_chain_kernel": (121631083, "chain.hip", "488bc3d7ed32d98347782099e64845046d93bd2e6ff3309aeea259ef98ac9c58"),
 }
 
 
@@ -274,15 +275,16 @@ def main():
                                  "traffic": measured_traffic("batch_matmul_f16_%dx%dx%dx%d%s" % (batch, m, n, k, "_tB" if tb else ""))}}
         return build
 
-    def op_pointwise_f16(n):
-        """1x1 conv 56x56x128 -> 128 + bias + ReLU6 on 16-bit storage, as a matMul of x [N*56*56,128] with the
-        filter stored [128,128] (inC, outC).  3.3 flop per byte moved: bound by HBM, not by the matrix cores."""
+    def op_pointwise_f16(n, hw=56, k=128, co=128):
+        """1x1 conv hw x hw x k -> co + bias + ReLU6 on 16-bit storage, as a matMul of x [N*hw*hw,k] with the
+        filter stored [k,co] (inC, outC).  56x56x128 -> 128 has 3.3 flop per byte moved, 14x14x512 -> 512 has 250
+        (the balance of the chip is 312): bound by HBM, not by the matrix cores."""
         def build():
-            m = n * 56 * 56
-            copies = 1 if n < 64 else 8          # rotate over > 256 MB of activations at batch 64
-            xs = [torch.empty((1, m, 128), device="cuda:0").uniform_(-1, 1).to(torch.float16) for _ in range(copies)]
-            f = (torch.empty((1, 128, 128), device="cuda:0").normal_() * (2.0 / 128) ** 0.5).to(torch.float16)
-            bias = (torch.empty(128, device="cuda:0").normal_() * 0.01).to(torch.float16)
+            m = n * hw * hw
+            copies = 1 if n < 64 else -(-(3 << 28) // (2 * m * (k + co)))   # rotate over 3 x 256 MB of activations at batch 64
+            xs = [torch.empty((1, m, k), device="cuda:0").uniform_(-1, 1).to(torch.float16) for _ in range(copies)]
+            f = (torch.empty((1, k, co), device="cuda:0").normal_() * (2.0 / k) ** 0.5).to(torch.float16)
+            bias = (torch.empty(co, device="cuda:0").normal_() * 0.01).to(torch.float16)
             ys = [tfx.tfx_batch_matmul_f16(x, f, False, False, bias, tfx.ACT_RELU6) for x in xs]
             state = {"i": 0}
 
@@ -290,12 +292,12 @@ def main():
                 i = state["i"] = (state["i"] + 1) % copies
                 tfx.tfx_batch_matmul_f16(xs[i], f, False, False, bias, tfx.ACT_RELU6, out=ys[i])
             t = time_loop(fn, max(reps, copies * 2), warmup=copies, inner=copies if copies > 1 else None)
-            flop, nbytes = 2 * m * 128 * 128, 2 * (2 * m * 128 + 128 * 128 + 128)
+            flop, nbytes = 2 * m * k * co, 2 * (m * k + m * co + k * co + co)
             return {"us": round(t * 1e6, 3), "TFLOPs": round(flop / t / 1e12, 3), "GBps": round(nbytes / t / 1e9, 1),
                     "algorithmic_bytes": nbytes,
                     "roofline": {"bound": "hbm", "achieved": round(nbytes / t / 1e9, 1), "peak": PEAK_HBM / 1e9,
                                  "unit": "GB/s", "frac": round(nbytes / t / PEAK_HBM, 5),
-                                 "traffic": measured_traffic("pointwise_f16_%dx56x56x128_to_128" % n)}}
+                                 "traffic": measured_traffic("pointwise_f16_%dx%dx%dx%d_to_%d" % (n, hw, hw, k, co))}}
         return build
 
     def op_conv3x3_f16(n):
@@ -320,6 +322,7 @@ def main():
     single_ops["batch_matmul_f16_1x4096x4096x4096"] = op_matmul_f16(1, 4096, 4096, 4096, tb=False)
     single_ops["pointwise_f16_64x56x56x128_to_128"] = op_pointwise_f16(64)
     single_ops["pointwise_f16_8x56x56x128_to_128"] = op_pointwise_f16(8)
+    single_ops["pointwise_f16_64x14x14x512_to_512"] = op_pointwise_f16(64, 14, 512, 512)
     single_ops["conv3x3_f16_64x56x56x64_to_64"] = op_conv3x3_f16(64)
     single_ops["conv3x3_f16_8x56x56x64_to_64"] = op_conv3x3_f16(8)
     single_ops["depthwise_f16_64x112x112x64_s1_cold_rotation"] = op_depthwise_f16(64, 1, 6)
