@@ -330,6 +330,20 @@ def main():
     single_ops["add_f32_64M"] = op_add(1 << 26, False)
     single_ops["add_f16_64M"] = op_add(1 << 26, True)
     calibration_ops = {"copy_calibration_205MB": op_copy}
+
+    def op_network(nb, f16):
+        """The whole network at batch nb alone (for a per-kernel profile of the batched forward pass)."""
+        def build():
+            dd = (inputs.mobilenet_v1_f16 if f16 else inputs.mobilenet_v1)(seed=4, batch=1)
+            model = (tfx.MobileNetV1F16 if f16 else tfx.MobileNetV1)(dd["weights"], batch=nb)
+            imgs = torch.empty((nb, 224, 224, 3), device="cuda:0").uniform_(-1, 1)
+            imgs = imgs.to(torch.float16) if f16 else imgs
+            t = time_loop(lambda: model.forward(imgs), max(20, reps // 4), warmup=3, inner=5)
+            return {"ms_per_batch": round(t * 1e3, 4), "images_per_s": round(nb / t, 1),
+                    "TFLOPs": round(nb * 1.137480704e9 / t / 1e12, 3)}
+        return build
+    network_ops = {"mobilenet_v1_batch64": op_network(64, False), "mobilenet_v1_f16_batch64": op_network(64, True),
+                   "mobilenet_v1_batch8": op_network(8, False), "mobilenet_v1_f16_batch8": op_network(8, True)}
     for n in (1, 8, 64):
         single_ops["pointwise_%dx56x56x128_to_128" % n] = op_pointwise(n)
         single_ops["conv3x3_%dx56x56x64_to_64" % n] = op_conv3x3(n)
@@ -339,7 +353,7 @@ def main():
         single_ops["depthwise_8x112x112x64_s%d_warm" % s] = op_depthwise(8, s, 1)
         single_ops["depthwise_64x112x112x64_s%d_cold_rotation" % s] = op_depthwise(64, s, 3)
     if args.op is not None:
-        every = {**single_ops, **calibration_ops}
+        every = {**single_ops, **calibration_ops, **network_ops}
         if args.op not in every:
             print("\n".join(every))
             sys.exit(0 if args.op == "list" else 2)
