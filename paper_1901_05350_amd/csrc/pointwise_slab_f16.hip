@@ -1,7 +1,8 @@
-// Pointwise (1x1) conv2d on 16-bit float storage with a filter too large for one workgroup's LDS:
-//   y[M,N] = half(act(x[M,K] * w[K,N] + bias)),  K = 256 or 512, N = 256 ... 2048, M in the thousands
+// Pointwise (1x1) conv2d on 16-bit float storage with a filter too large for one workgroup's LDS, or too few rows
+// for the kernel that keeps the whole filter there:
+//   y[M,N] = half(act(x[M,K] * w[K,N] + bias)),  K = 64, 128, 256 or 512, N = 128 ... 2048, M in the thousands
 // (Section 4.1 storage format; the pointwise layers of the 28 x 28 ... 7 x 7 maps of the Section 3.9 network at
-// large batch).  At fp16 rate the matrix cores need 3 us for such a layer and a tiled GEMM spends its time around
+// large batch, and of its larger maps at batch 1 to 5).  At fp16 rate the matrix cores need 3 us for such a layer and a tiled GEMM spends its time around
 // them: slices of both operands through LDS, two barriers per slice, 16 slices per tile.  Here a workgroup keeps a
 // column slab of the filter -- all K rows of NS = 128 columns, up to 133 KB -- in LDS (stream_f16.h: transposed once, rows in
 // the order that leaves a lane with 8 consecutive output channels), and each of its 8 wavefronts takes units of
@@ -141,9 +142,9 @@ constexpr int kSlabColumns = 128;
 }  // namespace
 
 bool pointwise_slab_f16_supported(int m, int k, int n, const void* x, const void* w, const void* y) {
-  if (k != 256 && k != 512) return false;
+  if (k != 64 && k != 128 && k != 256 && k != 512) return false;
   const int slabs = n % kSlabColumns == 0 ? n / kSlabColumns : 0;
-  const bool shape = slabs == 2 || slabs == 4 || slabs == 8 || slabs == 16;
+  const bool shape = slabs == 1 || slabs == 2 || slabs == 4 || slabs == 8 || slabs == 16;
   const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 &&
                        reinterpret_cast<uintptr_t>(y) % 16 == 0;
   return shape && aligned && m >= 1536 && (long long)m * (k > n ? k : n) < (1ll << 31);
@@ -155,6 +156,8 @@ int launch_pointwise_slab_f16(const uint16_t* x16, const uint16_t* w16, const ui
   const half_t* w = reinterpret_cast<const half_t*>(w16);
   const half_t* bias = reinterpret_cast<const half_t*>(bias16);
   half_t* y = reinterpret_cast<half_t*>(y16);
+  if (k == 64) return launch_slab<64, kSlabColumns, 2, 2>(x, w, bias, y, m, n, act, stream);
+  if (k == 128) return launch_slab<128, kSlabColumns, 2, 4>(x, w, bias, y, m, n, act, stream);
   if (k == 256) return launch_slab<256, kSlabColumns, 2, 8>(x, w, bias, y, m, n, act, stream);
   if (k == 512) return launch_slab<512, kSlabColumns, 2, 8>(x, w, bias, y, m, n, act, stream);
   return TFX_ERR_UNSUPPORTED;

@@ -263,8 +263,8 @@ int launch_pool_fc_softmax_f16(const uint16_t* a, const uint16_t* w, const uint1
 bool pointwise_stream_f16_supported(int m, int k, int n, const void* x, const void* w, const void* y);
 int launch_pointwise_stream_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int m, int k,
                                 int n, int act, hipStream_t stream);
-// The same with a filter too large for LDS (K = 256 or 512; N = 2, 4, 8 or 16 slabs of 128 columns): a workgroup keeps
-// one column slab (pointwise_slab_f16.hip).
+// The same with a filter too large for LDS or fewer rows (K = 64, 128, 256 or 512; N = 1, 2, 4, 8 or 16 slabs of 128
+// columns; from 1536 rows on): a workgroup keeps one column slab (pointwise_slab_f16.hip).
 bool pointwise_slab_f16_supported(int m, int k, int n, const void* x, const void* w, const void* y);
 int launch_pointwise_slab_f16(const uint16_t* x, const uint16_t* w, const uint16_t* bias, uint16_t* y, int m, int k,
                               int n, int act, hipStream_t stream);

@@ -144,10 +144,14 @@ def test_conv2d_f16_filter_stationary_one_hot():
     ((33, 7, 7, 512, 1024), ACT_RELU6),      # M = 1617, 8 slabs
     ((2, 28, 28, 256, 2048), ACT_RELU6),     # 16 slabs: one part of the rows per XCD pair
     ((40, 14, 14, 512, 512), ACT_RELU6),     # M = 7840: several units per wavefront
+    ((1, 56, 56, 64, 128), ACT_RELU6),       # K = 64 (two k-steps), one slab
+    ((2, 28, 29, 128, 256), ACT_RELU),       # K = 128, M = 1624
+    ((1, 56, 56, 128, 128), ACT_NONE),
 ])
 def test_conv2d_f16_pointwise_column_slabs(shape, act):
-    """Pointwise layers with K = 256 or 512 and N a multiple of 128, from 1536 output pixels on: a workgroup keeps a
-    128-column slab of the filter in LDS and streams rows against it."""
+    """Pointwise layers with K = 64 ... 512 and N a multiple of 128, from 1536 output pixels on (below 16384 for the
+    filters that fit in LDS whole): a workgroup keeps a 128-column slab of the filter in LDS and streams rows against
+    it."""
     import paper_1901_05350_amd as tfx
     n, hh, ww, cin, cout = shape
     x, f, b = conv_case(700 + cin + cout + n, n, hh, ww, cin, cout, 1, 1)
