@@ -432,7 +432,7 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* scrat
   return r;
 }
 
-// Global average pool alone, for batches where the fully connected layer is worth a GEMM of its own: workgroup
+// Global average pool alone, in front of the fully connected layer as a GEMM: workgroup
 // (image, 256 channels), thread (pixel group p0 of 8, 8 channels): 16-byte loads, fp32 sums, one rounding.
 __global__ __launch_bounds__(256) void pool_f16_kernel(const half_t* __restrict__ a, half_t* __restrict__ pooled, int hw,
                                                        int k) {
@@ -604,11 +604,13 @@ int launch_pool_fc_softmax_f16(const uint16_t* a, const uint16_t* w, const uint1
                                uint16_t* logits, uint16_t* probs, int n, int hw, int k, int classes,
                                hipStream_t stream) {
   if (classes > 256 * kMaxPerThread) return TFX_ERR_UNSUPPORTED;
-  // From 16 images on the fully connected layer is a matrix product worth its own launch: pool, then the GEMM (bias
-  // and the rounding of the logits in its epilogue), then the softmax of the stored logits.  The pooled vectors,
-  // and the logits if the caller does not ask for them, live where the partial sums would (32 n classes floats).
+  // With a class count that is a multiple of 8 (16-byte rows of the weights): pool, then the fully connected layer as
+  // a GEMM (bias and the rounding of the logits in its epilogue), then the softmax of the stored logits -- three
+  // launches, faster than the two below at every batch (those re-read the weights once per 4 images and write 32 n
+  // classes partial sums).  The pooled vectors, and the logits if the caller does not ask for them, live where the
+  // partial sums would.
   const size_t partial_bytes = (size_t)kFcSlices * n * classes * sizeof(float);
-  if (n >= 16 && hw <= 64 && k % 8 == 0 && classes % 8 == 0 && reinterpret_cast<uintptr_t>(a) % 16 == 0 &&
+  if (hw <= 64 && k % 8 == 0 && classes % 8 == 0 && reinterpret_cast<uintptr_t>(a) % 16 == 0 &&
       ((size_t)n * k + 127) / 128 * 256 + (size_t)n * classes * 2 <= partial_bytes) {
     uint16_t* const pooled = reinterpret_cast<uint16_t*>(partial);
     uint16_t* const lg = logits ? logits : pooled + (((size_t)n * k + 127) / 128) * 128;

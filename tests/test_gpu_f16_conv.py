@@ -398,11 +398,12 @@ def test_mobilenet_f16_nan_and_inf_through_the_fused_blocks_at_large_batch():
         end_to_end_bar(got[keep], ref[keep], "finite pixels after block %d" % k, 4)
 
 
-@pytest.mark.parametrize("size,q,classes,batch", [(64, 1, 40, 16), (96, 2, 1000, 17), (64, 4, 8, 40), (64, 1, 37, 16)])
+@pytest.mark.parametrize("size,q,classes,batch", [(64, 1, 40, 16), (96, 2, 1000, 17), (64, 4, 8, 40), (64, 1, 37, 16),
+                                                  (64, 2, 24, 1), (128, 1, 16, 3), (64, 1, 1001, 5)])
 def test_mobilenet_f16_tail_at_large_batch(size, q, classes, batch):
-    """From 16 images on (class count a multiple of 8) the tail is pool, GEMM, softmax as three launches, with the
-    pooled vectors -- and the logits, if the caller passes no buffer for them -- in the workspace; 37 classes take the
-    fused tail.  With and without a logits buffer the probabilities have the same bits."""
+    """With a class count that is a multiple of 8 the tail is pool, GEMM, softmax as three launches, with the pooled
+    vectors -- and the logits, if the caller passes no buffer for them -- in the workspace; 37 and 1001 classes take
+    the two-launch tail.  With and without a logits buffer the probabilities have the same bits."""
     import ctypes
     import torch
     import paper_1901_05350_amd as tfx
