@@ -313,7 +313,9 @@ def main():
                     "TFLOPs": round(flop / t / 1e12, 3), "GBps": round(nbytes / t / 1e9, 1), "algorithmic_bytes": nbytes,
                     "roofline": {"bound": "mfma", "achieved": round(flop / t / 1e12, 3), "peak": PEAK_MFMA_F16 / 1e12,
                                  "unit": "TFLOP/s", "frac": round(flop / t / PEAK_MFMA_F16, 5),
-                                 "traffic": measured_traffic("conv3x3_f16_%dx56x56x64_to_64" % n)}}
+                                 "traffic": measured_traffic("conv3x3_f16_%dx56x56x64_to_64" % n),
+                                 # 144 FLOP per algorithmic byte against the chip's 312: on the HBM side of the roofline
+                                 "hbm_frac_of_the_same_launch": round(nbytes / t / PEAK_HBM, 5)}}
         return build
 
     single_ops = {"matmul_64x128x64": op_matmul, "batch_matmul_8x1024x1024x1024_tB": op_batch_matmul}
