@@ -165,6 +165,16 @@ def test_mobilenet_variant_validation():
     assert fwd(ctypes.byref(V(8, 4, 1000)), FAKE, 1, ctypes.byref(w), FAKE, base, FAKE, None, None) == -3
     assert fwd(ctypes.byref(ok), FAKE, 0, ctypes.byref(w), FAKE, nbytes, FAKE, None, None) == -2
     assert fwd(ctypes.byref(ok), FAKE, 1, ctypes.byref(w), FAKE, nbytes - 1, FAKE, None, None) == -5
+    # from batch 32 on the pass runs as two half batches with a part of the workspace each: the same checks, first
+    big = tfx.tfx_mobilenet_v1_variant_workspace_bytes(ok, 33)
+    assert big % 256 == 0 and big >= tfx.tfx_mobilenet_v1_variant_workspace_bytes(ok, 31)
+    assert fwd(ctypes.byref(ok), FAKE, 33, ctypes.byref(w), FAKE, big - 1, FAKE, None, None) == -5
+    assert fwd(ctypes.byref(ok), FAKE, 33, ctypes.byref(w), ctypes.c_void_p(0x1010), big, FAKE, None, None) == -5
+    assert fwd(ctypes.byref(ok), FAKE, 33, ctypes.byref(w), FAKE, big, None, None, None) == -1
+    assert fwd(ctypes.byref(V(224, 7, 1000)), FAKE, 64, ctypes.byref(w), FAKE, big, FAKE, None, None) == -3
+    assert fwd(ctypes.byref(ok), FAKE, 1025, ctypes.byref(w), FAKE, big, FAKE, None, None) == -4
+    w.dw_b[3] = 0
+    assert fwd(ctypes.byref(ok), FAKE, 40, ctypes.byref(w), FAKE, big, FAKE, None, None) == -1
 
 
 def test_features_shape_follows_the_strides_of_table_1():

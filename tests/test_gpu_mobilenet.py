@@ -252,6 +252,37 @@ def test_batched_forward_first_called_under_graph_capture():
     assert_close(l_graph, logits, "logits batch 8 (192 x 192)")
 
 
+def test_forward_in_two_halves_from_batch_32():
+    """From batch 32 on the forward pass is two half batches (17 + 16 images here), the second on a stream of the
+    library's own, forked from and joined to the caller's.  Every image against the oracle; the same bits on a second
+    call; and captured into a graph (fork and join become edges of the graph) every replay gives the eager bits."""
+    import torch
+    import paper_1901_05350_amd as tfx
+    batch = 33
+    data = inputs.mobilenet_v1(seed=12, batch=batch, image_size=96, width_quarters=2, classes=10)
+    probs, logits = oracle.mobilenet_v1_forward(data["image"], data["weights"])
+    model = tfx.MobileNetV1(data["weights"], batch=batch, image_size=96, width_quarters=2)
+    image = dev(data["image"])
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):          # not the default stream: the fork has to follow the caller's stream
+        p, l = model.forward(image)
+    stream.synchronize()
+    p, l = host(p).copy(), host(l).copy()
+    assert_close(l, logits, "logits batch 33")
+    assert_close(p, probs, "probs batch 33")
+    p2, l2 = model.forward(image)
+    assert np.array_equal(host(p2), p) and np.array_equal(host(l2), l)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        model.forward(image)
+    other = dev(np.random.Generator(np.random.PCG64(98)).uniform(-1, 1, (batch, 96, 96, 3)))
+    for _ in range(3):
+        assert not np.array_equal(host(model.forward(other)[0]), p)     # eager work on the same workspace in between
+        model.probs.zero_()
+        g.replay()
+        assert np.array_equal(host(model.probs), p) and np.array_equal(host(model.logits), l)
+
+
 # ---- the chained small-map kernel (batch 1, full width: blocks 5 .. 13, pool, fully connected, softmax in one launch) ----
 @pytest.mark.parametrize("size,classes", [(32, 3), (64, 1000), (100, 5), (128, 1024), (160, 37), (192, 1000), (250, 130),
                                           (256, 1)])
