@@ -283,6 +283,39 @@ def test_forward_in_two_halves_from_batch_32():
         assert np.array_equal(host(model.probs), p) and np.array_equal(host(model.logits), l)
 
 
+def test_two_host_threads_share_the_second_stream():
+    """Two host threads, each with a stream and a model of its own, run batch-32 forward passes at the same time: both
+    fork to the library's one second stream (its events are re-recorded call after call, under a lock).  All results
+    must have the bits of an undisturbed run."""
+    import threading
+    import torch
+    import paper_1901_05350_amd as tfx
+    batch = 32
+    data = inputs.mobilenet_v1(seed=13, batch=batch, image_size=64, width_quarters=1, classes=16)
+    models = [tfx.MobileNetV1(data["weights"], batch=batch, image_size=64, width_quarters=1) for _ in range(2)]
+    images = [dev(data["image"]), dev(data["image"][::-1].copy())]
+    want = [host(m.forward(x)[0]).copy() for m, x in zip(models, images)]
+    assert not np.array_equal(want[0], want[1])
+    outs = [[torch.zeros_like(m.probs) for _ in range(20)] for m in models]
+    streams = [torch.cuda.Stream() for _ in models]
+    torch.cuda.synchronize()
+
+    def worker(i):
+        with torch.cuda.stream(streams[i]):
+            for o in outs[i]:
+                tfx.tfx_mobilenet_v1_variant_forward(models[i].variant, images[i], models[i].struct, models[i].workspace, o)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for i in range(2):
+        for o in outs[i]:
+            assert np.array_equal(host(o), want[i])
+
+
 # ---- the chained small-map kernel (batch 1, full width: blocks 5 .. 13, pool, fully connected, softmax in one launch) ----
 @pytest.mark.parametrize("size,classes", [(32, 3), (64, 1000), (100, 5), (128, 1024), (160, 37), (192, 1000), (250, 130),
                                           (256, 1)])
