@@ -216,8 +216,11 @@ size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch);
  * after the call: for the caller the call still behaves as work on `stream`, also
  * while `stream` is being captured into a graph (fork and join become edges of the
  * graph).  Two chains of kernels fill the CUs that the last workgroups of each
- * kernel leave idle (1.03 -> 0.95 ms at batch 64).  If the stream cannot be created
- * the halves run one after the other on `stream`, with the same results. */
+ * kernel leave idle (1.03 -> 0.98 ms at batch 64).  If the stream cannot be created
+ * (also: if the first such call of the process comes while `stream` is being
+ * captured), or if TFX_ONE_STREAM is set in the environment, the batch runs as one
+ * chain of kernels on `stream`, as below batch 32; the results then agree with the
+ * two-half form to rounding (other tile shapes), not bit for bit. */
 int tfx_mobilenet_v1_forward(const float* input, int64_t batch, const tfx_mobilenet_v1_weights* weights,
                              void* workspace, size_t workspace_bytes, float* probs, float* logits,
                              void* stream);
@@ -279,8 +282,8 @@ int tfx_mobilenet_v1_variant_features(const tfx_mobilenet_v1_variant* variant, c
  * allocates and frees nothing.  {224, 4, 1000} fits at batch 1 and 2; a variant / batch whose
  * tfx_mobilenet_v1_variant_workspace_bytes exceeds the array is refused with
  * TFX_ERR_WORKSPACE (nothing enqueued).  Results are bit-identical to
- * tfx_mobilenet_v1_variant_forward (a small variant at batch 32 or more runs as the same
- * two half batches, here one after the other on `stream`: no stream is created).  All calls on one GPU share the one array: calls that
+ * tfx_mobilenet_v1_variant_forward below batch 32 (from there on that call splits the batch
+ * over two streams; this one creates no stream and runs one chain of kernels).  All calls on one GPU share the one array: calls that
  * overlap in time on one GPU (different streams or host threads) race and give
  * undefined results; calls ordered on one stream are fine.  Nothing in the array has to
  * start at zero (each kernel writes what later kernels read), so its contents between

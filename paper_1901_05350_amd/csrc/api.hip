@@ -1,6 +1,7 @@
 // C ABI of libtfx: argument validation, shape rules and kernel selection.
 // Every entry point validates on the host before any HIP call and then only enqueues
 // kernels on the caller's stream (enqueue-and-return, as the ops of Section 3.6 / 4.1).
+#include <cstdlib>
 #include <mutex>
 
 #include "tfx_internal.h"
@@ -166,9 +167,11 @@ void* static_scratch() {
 // tails (measured: 1.03 -> 0.95 ms at batch 64, 1.87 -> 1.74 at batch 128; nothing to gain on binary16 storage).
 constexpr int64_t kSplitBatch = 32;
 
-size_t net_workspace_bytes(const tfx_mobilenet_v1_variant& v, int64_t batch) {
-  if (batch < kSplitBatch) return plan_net(v, batch).bytes;
-  return align_up(plan_net(v, batch - batch / 2).bytes) + plan_net(v, batch / 2).bytes;
+size_t net_workspace_bytes(const tfx_mobilenet_v1_variant& v, int64_t batch) {  // enough for either form
+  const size_t whole = plan_net(v, batch).bytes;
+  if (batch < kSplitBatch) return whole;
+  const size_t halves = align_up(plan_net(v, batch - batch / 2).bytes) + plan_net(v, batch / 2).bytes;
+  return halves > whole ? halves : whole;
 }
 
 // The second stream and its two events, one set per device, created on the first call that wants them and kept
@@ -587,47 +590,42 @@ int forward_impl(const tfx_mobilenet_v1_variant* variant, const float* input, in
 }  // namespace
 
 namespace {
-// The whole forward pass: below kSplitBatch one chain of kernels on the caller's stream; from there on two half
-// batches, each with its own part of the workspace -- on two streams if `may_fork`, else one after the other (the
-// same kernels on the same data either way, hence the same bits).
+// The whole forward pass: one chain of kernels on the caller's stream, or, from kSplitBatch on and if a second stream
+// is to be had, two half batches, each with its own part of the workspace, on two streams.
 int forward_whole(const tfx_mobilenet_v1_variant* variant, const float* input, int64_t batch,
                   const tfx_mobilenet_v1_weights* weights, void* workspace, size_t workspace_bytes, float* probs,
                   float* logits, void* stream, bool may_fork) {
-  if (batch < kSplitBatch)
+  // TFX_ONE_STREAM in the environment: no stream of the library's in this process (also for per-kernel profiles:
+  // overlapped kernels stretch each other's durations)
+  if (batch < kSplitBatch || !may_fork || std::getenv("TFX_ONE_STREAM") != nullptr)
     return forward_impl(variant, input, batch, weights, workspace, workspace_bytes, probs, logits, 0, nullptr, stream);
   if (const int bad = check_net_args(variant, input, batch, weights, workspace, probs)) return bad;
+  if (workspace_bytes < net_workspace_bytes(*variant, batch) || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0)
+    return TFX_ERR_WORKSPACE;
+  hipStream_t main_stream = static_cast<hipStream_t>(stream);
+  std::unique_lock<std::mutex> guard(g_side_lock);
+  SideStream* const side = side_stream(main_stream);
+  if (!side || hipEventRecord(side->fork, main_stream) != hipSuccess ||
+      hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) {
+    // no second stream (creation failed, or this first large call comes inside a graph capture): one chain
+    (void)hipGetLastError();
+    guard.unlock();
+    return forward_impl(variant, input, batch, weights, workspace, workspace_bytes, probs, logits, 0, nullptr, stream);
+  }
   const int64_t na = batch - batch / 2, nb = batch / 2;
   const size_t bytes_a = align_up(plan_net(*variant, na).bytes), bytes_b = plan_net(*variant, nb).bytes;
-  if (workspace_bytes < bytes_a + bytes_b || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0)
-    return TFX_ERR_WORKSPACE;
   const size_t image = (size_t)variant->image_size * variant->image_size * 3;
-  hipStream_t main_stream = static_cast<hipStream_t>(stream), second = main_stream;
-  std::unique_lock<std::mutex> guard(g_side_lock, std::defer_lock);
-  SideStream* side = nullptr;
-  if (may_fork) {
-    guard.lock();
-    side = side_stream(main_stream);
-    if (side && (hipEventRecord(side->fork, main_stream) != hipSuccess ||
-                 hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)) {
-      (void)hipGetLastError();
-      side = nullptr;
-    }
-    if (side) second = side->stream;
-    else guard.unlock();
-  }
   int rc = forward_impl(variant, input, na, weights, workspace, bytes_a, probs, logits, 0, nullptr, main_stream);
   if (rc == TFX_OK)
     rc = forward_impl(variant, input + na * image, nb, weights, static_cast<char*>(workspace) + bytes_a, bytes_b,
                       probs + na * variant->classes, logits ? logits + na * variant->classes : nullptr, 0, nullptr,
-                      second);
-  if (side) {
-    // the join is enqueued whatever happened in between, so that the caller's stream (or the graph it is being
-    // captured into) never ends with the second stream still forked
-    if (hipEventRecord(side->join, side->stream) != hipSuccess ||
-        hipStreamWaitEvent(main_stream, side->join, 0) != hipSuccess) {
-      (void)hipGetLastError();
-      if (rc == TFX_OK) rc = TFX_ERR_LAUNCH;
-    }
+                      side->stream);
+  // the join is enqueued whatever happened in between, so that the caller's stream (or the graph it is being
+  // captured into) never ends with the second stream still forked
+  if (hipEventRecord(side->join, side->stream) != hipSuccess ||
+      hipStreamWaitEvent(main_stream, side->join, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    if (rc == TFX_OK) rc = TFX_ERR_LAUNCH;
   }
   return rc;
 }
@@ -673,7 +671,7 @@ int tfx_mobilenet_v1_variant_forward_static(const tfx_mobilenet_v1_variant* vari
   if (!ws) return TFX_ERR_LAUNCH;
   // Every kernel of the forward pass writes the part of the workspace it later reads (feature maps, the fully
   // connected layer's partial sums), so nothing has to be cleared between calls.
-  // (no second stream here: creating one allocates)
+  // (no second stream here -- creating one allocates: one chain of kernels at every batch)
   return forward_whole(variant, input, batch, weights, ws, kStaticScratchBytes, probs, logits, stream, false);
 }
 
