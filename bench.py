@@ -527,7 +527,9 @@ def main():
             imgs = torch.empty((nb, 224, 224, 3), device="cuda:0").uniform_(-1, 1)
             t = time_loop(lambda: mb.forward(imgs), max(20, reps // 4), warmup=3, inner=5)
             batched["batch_%d" % nb] = {"ms_per_batch": round(t * 1e3, 4), "images_per_s": round(nb / t, 1),
-                                        "TFLOPs": round(nb * 1.137480704e9 / t / 1e12, 3)}
+                                        "TFLOPs": round(nb * 1.137480704e9 / t / 1e12, 3),
+                                        "form": "two half batches on two streams" if nb >= 32 and not os.environ.get("TFX_ONE_STREAM")
+                                        else "one chain of kernels"}
             del mb, imgs
         out["mobilenet_batched"] = batched
 
