@@ -1,6 +1,8 @@
 // C ABI of libtfx: argument validation, shape rules and kernel selection.
 // Every entry point validates on the host before any HIP call and then only enqueues
-// kernels on the caller's stream (enqueue-and-return, as the ops of Section 3.6 / 4.1).
+// kernels on the caller's stream (enqueue-and-return, as the ops of Section 3.6 / 4.1);
+// the fp32 forward pass of 32 or more images also uses one stream of the library's own,
+// forked from and joined to the caller's (forward_whole).
 #include <cstdlib>
 #include <mutex>
 
