@@ -2,17 +2,17 @@
 // for the kernel that keeps the whole filter there:
 //   y[M,N] = half(act(x[M,K] * w[K,N] + bias)),  K = 64, 128, 256 or 512, N = 128 ... 2048, M in the thousands
 // (Section 4.1 storage format; the pointwise layers of the 28 x 28 ... 7 x 7 maps of the Section 3.9 network at
-// large batch, and of its larger maps at batch 1 to 5).  At fp16 rate the matrix cores need 3 us for such a layer and a tiled GEMM spends its time around
-// them: slices of both operands through LDS, two barriers per slice, 16 slices per tile.  Here a workgroup keeps a
-// column slab of the filter -- all K rows of NS = 128 columns, up to 133 KB -- in LDS (stream_f16.h: transposed once, rows in
-// the order that leaves a lane with 8 consecutive output channels), and each of its 8 wavefronts takes units of
-// 16 SL rows of x against it: a lane loads its own v_mfma_f32_16x16x32_f16 operands (its rows, 8 consecutive k per
-// 16-byte load) straight from global memory, D k-steps ahead of their use and across the end of a unit, reads each
-// filter fragment from LDS once for the SL slabs, and stores its outputs as 16-byte pieces.  No barrier after the
-// filter is in place.  The N / NS workgroups that take the same rows against different slabs run on one XCD, so x
-// comes from memory once and from that XCD's L2 afterwards.  What bounds it is the path from L2: 256 workgroups
-// fetch a slab each and every row of x N / NS times (with K = 1024 only 64 columns fit, x would be fetched N / 64
-// times, and the tiled GEMM is faster).
+// large batch, and of its larger maps at batch 1 to 5).  At fp16 rate the matrix cores need 3 us for such a layer
+// and a tiled GEMM spends its time around them: slices of both operands through LDS, two barriers per slice, 16
+// slices per tile.  Here a workgroup keeps a column slab of the filter -- all K rows of NS = 128 columns, up to
+// 133 KB -- in LDS (stream_f16.h: transposed once, rows in the order that leaves a lane with 8 consecutive output
+// channels), and each of its 8 wavefronts takes units of 16 SL rows of x against it: a lane loads its own
+// v_mfma_f32_16x16x32_f16 operands (its rows, 8 consecutive k per 16-byte load) straight from global memory, D
+// k-steps ahead of their use and across the end of a unit, reads each filter fragment from LDS once for the SL
+// slabs, and stores its outputs as 16-byte pieces.  No barrier after the filter is in place.  The N / NS
+// workgroups that take the same rows against different slabs run on one XCD, so x comes from memory once and from
+// that XCD's L2 afterwards.  What bounds it is the path from L2: 256 workgroups fetch a slab each and every row of
+// x N / NS times (with K = 1024 only 64 columns fit, x would be fetched N / 64 times, and the tiled GEMM is faster).
 #include "stream_f16.h"
 
 namespace tfx {
