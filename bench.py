@@ -40,7 +40,7 @@ MEASURED_TRAFFIC = {
     "pointwise_f16_64x56x56x128_to_128": (104307312, "pointwise_f16.hip", "ce1b39f22ab2de85935114032f7da23fa19670dd2587c5787ce442e1a65ef9ae"),
     "depthwise_f16_64x112x112x64_s1_cold_rotation": (205682035, "conv_f16.hip", "afe6f8ef43c1ef8148e17ecfb1317d9bb5da79a3024c8dff8ff47b6ebdc20a4d"),
     "depthwise_f16_64x112x112x64_s2_cold_rotation": (128552759, "conv_f16.hip", "afe6f8ef43c1ef8148e17ecfb1317d9bb5da79a3024c8dff8ff47b6ebdc20a4d"),
-    "pointwise_f16_64x14x14x512_to_512": (30192349, "pointwise_slab_f16.hip", "d38787ba3c0b2141e912644c82f030eb40800eb0135dc96b8617be2c3f85cd43"),
+    "pointwise_f16_64x14x14x512_to_512": (30192349, "pointwise_slab_f16.hip", "af2faf347eb820ccf9a29fb135a9ca89ecf628f4ce49a11949d8b30c7e1a5587"),
     "conv3x3_f16_64x56x56x64_to_64": (55026541, "conv_stream_f16.hip", "5d25ba83ebb077dcddf0dcaed1a88b53a1395351810b957ba4056c3c06bc7fe9"),
     "add_f32_64M": (805263264, "elementwise.hip", "7f84a8e7a8ec924bce5600deb9d686a5a76abe82b88ca3d841c7cda5219bee52"),
     "add_f16_64M": (402651867, "elementwise.hip", "7f84a8e7a8ec924bce5600deb9d686a5a76abe82b88ca3d841c7cda5219bee52"),
