@@ -528,7 +528,7 @@ def main():
             t = time_loop(lambda: mb.forward(imgs), max(20, reps // 4), warmup=3, inner=5)
             batched["batch_%d" % nb] = {"ms_per_batch": round(t * 1e3, 4), "images_per_s": round(nb / t, 1),
                                         "TFLOPs": round(nb * 1.137480704e9 / t / 1e12, 3),
-                                        "form": "two half batches on two streams" if nb >= 32 and not os.environ.get("TFX_ONE_STREAM")
+                                        "form": "three parts of the batch on three streams" if nb >= 60 and not os.environ.get("TFX_ONE_STREAM")
                                         else "one chain of kernels"}
             del mb, imgs
         out["mobilenet_batched"] = batched

@@ -17,7 +17,7 @@
  *     keep, per process and per device, are launch attributes it has looked up
  *     once (which kernels were allowed their dynamic LDS size, how many
  *     workgroups of a kernel are resident at once) and, once a forward pass
- *     of 32 or more images has run, one stream and two events of its own (see
+ *     of 32 or more images has run, two streams and three events of its own (see
  *     tfx_mobilenet_v1_forward); these never change a result.  Inputs are never
  *     written
  *     (ops are functional, Section 3.7); the output must not overlap any input
@@ -209,18 +209,18 @@ size_t tfx_mobilenet_v1_workspace_bytes(int64_t batch);
  * input: device [batch,224,224,3]; workspace: device, >= the size above, 256-byte
  * aligned, contents undefined before and after; probs: device [batch,1000];
  * logits: device [batch,1000] or NULL.  All kernels are enqueued on `stream`,
- * with one exception: from batch 32 on the pass runs as two half batches (each in
- * its own part of the workspace), and the second half is enqueued on a stream the
- * library creates once per device, which waits for everything queued on `stream`
- * before the call (an event) and which `stream` waits for before anything queued
- * after the call: for the caller the call still behaves as work on `stream`, also
+ * with one exception: from batch 32 on the pass runs as two parts of the batch, from
+ * batch 60 on as three (each in its own part of the workspace), and all but the first
+ * are enqueued on streams the library creates once per device, which wait for
+ * everything queued on `stream` before the call (an event) and which `stream` waits
+ * for before anything queued after the call: for the caller the call still behaves as work on `stream`, also
  * while `stream` is being captured into a graph (fork and join become edges of the
- * graph).  Two chains of kernels fill the CUs that the last workgroups of each
- * kernel leave idle (1.03 -> 0.98 ms at batch 64).  If the stream cannot be created
+ * graph).  Independent chains of kernels fill the CUs that the last workgroups of
+ * each kernel leave idle (1.03 -> 0.96 ms at batch 64).  If the streams cannot be created
  * (also: if the first such call of the process comes while `stream` is being
  * captured), or if TFX_ONE_STREAM is set in the environment, the batch runs as one
  * chain of kernels on `stream`, as below batch 32; the results then agree with the
- * two-half form to rounding (other tile shapes), not bit for bit. */
+ * split form to rounding (other tile shapes), not bit for bit. */
 int tfx_mobilenet_v1_forward(const float* input, int64_t batch, const tfx_mobilenet_v1_weights* weights,
                              void* workspace, size_t workspace_bytes, float* probs, float* logits,
                              void* stream);

@@ -1,8 +1,8 @@
 // C ABI of libtfx: argument validation, shape rules and kernel selection.
 // Every entry point validates on the host before any HIP call and then only enqueues
 // kernels on the caller's stream (enqueue-and-return, as the ops of Section 3.6 / 4.1);
-// the fp32 forward pass of 32 or more images also uses one stream of the library's own,
-// forked from and joined to the caller's (forward_whole).
+// the fp32 forward pass of 32 or more images also uses one or two streams of the library's
+// own, forked from and joined to the caller's (forward_whole).
 #include <cstdlib>
 #include <mutex>
 
@@ -163,28 +163,36 @@ void* static_scratch() {
   return p;
 }
 
-// From this batch on the fp32 forward pass runs as two half batches, the second on a stream of the library's own
-// that is forked from the caller's stream and joined back to it with events: the layers of such a batch are kernels
-// of 10 - 90 us whose last workgroups leave most CUs idle, and two independent chains of them fill each other's
-// tails (measured: 1.03 -> 0.95 ms at batch 64, 1.87 -> 1.74 at batch 128; nothing to gain on binary16 storage).
-constexpr int64_t kSplitBatch = 32;
+// From batch 32 on the fp32 forward pass runs as two parts of the batch, from batch 60 on as three, all but the first
+// on streams of the library's own that are forked from the caller's stream and joined back to it with events: the
+// layers of such a batch are kernels of 10 - 90 us whose last workgroups leave most CUs idle, and independent chains
+// of them fill each other's tails (measured: batch 64 1.03 -> 0.975 ms with two chains, 0.96 with three; batch 128
+// 1.87 -> 1.76 either way; at batch 48 three are no better than two; nothing to gain on binary16 storage).
+constexpr int64_t kSplitBatch = 32, kThreeChains = 60;
+constexpr int kMaxChains = 3;
+
+int net_chains(int64_t batch) { return batch < kSplitBatch ? 1 : batch < kThreeChains ? 2 : 3; }
+// images of part i of `chains`: the first batch % chains parts take one more
+int64_t part_images(int64_t batch, int chains, int i) { return batch / chains + (i < batch % chains ? 1 : 0); }
 
 size_t net_workspace_bytes(const tfx_mobilenet_v1_variant& v, int64_t batch) {  // enough for either form
   const size_t whole = plan_net(v, batch).bytes;
-  if (batch < kSplitBatch) return whole;
-  const size_t halves = align_up(plan_net(v, batch - batch / 2).bytes) + plan_net(v, batch / 2).bytes;
-  return halves > whole ? halves : whole;
+  const int chains = net_chains(batch);
+  if (chains == 1) return whole;
+  size_t parts = 0;
+  for (int i = 0; i < chains; ++i) parts += align_up(plan_net(v, part_images(batch, chains, i)).bytes);
+  return parts > whole ? parts : whole;
 }
 
-// The second stream and its two events, one set per device, created on the first call that wants them and kept
+// The library's own streams and events, one set per device, created on the first call that wants them and kept
 // until the process ends.  Calls that use them hold the lock while they enqueue.
-struct SideStream {
-  hipStream_t stream;
-  hipEvent_t fork, join;
+struct SideStreams {
+  hipStream_t stream[kMaxChains - 1];
+  hipEvent_t fork, join[kMaxChains - 1];
 };
 std::mutex g_side_lock;
-SideStream* side_stream(hipStream_t caller) {  // with g_side_lock held; null: run the halves one after the other
-  static SideStream table[kMaxDevices];
+SideStreams* side_streams(hipStream_t caller) {  // with g_side_lock held; null: none to be had
+  static SideStreams table[kMaxDevices];
   static int state[kMaxDevices];  // 0 not tried, 1 there, 2 failed
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
@@ -196,10 +204,11 @@ SideStream* side_stream(hipStream_t caller) {  // with g_side_lock held; null: r
       (void)hipGetLastError();
       return nullptr;
     }
-    SideStream& t = table[dev];
-    const bool ok = hipStreamCreateWithFlags(&t.stream, hipStreamNonBlocking) == hipSuccess &&
-                    hipEventCreateWithFlags(&t.fork, hipEventDisableTiming) == hipSuccess &&
-                    hipEventCreateWithFlags(&t.join, hipEventDisableTiming) == hipSuccess;
+    SideStreams& t = table[dev];
+    bool ok = hipEventCreateWithFlags(&t.fork, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < kMaxChains - 1 && ok; ++i)
+      ok = hipStreamCreateWithFlags(&t.stream[i], hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&t.join[i], hipEventDisableTiming) == hipSuccess;
     if (!ok) (void)hipGetLastError();
     state[dev] = ok ? 1 : 2;
   }
@@ -605,30 +614,42 @@ int forward_whole(const tfx_mobilenet_v1_variant* variant, const float* input, i
   if (workspace_bytes < net_workspace_bytes(*variant, batch) || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0)
     return TFX_ERR_WORKSPACE;
   hipStream_t main_stream = static_cast<hipStream_t>(stream);
+  const int chains = net_chains(batch);
   std::unique_lock<std::mutex> guard(g_side_lock);
-  SideStream* const side = side_stream(main_stream);
-  if (!side || hipEventRecord(side->fork, main_stream) != hipSuccess ||
-      hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) {
-    // no second stream (creation failed, or this first large call comes inside a graph capture): one chain
-    (void)hipGetLastError();
-    guard.unlock();
-    return forward_impl(variant, input, batch, weights, workspace, workspace_bytes, probs, logits, 0, nullptr, stream);
-  }
-  const int64_t na = batch - batch / 2, nb = batch / 2;
-  const size_t bytes_a = align_up(plan_net(*variant, na).bytes), bytes_b = plan_net(*variant, nb).bytes;
+  SideStreams* const side = side_streams(main_stream);
+  bool forked = side != nullptr && hipEventRecord(side->fork, main_stream) == hipSuccess;
+  int waiting = 0;  // side streams that have joined the caller's stream (or the graph it is being captured into)
+  for (; forked && waiting < chains - 1; ++waiting)
+    if (hipStreamWaitEvent(side->stream[waiting], side->fork, 0) != hipSuccess) break;
+  const bool all = forked && waiting == chains - 1;
   const size_t image = (size_t)variant->image_size * variant->image_size * 3;
-  int rc = forward_impl(variant, input, na, weights, workspace, bytes_a, probs, logits, 0, nullptr, main_stream);
-  if (rc == TFX_OK)
-    rc = forward_impl(variant, input + na * image, nb, weights, static_cast<char*>(workspace) + bytes_a, bytes_b,
-                      probs + na * variant->classes, logits ? logits + na * variant->classes : nullptr, 0, nullptr,
-                      side->stream);
-  // the join is enqueued whatever happened in between, so that the caller's stream (or the graph it is being
-  // captured into) never ends with the second stream still forked
-  if (hipEventRecord(side->join, side->stream) != hipSuccess ||
-      hipStreamWaitEvent(main_stream, side->join, 0) != hipSuccess) {
+  int rc = TFX_OK;
+  if (all) {
+    int64_t first = 0;
+    char* ws = static_cast<char*>(workspace);
+    for (int i = 0; i < chains && rc == TFX_OK; ++i) {
+      const int64_t n = part_images(batch, chains, i);
+      const size_t bytes = align_up(plan_net(*variant, n).bytes);
+      rc = forward_impl(variant, input + first * image, n, weights, ws, bytes, probs + first * variant->classes,
+                        logits ? logits + first * variant->classes : nullptr, 0, nullptr,
+                        i == 0 ? main_stream : side->stream[i - 1]);
+      first += n;
+      ws += bytes;
+    }
+  } else {
+    // no streams of the library's (creation failed, or this first large call comes inside a graph capture), or a
+    // wait could not be enqueued: one chain on the caller's stream
     (void)hipGetLastError();
-    if (rc == TFX_OK) rc = TFX_ERR_LAUNCH;
+    rc = forward_impl(variant, input, batch, weights, workspace, workspace_bytes, probs, logits, 0, nullptr, stream);
   }
+  // every stream that waits for the fork is joined whatever happened in between, so that the caller's stream (or the
+  // graph it is being captured into) never ends with a side stream still forked
+  for (int i = 0; i < waiting; ++i)
+    if (hipEventRecord(side->join[i], side->stream[i]) != hipSuccess ||
+        hipStreamWaitEvent(main_stream, side->join[i], 0) != hipSuccess) {
+      (void)hipGetLastError();
+      if (rc == TFX_OK) rc = TFX_ERR_LAUNCH;
+    }
   return rc;
 }
 }  // namespace

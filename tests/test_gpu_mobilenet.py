@@ -252,13 +252,14 @@ def test_batched_forward_first_called_under_graph_capture():
     assert_close(l_graph, logits, "logits batch 8 (192 x 192)")
 
 
-def test_forward_in_two_halves_from_batch_32():
-    """From batch 32 on the forward pass is two half batches (17 + 16 images here), the second on a stream of the
-    library's own, forked from and joined to the caller's.  Every image against the oracle; the same bits on a second
-    call; and captured into a graph (fork and join become edges of the graph) every replay gives the eager bits."""
+@pytest.mark.parametrize("batch", [33, 61])
+def test_forward_in_two_halves_from_batch_32(batch):
+    """From batch 32 on the forward pass is two parts of the batch (17 + 16 images), from batch 60 on three (21 + 20 +
+    20), all but the first on streams of the library's own, forked from and joined to the caller's.  Every image
+    against the oracle; the same bits on a second call; and captured into a graph (fork and joins become edges of the
+    graph) every replay gives the eager bits."""
     import torch
     import paper_1901_05350_amd as tfx
-    batch = 33
     data = inputs.mobilenet_v1(seed=12, batch=batch, image_size=96, width_quarters=2, classes=10)
     probs, logits = oracle.mobilenet_v1_forward(data["image"], data["weights"])
     model = tfx.MobileNetV1(data["weights"], batch=batch, image_size=96, width_quarters=2)
@@ -268,8 +269,8 @@ def test_forward_in_two_halves_from_batch_32():
         p, l = model.forward(image)
     stream.synchronize()
     p, l = host(p).copy(), host(l).copy()
-    assert_close(l, logits, "logits batch 33")
-    assert_close(p, probs, "probs batch 33")
+    assert_close(l, logits, "logits batch %d" % batch)
+    assert_close(p, probs, "probs batch %d" % batch)
     p2, l2 = model.forward(image)
     assert np.array_equal(host(p2), p) and np.array_equal(host(l2), l)
     g = torch.cuda.CUDAGraph()
