@@ -2,7 +2,8 @@
 // (Section 4.1):  y = half(relu6(pointwise(half(relu6(depthwise3x3(x) + dw_b))) + pw_b)),  stride 1 or 2, SAME.
 // The fp32 kernel of block_stream.hip with the operand layout of pointwise_f16.hip: the pointwise filter is the
 // stationary operand in LDS (stream_f16.h), a unit is a 4 x 8 patch of output pixels of one image = two
-// v_mfma_f32_16x16x32_f16 slabs of 2 x 8 pixels, the wavefront copies the patch's input window, 64 or 32 channels
+// v_mfma_f32_16x16x32_f16 slabs of 2 x 8 pixels (one slab, 2 x 8, for 128 -> 256 channels at stride 2, whose filter
+// leaves less room for windows; its 256 output channels take two passes over the operands), the wavefront copies the patch's input window, 64 or 32 channels
 // at a time, into its own piece of LDS, and lane (li, q) forms its operand of k-step s -- channels 32 s + 8 q ... + 7
 // of slab pixel (li / 8, li % 8) -- as the depthwise result of that pixel: 9 taps of 16 bytes from the window times
 // the depthwise filter (also in LDS), accumulated in fp32, clamped and rounded to binary16 exactly as the
@@ -18,7 +19,11 @@ namespace {
 using namespace f16s;
 
 constexpr int kThreads = 512, kWaves = kThreads / 64;
-constexpr int kPatchH = 4, kPatchW = 8;  // output pixels of a unit (two slabs of 2 x 8)
+constexpr int kPatchW = 8;  // a unit is PH x 8 output pixels: PH / 2 slabs of 2 x 8 (PH = 4; 2 where the windows of 4 rows do not fit)
+template <int K, int N, int S>
+constexpr int patch_rows() {
+  return (K == 128 && N == 256 && S == 2) ? 2 : 4;
+}
 
 struct WindowBlockGeom16 {
   int H, W, OH, OW, pt, pl;
@@ -29,9 +34,9 @@ struct WindowBlockGeom16 {
 // LDS layout of a window chunk of CC channels in 16-byte pieces (8 channels each): pixel stride PS >= CC / 8 and
 // row stride RS >= WW * PS, the least ones for which the tap read of a wavefront (pixel (li / 8, li % 8) * S plus a
 // constant, piece q) has no bank conflict.
-template <int S, int CC>
+template <int S, int CC, int PH>
 struct WindowLayout16 {
-  static constexpr int WH = (kPatchH - 1) * S + 3, WW = (kPatchW - 1) * S + 3, QC = CC / 8;
+  static constexpr int WH = (PH - 1) * S + 3, WW = (kPatchW - 1) * S + 3, QC = CC / 8;
   struct Piece {
     int ps, rs;
     constexpr int operator()(int li, int q) const { return (li / 8) * S * rs + (li % 8) * S * ps + q; }
@@ -65,11 +70,13 @@ __global__ __launch_bounds__(kThreads) void separable_window_f16_kernel(const ha
                                                                         half_t* __restrict__ y, WindowBlockGeom16 g,
                                                                         int units, int dw_act, int pw_act) {
   constexpr int CC = chunk_channels<K, S>();
-  using WL = WindowLayout16<S, CC>;
+  constexpr int PH = patch_rows<K, N, S>(), SL = PH / 2;  // slabs per unit
+  using WL = WindowLayout16<S, CC, PH>;
   using Stage = FilterStage<K, N, kThreads>;
   constexpr int KS = K / 32, NB = N / 16, LD = Stage::LD, CH = K / CC, SPC = CC / 32;  // k-steps, blocks, chunks, steps per chunk
   constexpr int PS = WL::PS, RS = WL::RS, WW = WL::WW, LI = WL::kLoads, QC = WL::QC;
-  static_assert(K % CC == 0 && N % 32 == 0 && NB <= 8 && N <= kThreads && 9 * K / 8 <= kThreads, "shape");
+  constexpr int NBP = NB < 8 ? NB : 8, PASSES = NB / NBP;  // 16-channel blocks per pass over the unit's operands
+  static_assert(K % CC == 0 && N % 32 == 0 && NB % NBP == 0 && N <= kThreads && 9 * K / 8 <= kThreads, "shape");
   // pointwise filter [N][LD] halfs, its bias (N floats, in the filter's row order), depthwise filter [9][K] halfs,
   // its bias (K floats), then one window per wavefront
   extern __shared__ __align__(16) half_t wl[];
@@ -104,7 +111,7 @@ __global__ __launch_bounds__(kThreads) void separable_window_f16_kernel(const ha
     const int t1 = unit / g.tiles_c;
     p.tr = t1 % g.tiles_r;
     p.n = t1 / g.tiles_r;
-    p.ih0 = kPatchH * p.tr * S - g.pt;
+    p.ih0 = PH * p.tr * S - g.pt;
     p.iw0 = kPatchW * p.tc * S - g.pl;
     p.base = ((p.n * g.H + p.ih0) * g.W + p.iw0) * K * 2;
     return p;
@@ -161,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void separable_window_f16_kernel(const ha
     // operands of the chunk's k-steps are formed for both slabs.  The clamp is a median of three; that
     // instruction drops a NaN, so NaNs are looked for on the side and a wavefront that holds one repeats the
     // layer with the exact form.
-    h8 a[2][KS];
+    h8 a[SL][KS];
     auto depthwise = [&](auto exact) {
       unsigned long long nan = 0;
       if constexpr (decltype(exact)::value) load_chunk(oc, 0);
@@ -180,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void separable_window_f16_kernel(const ha
           const f32x4 b0 = *reinterpret_cast<const f32x4*>(dwb_l + 32 * s + 8 * q);
           const f32x4 b1 = *reinterpret_cast<const f32x4*>(dwb_l + 32 * s + 8 * q + 4);
 #pragma unroll
-          for (int sl = 0; sl < 2; ++sl) {
+          for (int sl = 0; sl < SL; ++sl) {
             float acc[8] = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
             // (a loop over the window's rows that is not unrolled: unrolled, the compiler reads all nine taps of
             // both operands ahead and runs out of registers)
@@ -220,36 +227,44 @@ __global__ __launch_bounds__(kThreads) void separable_window_f16_kernel(const ha
     const Offsets on = offsets_of(pn, nxt < u1);
     load_chunk(on, 0);
 
-    // pointwise layer, one k-step's filter fragments at a time (the scheduling barriers keep the compiler from
-    // gathering all the reads in front, which does not fit the registers); the accumulators start from the bias
-    f32x4 acc0[NB], acc1[NB];
+    // pointwise layer, 128 output channels per pass over the operands and one k-step's filter fragments at a time
+    // (the scheduling barriers keep the compiler from gathering all the reads in front, which does not fit the
+    // registers); the accumulators start from the bias
 #pragma unroll
-    for (int j = 0; j < NB; ++j) acc0[j] = acc1[j] = *reinterpret_cast<const f32x4*>(pwb_l + 16 * j + 4 * q);
+    for (int p = 0; p < PASSES; ++p) {
+      f32x4 acc[SL][NBP];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      h8 fw[NB];
+      for (int j = 0; j < NBP; ++j) {
+        const f32x4 b = *reinterpret_cast<const f32x4*>(pwb_l + 16 * (NBP * p + j) + 4 * q);
 #pragma unroll
-      for (int j = 0; j < NB; ++j) fw[j] = *reinterpret_cast<const h8*>(w_base + 16 * j * LD + 32 * s);
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        acc0[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw[j], a[0][s], acc0[j], 0, 0, 0);
-        acc1[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw[j], a[1][s], acc1[j], 0, 0, 0);
+        for (int sl = 0; sl < SL; ++sl) acc[sl][j] = b;
       }
-      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        h8 fw[NBP];
+#pragma unroll
+        for (int j = 0; j < NBP; ++j) fw[j] = *reinterpret_cast<const h8*>(w_base + 16 * (NBP * p + j) * LD + 32 * s);
+#pragma unroll
+        for (int j = 0; j < NBP; ++j)
+#pragma unroll
+          for (int sl = 0; sl < SL; ++sl)
+            acc[sl][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw[j], a[sl][s], acc[sl][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // epilogue: activation, and one 16-byte store per lane, slab and 32 channels
+      auto emit = [&](const f32x4 (&acc)[NBP], int slab) {
+        const int oh = PH * pc.tr + 2 * slab + li / 8, ow = kPatchW * pc.tc + li % 8;
+        half_t* const yp = y + ((size_t)(pc.n * g.OH + oh) * g.OW + ow) * N + 16 * NBP * p + 8 * q;
+        h8 o[NBP / 2];
+        activate_and_pack(acc, pw_clamp, o);
+        if (oh < g.OH && ow < g.OW) {
+#pragma unroll
+          for (int m = 0; m < NBP / 2; ++m) *reinterpret_cast<h8*>(yp + 32 * m) = o[m];
+        }
+      };
+#pragma unroll
+      for (int sl = 0; sl < SL; ++sl) emit(acc[sl], sl);
     }
-    // epilogue: activation, and one 16-byte store per lane, slab and 32 channels
-    auto emit = [&](const f32x4 (&acc)[NB], int slab) {
-      const int oh = kPatchH * pc.tr + 2 * slab + li / 8, ow = kPatchW * pc.tc + li % 8;
-      half_t* const yp = y + ((size_t)(pc.n * g.OH + oh) * g.OW + ow) * N + 8 * q;
-      h8 o[NB / 2];
-      activate_and_pack(acc, pw_clamp, o);
-      if (oh < g.OH && ow < g.OW) {
-#pragma unroll
-        for (int m = 0; m < NB / 2; ++m) *reinterpret_cast<h8*>(yp + 32 * m) = o[m];
-      }
-    };
-    emit(acc0, 0);
-    emit(acc1, 1);
     cur = nxt;
     pc = pn;
     oc = on;
@@ -259,7 +274,7 @@ __global__ __launch_bounds__(kThreads) void separable_window_f16_kernel(const ha
 template <int K, int N, int S>
 int launch_cfg(const half_t* x, const half_t* dw_w, const half_t* dw_b, const half_t* pw_w, const half_t* pw_b,
                half_t* y, const WindowBlockGeom16& g, int units, int dw_act, int pw_act, hipStream_t stream) {
-  using WL = WindowLayout16<S, chunk_channels<K, S>()>;
+  using WL = WindowLayout16<S, chunk_channels<K, S>(), patch_rows<K, N, S>()>;
   constexpr size_t lds_bytes = (size_t)N * filter_row_halfs(K) * 2 + N * 4 + 9 * K * 2 + K * 4 + (size_t)kWaves * WL::kHalfs * 2;
   static_assert(lds_bytes + 64 <= 160 * 1024, "LDS budget per workgroup");
   auto kern = separable_window_f16_kernel<K, N, S>;
@@ -283,13 +298,13 @@ int launch_cfg(const half_t* x, const half_t* dw_w, const half_t* dw_b, const ha
 
 }  // namespace
 
-// Blocks (channels -> filters, stride) of the full-width network's 112 x 112 and 56 x 56 maps, many output pixels,
+// Blocks 1 - 4 (channels -> filters, stride) of the full-width network, many output pixels,
 // 16-byte aligned operands, an input below 2^31 bytes.
 bool separable_stream_f16_supported(int batch, int h, int w, int c, int n, int stride, int oh, int ow, const void* x,
                                     const void* dw_w, const void* dw_b, const void* pw_w, const void* pw_b,
                                     const void* y) {
   const bool shape = (c == 128 && n == 128 && stride == 1) || (c == 64 && n == 128 && stride == 2) ||
-                     (c == 32 && n == 64 && stride == 1);
+                     (c == 32 && n == 64 && stride == 1) || (c == 128 && n == 256 && stride == 2);
   const void* ptrs[] = {x, dw_w, dw_b, pw_w, pw_b, y};
   bool aligned = true;
   for (const void* p : ptrs) aligned = aligned && reinterpret_cast<uintptr_t>(p) % 16 == 0;
@@ -306,7 +321,8 @@ int launch_separable_stream_f16(const uint16_t* x16, const uint16_t* dw_w16, con
   const half_t* pw_w = reinterpret_cast<const half_t*>(pw_w16);
   const half_t* pw_b = reinterpret_cast<const half_t*>(pw_b16);
   half_t* y = reinterpret_cast<half_t*>(y16);
-  const WindowBlockGeom16 g{h, w, oh, ow, pt, pl, (ow + kPatchW - 1) / kPatchW, (oh + kPatchH - 1) / kPatchH,
+  const int ph = (c == 128 && n == 256 && stride == 2) ? patch_rows<128, 256, 2>() : patch_rows<32, 64, 1>();
+  const WindowBlockGeom16 g{h, w, oh, ow, pt, pl, (ow + kPatchW - 1) / kPatchW, (oh + ph - 1) / ph,
                             (unsigned)((long long)batch * h * w * c * 2)};
   const long long units = (long long)batch * g.tiles_c * g.tiles_r;
   if (units > 0x3fffffffLL) return TFX_ERR_UNSUPPORTED;
@@ -316,6 +332,7 @@ int launch_separable_stream_f16(const uint16_t* x16, const uint16_t* dw_w16, con
   TFX_WINDOW_BLOCK16(128, 128, 1)
   TFX_WINDOW_BLOCK16(64, 128, 2)
   TFX_WINDOW_BLOCK16(32, 64, 1)
+  TFX_WINDOW_BLOCK16(128, 256, 2)
 #undef TFX_WINDOW_BLOCK16
   return TFX_ERR_UNSUPPORTED;
 }

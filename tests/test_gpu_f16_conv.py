@@ -353,12 +353,14 @@ def test_mobilenet_f16_end_to_end(size, q, classes, batch):
     assert np.array_equal(host(p2), p) and np.array_equal(host(l2), l)
 
 
-@pytest.mark.parametrize("size,batch,blocks", [(224, 8, (1, 2, 3, 4)), (200, 12, (1, 2, 3)), (224, 3, (1, 2, 3, 5, 13))])
+@pytest.mark.parametrize("size,batch,blocks", [(224, 8, (1, 2, 3, 4)), (200, 12, (1, 2, 3)), (224, 3, (1, 2, 3, 5, 13)),
+                                               (224, 22, (4, 5)), (200, 27, (3, 4))])
 def test_mobilenet_f16_internal_activations(size, batch, blocks):
-    """tfx_mobilenet_v1_features_f16 against the oracle's own feature maps.  From 16384 output pixels on, blocks 1, 2
-    and 3 of the full-width network run as one filter-stationary launch each (batch 8 and 12 here; 200 x 200 images
-    give 100 x 100 and 50 x 50 maps: ragged last patches, an odd padding under stride 2); batch 3 takes the single-op
-    kernels throughout.  The maps are the end of a chain of layers that each round once, so the end-to-end bar
+    """tfx_mobilenet_v1_features_f16 against the oracle's own feature maps.  From 16384 output pixels on, blocks 1, 2,
+    3 and 4 of the full-width network run as one filter-stationary launch each (blocks 1 - 3 at batch 8 and 12, block
+    4 -- one slab per unit, 256 output channels in two passes -- at batch 22 and 27; 200 x 200 images give 100 x 100,
+    50 x 50 and 25 x 25 maps: ragged last patches, an odd padding under stride 2); batch 3 takes the single-op kernels
+    throughout.  The maps are the end of a chain of layers that each round once, so the end-to-end bar
     applies (4 steps at the pixel's largest channel up to block 5, 8 -- the bar of the logits -- beyond), and in the
     first four blocks all but a small share of the
     values -- growing with the depth -- must be the oracle's bit for bit."""
@@ -377,12 +379,12 @@ def test_mobilenet_f16_internal_activations(size, batch, blocks):
     end_to_end_bar(host(l), logits, "f16 logits batch %d size %d" % (batch, size), 8)
 
 
-def test_mobilenet_f16_nan_and_inf_through_the_fused_blocks_at_large_batch():
+@pytest.mark.parametrize("batch,blocks", [(8, (1, 2, 3)), (21, (4,))])
+def test_mobilenet_f16_nan_and_inf_through_the_fused_blocks_at_large_batch(batch, blocks):
     """A NaN in one image reaches exactly the outputs whose windows hold it, block after block, and no other image;
     +inf and -inf clamp as the oracle's relu6 does (the fused kernel clamps both layers with a median of three and
     must notice the NaN on the side)."""
     import paper_1901_05350_amd as tfx
-    batch = 8
     data = inputs.mobilenet_v1_f16(seed=53, batch=batch, image_size=224, width_quarters=4, classes=10)
     img = data["image"].copy()
     img[3, 100, 37, 1] = np.nan
@@ -390,7 +392,7 @@ def test_mobilenet_f16_nan_and_inf_through_the_fused_blocks_at_large_batch():
     img[6, 200, 220, 2] = -np.inf
     probs, logits, acts = oracle.mobilenet_v1_forward_f16(img, data["weights"], return_activations=True)
     model = tfx.MobileNetV1F16(data["weights"], batch=batch, image_size=224, width_quarters=4)
-    for k in (1, 2, 3):
+    for k in blocks:
         got, ref = host(model.features(dev16(img), k)), acts[2 * k]
         assert np.isnan(ref).any() and not np.isnan(ref[3]).all() and not np.isnan(np.delete(ref, 3, axis=0)).any()
         assert np.array_equal(np.isnan(got), np.isnan(ref)), "NaN positions after block %d" % k
