@@ -309,7 +309,9 @@ bool separable_stream_f16_supported(int batch, int h, int w, int c, int n, int s
   bool aligned = true;
   for (const void* p : ptrs) aligned = aligned && reinterpret_cast<uintptr_t>(p) % 16 == 0;
   const long long m = (long long)batch * oh * ow, x_bytes = (long long)batch * h * w * c * 2;
-  return shape && aligned && m >= 16384 && m <= 0x3fffffffLL && x_bytes < (1ll << 31);
+  // least output pixels from which the one launch beats the two kernels (measured on the network, per block)
+  const long long least = n == 256 ? 6272 : 16384;
+  return shape && aligned && m >= least && m <= 0x3fffffffLL && x_bytes < (1ll << 31);
 }
 
 int launch_separable_stream_f16(const uint16_t* x16, const uint16_t* dw_w16, const uint16_t* dw_b16, const uint16_t* pw_w16,

@@ -358,7 +358,7 @@ def test_mobilenet_f16_end_to_end(size, q, classes, batch):
 def test_mobilenet_f16_internal_activations(size, batch, blocks):
     """tfx_mobilenet_v1_features_f16 against the oracle's own feature maps.  From 16384 output pixels on, blocks 1, 2,
     3 and 4 of the full-width network run as one filter-stationary launch each (blocks 1 - 3 at batch 8 and 12, block
-    4 -- one slab per unit, 256 output channels in two passes -- at batch 22 and 27; 200 x 200 images give 100 x 100,
+    4 -- from 6272 pixels on; one slab per unit, 256 output channels in two passes -- at batch 8, 22 and 27; 200 x 200 images give 100 x 100,
     50 x 50 and 25 x 25 maps: ragged last patches, an odd padding under stride 2); batch 3 takes the single-op kernels
     throughout.  The maps are the end of a chain of layers that each round once, so the end-to-end bar
     applies (4 steps at the pixel's largest channel up to block 5, 8 -- the bar of the logits -- beyond), and in the
