@@ -30,21 +30,21 @@ PEAK_HBM = 8.0e12          # B/s
 # source it was measured on, with the digest of that file followed by the shared headers csrc/tfx_internal.h and
 # csrc/stream_f16.h; if any of them has changed since, the entry is reported as null.
 MEASURED_TRAFFIC = {
-    "batch_matmul_8x1024x1024x1024_tB": (100848627, "gemm.hip", "bac39288fc357e2c8673f7ea33783fd405976589242fc0199c98fa77957e03ca"),
-    "pointwise_64x56x56x128_to_128": (206181201, "pointwise.hip", "0a9baa78bfad3ce283cef204e55f924712128b899e78c4fe2fc3060cb0f5c4d8"),
-    "conv3x3_64x56x56x64_to_64": (104547477, "gemm.hip", "bac39288fc357e2c8673f7ea33783fd405976589242fc0199c98fa77957e03ca"),
-    "depthwise_64x112x112x64_s1_cold_rotation": (411140163, "depthwise.hip", "5bf610ceb3e6bbe368ffc0883ae29a9d12cb14357f03d0d20b13db3d36e3b37e"),
-    "depthwise_64x112x112x64_s2_cold_rotation": (257167960, "depthwise.hip", "5bf610ceb3e6bbe368ffc0883ae29a9d12cb14357f03d0d20b13db3d36e3b37e"),
-    "batch_matmul_f16_1x4096x4096x4096_tB": (235078200, "gemm_f16.hip", "924ffb57eaeeb75ba9838b04777ece730400211aedcaf1172be3e0061bfdce75"),
-    "batch_matmul_f16_8x1024x1024x1024_tB": (50493612, "gemm_f16.hip", "924ffb57eaeeb75ba9838b04777ece730400211aedcaf1172be3e0061bfdce75"),
-    "pointwise_f16_64x56x56x128_to_128": (104307312, "pointwise_f16.hip", "ce1b39f22ab2de85935114032f7da23fa19670dd2587c5787ce442e1a65ef9ae"),
-    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205682035, "conv_f16.hip", "afe6f8ef43c1ef8148e17ecfb1317d9bb5da79a3024c8dff8ff47b6ebdc20a4d"),
-    "depthwise_f16_64x112x112x64_s2_cold_rotation": (128552759, "conv_f16.hip", "afe6f8ef43c1ef8148e17ecfb1317d9bb5da79a3024c8dff8ff47b6ebdc20a4d"),
-    "pointwise_f16_64x14x14x512_to_512": (30192349, "pointwise_slab_f16.hip", "af2faf347eb820ccf9a29fb135a9ca89ecf628f4ce49a11949d8b30c7e1a5587"),
-    "conv3x3_f16_64x56x56x64_to_64": (55026541, "conv_stream_f16.hip", "5d25ba83ebb077dcddf0dcaed1a88b53a1395351810b957ba4056c3c06bc7fe9"),
-    "add_f32_64M": (805263264, "elementwise.hip", "7f84a8e7a8ec924bce5600deb9d686a5a76abe82b88ca3d841c7cda5219bee52"),
-    "add_f16_64M": (402651867, "elementwise.hip", "7f84a8e7a8ec924bce5600deb9d686a5a76abe82b88ca3d841c7cda5219bee52"),
-    "mobilenet_chain_kernel": (121651875, "chain.hip", "d6e4fe4eea090fda5555f06e369f20246b30e6da62bbd03727c1832248106007"),
+    "batch_matmul_8x1024x1024x1024_tB": (100848549, "gemm.hip", "bac39288fc357e2c8673f7ea33783fd405976589242fc0199c98fa77957e03ca"),
+    "pointwise_64x56x56x128_to_128": (206181264, "pointwise.hip", "0a9baa78bfad3ce283cef204e55f924712128b899e78c4fe2fc3060cb0f5c4d8"),
+    "conv3x3_64x56x56x64_to_64": (104528320, "gemm.hip", "bac39288fc357e2c8673f7ea33783fd405976589242fc0199c98fa77957e03ca"),
+    "depthwise_64x112x112x64_s1_cold_rotation": (411139682, "depthwise.hip", "5bf610ceb3e6bbe368ffc0883ae29a9d12cb14357f03d0d20b13db3d36e3b37e"),
+    "depthwise_64x112x112x64_s2_cold_rotation": (257119699, "depthwise.hip", "5bf610ceb3e6bbe368ffc0883ae29a9d12cb14357f03d0d20b13db3d36e3b37e"),
+    "batch_matmul_f16_1x4096x4096x4096_tB": (235078145, "gemm_f16.hip", "924ffb57eaeeb75ba9838b04777ece730400211aedcaf1172be3e0061bfdce75"),
+    "batch_matmul_f16_8x1024x1024x1024_tB": (50493600, "gemm_f16.hip", "924ffb57eaeeb75ba9838b04777ece730400211aedcaf1172be3e0061bfdce75"),
+    "pointwise_f16_64x56x56x128_to_128": (104298589, "pointwise_f16.hip", "ce1b39f22ab2de85935114032f7da23fa19670dd2587c5787ce442e1a65ef9ae"),
+    "depthwise_f16_64x112x112x64_s1_cold_rotation": (205682029, "conv_f16.hip", "afe6f8ef43c1ef8148e17ecfb1317d9bb5da79a3024c8dff8ff47b6ebdc20a4d"),
+    "depthwise_f16_64x112x112x64_s2_cold_rotation": (128552106, "conv_f16.hip", "afe6f8ef43c1ef8148e17ecfb1317d9bb5da79a3024c8dff8ff47b6ebdc20a4d"),
+    "pointwise_f16_64x14x14x512_to_512": (30193140, "pointwise_slab_f16.hip", "af2faf347eb820ccf9a29fb135a9ca89ecf628f4ce49a11949d8b30c7e1a5587"),
+    "conv3x3_f16_64x56x56x64_to_64": (55026506, "conv_stream_f16.hip", "5d25ba83ebb077dcddf0dcaed1a88b53a1395351810b957ba4056c3c06bc7fe9"),
+    "add_f32_64M": (805262989, "elementwise.hip", "7f84a8e7a8ec924bce5600deb9d686a5a76abe82b88ca3d841c7cda5219bee52"),
+    "add_f16_64M": (402651879, "elementwise.hip", "7f84a8e7a8ec924bce5600deb9d686a5a76abe82b88ca3d841c7cda5219bee52"),
+    "mobilenet_chain_kernel": (121651524, "chain.hip", "d6e4fe4eea090fda5555f06e369f20246b30e6da62bbd03727c1832248106007"),
 }
 
 
